@@ -1,0 +1,158 @@
+/*
+ * wush.h -- C ABI of the MI355X (gfx950) W4A4 WUSH linear-layer library.
+ *
+ * The library computes the per-layer forward of a weight+activation MXFP4
+ * quantized linear layer with block-diagonal, data-aware transforms (paper:
+ * Methodology, "Block-independent constraint", the WUSH construction equation,
+ * Alg. 2 RTN case, and the layer forward-pass equation; kernels: section
+ * "GPU Kernel Support").
+ *
+ * Notation (ours <-> paper).  Tensors are row-major with channels last:
+ *   X [M][K]  activations, M = d_batch tokens, K = d_in channels (paper: X^T)
+ *   W [N][K]  weights, N = d_out (paper: W^T)
+ *   block b = channels 32b .. 32b+31, C = K/32 blocks, d = 32
+ *   T [C][32][32]  T[b][j][k] = (T_wush of block b)[j][k]: input channel k ->
+ *                  transformed channel j
+ *
+ *   Yt[m,32b+j] = sum_k X[m,32b+k] T[b][j][k]                (T_wush X)
+ *   Wt[n,32b+j] = sum_k W[n,32b+k] inv(T[b])[k][j]           (T_wush^{-T} W)
+ *   Y [m,n]     = sum_kappa deq(q(Yt))[m,kappa] deq(q(Wt))[n,kappa]
+ *
+ * Quantizer q (RTN with AbsMax scale per group of 32 consecutive channels):
+ *   element E2M1: 4-bit pattern s|e1 e0|m, codes 0..7 = 0,.5,1,1.5,2,3,4,6;
+ *   scale E8M0: byte s means 2^(s-127), s in 0..254 (255 is never written);
+ *   WUSH_SCALE_NOSAT : smallest power of two with AbsMax <= 6*2^e (no clipping)
+ *   WUSH_SCALE_OCP_FLOOR : e = floor(log2 AbsMax) - 2 (maxima in (6,8)*2^e clip)
+ *   rounding to nearest, ties to the even code; the input's sign bit is kept
+ *   even if the magnitude rounds to zero; an all-zero group gets byte 0.
+ *   NaN/Inf inputs are undefined behaviour.
+ *
+ * Packed layouts (canonical, what every entry point reads and writes):
+ *   codes  [rows][K/2] bytes, element k in byte k/2, even k = low nibble;
+ *   scales [rows][K/32] bytes.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only
+ *     enqueue work and return; results are valid after the stream is
+ *     synchronized.
+ *   - All arguments are validated before any launch.  On any error nothing is
+ *     launched and no output byte is touched; the return value says why.
+ *   - Requirements: M, N, K > 0; K % 32 == 0; data pointers 16-byte aligned;
+ *     input leading dimensions (in elements) >= K and a multiple of 8;
+ *     fmt.block == 32, fmt.elem == WUSH_E2M1, fmt.scale == WUSH_E8M0.
+ */
+#ifndef WUSH_H_
+#define WUSH_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  WUSH_OK = 0,
+  WUSH_ERR_NULL = 1,      /* a required pointer is NULL */
+  WUSH_ERR_SHAPE = 2,     /* non-positive size, K % 32 != 0, bad leading dimension */
+  WUSH_ERR_ALIGN = 3,     /* pointer not 16-byte aligned */
+  WUSH_ERR_FMT = 4,       /* unsupported format descriptor */
+  WUSH_ERR_WORKSPACE = 5, /* workspace missing or too small */
+  WUSH_ERR_DEVICE = 6,    /* the HIP runtime reported a launch error */
+  WUSH_ERR_SINGULAR = 7   /* a transform block is singular (wush_workspace_status) */
+} wush_status;
+
+enum { WUSH_E2M1 = 1 };
+enum { WUSH_E8M0 = 1 };
+enum { WUSH_SCALE_NOSAT = 0, WUSH_SCALE_OCP_FLOOR = 1 };
+enum { WUSH_OUT_BF16 = 0, WUSH_OUT_F32 = 1 };
+
+typedef struct {
+  int32_t block;      /* 32 */
+  int32_t elem;       /* WUSH_E2M1 */
+  int32_t scale;      /* WUSH_E8M0 */
+  int32_t scale_rule; /* WUSH_SCALE_NOSAT (default) or WUSH_SCALE_OCP_FLOOR */
+  int32_t out_dtype;  /* wush_linear only: WUSH_OUT_BF16 (default) or WUSH_OUT_F32 */
+} wush_fmt;
+
+/* The default descriptor: MXFP4, block 32, no-saturation scale, BF16 output. */
+wush_fmt wush_default_fmt(void);
+
+/*
+ * Fused activation transform + quantization: q(T_wush X) of the layer
+ * forward-pass equation, one fused kernel as in "GPU Kernel Support".
+ *   X        in   bf16 [M][ldx] (device), K contiguous channels per row
+ *   T_blocks in   bf16 [K/32][32][32] (device)
+ *   Xq       out  u8 [M][K/2] packed E2M1 codes
+ *   Xs       out  u8 [M][K/32] E8M0 scale bytes
+ *   dbg_Yt   out  optional (may be NULL): f32 [M][K], the transformed values
+ *                 exactly as the kernel fed them to its quantizer (FP32 MFMA
+ *                 accumulators).  Test tap; costs 4 B/element of extra writes.
+ */
+wush_status wush_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx,
+                              const void* T_blocks, wush_fmt fmt,
+                              void* Xq, void* Xs, float* dbg_Yt, void* stream);
+
+/*
+ * Offline weight preparation (Alg. 2, RTN case, last two steps):
+ * T_xvsh = T_wush^{-T}, then q(T_xvsh W).  The inverse of every 32x32 block
+ * is taken in FP64 on the device (Gauss-Jordan, partial pivoting), the product
+ * W_blk inv(T_b) is formed in FP64 and quantized with the same rules as the
+ * activations.
+ *   W        in   bf16 [N][ldw] (device)
+ *   T_blocks in   bf16 [K/32][32][32] (device), the SAME tensor the
+ *                 activation side uses
+ *   Wq, Ws   out  u8 [N][K/2], u8 [N][K/32]
+ *   workspace     device scratch of at least wush_prepare_weight_workspace(N,K)
+ *                 bytes, 16-byte aligned; holds the inverses and a status word.
+ * A singular block (no usable pivot) cannot be reported synchronously; it sets
+ * a flag in the workspace that wush_workspace_status reads back.
+ */
+wush_status wush_prepare_weight(const void* W, int64_t N, int64_t K, int64_t ldw,
+                                const void* T_blocks, wush_fmt fmt,
+                                void* Wq, void* Ws,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+size_t wush_prepare_weight_workspace(int64_t N, int64_t K);
+
+/*
+ * Synchronizes `stream`, copies the status word of a workspace last used by
+ * wush_prepare_weight (for input size K) to the host and returns WUSH_OK or
+ * WUSH_ERR_SINGULAR.  This is the only entry point that blocks.
+ */
+wush_status wush_workspace_status(const void* workspace, int64_t K, void* stream);
+
+/*
+ * MXFP4 x MXFP4 GEMM with FP32 accumulation: the sum over blocks of the layer
+ * forward-pass equation, Y = deq(Xq,Xs) . deq(Wq,Ws)^T, on block-scaled MFMA.
+ *   Xq, Xs   in   u8 [M][K/2], u8 [M][K/32]
+ *   Wq, Ws   in   u8 [N][K/2], u8 [N][K/32]
+ *   Y        out  [M][ldy], bf16 (fmt.out_dtype == WUSH_OUT_BF16, rounded to
+ *                 nearest even from the FP32 accumulator) or f32
+ * ldy >= N (elements); Y aligned to its element size.  The tiled kernel needs
+ * Y 16-byte aligned and ldy a multiple of 8; other layouts take a slower
+ * general kernel.
+ */
+wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
+                        int64_t M, int64_t N, int64_t K, wush_fmt fmt,
+                        void* Y, int64_t ldy, void* stream);
+
+/*
+ * Test tap: the quantizer alone on FP32 values (same device function the fused
+ * kernel uses).  Yt f32 [M][K] (device) -> q u8 [M][K/2], s u8 [M][K/32].
+ */
+wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fmt,
+                              void* q, void* s, void* stream);
+
+/* Human-readable name of a status code; static storage, never NULL. */
+const char* wush_status_string(wush_status st);
+
+/* Library version, "major.minor"; static storage. */
+const char* wush_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WUSH_H_ */

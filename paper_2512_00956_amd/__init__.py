@@ -1,0 +1,27 @@
+"""MI355X-native W4A4 WUSH linear-layer hot path.
+
+The package is a thin ctypes binding over the C-ABI library `libwush.so`
+(hand-written HIP kernels for gfx950).  Nothing here computes: every step of the
+path runs inside the library.  Importing the package does not load the
+library; the first call does, and fails loudly if it has not been built.
+"""
+from .binding import (  # noqa: F401
+    WushError,
+    WushFmt,
+    default_fmt,
+    lib,
+    lib_path,
+    wush_linear,
+    wush_prepare_weight,
+    wush_prepare_weight_workspace,
+    wush_quantize_act,
+    wush_quantize_f32,
+    wush_status_string,
+    wush_workspace_status,
+)
+
+__all__ = [
+    "WushError", "WushFmt", "default_fmt", "lib", "lib_path", "wush_linear", "wush_prepare_weight",
+    "wush_prepare_weight_workspace", "wush_quantize_act", "wush_quantize_f32", "wush_status_string",
+    "wush_workspace_status",
+]

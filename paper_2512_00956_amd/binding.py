@@ -1,0 +1,152 @@
+"""ctypes binding of include/wush.h: argument marshalling only.
+
+Tensor arguments are torch tensors on the GPU (torch is used for device memory
+and streams); each wrapper passes `data_ptr()`s, sizes and the current HIP
+stream to the C entry point of the same name and raises `WushError` on a
+non-zero status.  No fallback exists: if `libwush.so` is missing the first call
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, c_char_p, c_float, c_int32, c_int64, c_size_t, c_void_p
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libwush.so"
+
+WUSH_SCALE_NOSAT, WUSH_SCALE_OCP_FLOOR = 0, 1
+WUSH_OUT_BF16, WUSH_OUT_F32 = 0, 1
+
+STATUS_NAMES = {
+    0: "WUSH_OK", 1: "WUSH_ERR_NULL", 2: "WUSH_ERR_SHAPE", 3: "WUSH_ERR_ALIGN", 4: "WUSH_ERR_FMT",
+    5: "WUSH_ERR_WORKSPACE", 6: "WUSH_ERR_DEVICE", 7: "WUSH_ERR_SINGULAR",
+}
+
+# every symbol include/wush.h declares
+EXPORTS = (
+    "wush_default_fmt", "wush_quantize_act", "wush_prepare_weight", "wush_prepare_weight_workspace",
+    "wush_workspace_status", "wush_linear", "wush_quantize_f32", "wush_status_string", "wush_version",
+)
+
+
+class WushFmt(ctypes.Structure):
+    _fields_ = [("block", c_int32), ("elem", c_int32), ("scale", c_int32),
+                ("scale_rule", c_int32), ("out_dtype", c_int32)]
+
+
+class WushError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {STATUS_NAMES.get(code, code)} ({wush_status_string(code)})")
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C library (loads it on first use)."""
+    global _lib
+    if _lib is None:
+        p = lib_path()
+        if not os.path.exists(p):
+            raise RuntimeError(
+                f"{p} not found: build it first (python -m paper_2512_00956_amd.build); "
+                "there is no fallback path")
+        L = ctypes.CDLL(p)
+        L.wush_default_fmt.restype = WushFmt
+        L.wush_default_fmt.argtypes = []
+        L.wush_quantize_act.restype = c_int32
+        L.wush_quantize_act.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, WushFmt,
+                                        c_void_p, c_void_p, c_void_p, c_void_p]
+        L.wush_prepare_weight.restype = c_int32
+        L.wush_prepare_weight.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, WushFmt,
+                                          c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+        L.wush_prepare_weight_workspace.restype = c_size_t
+        L.wush_prepare_weight_workspace.argtypes = [c_int64, c_int64]
+        L.wush_workspace_status.restype = c_int32
+        L.wush_workspace_status.argtypes = [c_void_p, c_int64, c_void_p]
+        L.wush_linear.restype = c_int32
+        L.wush_linear.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64,
+                                  WushFmt, c_void_p, c_int64, c_void_p]
+        L.wush_quantize_f32.restype = c_int32
+        L.wush_quantize_f32.argtypes = [c_void_p, c_int64, c_int64, WushFmt, c_void_p, c_void_p, c_void_p]
+        L.wush_status_string.restype = c_char_p
+        L.wush_status_string.argtypes = [c_int32]
+        L.wush_version.restype = c_char_p
+        L.wush_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def default_fmt(scale_rule: int = WUSH_SCALE_NOSAT, out_dtype: int = WUSH_OUT_BF16) -> WushFmt:
+    f = lib().wush_default_fmt()
+    f.scale_rule = scale_rule
+    f.out_dtype = out_dtype
+    return f
+
+
+def wush_status_string(code: int) -> str:
+    return lib().wush_status_string(int(code)).decode()
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return c_void_p(torch.cuda.current_stream().cuda_stream)
+    return c_void_p(stream if isinstance(stream, int) else stream.cuda_stream)
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise WushError(code, where)
+
+
+def wush_quantize_act(X, T_blocks, Xq, Xs, fmt: WushFmt | None = None, dbg_Yt=None, stream=None):
+    """X bf16 [M][K] (row stride X.stride(0)), T_blocks bf16 [K/32][32][32] ->
+    Xq u8 [M][K/2], Xs u8 [M][K/32] (pre-allocated by the caller)."""
+    M, K = X.shape
+    _check(lib().wush_quantize_act(_ptr(X), M, K, X.stride(0), _ptr(T_blocks), fmt or default_fmt(),
+                                   _ptr(Xq), _ptr(Xs), _ptr(dbg_Yt), _stream(stream)), "wush_quantize_act")
+
+
+def wush_prepare_weight_workspace(N: int, K: int) -> int:
+    return int(lib().wush_prepare_weight_workspace(N, K))
+
+
+def wush_prepare_weight(W, T_blocks, Wq, Ws, workspace, fmt: WushFmt | None = None, stream=None):
+    """W bf16 [N][K] -> Wq u8 [N][K/2], Ws u8 [N][K/32]; workspace: u8 tensor of
+    at least wush_prepare_weight_workspace(N, K) bytes."""
+    N, K = W.shape
+    _check(lib().wush_prepare_weight(_ptr(W), N, K, W.stride(0), _ptr(T_blocks), fmt or default_fmt(),
+                                     _ptr(Wq), _ptr(Ws), _ptr(workspace),
+                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                     _stream(stream)), "wush_prepare_weight")
+
+
+def wush_workspace_status(workspace, K: int, stream=None):
+    _check(lib().wush_workspace_status(_ptr(workspace), K, _stream(stream)), "wush_workspace_status")
+
+
+def wush_linear(Xq, Xs, Wq, Ws, Y, fmt: WushFmt | None = None, stream=None):
+    """Y [M][N] (bf16 or f32 per fmt.out_dtype, row stride Y.stride(0)) =
+    deq(Xq, Xs) . deq(Wq, Ws)^T."""
+    M, K2 = Xq.shape
+    N = Wq.shape[0]
+    _check(lib().wush_linear(_ptr(Xq), _ptr(Xs), _ptr(Wq), _ptr(Ws), M, N, 2 * K2, fmt or default_fmt(),
+                             _ptr(Y), Y.stride(0), _stream(stream)), "wush_linear")
+
+
+def wush_quantize_f32(Yt, q, s, fmt: WushFmt | None = None, stream=None):
+    """Quantizer-only test tap: Yt f32 [M][K] -> q u8 [M][K/2], s u8 [M][K/32]."""
+    M, K = Yt.shape
+    _check(lib().wush_quantize_f32(_ptr(Yt), M, K, fmt or default_fmt(), _ptr(q), _ptr(s), _stream(stream)),
+           "wush_quantize_f32")

@@ -1,0 +1,168 @@
+// Fused activation transform + MXFP4 quantization for gfx950:
+//   Xq, Xs = q(T_wush X)   (layer forward-pass equation; "Fused WUSH + Quant
+//   kernel" in section "GPU Kernel Support" states the operation: C independent
+//   dense GxG transforms fused with the quantizer, memory bound at G = 32).
+//
+// Design (ours, for CDNA4).  The product is computed transposed,
+// Yt_b^T = T_b . X_b^T, on v_mfma_f32_32x32x16_bf16 (two issues per 32x32x32
+// block product).  With that orientation
+//   * the X-side operand of a lane is 16 consecutive BF16 of one token: two
+//     128-bit global loads straight into VGPRs, no LDS round trip;
+//   * T_b is the A operand and stays in registers while the wave walks down
+//     the token dimension (each wave owns 4 adjacent blocks = 256 B of every
+//     token row, the 4 waves of a workgroup cover 1 KiB of the row);
+//   * after the MFMA a lane holds 16 output channels of ONE token, so the
+//     per-32 AbsMax is 15 in-register max + one v_permlane32_swap;
+//   * rows of T_b are fed in a permuted order so that those 16 channels are
+//     a contiguous half of the group; the hardware fp4 convert then emits the
+//     codes in canonical nibble order.
+// Codes of two blocks are exchanged between the wave halves so every lane
+// stores 32 contiguous bytes; the 4 scale bytes of a token go out as one dword.
+#include "wush_device.hpp"
+#include "wush_kernels.hpp"
+
+namespace wush {
+
+namespace {
+
+constexpr int kNB = 4;       // blocks per wave
+constexpr int kWaves = 4;    // waves per workgroup
+constexpr int kTileM = 32;   // tokens per MFMA tile
+
+struct XFrag {
+  v8bf lo, hi;  // channels 16h..16h+7 and 16h+8..16h+15 of one token, one block
+};
+
+__device__ __forceinline__ void load_tile(XFrag (&x)[kNB], const uint16_t* __restrict__ X,
+                                          int64_t ldx, int row, int bfirst, int C, int h) {
+#pragma unroll
+  for (int bb = 0; bb < kNB; ++bb) {
+    const int b = min(bfirst + bb, C - 1);  // clamped: out-of-range blocks reload a valid one
+    const uint16_t* p = X + (int64_t)row * ldx + 32 * b + 16 * h;
+    x[bb].lo = *reinterpret_cast<const v8bf*>(p);
+    x[bb].hi = *reinterpret_cast<const v8bf*>(p + 8);
+  }
+}
+
+template <bool DBG>
+__global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
+    const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ T,
+    uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs, float* __restrict__ dbg,
+    int M, int K, int C, int tiles_per_wg, int rule) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int tok = lane & 31;
+  const int h = lane >> 5;
+  const int bfirst = (blockIdx.y * kWaves + wave) * kNB;
+  if (bfirst >= C) return;  // wave-uniform
+  const int nb = min(kNB, C - bfirst);
+
+  // A operand: MFMA row position i carries output channel c(i), chosen so that
+  // accumulator r of lane half h is channel 16h + r.
+  const int crow = 16 * ((tok >> 2) & 1) + 4 * (tok >> 3) + (tok & 3);
+  v8bf ta[kNB][2];
+#pragma unroll
+  for (int bb = 0; bb < kNB; ++bb) {
+    const int b = min(bfirst + bb, C - 1);
+    const uint16_t* p = T + ((int64_t)b * 32 + crow) * 32 + 16 * h;
+    ta[bb][0] = *reinterpret_cast<const v8bf*>(p);
+    ta[bb][1] = *reinterpret_cast<const v8bf*>(p + 8);
+  }
+
+  const int ntiles = (M + kTileM - 1) / kTileM;
+  int t = blockIdx.x * tiles_per_wg;
+  const int tend = min(t + tiles_per_wg, ntiles);
+  if (t >= tend) return;
+
+  XFrag cur[kNB], nxt[kNB];
+  load_tile(cur, X, ldx, min(t * kTileM + tok, M - 1), bfirst, C, h);
+
+  for (; t < tend; ++t) {
+    const int m = t * kTileM + tok;
+    const bool row_ok = m < M;
+    if (t + 1 < tend) load_tile(nxt, X, ldx, min((t + 1) * kTileM + tok, M - 1), bfirst, C, h);
+
+    uint32_t w[kNB][2];
+    uint32_t sbytes = 0;
+#pragma unroll
+    for (int bb = 0; bb < kNB; ++bb) {
+      v16f acc = {0};
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta[bb][0], cur[bb].lo, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta[bb][1], cur[bb].hi, acc, 0, 0, 0);
+      float v[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) v[r] = acc[r];
+      if (DBG) {
+        if (row_ok && bb < nb) {
+          float* d = dbg + (int64_t)m * K + 32 * (bfirst + bb) + 16 * h;
+#pragma unroll
+          for (int r = 0; r < 16; r += 4)
+            *reinterpret_cast<v4f*>(d + r) = (v4f){v[r], v[r + 1], v[r + 2], v[r + 3]};
+        }
+      }
+      float amax = fabsf(v[0]);
+#pragma unroll
+      for (int r = 1; r < 16; ++r) amax = fmaxf(amax, fabsf(v[r]));
+      // other half of the group lives in lane ^ 32
+      const uint32_t ab = __float_as_uint(amax);
+      const auto sw = __builtin_amdgcn_permlane32_swap(ab, ab, false, false);
+      amax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+      const int byte = scale_byte_f32(amax, rule);
+      const float sc = scale_as_f32(byte);
+      w[bb][0] = pack8_e2m1(v, sc);
+      w[bb][1] = pack8_e2m1(v + 8, sc);
+      sbytes |= (uint32_t)byte << (8 * bb);
+    }
+
+    // Exchange halves: lanes 0..31 end up with the full 16 bytes of blocks 0
+    // and 1 of their token, lanes 32..63 with blocks 2 and 3.
+    v4u out[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const auto s0 = __builtin_amdgcn_permlane32_swap(w[p][0], w[p + 2][0], false, false);
+      const auto s1 = __builtin_amdgcn_permlane32_swap(w[p][1], w[p + 2][1], false, false);
+      out[p] = (v4u){s0[0], s1[0], s0[1], s1[1]};
+    }
+    if (row_ok) {
+      uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
+      if (nb == kNB && (C & 3) == 0) {
+        *reinterpret_cast<v4u*>(q) = out[0];
+        *reinterpret_cast<v4u*>(q + 16) = out[1];
+        if (h == 0) *reinterpret_cast<uint32_t*>(Xs + (int64_t)m * C + bfirst) = sbytes;
+      } else {
+        // ragged tail of the channel dimension: blocks 2h and 2h+1 of this lane
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+          if (2 * h + p < nb) *reinterpret_cast<v4u*>(q + 16 * p) = out[p];
+        if (h == 0)
+          for (int bb = 0; bb < nb; ++bb) Xs[(int64_t)m * C + bfirst + bb] = (uint8_t)(sbytes >> (8 * bb));
+      }
+    }
+#pragma unroll
+    for (int bb = 0; bb < kNB; ++bb) cur[bb] = nxt[bb];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T,
+                                  int rule, void* Xq, void* Xs, float* dbg, hipStream_t stream) {
+  const int C = (int)(K / 32);
+  const int col_groups = (C + kWaves * kNB - 1) / (kWaves * kNB);
+  const int ntiles = (int)((M + kTileM - 1) / kTileM);
+  // Enough workgroups to fill 256 CUs several times over, but long enough
+  // token walks that the register-resident T_b is amortized.
+  int tiles_per_wg = 8;
+  while (tiles_per_wg > 1 && (int64_t)col_groups * ((ntiles + tiles_per_wg - 1) / tiles_per_wg) < 2048) tiles_per_wg >>= 1;
+  dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
+  dim3 block(kWaves * 64);
+  if (dbg)
+    transform_quant_kernel<true><<<grid, block, 0, stream>>>(
+        (const uint16_t*)X, ldx, (const uint16_t*)T, (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M, (int)K, C, tiles_per_wg, rule);
+  else
+    transform_quant_kernel<false><<<grid, block, 0, stream>>>(
+        (const uint16_t*)X, ldx, (const uint16_t*)T, (uint8_t*)Xq, (uint8_t*)Xs, nullptr, (int)M, (int)K, C, tiles_per_wg, rule);
+  return hipGetLastError();
+}
+
+}  // namespace wush

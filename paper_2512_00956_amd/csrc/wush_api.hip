@@ -1,0 +1,126 @@
+// C ABI of the library: argument validation, then kernel launches on the
+// caller's stream.  No allocation, no global state, no host synchronization
+// (except wush_workspace_status, which is documented to block).
+#include "../../include/wush.h"
+
+#include <hip/hip_runtime.h>
+
+#include "wush_kernels.hpp"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline wush_status check_fmt(const wush_fmt& f) {
+  if (f.block != 32 || f.elem != WUSH_E2M1 || f.scale != WUSH_E8M0) return WUSH_ERR_FMT;
+  if (f.scale_rule != WUSH_SCALE_NOSAT && f.scale_rule != WUSH_SCALE_OCP_FLOOR) return WUSH_ERR_FMT;
+  if (f.out_dtype != WUSH_OUT_BF16 && f.out_dtype != WUSH_OUT_F32) return WUSH_ERR_FMT;
+  return WUSH_OK;
+}
+
+// Kernel index arithmetic uses 32-bit row/column counters and 64-bit offsets.
+constexpr int64_t kMaxDim = (int64_t)1 << 30;
+
+inline wush_status check_rows(int64_t rows, int64_t K, int64_t ld) {
+  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxDim) return WUSH_ERR_SHAPE;
+  if (K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (ld < K || ld % 8 != 0) return WUSH_ERR_SHAPE;
+  return WUSH_OK;
+}
+
+inline wush_status from_hip(hipError_t e) { return e == hipSuccess ? WUSH_OK : WUSH_ERR_DEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+wush_fmt wush_default_fmt(void) {
+  wush_fmt f;
+  f.block = 32;
+  f.elem = WUSH_E2M1;
+  f.scale = WUSH_E8M0;
+  f.scale_rule = WUSH_SCALE_NOSAT;
+  f.out_dtype = WUSH_OUT_BF16;
+  return f;
+}
+
+wush_status wush_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T_blocks,
+                              wush_fmt fmt, void* Xq, void* Xs, float* dbg_Yt, void* stream) {
+  if (!X || !T_blocks || !Xq || !Xs) return WUSH_ERR_NULL;
+  if (wush_status s = check_fmt(fmt)) return s;
+  if (wush_status s = check_rows(M, K, ldx)) return s;
+  if (!aligned16(X) || !aligned16(T_blocks) || !aligned16(Xq) || !aligned16(Xs) || !aligned16(dbg_Yt))
+    return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_transform_quant(X, M, K, ldx, T_blocks, fmt.scale_rule, Xq, Xs, dbg_Yt,
+                                               static_cast<hipStream_t>(stream)));
+}
+
+size_t wush_prepare_weight_workspace(int64_t N, int64_t K) {
+  if (N <= 0 || K <= 0 || K % 32 != 0) return 0;
+  return wush::weight_prep_workspace_bytes(N, K);
+}
+
+wush_status wush_prepare_weight(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T_blocks,
+                                wush_fmt fmt, void* Wq, void* Ws, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+  if (!W || !T_blocks || !Wq || !Ws) return WUSH_ERR_NULL;
+  if (wush_status s = check_fmt(fmt)) return s;
+  if (wush_status s = check_rows(N, K, ldw)) return s;
+  if (!aligned16(W) || !aligned16(T_blocks) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
+  if (!workspace || workspace_bytes < wush::weight_prep_workspace_bytes(N, K)) return WUSH_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_weight_prep(W, N, K, ldw, T_blocks, fmt.scale_rule, Wq, Ws, workspace,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_workspace_status(const void* workspace, int64_t K, void* stream) {
+  if (!workspace) return WUSH_ERR_NULL;
+  if (K <= 0 || K % 32 != 0) return WUSH_ERR_SHAPE;
+  int flag = 0;
+  const char* p = static_cast<const char*>(workspace) + wush::weight_prep_status_offset(K);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&flag, p, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess) return WUSH_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return WUSH_ERR_DEVICE;
+  return flag ? WUSH_ERR_SINGULAR : WUSH_OK;
+}
+
+wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M,
+                        int64_t N, int64_t K, wush_fmt fmt, void* Y, int64_t ldy, void* stream) {
+  if (!Xq || !Xs || !Wq || !Ws || !Y) return WUSH_ERR_NULL;
+  if (wush_status s = check_fmt(fmt)) return s;
+  if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim || K % 32 != 0)
+    return WUSH_ERR_SHAPE;
+  if (ldy < N) return WUSH_ERR_SHAPE;
+  if (!aligned16(Xq) || !aligned16(Xs) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
+  const uintptr_t elem = fmt.out_dtype == WUSH_OUT_F32 ? 4 : 2;
+  if (reinterpret_cast<uintptr_t>(Y) % elem != 0) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_mxfp4_gemm(Xq, Xs, Wq, Ws, M, N, K, fmt.out_dtype == WUSH_OUT_F32, Y, ldy,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fmt, void* q, void* s,
+                              void* stream) {
+  if (!Yt || !q || !s) return WUSH_ERR_NULL;
+  if (wush_status st = check_fmt(fmt)) return st;
+  if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (!aligned16(Yt) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_quantize_f32(Yt, M, K, fmt.scale_rule, q, s, static_cast<hipStream_t>(stream)));
+}
+
+const char* wush_status_string(wush_status st) {
+  switch (st) {
+    case WUSH_OK: return "ok";
+    case WUSH_ERR_NULL: return "null pointer";
+    case WUSH_ERR_SHAPE: return "bad shape or leading dimension";
+    case WUSH_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case WUSH_ERR_FMT: return "unsupported format";
+    case WUSH_ERR_WORKSPACE: return "workspace missing or too small";
+    case WUSH_ERR_DEVICE: return "HIP runtime error";
+    case WUSH_ERR_SINGULAR: return "singular transform block";
+  }
+  return "unknown status";
+}
+
+const char* wush_version(void) { return "0.1"; }
+
+}  // extern "C"

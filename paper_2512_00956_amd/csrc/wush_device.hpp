@@ -1,0 +1,70 @@
+// Device-side helpers shared by the gfx950 kernels: vector types, the E8M0
+// scale rule on FP32 bit patterns, and E2M1 packing through the hardware
+// convert.  (Quantizer: RTN with AbsMax scales per group of 32 -- paper,
+// Methodology, "Block-independent constraint".)
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace wush {
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+constexpr int kBlock = 32;  // transform block = quantization group
+
+// E8M0 byte for a group whose largest magnitude is `amax` (>= 0, finite).
+//   rule 0 (no saturation): smallest e with amax <= 6 * 2^e.  6 * 2^e is
+//   1.5 * 2^(e+2), so e = exponent(amax) - 2, plus one when the significand
+//   exceeds 1.5; adding 0x3FFFFF to the bit pattern carries into the exponent
+//   field exactly in that case.
+//   rule 1 (OCP floor): e = exponent(amax) - 2.
+// Zero and FP32 denormals fall through to byte 0.
+__device__ __forceinline__ int scale_byte_f32(float amax, int rule) {
+  const uint32_t bits = __float_as_uint(amax);
+  const int biased = rule == 0 ? (int)((bits + 0x3FFFFFu) >> 23) : (int)(bits >> 23);
+  return min(max(biased - 2, 0), 254);
+}
+
+// The power of two 2^(byte-127) as an FP32 bit pattern.  Byte 0 (2^-127) is
+// an FP32 denormal; the fp4 convert only looks at the exponent field of its
+// scale operand, where an all-zero field already means 2^-127.
+__device__ __forceinline__ float scale_as_f32(int byte) {
+  return __uint_as_float((uint32_t)byte << 23);
+}
+
+// Round two FP32 values divided by the power-of-two `scale` to E2M1 (nearest,
+// ties to even, saturating, sign of zero kept) and place the byte
+// (first value = low nibble) at byte position SEL of `word`.
+template <int SEL>
+__device__ __forceinline__ uint32_t pack2_e2m1(uint32_t word, float a, float b, float scale) {
+  return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(word, a, b, scale, SEL);
+}
+
+// Eight FP32 values -> one 32-bit word of E2M1 codes, element i in nibble i.
+__device__ __forceinline__ uint32_t pack8_e2m1(const float* v, float scale) {
+  uint32_t w = 0;
+  w = pack2_e2m1<0>(w, v[0], v[1], scale);
+  w = pack2_e2m1<1>(w, v[2], v[3], scale);
+  w = pack2_e2m1<2>(w, v[4], v[5], scale);
+  w = pack2_e2m1<3>(w, v[6], v[7], scale);
+  return w;
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+  return __uint_as_float((uint32_t)b << 16);
+}
+
+// FP32 -> BF16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+}  // namespace wush

@@ -1,0 +1,109 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before any launch (so fake,
+never-dereferenced device addresses are enough here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2512_00956_amd as P
+from paper_2512_00956_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(P.lib_path()):
+        from paper_2512_00956_amd.build import build
+        build()
+    return P.lib()
+
+
+def test_header_symbols_are_exported(L):
+    text = open(os.path.join(ROOT, "include", "wush.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(wush_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert L.wush_version() == b"0.1"
+
+
+def test_default_fmt_and_status_strings(L):
+    f = P.default_fmt()
+    assert (f.block, f.elem, f.scale, f.scale_rule, f.out_dtype) == (32, 1, 1, 0, 0)
+    names = {P.wush_status_string(c) for c in range(8)}
+    assert len(names) == 8 and "ok" in names
+    assert P.wush_status_string(99) == "unknown status"
+
+
+A = 0x10000  # a 16-byte aligned fake address; never dereferenced on error paths
+
+
+def test_quantize_act_validation(L):
+    f = P.default_fmt()
+    q = lambda *a: L.wush_quantize_act(*a)
+    assert q(None, 4, 64, 64, A, f, A, A, None, None) == 1          # null X
+    assert q(A, 4, 64, 64, None, f, A, A, None, None) == 1          # null T
+    assert q(A, 4, 64, 64, A, f, None, A, None, None) == 1
+    assert q(A, 0, 64, 64, A, f, A, A, None, None) == 2             # M = 0
+    assert q(A, 4, 48, 48, A, f, A, A, None, None) == 2             # K % 32
+    assert q(A, 4, 64, 56, A, f, A, A, None, None) == 2             # ldx < K
+    assert q(A, 4, 64, 68, A, f, A, A, None, None) == 2             # ldx % 8
+    assert q(A + 2, 4, 64, 64, A, f, A, A, None, None) == 3         # misaligned
+    assert q(A, 4, 64, 64, A, f, A, A + 8, None, None) == 3
+    assert q(A, 4, 64, 64, A, f, A, A, A + 4, None) == 3            # misaligned debug tap
+    for field, val in (("block", 16), ("elem", 2), ("scale", 0), ("scale_rule", 2), ("out_dtype", 5)):
+        g = P.default_fmt()
+        setattr(g, field, val)
+        assert q(A, 4, 64, 64, A, g, A, A, None, None) == 4
+
+
+def test_prepare_weight_validation(L):
+    f = P.default_fmt()
+    need = L.wush_prepare_weight_workspace(8, 64)
+    assert need >= 2 * 32 * 32 * 8 + 4
+    assert L.wush_prepare_weight_workspace(8, 48) == 0
+    w = lambda *a: L.wush_prepare_weight(*a)
+    assert w(A, 8, 64, 64, A, f, A, A, None, need, None) == 5       # no workspace
+    assert w(A, 8, 64, 64, A, f, A, A, A, need - 1, None) == 5      # too small
+    assert w(A, 8, 64, 64, A, f, A, A, A + 4, need, None) == 3
+    assert w(None, 8, 64, 64, A, f, A, A, A, need, None) == 1
+    assert w(A, 8, 40, 64, A, f, A, A, A, need, None) == 2
+    assert L.wush_workspace_status(None, 64, None) == 1
+    assert L.wush_workspace_status(A, 50, None) == 2
+
+
+def test_linear_and_tap_validation(L):
+    f = P.default_fmt()
+    g = P.default_fmt(out_dtype=1)
+    lin = lambda *a: L.wush_linear(*a)
+    assert lin(A, A, A, A, 4, 8, 64, f, None, 8, None) == 1
+    assert lin(A, A, A, A, 4, 8, 96 + 16, f, A, 8, None) == 2       # K % 32
+    assert lin(A, A, A, A, 4, 9, 64, f, A, 8, None) == 2            # ldy < N
+    assert lin(A, A, A, A, 4, 9, 64, f, A + 1, 12, None) == 3       # bf16 Y at an odd address
+    assert lin(A, A, A, A, 4, 9, 64, g, A + 2, 12, None) == 3       # f32 Y not 4-byte aligned
+    assert lin(A, A, A, A, -1, 9, 64, f, A, 16, None) == 2
+    assert lin(A, A + 1, A, A, 4, 8, 64, f, A, 8, None) == 3
+    tap = lambda *a: L.wush_quantize_f32(*a)
+    assert tap(None, 4, 64, f, A, A, None) == 1
+    assert tap(A, 4, 65, f, A, A, None) == 2
+    assert tap(A + 4, 4, 64, f, A, A, None) == 3
+
+
+def test_binding_raises_typed_error(L):
+    class Fake:
+        def __init__(self, shape, stride0, ptr=A):
+            self.shape, self._s, self._p = shape, stride0, ptr
+
+        def stride(self, i):
+            return self._s
+
+        def data_ptr(self):
+            return self._p
+
+    with pytest.raises(P.WushError) as ei:
+        P.wush_quantize_act(Fake((4, 48), 48), Fake((1, 32, 32), 1024), Fake((4, 24), 24), Fake((4, 1), 1), stream=0)
+    assert ei.value.code == 2 and "WUSH_ERR_SHAPE" in str(ei.value)

@@ -1,0 +1,257 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element on the same seeded inputs.  Acceptance bars:
+  * quantizer: packed codes and scale bytes bit-exact when both sides see the
+    same FP32 values;
+  * fused transform: per-group max error <= 1e-5 of the group's AbsMax; codes
+    against the full-FP64 oracle differ on <= 1e-4 of the elements, every
+    difference explained by a rounding midpoint or a scale threshold;
+  * GEMM: relative Frobenius error <= 2e-3 against the oracle's dequantized
+    FP64 GEMM (BF16 output); FP32 output <= 1e-5.
+"""
+import numpy as np
+import pytest
+
+import wush_inputs as I
+from oracle import wush_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+RULES = {"nosat": 0, "ocp_floor": 1}
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2512_00956_amd as P
+    P.lib()  # fail loudly if the HIP library is missing
+    return P
+
+
+@pytest.fixture(scope="module")
+def G():
+    from tests import gpu_util
+    return gpu_util
+
+
+def _adversarial_f32():
+    """Groups that sit on every rounding midpoint and scale threshold."""
+    rows = []
+    mids = [0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0]
+    pts = []
+    for mpt in mids:
+        f = np.float32(mpt)
+        pts += [f, np.nextafter(f, np.float32(0)), np.nextafter(f, np.float32(10)), -f]
+    pts += [0.0, -0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0]
+    for e in (-130, -126, -100, -10, -1, 0, 1, 5, 60, 120):
+        for top in (6.0, 4.0, np.nextafter(np.float32(6), np.float32(7)), np.nextafter(np.float32(4), np.float32(3)),
+                    3.0, np.nextafter(np.float32(3), np.float32(4)), 7.5, 5.0):
+            g = np.zeros(32, dtype=np.float32)
+            g[: len(pts)][:31] = np.array(pts, dtype=np.float32)[:31]
+            g[31] = -np.float32(top)
+            rows.append(np.ldexp(g, e).astype(np.float32))
+    rows.append(np.zeros(32, dtype=np.float32))
+    tiny = np.zeros(32, dtype=np.float32)
+    tiny[3] = np.float32(1e-42)
+    tiny[4] = -np.float32(3e-39)
+    rows.append(tiny)
+    return np.stack(rows)
+
+
+@pytest.mark.parametrize("rule", ["nosat", "ocp_floor"])
+def test_quantizer_tap_bit_exact(P, G, rule):
+    import torch
+    adv = _adversarial_f32()
+    rnd = I.random_f32((257, 32 * 9), seed=11, spread=12.0)
+    pad = (-adv.shape[0]) % 9
+    adv = np.concatenate([adv, np.zeros((pad, 32), np.float32)]).reshape(-1, 32 * 9)
+    Y = np.concatenate([rnd, adv])
+    M, K = Y.shape
+    q, s = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+    P.wush_quantize_f32(torch.from_numpy(Y).cuda(), q, s, P.default_fmt(scale_rule=RULES[rule]))
+    torch.cuda.synchronize()
+    qr, sr = G.oracle_quant_packed(Y.astype(np.float64), rule)
+    assert np.array_equal(G.host(s), sr)
+    assert np.array_equal(G.host(q), qr)
+
+
+def _layer(cfg, lam=1e-2):
+    L = I.make_layer(cfg)
+    X, Xc, W = (O.bf16_bits_to_f64(L[k]) for k in ("X", "X_cal", "W"))
+    T = O.round_to_bf16(O.build_transforms(W, Xc, lam))
+    return L, X, W, T
+
+
+SHAPES = {
+    "c1": I.CONFIGS["c1"],
+    "ragged": I.scaled(I.CONFIGS["c1"], M=77, K=32 * 13, N=45, calib_tokens=256, n_outlier=3),
+    "tiles": I.scaled(I.CONFIGS["c2"], M=300, K=1024, N=200, calib_tokens=1024, n_outlier=5),
+    "t3": I.scaled(I.CONFIGS["c3"], M=130, K=32 * 20, N=96, calib_tokens=1024, n_outlier=6),
+    "one_token": I.scaled(I.CONFIGS["c1"], M=1, K=128, N=32, calib_tokens=256, n_outlier=1),
+}
+
+
+@pytest.fixture(scope="module", params=list(SHAPES))
+def case(request):
+    cfg = SHAPES[request.param]
+    return (cfg,) + _layer(cfg)
+
+
+@pytest.mark.parametrize("rule", ["nosat", "ocp_floor"])
+def test_transform_quant(P, G, case, rule):
+    import torch
+    cfg, L, X, W, T = case
+    M, K = cfg.M, cfg.K
+    Xd, Td = G.bf16_dev(L["X"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    fmt = P.default_fmt(scale_rule=RULES[rule])
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+    dbg = torch.full((M, K), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_quantize_act(Xd, Td, Xq, Xs, fmt, dbg_Yt=dbg)
+    Xq2, Xs2 = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+    P.wush_quantize_act(Xd, Td, Xq2, Xs2, fmt)
+    torch.cuda.synchronize()
+    xq, xs, yt = G.host(Xq), G.host(Xs), G.host(dbg)
+    # the debug tap does not change the result
+    assert np.array_equal(xq, G.host(Xq2)) and np.array_equal(xs, G.host(Xs2))
+    # (1) quantizer bit-exact on the kernel's own FP32 values
+    assert np.isfinite(yt).all()
+    qr, sr = G.oracle_quant_packed(yt.astype(np.float64), rule)
+    assert np.array_equal(xs, sr)
+    assert np.array_equal(xq, qr)
+    # (2) transformed values against FP64
+    Yt = O.transform_act(X, T)
+    amax = np.max(np.abs(Yt.reshape(M, K // 32, 32)), axis=-1)
+    err = np.max(np.abs(yt.astype(np.float64) - Yt).reshape(M, K // 32, 32), axis=-1)
+    assert np.max(err / amax) <= 1e-5
+    # (3) codes against the full-FP64 oracle path
+    cr, sref = O.quantize_mxfp4(Yt, rule)
+    rate, unexplained = G.code_mismatch_report(Yt, O.unpack_codes(xq), xs, cr, sref)
+    assert rate <= 1e-4 and unexplained == 0, (rate, unexplained)
+
+
+def test_transform_quant_strided_rows(P, G):
+    """ldx > K: the kernel reads rows of a wider buffer."""
+    import torch
+    cfg, L, X, W, T = (SHAPES["ragged"],) + _layer(SHAPES["ragged"])
+    M, K = cfg.M, cfg.K
+    wide = torch.zeros((M, K + 64), dtype=torch.bfloat16, device="cuda")
+    wide[:, :K] = G.bf16_dev(L["X"])
+    Td = G.bf16_dev(O.bf16_values_to_bits(T))
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+    Xq2, Xs2 = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+    P.wush_quantize_act(wide[:, :K], Td, Xq, Xs)
+    P.wush_quantize_act(G.bf16_dev(L["X"]), Td, Xq2, Xs2)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.host(Xq), G.host(Xq2)) and np.array_equal(G.host(Xs), G.host(Xs2))
+
+
+@pytest.mark.parametrize("rule", ["nosat", "ocp_floor"])
+def test_prepare_weight(P, G, case, rule):
+    import torch
+    cfg, L, X, W, T = case
+    N, K = cfg.N, cfg.K
+    Wd, Td = G.bf16_dev(L["W"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    Wq, Ws = G.empty_u8(N, K // 2), G.empty_u8(N, K // 32)
+    ws = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+    P.wush_prepare_weight(Wd, Td, Wq, Ws, ws, P.default_fmt(scale_rule=RULES[rule]))
+    P.wush_workspace_status(ws, K)
+    Wt = O.transform_weight(W, T)
+    cr, sref = O.quantize_mxfp4(Wt, rule)
+    rate, unexplained = G.code_mismatch_report(Wt, O.unpack_codes(G.host(Wq)), G.host(Ws), cr, sref, tol=1e-9)
+    assert rate <= 1e-4 and unexplained == 0, (rate, unexplained)
+
+
+def test_prepare_weight_flags_singular_block(P, G):
+    import torch
+    K, N = 64, 40
+    T = np.stack([np.eye(32), np.eye(32)])
+    T[1, 5, :] = 0.0                                   # rank-deficient second block
+    Wd = G.bf16_dev(I.f32_to_bf16_bits(I.random_f32((N, K), 5, 1.0)))
+    Td = G.bf16_dev(O.bf16_values_to_bits(T))
+    Wq, Ws = G.empty_u8(N, K // 2), G.empty_u8(N, K // 32)
+    ws = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+    P.wush_prepare_weight(Wd, Td, Wq, Ws, ws)
+    with pytest.raises(P.WushError) as ei:
+        P.wush_workspace_status(ws, K)
+    assert ei.value.code == 7
+    # a good tensor clears the flag again
+    P.wush_prepare_weight(Wd, G.bf16_dev(O.bf16_values_to_bits(np.stack([np.eye(32)] * 2))), Wq, Ws, ws)
+    P.wush_workspace_status(ws, K)
+
+
+def test_linear_against_oracle_codes(P, G, case):
+    """GEMM alone: oracle codes in, compare with the oracle's FP64 product."""
+    import torch
+    cfg, L, X, W, T = case
+    M, N, K = cfg.M, cfg.N, cfg.K
+    xc, xs = O.quantize_mxfp4(O.transform_act(X, T))
+    wc, wsc = O.quantize_mxfp4(O.transform_weight(W, T))
+    Yref = O.linear_dequant(xc, xs, wc, wsc)
+    args = (G.u8_dev(O.pack_codes(xc)), G.u8_dev(xs), G.u8_dev(O.pack_codes(wc)), G.u8_dev(wsc))
+    Yb = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    Yf = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_linear(*args, Yb)
+    P.wush_linear(*args, Yf, P.default_fmt(out_dtype=1))
+    torch.cuda.synchronize()
+    yb = O.bf16_bits_to_f64(G.host(Yb))
+    yf = G.host(Yf).astype(np.float64)
+    assert O.rel_fro(yf, Yref) <= 1e-5
+    assert O.rel_fro(yb, Yref) <= 2e-3
+    # BF16 output is the FP32 result rounded to nearest even
+    assert np.array_equal(yb, O.round_to_bf16(yf))
+
+
+def test_layer_end_to_end(P, G, case):
+    """quantize_act -> prepare_weight -> linear on the GPU, against the oracle's
+    quantized forward and (for context) the unquantized product."""
+    import torch
+    cfg, L, X, W, T = case
+    M, N, K = cfg.M, cfg.N, cfg.K
+    Td = G.bf16_dev(O.bf16_values_to_bits(T))
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+    Wq, Ws = G.empty_u8(N, K // 2), G.empty_u8(N, K // 32)
+    ws = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    P.wush_prepare_weight(G.bf16_dev(L["W"]), Td, Wq, Ws, ws)
+    P.wush_quantize_act(G.bf16_dev(L["X"]), Td, Xq, Xs)
+    P.wush_linear(Xq, Xs, Wq, Ws, Y)
+    torch.cuda.synchronize()
+    y = O.bf16_bits_to_f64(G.host(Y))
+    Yq = O.layer_forward(X, W, T)
+    # a handful of boundary codes may differ; their effect on the output is far below the bar
+    assert O.rel_fro(y, Yq) <= 2e-3
+    # and the GEMM on the GPU's own codes is exact to FP32/BF16 rounding
+    Yown = O.linear_dequant(O.unpack_codes(G.host(Xq)), G.host(Xs), O.unpack_codes(G.host(Wq)), G.host(Ws))
+    assert O.rel_fro(y, Yown) <= 2e-3
+
+
+def test_outputs_untouched_outside_their_extent(P, G):
+    """Guard bands around every output stay intact (ragged M, N, K/32)."""
+    import torch
+    cfg = SHAPES["ragged"]
+    _, L, X, W, T = (cfg,) + _layer(cfg)
+    M, N, K = cfg.M, cfg.N, cfg.K
+    Td = G.bf16_dev(O.bf16_values_to_bits(T))
+    pad = 4096
+
+    def guarded(nbytes):
+        buf = torch.full((nbytes + 2 * pad,), 0xA5, dtype=torch.uint8, device="cuda")
+        return buf, buf[pad:pad + nbytes]
+
+    bq, Xq = guarded(M * K // 2)
+    bs, Xs = guarded(M * K // 32)
+    by, Yb = guarded(M * N * 2)
+    P.wush_quantize_act(G.bf16_dev(L["X"]), Td, Xq.view(M, K // 2), Xs.view(M, K // 32))
+    Wq, Ws = G.empty_u8(N, K // 2), G.empty_u8(N, K // 32)
+    ws = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+    P.wush_prepare_weight(G.bf16_dev(L["W"]), Td, Wq, Ws, ws)
+    # N = 45 is odd: use ldy = 48 inside a guarded buffer
+    by, Yraw = guarded(M * 48 * 2)
+    Y = Yraw.view(torch.bfloat16).view(M, 48)
+    P.wush_linear(Xq.view(M, K // 2), Xs.view(M, K // 32), Wq, Ws, Y[:, :N])
+    torch.cuda.synchronize()
+    for b in (bq, bs, by):
+        h = b.cpu().numpy()
+        assert (h[:pad] == 0xA5).all() and (h[-pad:] == 0xA5).all()
+    yh = Yraw.cpu().numpy().reshape(M, 96)
+    assert (yh[:, 2 * N:] == 0xA5).all()       # columns N..47 of every row untouched
