@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A4 WUSH layer forward on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+wush_quantize_act (fused transform + MXFP4 quantization of the activations)
+followed by wush_linear (MXFP4 GEMM) against weights prepared once, offline,
+by wush_prepare_weight.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line:
+  value      layer TFLOP/s = 2*M*N*K / (time of one step)
+  roofline   the dominant kernel (the GEMM; for the activation-only workload
+             the transform+quantize kernel) against the MI355X peak, with its
+             average launch duration measured by HIP events on the launch stream
+  cpu_baseline  the CPU oracle's layer forward timed on this machine's host cores
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import wush_inputs as I  # noqa: E402
+
+PEAK_FP4_TFLOPS = 10100.0   # MI355X dense MXFP4 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+WORKLOADS = {
+    "c2": "Llama-3.1-8B fused QKV projection, M=2048 K=4096 N=6144, MXFP4 W4A4, 128 WUSH blocks",
+    "c3": "Llama-3.1-8B MLP down projection, M=4096 K=14336 N=4096, MXFP4 W4A4, 448 WUSH blocks",
+    "c4": "activation path only (wush_quantize_act), M=16384 K=4096",
+    "c5": "Llama-70B MLP gate+up projection, M=8192 K=8192 N=57344, MXFP4 W4A4, 256 WUSH blocks",
+}
+
+
+def quant_bytes(M, K):
+    """Algorithmic HBM bytes of transform+quantize: 2 B read + 0.5 B codes +
+    1/32 B scale per element, plus the transforms once."""
+    return M * K * (2 + 0.5 + 1 / 32) + (K // 32) * 2048
+
+
+def cpu_baseline(cfg, T_bits, L, budget_rows):
+    """The oracle's forward (FP64 transform, quantize, dequantize, FP64 GEMM) on
+    a slab of the workload's tokens; weights pre-quantized outside the timing,
+    as on the GPU."""
+    from oracle import wush_oracle as O
+    T = O.bf16_bits_to_f64(T_bits)
+    rows = min(cfg.M, budget_rows)
+    X = O.bf16_bits_to_f64(L["X"][:rows])
+    cores = len(os.sched_getaffinity(0))
+    n_out = min(cfg.N, 8192)
+    if cfg.N:
+        W = O.bf16_bits_to_f64(L["W"][:n_out])
+        wc, ws = O.quantize_mxfp4(O.transform_weight(W, T))
+        del W
+    t0 = time.perf_counter()
+    xc, xs = O.quantize_mxfp4(O.transform_act(X, T))
+    if cfg.N:
+        O.linear_dequant(xc, xs, wc, ws)
+    dt = time.perf_counter() - t0
+    if cfg.N:
+        return {"value": 2.0 * rows * n_out * cfg.K / dt / 1e12, "unit": "TFLOP/s", "cores": cores,
+                "kind": "oracle", "seconds": dt,
+                "sample": f"oracle layer forward on the first {rows} of {cfg.M} tokens and the first {n_out} of "
+                          f"{cfg.N} output channels, full K, weights pre-quantized"}
+    return {"value": quant_bytes(rows, cfg.K) / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "seconds": dt, "sample": f"oracle transform+quantize on the first {rows} of {cfg.M} tokens"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold", type=int, default=0,
+                    help="rotate over this many input/output buffer sets (>1 defeats the 256 MB last-level cache)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_2512_00956_amd as P
+    P.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = I.CONFIGS[args.workload]
+    if args.workload == "c4":
+        cfg = I.scaled(cfg, N=0)
+    M, K, N = cfg.M, cfg.K, cfg.N
+    L = I.make_layer(I.scaled(cfg, calib_tokens=32))  # calibration tokens are not needed for timing
+    T_bits = I.make_transforms_random(K // 32, cfg.seed)
+
+    def bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    nset = max(1, args.cold)
+    Td = bf16(T_bits)
+    Xd = [bf16(L["X"]) for _ in range(nset)]
+    Xq = [torch.empty((M, K // 2), dtype=torch.uint8, device=dev) for _ in range(nset)]
+    Xs = [torch.empty((M, K // 32), dtype=torch.uint8, device=dev) for _ in range(nset)]
+    fmt = P.default_fmt()
+    if N:
+        Wd = bf16(L["W"])
+        Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+        Ws = torch.empty((N, K // 32), dtype=torch.uint8, device=dev)
+        wsp = torch.empty(P.wush_prepare_weight_workspace(N, K), dtype=torch.uint8, device=dev)
+        P.wush_prepare_weight(Wd, Td, Wq, Ws, wsp, fmt)
+        P.wush_workspace_status(wsp, K)
+        del Wd
+        Y = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(nset)]
+
+    def quant(i):
+        P.wush_quantize_act(Xd[i % nset], Td, Xq[i % nset], Xs[i % nset], fmt)
+
+    def gemm(i):
+        P.wush_linear(Xq[i % nset], Xs[i % nset], Wq, Ws, Y[i % nset], fmt)
+
+    def step(i):
+        quant(i)
+        if N:
+            gemm(i)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    def kernel_ms(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    q_ms = kernel_ms(quant)
+    qb = quant_bytes(M, K)
+    kernels = {"wush_quantize_act": {"ms": q_ms, "GB/s": qb / q_ms / 1e6, "frac_hbm": qb / q_ms / 1e6 / PEAK_HBM_GBS,
+                                     "algorithmic_bytes": qb}}
+    if N:
+        g_ms = kernel_ms(gemm)
+        flops = 2.0 * M * N * K
+        kernels["wush_linear"] = {"ms": g_ms, "TFLOP/s": flops / g_ms / 1e9,
+                                  "frac_fp4_mfma": flops / g_ms / 1e9 / PEAK_FP4_TFLOPS}
+        value, unit = flops / ms_per_step / 1e9, "TFLOP/s"
+        roof = {"bound": "mfma", "kernel": "wush_linear (MXFP4 scaled-MFMA GEMM)", "achieved": flops / g_ms / 1e9,
+                "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s", "frac": flops / g_ms / 1e9 / PEAK_FP4_TFLOPS,
+                "traffic": None, "avg_launch_ms": g_ms}
+    else:
+        value, unit = qb / ms_per_step / 1e6, "GB/s"
+        roof = {"bound": "hbm", "kernel": "wush_quantize_act (fused transform+quantize)", "achieved": qb / q_ms / 1e6,
+                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": qb / q_ms / 1e6 / PEAK_HBM_GBS, "traffic": None,
+                "avg_launch_ms": q_ms}
+
+    out = {
+        "metric": "W4A4 layer TFLOP/s (transform+quant+MXFP4 GEMM); % of MXFP4 MFMA & HBM peak",
+        "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "mxfp4 (e2m1 x e8m0), bf16 in/out, f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
+                   "buffer_sets": nset},
+        "roofline": roof, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        rows = {"c2": 2048, "c3": 256, "c4": 2048, "c5": 64}[args.workload]
+        out["cpu_baseline"] = cpu_baseline(cfg, T_bits, L, rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
