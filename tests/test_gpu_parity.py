@@ -255,3 +255,30 @@ def test_outputs_untouched_outside_their_extent(P, G):
         assert (h[:pad] == 0xA5).all() and (h[-pad:] == 0xA5).all()
     yh = Yraw.cpu().numpy().reshape(M, 96)
     assert (yh[:, 2 * N:] == 0xA5).all()       # columns N..47 of every row untouched
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 256), (512, 768, 1024), (300, 200, 512), (129, 1000, 768), (2048, 6144, 4096)])
+def test_linear_tiled_kernel(P, G, M, N, K):
+    """Shapes with K % 256 == 0 run the 256x256 tiled kernel: random codes and
+    scales in, sampled rows against the oracle's FP64 product, plus agreement
+    with the general kernel on the full output."""
+    import torch
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    xc = rng.integers(0, 16, (M, K), dtype=np.uint8)
+    wc = rng.integers(0, 16, (N, K), dtype=np.uint8)
+    xs = rng.integers(118, 134, (M, K // 32), dtype=np.uint8)
+    ws = rng.integers(112, 128, (N, K // 32), dtype=np.uint8)
+    args = (G.u8_dev(O.pack_codes(xc)), G.u8_dev(xs), G.u8_dev(O.pack_codes(wc)), G.u8_dev(ws))
+    Yf = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    Yb = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    P.wush_linear(*args, Yf, P.default_fmt(out_dtype=1))
+    P.wush_linear(*args, Yb)
+    torch.cuda.synchronize()
+    yf = G.host(Yf).astype(np.float64)
+    yb = O.bf16_bits_to_f64(G.host(Yb))
+    rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 24)]))
+    ref = O.dequantize(xc[rows], xs[rows]) @ O.dequantize(wc, ws).T
+    assert np.isfinite(yf).all()
+    assert O.rel_fro(yf[rows], ref) <= 1e-5
+    assert O.rel_fro(yb[rows], ref) <= 2e-3
+    assert np.array_equal(yb, O.round_to_bf16(yf))
