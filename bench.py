@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layout", default="tiled", choices=["tiled", "canonical"],
+                    help="layout of the packed codes/scales between the kernels")
     ap.add_argument("--cold", type=int, default=0,
                     help="rotate over this many input/output buffer sets (>1 defeats the 256 MB last-level cache)")
     args = ap.parse_args()
@@ -111,13 +113,15 @@ def main():
     nset = max(1, args.cold)
     Td = bf16(T_bits)
     Xd = [bf16(L["X"]) for _ in range(nset)]
-    Xq = [torch.empty((M, K // 2), dtype=torch.uint8, device=dev) for _ in range(nset)]
-    Xs = [torch.empty((M, K // 32), dtype=torch.uint8, device=dev) for _ in range(nset)]
-    fmt = P.default_fmt()
+    fmt = P.default_fmt(layout=1 if args.layout == "tiled" else 0)
+    xcb, xsb = P.wush_packed_sizes(M, K, fmt)
+    Xq = [torch.empty(xcb, dtype=torch.uint8, device=dev) for _ in range(nset)]
+    Xs = [torch.empty(xsb, dtype=torch.uint8, device=dev) for _ in range(nset)]
     if N:
         Wd = bf16(L["W"])
-        Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
-        Ws = torch.empty((N, K // 32), dtype=torch.uint8, device=dev)
+        wcb, wsb = P.wush_packed_sizes(N, K, fmt)
+        Wq = torch.empty(wcb, dtype=torch.uint8, device=dev)
+        Ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
         wsp = torch.empty(P.wush_prepare_weight_workspace(N, K), dtype=torch.uint8, device=dev)
         P.wush_prepare_weight(Wd, Td, Wq, Ws, wsp, fmt)
         P.wush_workspace_status(wsp, K)
@@ -128,7 +132,7 @@ def main():
         P.wush_quantize_act(Xd[i % nset], Td, Xq[i % nset], Xs[i % nset], fmt)
 
     def gemm(i):
-        P.wush_linear(Xq[i % nset], Xs[i % nset], Wq, Ws, Y[i % nset], fmt)
+        P.wush_linear(Xq[i % nset], Xs[i % nset], Wq, Ws, Y[i % nset], fmt, K=K)
 
     def step(i):
         quant(i)
@@ -181,7 +185,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp4 (e2m1 x e8m0), bf16 in/out, f32 accumulate", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
-                   "buffer_sets": nset},
+                   "buffer_sets": nset, "packed_layout": args.layout},
         "roofline": roof, "kernels": kernels,
     }
     if not args.no_cpu_baseline:

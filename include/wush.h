@@ -27,9 +27,18 @@
  *   even if the magnitude rounds to zero; an all-zero group gets byte 0.
  *   NaN/Inf inputs are undefined behaviour.
  *
- * Packed layouts (canonical, what every entry point reads and writes):
- *   codes  [rows][K/2] bytes, element k in byte k/2, even k = low nibble;
- *   scales [rows][K/32] bytes.
+ * Packed layouts.
+ *   WUSH_LAYOUT_CANONICAL (default; the reference layout every test reads):
+ *     codes  [rows][K/2] bytes, element k in byte k/2, even k = low nibble;
+ *     scales [rows][K/32] bytes.
+ *   WUSH_LAYOUT_TILED (opaque, fast; K % 256 == 0): the same 16-byte groups and
+ *     scale bytes, reordered into the lane order of the block-scaled MFMA
+ *     operands so that the GEMM reads them with contiguous 128-bit accesses.
+ *     Buffers are padded to a multiple of 256 rows (wush_packed_sizes gives the
+ *     sizes; padding rows may be read but never reach a valid output).  The quantizers
+ *     write it and wush_linear reads it when fmt.layout says so; both operands
+ *     of one wush_linear call use the same layout.  wush_unpack_tiled converts
+ *     it back to canonical.
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
@@ -68,6 +77,7 @@ enum { WUSH_E2M1 = 1 };
 enum { WUSH_E8M0 = 1 };
 enum { WUSH_SCALE_NOSAT = 0, WUSH_SCALE_OCP_FLOOR = 1 };
 enum { WUSH_OUT_BF16 = 0, WUSH_OUT_F32 = 1 };
+enum { WUSH_LAYOUT_CANONICAL = 0, WUSH_LAYOUT_TILED = 1 };
 
 typedef struct {
   int32_t block;      /* 32 */
@@ -75,6 +85,7 @@ typedef struct {
   int32_t scale;      /* WUSH_E8M0 */
   int32_t scale_rule; /* WUSH_SCALE_NOSAT (default) or WUSH_SCALE_OCP_FLOOR */
   int32_t out_dtype;  /* wush_linear only: WUSH_OUT_BF16 (default) or WUSH_OUT_F32 */
+  int32_t layout;     /* packed codes/scales: WUSH_LAYOUT_CANONICAL (default) or WUSH_LAYOUT_TILED */
 } wush_fmt;
 
 /* The default descriptor: MXFP4, block 32, no-saturation scale, BF16 output. */
@@ -85,8 +96,8 @@ wush_fmt wush_default_fmt(void);
  * forward-pass equation, one fused kernel as in "GPU Kernel Support".
  *   X        in   bf16 [M][ldx] (device), K contiguous channels per row
  *   T_blocks in   bf16 [K/32][32][32] (device)
- *   Xq       out  u8 [M][K/2] packed E2M1 codes
- *   Xs       out  u8 [M][K/32] E8M0 scale bytes
+ *   Xq       out  u8 [M][K/2] packed E2M1 codes   } canonical shapes; sizes for the
+ *   Xs       out  u8 [M][K/32] E8M0 scale bytes   } tiled layout: wush_packed_sizes
  *   dbg_Yt   out  optional (may be NULL): f32 [M][K], the transformed values
  *                 exactly as the kernel fed them to its quantizer (FP32 MFMA
  *                 accumulators).  Test tap; costs 4 B/element of extra writes.
@@ -144,6 +155,22 @@ wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const vo
  * kernel uses).  Yt f32 [M][K] (device) -> q u8 [M][K/2], s u8 [M][K/32].
  */
 wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fmt,
+                              void* q, void* s, void* stream);
+
+/*
+ * Buffer sizes (bytes) of the packed codes and scales of a [rows][K] operand
+ * in the layout fmt.layout (quantizer outputs, wush_linear inputs).  Host
+ * pointers out.
+ */
+wush_status wush_packed_sizes(int64_t rows, int64_t K, wush_fmt fmt,
+                              size_t* code_bytes, size_t* scale_bytes);
+
+/*
+ * Tiled -> canonical copy of one packed operand (device pointers; q, s are
+ * canonical u8 [rows][K/2], u8 [rows][K/32]).  For inspection and tests: the
+ * hot path never needs it.
+ */
+wush_status wush_unpack_tiled(const void* q_tiled, const void* s_tiled, int64_t rows, int64_t K,
                               void* q, void* s, void* stream);
 
 /* Human-readable name of a status code; static storage, never NULL. */

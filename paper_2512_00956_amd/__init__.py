@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     lib,
     lib_path,
     wush_linear,
+    wush_packed_sizes,
+    wush_unpack_tiled,
     wush_prepare_weight,
     wush_prepare_weight_workspace,
     wush_quantize_act,
@@ -23,5 +25,5 @@ from .binding import (  # noqa: F401
 __all__ = [
     "WushError", "WushFmt", "default_fmt", "lib", "lib_path", "wush_linear", "wush_prepare_weight",
     "wush_prepare_weight_workspace", "wush_quantize_act", "wush_quantize_f32", "wush_status_string",
-    "wush_workspace_status",
+    "wush_workspace_status", "wush_packed_sizes", "wush_unpack_tiled",
 ]

@@ -17,6 +17,7 @@ _LIB_NAME = "libwush.so"
 
 WUSH_SCALE_NOSAT, WUSH_SCALE_OCP_FLOOR = 0, 1
 WUSH_OUT_BF16, WUSH_OUT_F32 = 0, 1
+WUSH_LAYOUT_CANONICAL, WUSH_LAYOUT_TILED = 0, 1
 
 STATUS_NAMES = {
     0: "WUSH_OK", 1: "WUSH_ERR_NULL", 2: "WUSH_ERR_SHAPE", 3: "WUSH_ERR_ALIGN", 4: "WUSH_ERR_FMT",
@@ -27,12 +28,13 @@ STATUS_NAMES = {
 EXPORTS = (
     "wush_default_fmt", "wush_quantize_act", "wush_prepare_weight", "wush_prepare_weight_workspace",
     "wush_workspace_status", "wush_linear", "wush_quantize_f32", "wush_status_string", "wush_version",
+    "wush_packed_sizes", "wush_unpack_tiled",
 )
 
 
 class WushFmt(ctypes.Structure):
     _fields_ = [("block", c_int32), ("elem", c_int32), ("scale", c_int32),
-                ("scale_rule", c_int32), ("out_dtype", c_int32)]
+                ("scale_rule", c_int32), ("out_dtype", c_int32), ("layout", c_int32)]
 
 
 class WushError(RuntimeError):
@@ -79,15 +81,35 @@ def lib() -> ctypes.CDLL:
         L.wush_status_string.argtypes = [c_int32]
         L.wush_version.restype = c_char_p
         L.wush_version.argtypes = []
+        L.wush_packed_sizes.restype = c_int32
+        L.wush_packed_sizes.argtypes = [c_int64, c_int64, WushFmt, POINTER(c_size_t), POINTER(c_size_t)]
+        L.wush_unpack_tiled.restype = c_int32
+        L.wush_unpack_tiled.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
         _lib = L
     return _lib
 
 
-def default_fmt(scale_rule: int = WUSH_SCALE_NOSAT, out_dtype: int = WUSH_OUT_BF16) -> WushFmt:
+def default_fmt(scale_rule: int = WUSH_SCALE_NOSAT, out_dtype: int = WUSH_OUT_BF16,
+                layout: int = WUSH_LAYOUT_CANONICAL) -> WushFmt:
     f = lib().wush_default_fmt()
     f.scale_rule = scale_rule
     f.out_dtype = out_dtype
+    f.layout = layout
     return f
+
+
+def wush_packed_sizes(rows: int, K: int, fmt: WushFmt | None = None):
+    """(code_bytes, scale_bytes) of a packed [rows][K] operand in fmt.layout."""
+    cb, sb = c_size_t(0), c_size_t(0)
+    _check(lib().wush_packed_sizes(rows, K, fmt or default_fmt(), ctypes.byref(cb), ctypes.byref(sb)),
+           "wush_packed_sizes")
+    return cb.value, sb.value
+
+
+def wush_unpack_tiled(q_tiled, s_tiled, rows: int, K: int, q, s, stream=None):
+    """Tiled -> canonical copy (q u8 [rows][K/2], s u8 [rows][K/32])."""
+    _check(lib().wush_unpack_tiled(_ptr(q_tiled), _ptr(s_tiled), rows, K, _ptr(q), _ptr(s), _stream(stream)),
+           "wush_unpack_tiled")
 
 
 def wush_status_string(code: int) -> str:
@@ -136,12 +158,14 @@ def wush_workspace_status(workspace, K: int, stream=None):
     _check(lib().wush_workspace_status(_ptr(workspace), K, _stream(stream)), "wush_workspace_status")
 
 
-def wush_linear(Xq, Xs, Wq, Ws, Y, fmt: WushFmt | None = None, stream=None):
+def wush_linear(Xq, Xs, Wq, Ws, Y, fmt: WushFmt | None = None, stream=None, K: int | None = None):
     """Y [M][N] (bf16 or f32 per fmt.out_dtype, row stride Y.stride(0)) =
-    deq(Xq, Xs) . deq(Wq, Ws)^T."""
-    M, K2 = Xq.shape
-    N = Wq.shape[0]
-    _check(lib().wush_linear(_ptr(Xq), _ptr(Xs), _ptr(Wq), _ptr(Ws), M, N, 2 * K2, fmt or default_fmt(),
+    deq(Xq, Xs) . deq(Wq, Ws)^T.  M and N come from Y; K from the canonical
+    shape of Xq unless given (the tiled layout has no 2-D shape to read it from)."""
+    M, N = Y.shape
+    if K is None:
+        K = 2 * Xq.shape[-1]
+    _check(lib().wush_linear(_ptr(Xq), _ptr(Xs), _ptr(Wq), _ptr(Ws), M, N, K, fmt or default_fmt(),
                              _ptr(Y), Y.stride(0), _stream(stream)), "wush_linear")
 
 

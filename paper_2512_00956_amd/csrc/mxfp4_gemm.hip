@@ -86,13 +86,18 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(
 // 64 is free as long as both operands agree.  Issue kk (0..3) of lane half kh
 // takes 32-element group 4*kh + kk of the 8 groups of the tile, so the four
 // scale bytes a lane needs in one iteration are one aligned dword of the
-// canonical scale row, consumed byte by byte through the op_sel field.
+// canonical scale row, consumed byte by byte through the op_sel field.  The
+// scale dwords travel through LDS as well (global_load_lds_dword into a
+// per-wave, lane-linear slot), so the main loop holds no VGPR-destination
+// global load and the only vmcnt wait is the one in front of the barrier.
 // ---------------------------------------------------------------------------
 constexpr int kTM = 256, kTN = 256;
 constexpr int kRowB = 128;                       // bytes of K per tile row (256 E2M1)
 constexpr int kATileB = kTM * kRowB;             // 32 KiB
 constexpr int kStageB = (kTM + kTN) * kRowB;     // 64 KiB
-constexpr int kGemmLds = 2 * kStageB;            // 128 KiB
+constexpr int kScaleStageB = 4 * 8 * 256;        // per stage: 4 waves x 8 sub-tiles x (64 lanes x 4 B)
+constexpr int kScaleBase = 2 * kStageB;          // scale staging sits behind the two operand stages
+constexpr int kGemmLds = 2 * kStageB + 2 * kScaleStageB;  // 144 KiB
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -155,6 +160,16 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
   }
   const int fill_off = (64 * wave) * kRowB;               // wave-uniform
 
+  // ---- scale sources: one dword (groups 4kh..4kh+3 of the tile) per row sub-tile
+  const uint8_t* sa_ptr[4];
+  const uint8_t* sb_ptr[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    sa_ptr[s] = Xs + (int64_t)min(m0 + wm * 128 + s * 32 + r, M - 1) * C + 4 * kh;
+    sb_ptr[s] = Ws + (int64_t)min(n0 + wn * 128 + s * 32 + r, N - 1) * C + 4 * kh;
+  }
+  const int scale_slot = kScaleBase + wave * (8 * 256);   // wave-uniform
+
   auto issue_tile = [&](int kt, int stage) {
     uint8_t* sa_ = smem + stage * kStageB + fill_off;
     uint8_t* sb_ = sa_ + kATileB;
@@ -162,6 +177,12 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     for (int j = 0; j < 8; ++j) {
       __builtin_amdgcn_global_load_lds((gptr_t)(a_src[j] + (int64_t)kt * kRowB), (lptr_t)(sa_ + j * 8 * kRowB), 16, 0, 0);
       __builtin_amdgcn_global_load_lds((gptr_t)(b_src[j] + (int64_t)kt * kRowB), (lptr_t)(sb_ + j * 8 * kRowB), 16, 0, 0);
+    }
+    uint8_t* sc_ = smem + scale_slot + stage * kScaleStageB;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      __builtin_amdgcn_global_load_lds((gptr_t)(sa_ptr[s] + 8 * kt), (lptr_t)(sc_ + s * 256), 4, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(sb_ptr[s] + 8 * kt), (lptr_t)(sc_ + (4 + s) * 256), 4, 0, 0);
     }
   };
 
@@ -173,16 +194,6 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
   const int a_rd = (wm * 128 + r) * kRowB;
   const int b_rd = kATileB + (wn * 128 + r) * kRowB;
 
-  // ---- scale pointers: one dword (groups 4kh..4kh+3 of the tile) per row sub-tile
-  const uint8_t* sa_ptr[4];
-  const uint8_t* sb_ptr[4];
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    sa_ptr[s] = Xs + (int64_t)min(m0 + wm * 128 + s * 32 + r, M - 1) * C + 4 * kh;
-    sb_ptr[s] = Ws + (int64_t)min(n0 + wn * 128 + s * 32 + r, N - 1) * C + 4 * kh;
-  }
-  int sa_cur[4], sb_cur[4], sa_nxt[4], sb_nxt[4];
-
   v16f acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -190,40 +201,33 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     for (int j = 0; j < 4; ++j) acc[i][j] = (v16f){0};
 
   issue_tile(0, 0);
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    sa_cur[s] = *reinterpret_cast<const int*>(sa_ptr[s]);
-    sb_cur[s] = *reinterpret_cast<const int*>(sb_ptr[s]);
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
 
   for (int kt = 0; kt < KT; ++kt) {
     const int stage = kt & 1;
-    if (kt + 1 < KT) {
-      issue_tile(kt + 1, stage ^ 1);
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        sa_nxt[s] = *reinterpret_cast<const int*>(sa_ptr[s] + 8 * (kt + 1));
-        sb_nxt[s] = *reinterpret_cast<const int*>(sb_ptr[s] + 8 * (kt + 1));
-      }
-    }
+    if (kt + 1 < KT) issue_tile(kt + 1, stage ^ 1);
     const uint8_t* st = smem + stage * kStageB;
+    const uint8_t* sc = smem + scale_slot + stage * kScaleStageB + 4 * lane;
+    int sa[4], sb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      sa[s] = *reinterpret_cast<const int*>(sc + s * 256);
+      sb[s] = *reinterpret_cast<const int*>(sc + (4 + s) * 256);
+    }
     v4i af[4], bf[4];
 #define WUSH_LOAD_FRAGS(KK)                                                              \
     _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                      \
       af[s] = *reinterpret_cast<const v4i*>(st + a_rd + s * 32 * kRowB + koff[KK]);      \
       bf[s] = *reinterpret_cast<const v4i*>(st + b_rd + s * 32 * kRowB + koff[KK]);      \
     }
-    WUSH_LOAD_FRAGS(0) mma_step<0>(acc, af, bf, sa_cur, sb_cur);
-    WUSH_LOAD_FRAGS(1) mma_step<1>(acc, af, bf, sa_cur, sb_cur);
-    WUSH_LOAD_FRAGS(2) mma_step<2>(acc, af, bf, sa_cur, sb_cur);
-    WUSH_LOAD_FRAGS(3) mma_step<3>(acc, af, bf, sa_cur, sb_cur);
+    WUSH_LOAD_FRAGS(0) mma_step<0>(acc, af, bf, sa, sb);
+    WUSH_LOAD_FRAGS(1) mma_step<1>(acc, af, bf, sa, sb);
+    WUSH_LOAD_FRAGS(2) mma_step<2>(acc, af, bf, sa, sb);
+    WUSH_LOAD_FRAGS(3) mma_step<3>(acc, af, bf, sa, sb);
 #undef WUSH_LOAD_FRAGS
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the next tile has landed
     __syncthreads();
-#pragma unroll
-    for (int s = 0; s < 4; ++s) { sa_cur[s] = sa_nxt[s]; sb_cur[s] = sb_nxt[s]; }
   }
 
   // ---- epilogue: accumulator i of lane (r, kh) in MFMA tile (sm, sn) is output
@@ -250,8 +254,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
 }  // namespace
 
 hipError_t launch_mxfp4_gemm(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
-                             int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
+                             int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y, int64_t ldy,
                              hipStream_t stream) {
+  if (tiled) return launch_mxfp4_gemm_frag(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
   // Debug knob: WUSH_GEMM=simple forces the general kernel.
   static const bool force_simple = [] {
     const char* e = getenv("WUSH_GEMM");

@@ -44,7 +44,7 @@ __device__ __forceinline__ void load_tile(XFrag (&x)[kNB], const uint16_t* __res
   }
 }
 
-template <bool DBG>
+template <bool DBG, bool TILED>
 __global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
     const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ T,
     uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs, float* __restrict__ dbg,
@@ -123,7 +123,22 @@ __global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
       const auto s1 = __builtin_amdgcn_permlane32_swap(w[p][1], w[p + 2][1], false, false);
       out[p] = (v4u){s0[0], s1[0], s0[1], s1[1]};
     }
-    if (row_ok) {
+    if (TILED) {
+      // fragment-order layout: K % 256 == 0, so nb == 4 and bfirst % 4 == 0.
+      // Lanes 0..31 hold blocks bfirst, bfirst+1 of their token (kk = 0, 1),
+      // lanes 32..63 blocks bfirst+2, bfirst+3 (kk = 2, 3); per instruction the
+      // 32 tokens of a half write 512 contiguous bytes.
+      if (row_ok) {
+        const int KT = K >> 8;
+        const int kt = bfirst >> 3, khg = (bfirst >> 2) & 1;
+        const int64_t frag = ((int64_t)t * KT + kt) * 4;   // row block = token tile t
+        uint8_t* q = Xq + ((frag + 2 * h) * 64 + khg * 32 + tok) * 16;
+        *reinterpret_cast<v4u*>(q) = out[0];
+        *reinterpret_cast<v4u*>(q + 1024) = out[1];
+        if (h == 0)
+          *reinterpret_cast<uint32_t*>(Xs + ((((int64_t)t * KT + kt) * 64) + khg * 32 + tok) * 4) = sbytes;
+      }
+    } else if (row_ok) {
       uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
       if (nb == kNB && (C & 3) == 0) {
         *reinterpret_cast<v4u*>(q) = out[0];
@@ -146,7 +161,7 @@ __global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
 }  // namespace
 
 hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T,
-                                  int rule, void* Xq, void* Xs, float* dbg, hipStream_t stream) {
+                                  int rule, int tiled, void* Xq, void* Xs, float* dbg, hipStream_t stream) {
   const int C = (int)(K / 32);
   const int col_groups = (C + kWaves * kNB - 1) / (kWaves * kNB);
   const int ntiles = (int)((M + kTileM - 1) / kTileM);
@@ -156,12 +171,16 @@ hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t l
   while (tiles_per_wg > 1 && (int64_t)col_groups * ((ntiles + tiles_per_wg - 1) / tiles_per_wg) < 2048) tiles_per_wg >>= 1;
   dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
   dim3 block(kWaves * 64);
-  if (dbg)
-    transform_quant_kernel<true><<<grid, block, 0, stream>>>(
-        (const uint16_t*)X, ldx, (const uint16_t*)T, (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M, (int)K, C, tiles_per_wg, rule);
-  else
-    transform_quant_kernel<false><<<grid, block, 0, stream>>>(
-        (const uint16_t*)X, ldx, (const uint16_t*)T, (uint8_t*)Xq, (uint8_t*)Xs, nullptr, (int)M, (int)K, C, tiles_per_wg, rule);
+#define WUSH_TQ_LAUNCH(DBG, TILED)                                                                   \
+  transform_quant_kernel<DBG, TILED><<<grid, block, 0, stream>>>(                                    \
+      (const uint16_t*)X, ldx, (const uint16_t*)T, (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M, (int)K, C, \
+      tiles_per_wg, rule)
+  if (dbg) {
+    if (tiled) WUSH_TQ_LAUNCH(true, true); else WUSH_TQ_LAUNCH(true, false);
+  } else {
+    if (tiled) WUSH_TQ_LAUNCH(false, true); else WUSH_TQ_LAUNCH(false, false);
+  }
+#undef WUSH_TQ_LAUNCH
   return hipGetLastError();
 }
 

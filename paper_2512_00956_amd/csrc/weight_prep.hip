@@ -109,7 +109,7 @@ __device__ __forceinline__ uint32_t e2m1_code_f64(double a) {
 
 __global__ __launch_bounds__(256) void weight_apply_quant_kernel(
     const uint16_t* __restrict__ W, int64_t ldw, const double* __restrict__ Tinv,
-    uint8_t* __restrict__ Wq, uint8_t* __restrict__ Ws, int N, int K, int C, int rule) {
+    uint8_t* __restrict__ Wq, uint8_t* __restrict__ Ws, int N, int K, int C, int rule, int tiled) {
   __shared__ double ti[32][32];  // inv(T_b)[k][j]
   const int b = blockIdx.y;
   for (int i = threadIdx.x; i < 1024; i += 256) ti[i >> 5][i & 31] = Tinv[(int64_t)b * 1024 + i];
@@ -151,15 +151,34 @@ __global__ __launch_bounds__(256) void weight_apply_quant_kernel(
     }
     words[g] = wd;
   }
-  *reinterpret_cast<v4u*>(Wq + (int64_t)n * (K / 2) + 16 * b) = (v4u){words[0], words[1], words[2], words[3]};
-  Ws[(int64_t)n * C + b] = (uint8_t)byte;
+  const v4u chunk = {words[0], words[1], words[2], words[3]};
+  if (tiled) {
+    *reinterpret_cast<v4u*>(Wq + tiled_chunk_offset(n, b, K >> 8)) = chunk;
+    Ws[tiled_scale_offset(n, b, K >> 8)] = (uint8_t)byte;
+  } else {
+    *reinterpret_cast<v4u*>(Wq + (int64_t)n * (K / 2) + 16 * b) = chunk;
+    Ws[(int64_t)n * C + b] = (uint8_t)byte;
+  }
+}
+
+// Tiled -> canonical copy of packed codes and scales (inspection / tests).
+__global__ __launch_bounds__(256) void unpack_tiled_kernel(const uint8_t* __restrict__ qt,
+                                                           const uint8_t* __restrict__ st,
+                                                           uint8_t* __restrict__ q, uint8_t* __restrict__ s,
+                                                           int64_t rows, int C) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;   // one (row, group) per thread
+  if (idx >= rows * C) return;
+  const int row = (int)(idx / C), g = (int)(idx % C);
+  *reinterpret_cast<v4u*>(q + (int64_t)row * C * 16 + 16 * g) =
+      *reinterpret_cast<const v4u*>(qt + tiled_chunk_offset(row, g, C >> 3));
+  s[(int64_t)row * C + g] = st[tiled_scale_offset(row, g, C >> 3)];
 }
 
 // Quantizer-only tap: one thread per group of 32 FP32 values.
 __global__ __launch_bounds__(256) void quantize_f32_kernel(const float* __restrict__ Y,
                                                            uint8_t* __restrict__ q,
                                                            uint8_t* __restrict__ s,
-                                                           int64_t groups, int rule) {
+                                                           int64_t groups, int C, int rule, int tiled) {
   const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (g >= groups) return;
   float v[32];
@@ -177,8 +196,14 @@ __global__ __launch_bounds__(256) void quantize_f32_kernel(const float* __restri
   v4u out;
 #pragma unroll
   for (int i = 0; i < 4; ++i) out[i] = pack8_e2m1(v + 8 * i, sc);
-  *reinterpret_cast<v4u*>(q + g * 16) = out;
-  s[g] = (uint8_t)byte;
+  if (tiled) {
+    const int row = (int)(g / C), grp = (int)(g % C);
+    *reinterpret_cast<v4u*>(q + tiled_chunk_offset(row, grp, C >> 3)) = out;
+    s[tiled_scale_offset(row, grp, C >> 3)] = (uint8_t)byte;
+  } else {
+    *reinterpret_cast<v4u*>(q + g * 16) = out;
+    s[g] = (uint8_t)byte;
+  }
 }
 
 }  // namespace
@@ -188,7 +213,7 @@ size_t weight_prep_status_offset(int64_t K) { return (size_t)(K / 32) * 1024 * s
 size_t weight_prep_workspace_bytes(int64_t /*N*/, int64_t K) { return weight_prep_status_offset(K) + 16; }
 
 hipError_t launch_weight_prep(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T, int rule,
-                              void* Wq, void* Ws, void* workspace, hipStream_t stream) {
+                              int tiled, void* Wq, void* Ws, void* workspace, hipStream_t stream) {
   const int C = (int)(K / 32);
   double* tinv = reinterpret_cast<double*>(workspace);
   int* status = reinterpret_cast<int*>(reinterpret_cast<char*>(workspace) + weight_prep_status_offset(K));
@@ -201,15 +226,23 @@ hipError_t launch_weight_prep(const void* W, int64_t N, int64_t K, int64_t ldw, 
   if (e != hipSuccess) return e;
   dim3 grid((unsigned)((N + 255) / 256), (unsigned)C);
   weight_apply_quant_kernel<<<grid, dim3(256), 0, stream>>>((const uint16_t*)W, ldw, tinv, (uint8_t*)Wq,
-                                                           (uint8_t*)Ws, (int)N, (int)K, C, rule);
+                                                           (uint8_t*)Ws, (int)N, (int)K, C, rule, tiled);
   return hipGetLastError();
 }
 
-hipError_t launch_quantize_f32(const float* Y, int64_t M, int64_t K, int rule, void* q, void* s,
+hipError_t launch_quantize_f32(const float* Y, int64_t M, int64_t K, int rule, int tiled, void* q, void* s,
                                hipStream_t stream) {
   const int64_t groups = M * (K / 32);
   quantize_f32_kernel<<<dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream>>>(
-      Y, (uint8_t*)q, (uint8_t*)s, groups, rule);
+      Y, (uint8_t*)q, (uint8_t*)s, groups, (int)(K / 32), rule, tiled);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpack_tiled(const void* qt, const void* st, int64_t rows, int64_t K, void* q, void* s,
+                               hipStream_t stream) {
+  const int64_t n = rows * (K / 32);
+  unpack_tiled_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(
+      (const uint8_t*)qt, (const uint8_t*)st, (uint8_t*)q, (uint8_t*)s, rows, (int)(K / 32));
   return hipGetLastError();
 }
 

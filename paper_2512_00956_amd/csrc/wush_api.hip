@@ -15,7 +15,13 @@ inline wush_status check_fmt(const wush_fmt& f) {
   if (f.block != 32 || f.elem != WUSH_E2M1 || f.scale != WUSH_E8M0) return WUSH_ERR_FMT;
   if (f.scale_rule != WUSH_SCALE_NOSAT && f.scale_rule != WUSH_SCALE_OCP_FLOOR) return WUSH_ERR_FMT;
   if (f.out_dtype != WUSH_OUT_BF16 && f.out_dtype != WUSH_OUT_F32) return WUSH_ERR_FMT;
+  if (f.layout != WUSH_LAYOUT_CANONICAL && f.layout != WUSH_LAYOUT_TILED) return WUSH_ERR_FMT;
   return WUSH_OK;
+}
+
+// The tiled layout exists only for K a multiple of 256.
+inline wush_status check_layout(const wush_fmt& f, int64_t K) {
+  return (f.layout == WUSH_LAYOUT_TILED && K % 256 != 0) ? WUSH_ERR_SHAPE : WUSH_OK;
 }
 
 // Kernel index arithmetic uses 32-bit row/column counters and 64-bit offsets.
@@ -41,6 +47,7 @@ wush_fmt wush_default_fmt(void) {
   f.scale = WUSH_E8M0;
   f.scale_rule = WUSH_SCALE_NOSAT;
   f.out_dtype = WUSH_OUT_BF16;
+  f.layout = WUSH_LAYOUT_CANONICAL;
   return f;
 }
 
@@ -49,9 +56,11 @@ wush_status wush_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx, 
   if (!X || !T_blocks || !Xq || !Xs) return WUSH_ERR_NULL;
   if (wush_status s = check_fmt(fmt)) return s;
   if (wush_status s = check_rows(M, K, ldx)) return s;
+  if (wush_status s = check_layout(fmt, K)) return s;
   if (!aligned16(X) || !aligned16(T_blocks) || !aligned16(Xq) || !aligned16(Xs) || !aligned16(dbg_Yt))
     return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_transform_quant(X, M, K, ldx, T_blocks, fmt.scale_rule, Xq, Xs, dbg_Yt,
+  return from_hip(wush::launch_transform_quant(X, M, K, ldx, T_blocks, fmt.scale_rule,
+                                               fmt.layout == WUSH_LAYOUT_TILED, Xq, Xs, dbg_Yt,
                                                static_cast<hipStream_t>(stream)));
 }
 
@@ -66,10 +75,12 @@ wush_status wush_prepare_weight(const void* W, int64_t N, int64_t K, int64_t ldw
   if (!W || !T_blocks || !Wq || !Ws) return WUSH_ERR_NULL;
   if (wush_status s = check_fmt(fmt)) return s;
   if (wush_status s = check_rows(N, K, ldw)) return s;
+  if (wush_status s = check_layout(fmt, K)) return s;
   if (!aligned16(W) || !aligned16(T_blocks) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
   if (!workspace || workspace_bytes < wush::weight_prep_workspace_bytes(N, K)) return WUSH_ERR_WORKSPACE;
   if (!aligned16(workspace)) return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_weight_prep(W, N, K, ldw, T_blocks, fmt.scale_rule, Wq, Ws, workspace,
+  return from_hip(wush::launch_weight_prep(W, N, K, ldw, T_blocks, fmt.scale_rule,
+                                           fmt.layout == WUSH_LAYOUT_TILED, Wq, Ws, workspace,
                                            static_cast<hipStream_t>(stream)));
 }
 
@@ -91,10 +102,12 @@ wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const vo
   if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim || K % 32 != 0)
     return WUSH_ERR_SHAPE;
   if (ldy < N) return WUSH_ERR_SHAPE;
+  if (wush_status s = check_layout(fmt, K)) return s;
   if (!aligned16(Xq) || !aligned16(Xs) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
   const uintptr_t elem = fmt.out_dtype == WUSH_OUT_F32 ? 4 : 2;
   if (reinterpret_cast<uintptr_t>(Y) % elem != 0) return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_mxfp4_gemm(Xq, Xs, Wq, Ws, M, N, K, fmt.out_dtype == WUSH_OUT_F32, Y, ldy,
+  return from_hip(wush::launch_mxfp4_gemm(Xq, Xs, Wq, Ws, M, N, K, fmt.out_dtype == WUSH_OUT_F32,
+                                          fmt.layout == WUSH_LAYOUT_TILED, Y, ldy,
                                           static_cast<hipStream_t>(stream)));
 }
 
@@ -103,8 +116,29 @@ wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fm
   if (!Yt || !q || !s) return WUSH_ERR_NULL;
   if (wush_status st = check_fmt(fmt)) return st;
   if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (wush_status st = check_layout(fmt, K)) return st;
   if (!aligned16(Yt) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_quantize_f32(Yt, M, K, fmt.scale_rule, q, s, static_cast<hipStream_t>(stream)));
+  return from_hip(wush::launch_quantize_f32(Yt, M, K, fmt.scale_rule, fmt.layout == WUSH_LAYOUT_TILED, q, s,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_packed_sizes(int64_t rows, int64_t K, wush_fmt fmt, size_t* code_bytes, size_t* scale_bytes) {
+  if (!code_bytes || !scale_bytes) return WUSH_ERR_NULL;
+  if (wush_status st = check_fmt(fmt)) return st;
+  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (wush_status st = check_layout(fmt, K)) return st;
+  const int64_t padded = fmt.layout == WUSH_LAYOUT_TILED ? (rows + 255) / 256 * 256 : rows;
+  *code_bytes = (size_t)(padded * (K / 2));
+  *scale_bytes = (size_t)(padded * (K / 32));
+  return WUSH_OK;
+}
+
+wush_status wush_unpack_tiled(const void* q_tiled, const void* s_tiled, int64_t rows, int64_t K, void* q,
+                              void* s, void* stream) {
+  if (!q_tiled || !s_tiled || !q || !s) return WUSH_ERR_NULL;
+  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxDim || K % 256 != 0) return WUSH_ERR_SHAPE;
+  if (!aligned16(q_tiled) || !aligned16(s_tiled) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_unpack_tiled(q_tiled, s_tiled, rows, K, q, s, static_cast<hipStream_t>(stream)));
 }
 
 const char* wush_status_string(wush_status st) {
@@ -121,6 +155,6 @@ const char* wush_status_string(wush_status st) {
   return "unknown status";
 }
 
-const char* wush_version(void) { return "0.1"; }
+const char* wush_version(void) { return "0.2"; }
 
 }  // extern "C"

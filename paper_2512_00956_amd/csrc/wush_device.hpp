@@ -56,6 +56,29 @@ __device__ __forceinline__ uint32_t pack8_e2m1(const float* v, float scale) {
   return w;
 }
 
+// ---------------------------------------------------------------------------
+// Tiled ("MFMA fragment order") layout of packed codes and scales, used between
+// the quantizers and the tiled GEMM.  Needs K % 256 == 0; buffers are padded to a
+// multiple of 256 rows.  With rb = row/32, r = row%32, and the 32-element group g of a
+// row split as kt = g/8 (K tile of 256), kh = (g%8)/4, kk = g%4:
+//   codes : the 16-byte chunk of (row, g) sits at
+//           ((((rb*KT + kt)*4 + kk)*64) + kh*32 + r) * 16
+//           i.e. [row block][K tile][issue kk][lane = kh*32 + r][16 B]: one
+//           (row block, K tile, kk) fragment is 1 KiB, contiguous, in the lane
+//           order of the scaled 32x32x64 MFMA operand;
+//   scales: the dword holding groups 4kh..4kh+3 of tile kt of the row sits at
+//           ((rb*KT + kt)*64 + kh*32 + r) * 4, byte kk = group 4kh + kk.
+// ---------------------------------------------------------------------------
+__host__ __device__ __forceinline__ int64_t tiled_chunk_offset(int row, int g, int KT) {
+  const int rb = row >> 5, r = row & 31, kt = g >> 3, kh = (g >> 2) & 1, kk = g & 3;
+  return ((((int64_t)rb * KT + kt) * 4 + kk) * 64 + kh * 32 + r) * 16;
+}
+
+__host__ __device__ __forceinline__ int64_t tiled_scale_offset(int row, int g, int KT) {
+  const int rb = row >> 5, r = row & 31, kt = g >> 3, kh = (g >> 2) & 1, kk = g & 3;
+  return (((int64_t)rb * KT + kt) * 64 + kh * 32 + r) * 4 + kk;
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
   return __uint_as_float((uint32_t)b << 16);
 }

@@ -7,20 +7,29 @@
 
 namespace wush {
 
+// `tiled` != 0 selects the fragment-order layout of wush_device.hpp (K % 256 == 0).
 hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T,
-                                  int rule, void* Xq, void* Xs, float* dbg, hipStream_t stream);
+                                  int rule, int tiled, void* Xq, void* Xs, float* dbg, hipStream_t stream);
 
-hipError_t launch_quantize_f32(const float* Y, int64_t M, int64_t K, int rule, void* q, void* s,
+hipError_t launch_quantize_f32(const float* Y, int64_t M, int64_t K, int rule, int tiled, void* q, void* s,
+                               hipStream_t stream);
+
+hipError_t launch_unpack_tiled(const void* qt, const void* st, int64_t rows, int64_t K, void* q, void* s,
                                hipStream_t stream);
 
 // workspace layout: [C][32][32] FP64 inverses, then one int32 status word.
 size_t weight_prep_workspace_bytes(int64_t N, int64_t K);
 size_t weight_prep_status_offset(int64_t K);
 hipError_t launch_weight_prep(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T,
-                              int rule, void* Wq, void* Ws, void* workspace, hipStream_t stream);
+                              int rule, int tiled, void* Wq, void* Ws, void* workspace, hipStream_t stream);
 
 hipError_t launch_mxfp4_gemm(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
-                             int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
+                             int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y, int64_t ldy,
                              hipStream_t stream);
+
+// Operands in the fragment-order layout (K % 256 == 0).
+hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
+                                  int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
+                                  hipStream_t stream);
 
 }  // namespace wush

@@ -28,12 +28,12 @@ def test_header_symbols_are_exported(L):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(L, name) is not None
-    assert L.wush_version() == b"0.1"
+    assert L.wush_version() == b"0.2"
 
 
 def test_default_fmt_and_status_strings(L):
     f = P.default_fmt()
-    assert (f.block, f.elem, f.scale, f.scale_rule, f.out_dtype) == (32, 1, 1, 0, 0)
+    assert (f.block, f.elem, f.scale, f.scale_rule, f.out_dtype, f.layout) == (32, 1, 1, 0, 0, 0)
     names = {P.wush_status_string(c) for c in range(8)}
     assert len(names) == 8 and "ok" in names
     assert P.wush_status_string(99) == "unknown status"
@@ -55,7 +55,9 @@ def test_quantize_act_validation(L):
     assert q(A + 2, 4, 64, 64, A, f, A, A, None, None) == 3         # misaligned
     assert q(A, 4, 64, 64, A, f, A, A + 8, None, None) == 3
     assert q(A, 4, 64, 64, A, f, A, A, A + 4, None) == 3            # misaligned debug tap
-    for field, val in (("block", 16), ("elem", 2), ("scale", 0), ("scale_rule", 2), ("out_dtype", 5)):
+    t = P.default_fmt(layout=1)
+    assert q(A, 4, 128, 128, A, t, A, A, None, None) == 2           # tiled layout needs K % 256 == 0
+    for field, val in (("block", 16), ("elem", 2), ("scale", 0), ("scale_rule", 2), ("out_dtype", 5), ("layout", 2)):
         g = P.default_fmt()
         setattr(g, field, val)
         assert q(A, 4, 64, 64, A, g, A, A, None, None) == 4
@@ -107,3 +109,14 @@ def test_binding_raises_typed_error(L):
     with pytest.raises(P.WushError) as ei:
         P.wush_quantize_act(Fake((4, 48), 48), Fake((1, 32, 32), 1024), Fake((4, 24), 24), Fake((4, 1), 1), stream=0)
     assert ei.value.code == 2 and "WUSH_ERR_SHAPE" in str(ei.value)
+
+
+def test_packed_sizes_and_unpack_validation(L):
+    assert P.wush_packed_sizes(100, 512) == (100 * 256, 100 * 16)
+    assert P.wush_packed_sizes(100, 512, P.default_fmt(layout=1)) == (256 * 256, 256 * 16)
+    assert P.wush_packed_sizes(257, 256, P.default_fmt(layout=1)) == (512 * 128, 512 * 8)
+    with pytest.raises(P.WushError):
+        P.wush_packed_sizes(100, 128, P.default_fmt(layout=1))
+    assert L.wush_unpack_tiled(A, A, 4, 128, A, A, None) == 2
+    assert L.wush_unpack_tiled(None, A, 4, 256, A, A, None) == 1
+    assert L.wush_unpack_tiled(A, A, 4, 256, A + 3, A, None) == 3

@@ -282,3 +282,84 @@ def test_linear_tiled_kernel(P, G, M, N, K):
     assert O.rel_fro(yf[rows], ref) <= 1e-5
     assert O.rel_fro(yb[rows], ref) <= 2e-3
     assert np.array_equal(yb, O.round_to_bf16(yf))
+
+
+# --------------------------------------------------------------------------
+# Tiled (fragment-order) layout: same codes and scales, different order.
+# --------------------------------------------------------------------------
+def _tiled_buffers(P, rows, K):
+    import torch
+    cb, sb = P.wush_packed_sizes(rows, K, P.default_fmt(layout=1))
+    assert cb == -(-rows // 256) * 256 * K // 2 and sb == cb // 16
+    # poison: padding rows must not matter
+    return (torch.full((cb,), 0xEE, dtype=torch.uint8, device="cuda"),
+            torch.full((sb,), 0xEE, dtype=torch.uint8, device="cuda"))
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 200, 512), (77, 45, 256), (2048, 6144, 4096)])
+def test_tiled_layout_is_a_permutation_of_canonical(P, G, M, N, K):
+    import torch
+    cfg = I.scaled(I.CONFIGS["c2"], M=M, K=K, N=N, calib_tokens=8, n_outlier=3)
+    L = I.make_layer(cfg)
+    Td = G.bf16_dev(I.make_transforms_random(K // 32, 7))
+    Xd, Wd = G.bf16_dev(L["X"]), G.bf16_dev(L["W"])
+    canon, tiled = P.default_fmt(), P.default_fmt(layout=1)
+    # activations
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+    P.wush_quantize_act(Xd, Td, Xq, Xs, canon)
+    Xqt, Xst = _tiled_buffers(P, M, K)
+    P.wush_quantize_act(Xd, Td, Xqt, Xst, tiled)
+    Xq2, Xs2 = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+    P.wush_unpack_tiled(Xqt, Xst, M, K, Xq2, Xs2)
+    # weights
+    ws = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+    Wq, Ws = G.empty_u8(N, K // 2), G.empty_u8(N, K // 32)
+    P.wush_prepare_weight(Wd, Td, Wq, Ws, ws, canon)
+    Wqt, Wst = _tiled_buffers(P, N, K)
+    P.wush_prepare_weight(Wd, Td, Wqt, Wst, ws, tiled)
+    Wq2, Ws2 = G.empty_u8(N, K // 2), G.empty_u8(N, K // 32)
+    P.wush_unpack_tiled(Wqt, Wst, N, K, Wq2, Ws2)
+    torch.cuda.synchronize()
+    assert torch.equal(Xq, Xq2) and torch.equal(Xs, Xs2)
+    assert torch.equal(Wq, Wq2) and torch.equal(Ws, Ws2)
+    # the offset formula of the layout, spelled out on the host for a few chunks
+    KT = K // 256
+    xt, xc = G.host(Xqt), G.host(Xq)
+    st_, sc_ = G.host(Xst), G.host(Xs)
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        row, g = int(rng.integers(M)), int(rng.integers(K // 32))
+        rb, r, kt, kh, kk = row // 32, row % 32, g // 8, (g % 8) // 4, g % 4
+        off = ((((rb * KT + kt) * 4 + kk) * 64) + kh * 32 + r) * 16
+        assert np.array_equal(xt[off:off + 16], xc[row, 16 * g:16 * g + 16])
+        assert st_[((rb * KT + kt) * 64 + kh * 32 + r) * 4 + kk] == sc_[row, g]
+    # GEMM on the tiled operands == GEMM on the canonical ones (same products,
+    # same K order inside a tile; FP32 accumulation order may differ across tiles)
+    Yc = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    Yt = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_linear(Xq, Xs, Wq, Ws, Yc, P.default_fmt(out_dtype=1))
+    P.wush_linear(Xqt, Xst, Wqt, Wst, Yt, P.default_fmt(out_dtype=1, layout=1), K=K)
+    torch.cuda.synchronize()
+    yc, yt = G.host(Yc).astype(np.float64), G.host(Yt).astype(np.float64)
+    assert np.isfinite(yt).all()
+    assert O.rel_fro(yt, yc) <= 1e-6
+    rows = np.unique(rng.integers(0, M, 16))
+    ref = O.dequantize(O.unpack_codes(xc[rows]), sc_[rows]) @ O.dequantize(O.unpack_codes(G.host(Wq)), G.host(Ws)).T
+    assert O.rel_fro(yt[rows], ref) <= 1e-5
+    Yb = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    P.wush_linear(Xqt, Xst, Wqt, Wst, Yb, P.default_fmt(layout=1), K=K)
+    torch.cuda.synchronize()
+    assert np.array_equal(O.bf16_bits_to_f64(G.host(Yb)), O.round_to_bf16(yt))
+
+
+def test_tiled_quantizer_tap(P, G):
+    import torch
+    Y = I.random_f32((100, 512), seed=21, spread=6.0)
+    q, s = G.empty_u8(100, 256), G.empty_u8(100, 16)
+    P.wush_quantize_f32(torch.from_numpy(Y).cuda(), q, s)
+    qt, st = _tiled_buffers(P, 100, 512)
+    P.wush_quantize_f32(torch.from_numpy(Y).cuda(), qt, st, P.default_fmt(layout=1))
+    q2, s2 = G.empty_u8(100, 256), G.empty_u8(100, 16)
+    P.wush_unpack_tiled(qt, st, 100, 512, q2, s2)
+    torch.cuda.synchronize()
+    assert torch.equal(q, q2) and torch.equal(s, s2)
