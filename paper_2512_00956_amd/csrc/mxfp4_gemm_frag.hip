@@ -4,20 +4,27 @@
 //
 // Workgroup tile 256 (M) x 256 (N), K advances 256 elements per iteration.
 // The four wavefronts split N: each owns all 256 rows and 64 columns
-// (8 x 2 MFMA tiles, 256 accumulator registers).
+// (8 x 2 MFMA tiles, 256 accumulator registers), so one wave per SIMD.
+// With a single wave per SIMD nothing hides memory or LDS latency but the
+// software pipeline.  Every stream runs two K iterations ahead, and the loads
+// of an iteration are spread one by one between its 64 MFMAs so that no burst
+// of memory instructions ever blocks the (in-order) MFMA issue:
 //   * W fragments (the wave's own 64 columns) go global -> VGPR directly: in
 //     the tiled layout a fragment is 1 KiB contiguous in lane order, so every
-//     load is a perfectly coalesced 128-bit access and no wave loads what
-//     another one loads.  They are fetched one K iteration ahead.
-//   * X fragments (shared by all four waves) go global -> VGPR -> LDS, also one
-//     iteration ahead, into a double-buffered 2 x 32 KiB stage; the LDS image
-//     is the same lane-linear fragment order, so ds_write_b128 / ds_read_b128
-//     are bank-conflict free without any swizzle.
-//   * Scales: one dword per lane per (row block, K tile) straight from the
-//     tiled scale array (256 contiguous bytes per load); its 4 bytes are the
-//     4 MFMA issues of the iteration, selected with op_sel.
-// (Measured on MI355X: direct-to-LDS global loads sustain only ~16 B/clk/CU,
-//  far below what this loop needs, hence the register-staged path.)
+//     load is a perfectly coalesced 128-bit access and no two waves load the
+//     same bytes.  Two register sets; a fragment register is refilled with
+//     tile kt+2 right after the MFMA issue of tile kt that consumed it.
+//   * X fragments and X scales (shared by all four waves) go global -> LDS with
+//     direct-to-LDS loads (no VGPRs in flight) into a 4-stage ring; the LDS
+//     image is the same lane-linear fragment order, so the ds_read_b128 of the
+//     MFMA operands are bank-conflict free without any swizzle.  A ring stage
+//     is made visible one full iteration before its tile is computed, so the
+//     first operand reads of tile kt+1 are issued during the last MFMAs of
+//     tile kt and the per-iteration barrier never exposes LDS latency.
+//   * W scales: one dword per lane per (column block, K tile); its 4 bytes are
+//     the 4 MFMA issues of the iteration, selected with op_sel.
+// vmcnt completes in order, so the wait in front of the per-iteration barrier
+// is a fixed count: everything issued after the ring stage about to be read.
 #include <type_traits>
 
 #include "wush_device.hpp"
@@ -29,32 +36,30 @@ namespace {
 
 constexpr int kTM = 256, kTN = 256;
 constexpr int kFragB = 1024;                 // one 32-row x 64-element fragment
-constexpr int kAStageB = 8 * 4 * kFragB;     // 8 row blocks x 4 issues = 32 KiB
-constexpr int kLds = 2 * kAStageB;
+constexpr int kXStageB = 8 * 4 * kFragB;     // 8 row blocks x 4 issues = 32 KiB
+constexpr int kXsStageB = 8 * 256;           // 8 row blocks x 64 lanes x 4 B
+constexpr int kStages = 4;
+constexpr int kXsBase = kStages * kXStageB;
+constexpr int kLds = kStages * (kXStageB + kXsStageB);   // 136 KiB
 
-struct BFrags { v4i f[2][4]; };              // [column block][issue]
-struct Scales { int a[8]; int b[2]; };
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 
-template <int KK>
-__device__ __forceinline__ void mma_issue(v16f (&acc)[8][2], const v4i (&af)[8], const BFrags& bf,
-                                          const Scales& sc) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const v8i A = {af[i][0], af[i][1], af[i][2], af[i][3], 0, 0, 0, 0};
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const v8i B = {bf.f[j][KK][0], bf.f[j][KK][1], bf.f[j][KK][2], bf.f[j][KK][3], 0, 0, 0, 0};
-      acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A, B, acc[i][j], 4, 4, KK, sc.a[i], KK, sc.b[j]);
-    }
-  }
-}
+struct WSet { v4i f[2][4]; int s[2]; };      // W fragments [column block][issue] and scale dwords
+
+// s_waitcnt immediate (gfx9 encoding) waiting only on vmcnt <= n.
+constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }
+
+// VMEM instructions one wave issues per pipelined iteration: 8 X fragment DMAs,
+// 2 X scale DMAs, 2 W scale loads, 8 W fragment loads.
+constexpr int kDmaPerIter = 10, kVmemPerIter = 20;
 
 template <bool OUT_F32>
 __global__ __launch_bounds__(256) void gemm_frag_kernel(
     const uint8_t* __restrict__ Xq, const uint8_t* __restrict__ Xs,
     const uint8_t* __restrict__ Wq, const uint8_t* __restrict__ Ws,
     int M, int N, int K, void* __restrict__ Y, int64_t ldy, int tiles_m, int tiles_n) {
-  __shared__ __attribute__((aligned(1024))) uint8_t smem[kLds];
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps bases in SGPRs
   const int r = lane & 31, kh = lane >> 5;
@@ -79,36 +84,43 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
 
   // Operand buffers are padded to whole 256-row tiles, so every address below
   // is "uniform base + lane offset"; rows past M or N are read but never stored.
-  // X tile: this wave stages row blocks 2*wave, 2*wave+1 (4 fragments each).
-  const uint8_t* xsrc = Xq + (int64_t)(tm * 8 + 2 * wave) * KT * tile_step;
-  // W fragments and scales of this wave's two column blocks.
-  const uint8_t* wsrc = Wq + (int64_t)(tn * 8 + 2 * wave) * KT * tile_step;
-  const uint8_t* wsc = Ws + (int64_t)(tn * 8 + 2 * wave) * KT * 256;
-  const uint8_t* xsc = Xs + (int64_t)(tm * 8) * KT * 256;
   const int loff = 16 * lane, soff = 4 * lane;
+  // X: this wave fills row blocks 2*wave, 2*wave+1 of every ring stage.
+  const uint8_t* xsrc = Xq + (int64_t)(tm * 8 + 2 * wave) * KT * tile_step + loff;
+  const uint8_t* xssrc = Xs + (int64_t)(tm * 8 + 2 * wave) * KT * 256 + soff;
+  // W fragments and scales of this wave's two column blocks.
+  const uint8_t* wsrc = Wq + (int64_t)(tn * 8 + 2 * wave) * KT * tile_step + loff;
+  const uint8_t* wssrc = Ws + (int64_t)(tn * 8 + 2 * wave) * KT * 256 + soff;
 
-  auto load_x = [&](v4i (&stg)[8], int kt) {
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-        stg[u * 4 + kk] = *reinterpret_cast<const v4i*>(xsrc + ((int64_t)u * KT + kt) * tile_step + kk * kFragB + loff);
+  // direct-to-LDS loads of tile kt: fragment f (0..7) of this wave's two row
+  // blocks, and their two scale dwords
+  auto dma_x_frag = [&](int kt, int f) {
+    const int u = f >> 2, kk = f & 3;
+    uint8_t* dst = smem + (kt % kStages) * kXStageB + ((2 * wave + u) * 4 + kk) * kFragB;
+    __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + ((int64_t)u * KT + kt) * tile_step + kk * kFragB), (lptr_t)dst, 16, 0, 0);
   };
-  auto store_x = [&](const v4i (&stg)[8], int stage) {
-    uint8_t* dst = smem + stage * kAStageB + (2 * wave) * (4 * kFragB) + loff;
-#pragma unroll
-    for (int f = 0; f < 8; ++f) *reinterpret_cast<v4i*>(dst + f * kFragB) = stg[f];
+  auto dma_x_scale = [&](int kt, int u) {
+    uint8_t* dst = smem + kXsBase + (kt % kStages) * kXsStageB + (2 * wave + u) * 256;
+    __builtin_amdgcn_global_load_lds((gptr_t)(xssrc + ((int64_t)u * KT + kt) * 256), (lptr_t)dst, 4, 0, 0);
   };
-  auto load_w_frag = [&](BFrags& bf, int kt, int kk) {
+  auto dma_x = [&](int kt) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      bf.f[j][kk] = *reinterpret_cast<const v4i*>(wsrc + ((int64_t)j * KT + kt) * tile_step + kk * kFragB + loff);
+    for (int f = 0; f < 8; ++f) dma_x_frag(kt, f);
+    dma_x_scale(kt, 0);
+    dma_x_scale(kt, 1);
   };
-  auto load_scales = [&](Scales& sc, int kt) {
+  auto load_w_scales = [&](WSet& w, int kt) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) sc.b[j] = *reinterpret_cast<const int*>(wsc + ((int64_t)j * KT + kt) * 256 + soff);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) sc.a[i] = *reinterpret_cast<const int*>(xsc + ((int64_t)i * KT + kt) * 256 + soff);
+    for (int j = 0; j < 2; ++j) w.s[j] = *reinterpret_cast<const int*>(wssrc + ((int64_t)j * KT + kt) * 256);
+  };
+  auto load_w_frag = [&](WSet& w, int kt, int kk, int j) {
+    w.f[j][kk] = *reinterpret_cast<const v4i*>(wsrc + ((int64_t)j * KT + kt) * tile_step + kk * kFragB);
+  };
+  auto read_x_frag = [&](int kt, int kk, int i) {
+    return *reinterpret_cast<const v4i*>(smem + (kt % kStages) * kXStageB + (i * 4 + kk) * kFragB + loff);
+  };
+  auto read_x_scale = [&](int kt, int i) {
+    return *reinterpret_cast<const int*>(smem + kXsBase + (kt % kStages) * kXsStageB + i * 256 + soff);
   };
 
   v16f acc[8][2];
@@ -117,66 +129,130 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = (v16f){0};
 
-  // ---- prologue
-  v4i stg[8];
-  BFrags bf;
-  Scales sc0, sc1;
-  load_x(stg, 0);
+  // ---- prologue.  The two W register sets (and X scale sets) alternate by
+  // iteration, chosen so that the LAST iteration always runs on set 0: the
+  // drain code then exists in a single version.
+  WSet wset[2];
+  int xsc[2][8];
+  v4i af0[8], af1[8];
+  const int p0 = (KT - 1) & 1;                 // set of iteration 0
+  dma_x(0);
+  if (KT > 1) dma_x(1);
+  if (KT > 2) dma_x(2);
+  if (p0 == 0) {
+    load_w_scales(wset[0], 0);
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) load_w_frag(bf, 0, kk);
-  load_scales(sc0, 0);
-  store_x(stg, 0);
-  __syncthreads();
-
-  // One K iteration: fetch tile kt+1 (X into staging registers, scales into the
-  // other scale set, each W fragment into its own registers as soon as the
-  // issue that used it is done), run the 64 MFMAs of tile kt, then park the
-  // staged X tile in the other LDS stage.
-  auto iteration = [&](int kt, const Scales& scur, Scales& snxt, auto more_tag) {
-    constexpr bool more = decltype(more_tag)::value;
-    if (more) {
-      load_x(stg, kt + 1);
-      load_scales(snxt, kt + 1);
+    for (int kk = 0; kk < 4; ++kk) { load_w_frag(wset[0], 0, kk, 0); load_w_frag(wset[0], 0, kk, 1); }
+    if (KT > 1) {
+      load_w_scales(wset[1], 1);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) { load_w_frag(wset[1], 1, kk, 0); load_w_frag(wset[1], 1, kk, 1); }
     }
-    const uint8_t* st = smem + (kt & 1) * kAStageB + loff;
-    v4i af0[8], af1[8];
-#define WUSH_READ_A(dst, KK)                                                      \
-    _Pragma("unroll") for (int i = 0; i < 8; ++i)                                 \
-      dst[i] = *reinterpret_cast<const v4i*>(st + (i * 4 + KK) * kFragB);
-    // sched_barrier(0) pins the order below: without it the compiler hoists all
-    // fragment reads and next-tile loads to the top of the iteration and spills.
+  } else {
+    load_w_scales(wset[1], 0);
+    load_w_scales(wset[0], 1);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) { load_w_frag(wset[1], 0, kk, 0); load_w_frag(wset[1], 0, kk, 1); }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) { load_w_frag(wset[0], 1, kk, 0); load_w_frag(wset[0], 1, kk, 1); }
+  }
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    af0[i] = read_x_frag(0, 0, i);
+    af1[i] = read_x_frag(0, 1, i);
+  }
+  if (p0 == 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) xsc[0][i] = read_x_scale(0, i);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) xsc[1][i] = read_x_scale(0, i);
+  }
+
+  // One K iteration on tile kt with W set w and X scales xs (af0, af1 already
+  // hold its issue-0 and issue-1 operands).  Flags say which streams still have
+  // work: PFX = tile kt+3 exists (X ring), PFW = tile kt+2 exists (W registers),
+  // NEXT = tile kt+1 exists (its first operands and scales are read here).
+  // Each slot = 2 MFMAs + at most one LDS read + at most one global load.
+#define WUSH_MMA2(KK, AF, i)                                                                                   \
+  {                                                                                                            \
+    const v8i A_ = {AF[i][0], AF[i][1], AF[i][2], AF[i][3], 0, 0, 0, 0};                                       \
+    const v8i B0_ = {w.f[0][KK][0], w.f[0][KK][1], w.f[0][KK][2], w.f[0][KK][3], 0, 0, 0, 0};                  \
+    const v8i B1_ = {w.f[1][KK][0], w.f[1][KK][1], w.f[1][KK][2], w.f[1][KK][3], 0, 0, 0, 0};                  \
+    acc[i][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A_, B0_, acc[i][0], 4, 4, KK, xs[i], KK, w.s[0]); \
+    acc[i][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A_, B1_, acc[i][1], 4, 4, KK, xs[i], KK, w.s[1]); \
+  }
 #define WUSH_FENCE __builtin_amdgcn_sched_barrier(0);
+  auto iteration = [&](int kt, WSet& w, const int (&xs)[8], int (&xs_next)[8], auto pfx_tag, auto pfw_tag,
+                       auto next_tag) {
+    constexpr bool PFX = decltype(pfx_tag)::value, PFW = decltype(pfw_tag)::value, NEXT = decltype(next_tag)::value;
     WUSH_FENCE
-    WUSH_READ_A(af0, 0)
-    WUSH_READ_A(af1, 1)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {            // issue 0: X ring refill, operands of issue 2
+      WUSH_MMA2(0, af0, i)
+      if (PFX) dma_x_frag(kt + 3, i);
+      af0[i] = read_x_frag(kt, 2, i);
+      WUSH_FENCE
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {            // issue 1: X scales, W fragments of issue 0, operands of issue 3
+      WUSH_MMA2(1, af1, i)
+      if (PFX && i < 2) dma_x_scale(kt + 3, i);
+      if (PFW && (i == 2 || i == 3)) load_w_frag(w, kt + 2, 0, i - 2);
+      af1[i] = read_x_frag(kt, 3, i);
+      WUSH_FENCE
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {            // issue 2: W fragments of issue 1, next tile's issue-0 operands
+      WUSH_MMA2(2, af0, i)
+      if (PFW && i < 2) load_w_frag(w, kt + 2, 1, i);
+      if (NEXT) af0[i] = read_x_frag(kt + 1, 0, i);
+      WUSH_FENCE
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {            // issue 3: W fragments of issue 2, next tile's issue-1 operands, scales
+      WUSH_MMA2(3, af1, i)
+      if (PFW && i < 2) load_w_frag(w, kt + 2, 2, i);
+      if (NEXT) {
+        af1[i] = read_x_frag(kt + 1, 1, i);
+        xs_next[i] = read_x_scale(kt + 1, i);
+      }
+      WUSH_FENCE
+    }
+    if (PFW) {
+      load_w_frag(w, kt + 2, 3, 0);
+      load_w_frag(w, kt + 2, 3, 1);
+      load_w_scales(w, kt + 2);
+    }
+    // Ring stage kt+2 (this wave's share, issued during iteration kt-1) must have
+    // landed before the barrier publishes it; vmcnt retires in order, and since
+    // that share the wave issued the 10 W loads of iteration kt-1 and all 20
+    // memory instructions of this one.
+    if (PFX) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmemPerIter - kDmaPerIter + kVmemPerIter));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     WUSH_FENCE
-    mma_issue<0>(acc, af0, bf, scur);
-    WUSH_FENCE
-    if (more) load_w_frag(bf, kt + 1, 0);
-    WUSH_READ_A(af0, 2)
-    WUSH_FENCE
-    mma_issue<1>(acc, af1, bf, scur);
-    WUSH_FENCE
-    if (more) load_w_frag(bf, kt + 1, 1);
-    WUSH_READ_A(af1, 3)
-    WUSH_FENCE
-    mma_issue<2>(acc, af0, bf, scur);
-    WUSH_FENCE
-    if (more) load_w_frag(bf, kt + 1, 2);
-    WUSH_FENCE
-    mma_issue<3>(acc, af1, bf, scur);
-    WUSH_FENCE
-    if (more) load_w_frag(bf, kt + 1, 3);
-#undef WUSH_FENCE
-#undef WUSH_READ_A
-    if (more) store_x(stg, (kt + 1) & 1);
     __syncthreads();
   };
-  for (int kt = 0; kt + 1 < KT; ++kt) {
-    iteration(kt, sc0, sc1, std::true_type{});
-    sc0 = sc1;
+  using T = std::true_type;
+  using F = std::false_type;
+  int kt = 0;
+  const int n_main = KT - 3;                   // iterations with every stream active
+  if (n_main > 0 && (n_main & 1)) {            // odd count: one iteration on set 1 first
+    iteration(0, wset[1], xsc[1], xsc[0], T{}, T{}, T{});
+    kt = 1;
   }
-  iteration(KT - 1, sc0, sc1, std::false_type{});
+  for (; kt + 3 < KT; kt += 2) {
+    iteration(kt, wset[0], xsc[0], xsc[1], T{}, T{}, T{});
+    iteration(kt + 1, wset[1], xsc[1], xsc[0], T{}, T{}, T{});
+  }
+  // drain: KT-3 on set 0, KT-2 on set 1, KT-1 on set 0
+  if (KT >= 3) iteration(KT - 3, wset[0], xsc[0], xsc[1], F{}, T{}, T{});
+  if (KT >= 2) iteration(KT - 2, wset[1], xsc[1], xsc[0], F{}, F{}, T{});
+  iteration(KT - 1, wset[0], xsc[0], xsc[1], F{}, F{}, F{});
+#undef WUSH_MMA2
+#undef WUSH_FENCE
   __builtin_amdgcn_sched_barrier(0);
 
   // ---- epilogue: accumulator e of lane (r, kh) in MFMA tile (i, j) is output
@@ -206,13 +282,21 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
 hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
                                   int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
                                   hipStream_t stream) {
+  static const hipError_t attr = [] {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_frag_kernel<false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_frag_kernel<true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  }();
+  if (attr != hipSuccess) return attr;
   const int tiles_m = (int)((M + kTM - 1) / kTM), tiles_n = (int)((N + kTN - 1) / kTN);
   dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
   if (out_f32)
-    gemm_frag_kernel<true><<<grid, block, 0, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, (const uint8_t*)Wq,
+    gemm_frag_kernel<true><<<grid, block, kLds, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, (const uint8_t*)Wq,
                                                       (const uint8_t*)Ws, (int)M, (int)N, (int)K, Y, ldy, tiles_m, tiles_n);
   else
-    gemm_frag_kernel<false><<<grid, block, 0, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, (const uint8_t*)Wq,
+    gemm_frag_kernel<false><<<grid, block, kLds, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, (const uint8_t*)Wq,
                                                        (const uint8_t*)Ws, (int)M, (int)N, (int)K, Y, ldy, tiles_m, tiles_n);
   return hipGetLastError();
 }
