@@ -58,7 +58,7 @@ template <bool OUT_F32>
 __global__ __launch_bounds__(256) void gemm_frag_kernel(
     const uint8_t* __restrict__ Xq, const uint8_t* __restrict__ Xs,
     const uint8_t* __restrict__ Wq, const uint8_t* __restrict__ Ws,
-    int M, int N, int K, void* __restrict__ Y, int64_t ldy, int tiles_m, int tiles_n) {
+    int M, int N, int K, void* __restrict__ Y, int64_t ldy, int tiles_m, int tiles_n, int vec_store) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps bases in SGPRs
@@ -255,8 +255,53 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
 #undef WUSH_FENCE
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- epilogue: accumulator e of lane (r, kh) in MFMA tile (i, j) is output
+  // ---- epilogue.  Accumulator e of lane (r, kh) in MFMA tile (i, j) is output
   // row 32*i + 8*(e/4) + 4*kh + e%4, column 64*wave + 32*j + r of the tile.
+  if (!OUT_F32 && vec_store) {
+    // BF16, 16-byte-aligned rows: transpose through LDS so that every lane
+    // stores 8 consecutive columns and a store instruction writes 8 full
+    // 128-byte row segments.  The ring is free after the last barrier; each wave
+    // uses a private 2 x 4 KiB area (32 rows x 64 BF16), so no barrier is needed.
+    // Adjacent lanes hold adjacent columns: a DPP swap pairs them so each lane
+    // writes one packed dword (two columns of one row).  Rows with bit 2 set keep
+    // their two 64-byte halves swapped, which spreads the two lane halves over
+    // all banks on the write and is a permutation within the row on the read.
+    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+    typedef float v2f __attribute__((ext_vector_type(2)));
+    uint8_t* area = smem + wave * 8192;
+    const bool odd_lane = lane & 1;
+    uint16_t* Yb = reinterpret_cast<uint16_t*>(Y);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_barrier(0);
+      uint8_t* buf = area + (i & 1) * 4096;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) {
+          const float lo = acc[i][j][e], hi = acc[i][j][e + 1];
+          const float keep = odd_lane ? hi : lo;
+          const float send = odd_lane ? lo : hi;
+          const float recv = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), 0xB1, 0xF, 0xF, true));
+          const v2f pair = odd_lane ? (v2f){recv, keep} : (v2f){keep, recv};
+          const v2bf packed = __builtin_convertvector(pair, v2bf);
+          const int row_l = 8 * (e >> 2) + 4 * kh + (e & 3) + (odd_lane ? 1 : 0);
+          const int d = (16 * j + (r >> 1)) ^ (16 * kh);
+          *reinterpret_cast<v2bf*>(buf + row_l * 128 + 4 * d) = packed;
+        }
+      }
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int row_l = (lane >> 3) + 8 * p;
+        const int chunk = lane & 7;
+        const v4i v = *reinterpret_cast<const v4i*>(buf + row_l * 128 + 16 * (chunk ^ (4 * ((row_l >> 2) & 1))));
+        const int row = m0 + 32 * i + row_l;
+        const int col = n0 + 64 * wave + 8 * chunk;
+        if (row < M && col < N) *reinterpret_cast<v4i*>(Yb + (int64_t)row * ldy + col) = v;
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
 #pragma unroll
@@ -292,12 +337,14 @@ hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq
   if (attr != hipSuccess) return attr;
   const int tiles_m = (int)((M + kTM - 1) / kTM), tiles_n = (int)((N + kTN - 1) / kTN);
   dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+  // 128-bit stores need whole 8-column chunks at 16-byte aligned addresses
+  const int vec_store = (N % 8 == 0) && (ldy % 8 == 0) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
   if (out_f32)
     gemm_frag_kernel<true><<<grid, block, kLds, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, (const uint8_t*)Wq,
-                                                      (const uint8_t*)Ws, (int)M, (int)N, (int)K, Y, ldy, tiles_m, tiles_n);
+                                                      (const uint8_t*)Ws, (int)M, (int)N, (int)K, Y, ldy, tiles_m, tiles_n, vec_store);
   else
     gemm_frag_kernel<false><<<grid, block, kLds, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, (const uint8_t*)Wq,
-                                                       (const uint8_t*)Ws, (int)M, (int)N, (int)K, Y, ldy, tiles_m, tiles_n);
+                                                       (const uint8_t*)Ws, (int)M, (int)N, (int)K, Y, ldy, tiles_m, tiles_n, vec_store);
   return hipGetLastError();
 }
 
