@@ -133,17 +133,18 @@ __global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
         const int kt = bfirst >> 3, khg = (bfirst >> 2) & 1;
         const int64_t frag = ((int64_t)t * KT + kt) * 4;   // row block = token tile t
         uint8_t* q = Xq + ((frag + 2 * h) * 64 + khg * 32 + tok) * 16;
-        *reinterpret_cast<v4u*>(q) = out[0];
-        *reinterpret_cast<v4u*>(q + 1024) = out[1];
+        // streaming output: non-temporal stores keep it from displacing X in the caches
+        __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(q));
+        __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(q + 1024));
         if (h == 0)
-          *reinterpret_cast<uint32_t*>(Xs + ((((int64_t)t * KT + kt) * 64) + khg * 32 + tok) * 4) = sbytes;
+          __builtin_nontemporal_store(sbytes, reinterpret_cast<uint32_t*>(Xs + ((((int64_t)t * KT + kt) * 64) + khg * 32 + tok) * 4));
       }
     } else if (row_ok) {
       uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
       if (nb == kNB && (C & 3) == 0) {
-        *reinterpret_cast<v4u*>(q) = out[0];
-        *reinterpret_cast<v4u*>(q + 16) = out[1];
-        if (h == 0) *reinterpret_cast<uint32_t*>(Xs + (int64_t)m * C + bfirst) = sbytes;
+        __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(q));
+        __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(q + 16));
+        if (h == 0) __builtin_nontemporal_store(sbytes, reinterpret_cast<uint32_t*>(Xs + (int64_t)m * C + bfirst));
       } else {
         // ragged tail of the channel dimension: blocks 2h and 2h+1 of this lane
 #pragma unroll
@@ -165,10 +166,10 @@ hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t l
   const int C = (int)(K / 32);
   const int col_groups = (C + kWaves * kNB - 1) / (kWaves * kNB);
   const int ntiles = (int)((M + kTileM - 1) / kTileM);
-  // Enough workgroups to fill 256 CUs several times over, but long enough
-  // token walks that the register-resident T_b is amortized.
-  int tiles_per_wg = 8;
-  while (tiles_per_wg > 1 && (int64_t)col_groups * ((ntiles + tiles_per_wg - 1) / tiles_per_wg) < 2048) tiles_per_wg >>= 1;
+  // Token walk per workgroup: 4 tiles amortize the register-resident T_b (measured
+  // best on 16384 x 4096); shorter walks when that would leave CUs without work.
+  int tiles_per_wg = 4;
+  while (tiles_per_wg > 1 && (int64_t)col_groups * ((ntiles + tiles_per_wg - 1) / tiles_per_wg) < 1024) tiles_per_wg >>= 1;
   dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
   dim3 block(kWaves * 64);
 #define WUSH_TQ_LAUNCH(DBG, TILED)                                                                   \

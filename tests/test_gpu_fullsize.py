@@ -1,0 +1,153 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py
+times (tiled packed layout, BF16 output).  The oracle cannot redo these sizes
+element by element in reasonable time, so it checks seeded samples that it can
+compute one by one: whole token rows of the activation path, whole rows of the
+prepared weights, and (rows x columns) blocks of the layer output.
+"""
+import numpy as np
+import pytest
+
+import wush_inputs as I
+from oracle import wush_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2512_00956_amd as P
+    P.lib()
+    return P
+
+
+@pytest.fixture(scope="module")
+def G():
+    from tests import gpu_util
+    return gpu_util
+
+
+def _transforms_blockwise(L, lam=1e-2):
+    """Alg. 2 (RTN case) per block with the oracle's functions, without holding
+    FP64 copies of the whole tensors."""
+    cfg = L["cfg"]
+    T = np.empty((cfg.C, 32, 32))
+    for b in range(cfg.C):
+        sl = slice(32 * b, 32 * b + 32)
+        Wb = O.bf16_bits_to_f64(L["W"][:, sl])
+        Xb = O.bf16_bits_to_f64(L["X_cal"][:, sl])
+        T[b] = O.wush_block(O.second_moment(Wb), O.second_moment(Xb), lam)
+    return O.round_to_bf16(T)
+
+
+def _run_layer(P, G, L, T, want_gemm=True):
+    import torch
+    cfg = L["cfg"]
+    M, K, N = cfg.M, cfg.K, cfg.N
+    fmt = P.default_fmt(layout=1)
+    Td = G.bf16_dev(O.bf16_values_to_bits(T))
+    xcb, xsb = P.wush_packed_sizes(M, K, fmt)
+    Xq, Xs = G.empty_u8(xcb), G.empty_u8(xsb)
+    P.wush_quantize_act(G.bf16_dev(L["X"]), Td, Xq, Xs, fmt)
+    Xqc, Xsc = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+    P.wush_unpack_tiled(Xq, Xs, M, K, Xqc, Xsc)
+    out = {"Xq": Xqc, "Xs": Xsc}
+    if want_gemm:
+        wcb, wsb = P.wush_packed_sizes(N, K, fmt)
+        Wq, Ws = G.empty_u8(wcb), G.empty_u8(wsb)
+        wsp = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+        P.wush_prepare_weight(G.bf16_dev(L["W"]), Td, Wq, Ws, wsp, fmt)
+        P.wush_workspace_status(wsp, K)
+        Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        P.wush_linear(Xq, Xs, Wq, Ws, Y, fmt, K=K)
+        Wqc, Wsc = G.empty_u8(N, K // 2), G.empty_u8(N, K // 32)
+        P.wush_unpack_tiled(Wq, Ws, N, K, Wqc, Wsc)
+        out.update(Wq=Wqc, Ws=Wsc, Y=Y)
+    torch.cuda.synchronize()
+    return out
+
+
+def _check_samples(G, L, T, out, rng, n_rows=48, n_wrows=48, n_cols=384):
+    cfg = L["cfg"]
+    M, K, N = cfg.M, cfg.K, cfg.N
+    rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, n_rows)]))
+    # ---- activation rows: codes and scales against the full-FP64 oracle path
+    X = O.bf16_bits_to_f64(L["X"][rows])
+    Yt = O.transform_act(X, T)
+    cr, sr = O.quantize_mxfp4(Yt)
+    xq = out["Xq"][rows.tolist()].cpu().numpy()
+    xs = out["Xs"][rows.tolist()].cpu().numpy()
+    rate, unexplained = G.code_mismatch_report(Yt, O.unpack_codes(xq), xs, cr, sr)
+    assert rate <= 1e-4 and unexplained == 0, ("activation codes", rate, unexplained)
+    if "Y" not in out:
+        return
+    # ---- weight rows
+    wrows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, n_wrows)]))
+    Wt = O.transform_weight(O.bf16_bits_to_f64(L["W"][wrows]), T)
+    cw, sw = O.quantize_mxfp4(Wt)
+    wq = out["Wq"][wrows.tolist()].cpu().numpy()
+    ws = out["Ws"][wrows.tolist()].cpu().numpy()
+    rate, unexplained = G.code_mismatch_report(Wt, O.unpack_codes(wq), ws, cw, sw, tol=1e-9)
+    assert rate <= 1e-4 and unexplained == 0, ("weight codes", rate, unexplained)
+    # ---- output block: sampled rows x sampled columns (plus the corners)
+    cols = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, n_cols)]))
+    wqc = out["Wq"][cols.tolist()].cpu().numpy()
+    wsc = out["Ws"][cols.tolist()].cpu().numpy()
+    y = O.bf16_bits_to_f64(G.host(out["Y"][rows.tolist()][:, cols.tolist()].contiguous()))
+    assert np.isfinite(y).all()
+    # GEMM on the GPU's own codes (exact inputs): only FP32 accumulation + BF16 rounding differ
+    own = O.dequantize(O.unpack_codes(xq), xs) @ O.dequantize(O.unpack_codes(wqc), wsc).T
+    assert O.rel_fro(y, own) <= 2e-3
+    # the oracle's complete quantized forward on the same sample.  It differs from
+    # `own` only through the few boundary codes counted above (each flips one
+    # element by a grid step), so the bar is set against the quantization error
+    # itself: the flips must change the output by under 5 % of what quantization
+    # changes it by -- and by under 2e-3 when no code differs at all.
+    Wt_c = O.transform_weight(O.bf16_bits_to_f64(L["W"][cols]), T)
+    ref = O.dequantize(cr, sr) @ O.dequantize(*O.quantize_mxfp4(Wt_c)).T
+    exact = X @ O.bf16_bits_to_f64(L["W"][cols]).T
+    q_err = O.rel_fro(ref, exact)
+    print(f"{cfg.name}: y vs own-codes oracle {O.rel_fro(y, own):.2e}, y vs full oracle {O.rel_fro(y, ref):.2e}, "
+          f"quantization error {q_err:.2e}")
+    assert O.rel_fro(y, ref) <= max(2e-3, 0.05 * q_err)
+    assert q_err < 0.25
+
+
+def test_c2_full(P, G):
+    L = I.make_layer(I.CONFIGS["c2"])
+    T = _transforms_blockwise(L)
+    out = _run_layer(P, G, L, T)
+    _check_samples(G, L, T, out, np.random.default_rng(2))
+    assert not bool(out["Y"].isnan().any())
+
+
+def test_c3_full_wush_and_hadamard(P, G):
+    L = I.make_layer(I.CONFIGS["c3"])
+    for name, T in (("wush", _transforms_blockwise(L)), ("hadamard", O.round_to_bf16(O.hadamard_transforms(L["cfg"].C)))):
+        out = _run_layer(P, G, L, T)
+        _check_samples(G, L, T, out, np.random.default_rng(3), n_rows=24, n_wrows=24, n_cols=256)
+
+
+def test_c4_activation_path_full_and_decode_sweep(P, G):
+    cfg = I.CONFIGS["c4"]
+    L = I.make_layer(cfg)
+    T = _transforms_blockwise(L)
+    out = _run_layer(P, G, L, T, want_gemm=False)
+    _check_samples(G, L, T, out, np.random.default_rng(4), n_rows=96)
+    # decode-sized batches: every M from 1 to 64 tokens must give the same codes as the big batch
+    import torch
+    Td = G.bf16_dev(O.bf16_values_to_bits(T))
+    Xd = G.bf16_dev(L["X"][:64])
+    for m in (1, 2, 3, 4, 8, 16, 31, 32, 33, 64):
+        q, s = G.empty_u8(m, cfg.K // 2), G.empty_u8(m, cfg.K // 32)
+        P.wush_quantize_act(Xd[:m], Td, q, s)
+        torch.cuda.synchronize()
+        assert torch.equal(q, out["Xq"][:m]) and torch.equal(s, out["Xs"][:m]), m
+
+
+def test_c5_full(P, G):
+    L = I.make_layer(I.CONFIGS["c5"])
+    T = _transforms_blockwise(L)
+    out = _run_layer(P, G, L, T)
+    _check_samples(G, L, T, out, np.random.default_rng(5), n_rows=24, n_wrows=32, n_cols=256)
