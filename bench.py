@@ -33,6 +33,13 @@ import wush_inputs as I  # noqa: E402
 PEAK_FP4_TFLOPS = 10100.0   # MI355X dense MXFP4 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM traffic per launch of the dominant kernel, bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# of this script scaled by a plain copy of known size (commands, raw counters and factors: profiles/*.md).
+MEASURED_TRAFFIC = {
+    ("c2", "tiled"): (48288 + 24576) * 1024,    # wush_linear
+    ("c4", "tiled"): (133280 + 34816) * 1024,   # wush_quantize_act, --cold 4
+}
+
 WORKLOADS = {
     "c2": "Llama-3.1-8B fused QKV projection, M=2048 K=4096 N=6144, MXFP4 W4A4, 128 WUSH blocks",
     "c3": "Llama-3.1-8B MLP down projection, M=4096 K=14336 N=4096, MXFP4 W4A4, 448 WUSH blocks",
@@ -84,6 +91,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layout", default="tiled", choices=["tiled", "canonical"],
                     help="layout of the packed codes/scales between the kernels")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (torch) so that a rocprofv3 --pmc run of this "
+                         "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--cold", type=int, default=0,
                     help="rotate over this many input/output buffer sets (>1 defeats the 256 MB last-level cache)")
     args = ap.parse_args()
@@ -139,6 +149,13 @@ def main():
         if N:
             gemm(i)
 
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -172,11 +189,12 @@ def main():
         value, unit = flops / ms_per_step / 1e9, "TFLOP/s"
         roof = {"bound": "mfma", "kernel": "wush_linear (MXFP4 scaled-MFMA GEMM)", "achieved": flops / g_ms / 1e9,
                 "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s", "frac": flops / g_ms / 1e9 / PEAK_FP4_TFLOPS,
-                "traffic": None, "avg_launch_ms": g_ms}
+                "traffic": MEASURED_TRAFFIC.get((args.workload, args.layout)), "avg_launch_ms": g_ms}
     else:
         value, unit = qb / ms_per_step / 1e6, "GB/s"
         roof = {"bound": "hbm", "kernel": "wush_quantize_act (fused transform+quantize)", "achieved": qb / q_ms / 1e6,
-                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": qb / q_ms / 1e6 / PEAK_HBM_GBS, "traffic": None,
+                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": qb / q_ms / 1e6 / PEAK_HBM_GBS,
+                "traffic": MEASURED_TRAFFIC.get((args.workload, args.layout)),
                 "avg_launch_ms": q_ms}
 
     out = {
