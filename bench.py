@@ -111,17 +111,24 @@ def main():
     torch.cuda.set_device(dev)
 
     cfg = I.CONFIGS[args.workload]
+    L = I.make_layer(cfg)          # c4 keeps its weights: they are only used to build the transforms
     if args.workload == "c4":
         cfg = I.scaled(cfg, N=0)
     M, K, N = cfg.M, cfg.K, cfg.N
-    L = I.make_layer(I.scaled(cfg, calib_tokens=32))  # calibration tokens are not needed for timing
-    T_bits = I.make_transforms_random(K // 32, cfg.seed)
 
     def bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
 
+    # The transforms come from the library's own offline path (Alg. 1 on the device)
+    # applied to the workload's weights and calibration tokens.
     nset = max(1, args.cold)
-    Td = bf16(T_bits)
+    Td = torch.empty((K // 32, 32, 32), dtype=torch.bfloat16, device=dev)
+    bws = torch.empty(P.wush_build_transforms_workspace(K), dtype=torch.uint8, device=dev)
+    Wcal = bf16(L["W"])
+    P.wush_build_transforms(Wcal, bf16(L["X_cal"]), 1e-2, Td, bws)
+    P.wush_build_transforms_status(bws, K)
+    del bws, Wcal
+    T_bits = Td.view(torch.int16).cpu().numpy().view(np.uint16)
     Xd = [bf16(L["X"]) for _ in range(nset)]
     fmt = P.default_fmt(layout=1 if args.layout == "tiled" else 0)
     xcb, xsb = P.wush_packed_sizes(M, K, fmt)

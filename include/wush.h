@@ -70,7 +70,7 @@ typedef enum {
   WUSH_ERR_FMT = 4,       /* unsupported format descriptor */
   WUSH_ERR_WORKSPACE = 5, /* workspace missing or too small */
   WUSH_ERR_DEVICE = 6,    /* the HIP runtime reported a launch error */
-  WUSH_ERR_SINGULAR = 7   /* a transform block is singular (wush_workspace_status) */
+  WUSH_ERR_SINGULAR = 7   /* a transform block is singular / a moment not positive definite */
 } wush_status;
 
 enum { WUSH_E2M1 = 1 };
@@ -134,6 +134,32 @@ size_t wush_prepare_weight_workspace(int64_t N, int64_t K);
  * WUSH_ERR_SINGULAR.  This is the only entry point that blocks.
  */
 wush_status wush_workspace_status(const void* workspace, int64_t K, void* stream);
+
+/*
+ * Offline construction of the transforms on the device (Alg. 2, RTN case:
+ * per-block second moments of the ORIGINAL weight block and of the calibration
+ * activations, then Alg. 1: damped Cholesky factors, SVD of W'^T X', and
+ * T_wush = H S^(-1/2) U^T W'^T with the normalized Sylvester Hadamard matrix),
+ * all in FP64, result rounded to BF16.  Conventions that make T unique:
+ * singular values descending, the largest-magnitude entry of every column of U
+ * positive.
+ *   W        in   bf16 [N][ldw] (device)
+ *   X_cal    in   bf16 [M_cal][ldx] (device), calibration tokens
+ *   lambda        damping ratio (>= 0): lambda * tr(M)/32 is added to the diagonal
+ *   T_blocks out  bf16 [K/32][32][32]
+ *   T_f64    out  optional (may be NULL): f64 [K/32][32][32], T before rounding
+ *   workspace     device scratch, >= wush_build_transforms_workspace(K) bytes,
+ *                 16-byte aligned
+ * A moment that is not positive definite after damping sets a flag that
+ * wush_build_transforms_status reads back (it synchronizes the stream).
+ */
+size_t wush_build_transforms_workspace(int64_t K);
+wush_status wush_build_transforms(const void* W, int64_t N, int64_t ldw,
+                                  const void* X_cal, int64_t M_cal, int64_t ldx,
+                                  int64_t K, double lambda,
+                                  void* T_blocks, double* T_f64,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+wush_status wush_build_transforms_status(const void* workspace, int64_t K, void* stream);
 
 /*
  * MXFP4 x MXFP4 GEMM with FP32 accumulation: the sum over blocks of the layer

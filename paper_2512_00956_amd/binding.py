@@ -10,7 +10,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import POINTER, c_char_p, c_float, c_int32, c_int64, c_size_t, c_void_p
+from ctypes import POINTER, c_char_p, c_double, c_int32, c_int64, c_size_t, c_void_p
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libwush.so"
@@ -29,6 +29,7 @@ EXPORTS = (
     "wush_default_fmt", "wush_quantize_act", "wush_prepare_weight", "wush_prepare_weight_workspace",
     "wush_workspace_status", "wush_linear", "wush_quantize_f32", "wush_status_string", "wush_version",
     "wush_packed_sizes", "wush_unpack_tiled",
+    "wush_build_transforms", "wush_build_transforms_workspace", "wush_build_transforms_status",
 )
 
 
@@ -81,6 +82,13 @@ def lib() -> ctypes.CDLL:
         L.wush_status_string.argtypes = [c_int32]
         L.wush_version.restype = c_char_p
         L.wush_version.argtypes = []
+        L.wush_build_transforms_workspace.restype = c_size_t
+        L.wush_build_transforms_workspace.argtypes = [c_int64]
+        L.wush_build_transforms.restype = c_int32
+        L.wush_build_transforms.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_int64, c_int64, c_int64, c_double,
+                                            c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+        L.wush_build_transforms_status.restype = c_int32
+        L.wush_build_transforms_status.argtypes = [c_void_p, c_int64, c_void_p]
         L.wush_packed_sizes.restype = c_int32
         L.wush_packed_sizes.argtypes = [c_int64, c_int64, WushFmt, POINTER(c_size_t), POINTER(c_size_t)]
         L.wush_unpack_tiled.restype = c_int32
@@ -167,6 +175,25 @@ def wush_linear(Xq, Xs, Wq, Ws, Y, fmt: WushFmt | None = None, stream=None, K: i
         K = 2 * Xq.shape[-1]
     _check(lib().wush_linear(_ptr(Xq), _ptr(Xs), _ptr(Wq), _ptr(Ws), M, N, K, fmt or default_fmt(),
                              _ptr(Y), Y.stride(0), _stream(stream)), "wush_linear")
+
+
+def wush_build_transforms_workspace(K: int) -> int:
+    return int(lib().wush_build_transforms_workspace(K))
+
+
+def wush_build_transforms(W, X_cal, lam: float, T_blocks, workspace, T_f64=None, stream=None):
+    """Alg. 1 + Alg. 2 (RTN case) on the device: W bf16 [N][K], X_cal bf16 [M_cal][K]
+    -> T_blocks bf16 [K/32][32][32] (and the unrounded f64 T if T_f64 is given)."""
+    N, K = W.shape
+    Mc = X_cal.shape[0]
+    _check(lib().wush_build_transforms(_ptr(W), N, W.stride(0), _ptr(X_cal), Mc, X_cal.stride(0), K, float(lam),
+                                       _ptr(T_blocks), _ptr(T_f64), _ptr(workspace),
+                                       0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                       _stream(stream)), "wush_build_transforms")
+
+
+def wush_build_transforms_status(workspace, K: int, stream=None):
+    _check(lib().wush_build_transforms_status(_ptr(workspace), K, _stream(stream)), "wush_build_transforms_status")
 
 
 def wush_quantize_f32(Yt, q, s, fmt: WushFmt | None = None, stream=None):

@@ -95,6 +95,36 @@ wush_status wush_workspace_status(const void* workspace, int64_t K, void* stream
   return flag ? WUSH_ERR_SINGULAR : WUSH_OK;
 }
 
+size_t wush_build_transforms_workspace(int64_t K) {
+  if (K <= 0 || K % 32 != 0 || K > kMaxDim) return 0;
+  return wush::build_transforms_workspace_bytes(K);
+}
+
+wush_status wush_build_transforms(const void* W, int64_t N, int64_t ldw, const void* X_cal, int64_t M_cal,
+                                  int64_t ldx, int64_t K, double lambda, void* T_blocks, double* T_f64,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (!W || !X_cal || !T_blocks) return WUSH_ERR_NULL;
+  if (wush_status s = check_rows(N, K, ldw)) return s;
+  if (wush_status s = check_rows(M_cal, K, ldx)) return s;
+  if (!(lambda >= 0.0) || !(lambda < 1e6)) return WUSH_ERR_SHAPE;
+  if (!aligned16(W) || !aligned16(X_cal) || !aligned16(T_blocks) || !aligned16(T_f64)) return WUSH_ERR_ALIGN;
+  if (!workspace || workspace_bytes < wush::build_transforms_workspace_bytes(K)) return WUSH_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_build_transforms(W, N, ldw, X_cal, M_cal, ldx, K, lambda, T_blocks, T_f64, workspace,
+                                                static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_build_transforms_status(const void* workspace, int64_t K, void* stream) {
+  if (!workspace) return WUSH_ERR_NULL;
+  if (K <= 0 || K % 32 != 0 || K > kMaxDim) return WUSH_ERR_SHAPE;
+  int flag = 0;
+  const char* p = static_cast<const char*>(workspace) + wush::build_transforms_status_offset(K);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&flag, p, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess) return WUSH_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return WUSH_ERR_DEVICE;
+  return flag ? WUSH_ERR_SINGULAR : WUSH_OK;
+}
+
 wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M,
                         int64_t N, int64_t K, wush_fmt fmt, void* Y, int64_t ldy, void* stream) {
   if (!Xq || !Xs || !Wq || !Ws || !Y) return WUSH_ERR_NULL;
@@ -155,6 +185,6 @@ const char* wush_status_string(wush_status st) {
   return "unknown status";
 }
 
-const char* wush_version(void) { return "0.2"; }
+const char* wush_version(void) { return "0.3"; }
 
 }  // extern "C"

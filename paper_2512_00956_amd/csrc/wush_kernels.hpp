@@ -27,6 +27,13 @@ hipError_t launch_mxfp4_gemm(const void* Xq, const void* Xs, const void* Wq, con
                              int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y, int64_t ldy,
                              hipStream_t stream);
 
+// Alg. 1 / Alg. 2 (RTN case) transform construction; workspace = partial moments + status word.
+size_t build_transforms_workspace_bytes(int64_t K);
+size_t build_transforms_status_offset(int64_t K);
+hipError_t launch_build_transforms(const void* W, int64_t N, int64_t ldw, const void* X, int64_t Mc, int64_t ldx,
+                                   int64_t K, double lambda, void* T_out, double* T_f64, void* workspace,
+                                   hipStream_t stream);
+
 // Operands in the fragment-order layout (K % 256 == 0).
 hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
                                   int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,

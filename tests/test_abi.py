@@ -28,7 +28,7 @@ def test_header_symbols_are_exported(L):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(L, name) is not None
-    assert L.wush_version() == b"0.2"
+    assert L.wush_version() == b"0.3"
 
 
 def test_default_fmt_and_status_strings(L):
@@ -120,3 +120,17 @@ def test_packed_sizes_and_unpack_validation(L):
     assert L.wush_unpack_tiled(A, A, 4, 128, A, A, None) == 2
     assert L.wush_unpack_tiled(None, A, 4, 256, A, A, None) == 1
     assert L.wush_unpack_tiled(A, A, 4, 256, A + 3, A, None) == 3
+
+
+def test_build_transforms_validation(L):
+    need = L.wush_build_transforms_workspace(64)
+    assert need >= 2 * 2 * 1024 * 8 + 4 and L.wush_build_transforms_workspace(48) == 0
+    bt = lambda *a: L.wush_build_transforms(*a)
+    assert bt(None, 8, 64, A, 16, 64, 64, 0.01, A, None, A, need, None) == 1
+    assert bt(A, 8, 64, A, 16, 64, 48, 0.01, A, None, A, need, None) == 2     # K % 32
+    assert bt(A, 8, 64, A, 0, 64, 64, 0.01, A, None, A, need, None) == 2      # no calibration tokens
+    assert bt(A, 8, 64, A, 16, 64, 64, -1.0, A, None, A, need, None) == 2     # negative damping
+    assert bt(A, 8, 64, A, 16, 64, 64, 0.01, A, A + 8, A, need, None) == 3    # misaligned f64 tap
+    assert bt(A, 8, 64, A, 16, 64, 64, 0.01, A, None, A, need - 1, None) == 5
+    assert bt(A, 8, 64, A, 16, 64, 64, 0.01, A, None, None, need, None) == 5
+    assert L.wush_build_transforms_status(None, 64, None) == 1
