@@ -94,14 +94,28 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
 
   // direct-to-LDS loads of tile kt: fragment f (0..7) of this wave's two row
   // blocks, and their two scale dwords
+  // The direct-to-LDS loads are issued from inline asm on purpose.  The compiler
+  // classifies global_load_lds as a load AND a store; with such an operation
+  // pending it assumes vmcnt may retire out of order and turns every wait for a
+  // W register load into vmcnt(0), which drains the whole two-iteration
+  // pipeline once per iteration.  Issued from asm they are invisible to its
+  // bookkeeping; its own vmcnt(n) waits then undercount the younger operations
+  // (they wait for more than needed, never for less) and the explicit wait in
+  // front of the barrier covers the LDS data.  m0 has no other user in this kernel.
+  const uint32_t lds_base = (uint32_t)(uintptr_t)smem;   // LDS byte address of the ring
+  auto dma16 = [&](const uint8_t* src, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr));
+  };
+  auto dma4 = [&](const uint8_t* src, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_addr));
+  };
   auto dma_x_frag = [&](int kt, int f) {
     const int u = f >> 2, kk = f & 3;
-    uint8_t* dst = smem + (kt % kStages) * kXStageB + ((2 * wave + u) * 4 + kk) * kFragB;
-    __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + ((int64_t)u * KT + kt) * tile_step + kk * kFragB), (lptr_t)dst, 16, 0, 0);
+    dma16(xsrc + ((int64_t)u * KT + kt) * tile_step + kk * kFragB,
+          lds_base + (kt % kStages) * kXStageB + ((2 * wave + u) * 4 + kk) * kFragB);
   };
   auto dma_x_scale = [&](int kt, int u) {
-    uint8_t* dst = smem + kXsBase + (kt % kStages) * kXsStageB + (2 * wave + u) * 256;
-    __builtin_amdgcn_global_load_lds((gptr_t)(xssrc + ((int64_t)u * KT + kt) * 256), (lptr_t)dst, 4, 0, 0);
+    dma4(xssrc + ((int64_t)u * KT + kt) * 256, lds_base + kXsBase + (kt % kStages) * kXsStageB + (2 * wave + u) * 256);
   };
   auto dma_x = [&](int kt) {
 #pragma unroll
@@ -233,7 +247,14 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
     if (PFX) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmemPerIter - kDmaPerIter + kVmemPerIter));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     WUSH_FENCE
-    __syncthreads();
+    // A bare s_barrier: __syncthreads() carries a workgroup fence for which the
+    // compiler drains vmcnt to 0, i.e. it would wait for the loads issued two
+    // iterations ahead on every iteration.  The only cross-wave data here are the
+    // direct-to-LDS writes, whose arrival the explicit vmcnt above already
+    // guarantees.  No "memory" clobber either: the compiler models such an asm as
+    // an unknown (flat) access and answers with vmcnt(0) lgkmcnt(0) at the next
+    // wait.  The sched_barrier fences keep the LDS reads on their side.
+    asm volatile("s_barrier");
   };
   using T = std::true_type;
   using F = std::false_type;
