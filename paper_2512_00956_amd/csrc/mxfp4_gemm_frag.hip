@@ -123,12 +123,22 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
     dma_x_scale(kt, 0);
     dma_x_scale(kt, 1);
   };
+  // W register loads are issued from asm as well, so that NO global load of the
+  // main loop is visible to the compiler's vmcnt bookkeeping and every vmcnt wait
+  // below is an explicit, exact count.  Their destination registers are written
+  // asynchronously; nothing may read them before the explicit wait at the start
+  // of the iteration that consumes them (the generated code is checked for that:
+  // no spill and no register copy in the loop).
   auto load_w_scales = [&](WSet& w, int kt) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) w.s[j] = *reinterpret_cast<const int*>(wssrc + ((int64_t)j * KT + kt) * 256);
+    for (int j = 0; j < 2; ++j) {
+      const uint8_t* p = wssrc + ((int64_t)j * KT + kt) * 256;
+      asm volatile("global_load_dword %0, %1, off" : "=v"(w.s[j]) : "v"(p));
+    }
   };
   auto load_w_frag = [&](WSet& w, int kt, int kk, int j) {
-    w.f[j][kk] = *reinterpret_cast<const v4i*>(wsrc + ((int64_t)j * KT + kt) * tile_step + kk * kFragB);
+    const uint8_t* p = wsrc + ((int64_t)j * KT + kt) * tile_step + kk * kFragB;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(w.f[j][kk]) : "v"(p));
   };
   auto read_x_frag = [&](int kt, int kk, int i) {
     return *reinterpret_cast<const v4i*>(smem + (kt % kStages) * kXStageB + (i * 4 + kk) * kFragB + loff);
@@ -202,6 +212,10 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   auto iteration = [&](int kt, WSet& w, const int (&xs)[8], int (&xs_next)[8], auto pfx_tag, auto pfw_tag,
                        auto next_tag) {
     constexpr bool PFX = decltype(pfx_tag)::value, PFW = decltype(pfw_tag)::value, NEXT = decltype(next_tag)::value;
+    // W fragments and scales of tile kt were issued two iterations ago; the last of
+    // them (the scales) is followed by exactly the operations of the previous
+    // iteration: 20 when that one prefetched X and W, 10 when only W, else 0.
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(PFW ? kVmemPerIter : (NEXT ? kVmemPerIter - kDmaPerIter : 0)));
     WUSH_FENCE
 #pragma unroll
     for (int i = 0; i < 8; ++i) {            // issue 0: X ring refill, operands of issue 2
