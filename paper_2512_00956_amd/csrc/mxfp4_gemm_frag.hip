@@ -84,13 +84,15 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
 
   // Operand buffers are padded to whole 256-row tiles, so every address below
   // is "uniform base + lane offset"; rows past M or N are read but never stored.
+  // Every global address is "wave-uniform 64-bit base (SGPR pair) + per-lane 32-bit
+  // offset (one constant VGPR) + immediate": no vector ALU work per load.
   const int loff = 16 * lane, soff = 4 * lane;
   // X: this wave fills row blocks 2*wave, 2*wave+1 of every ring stage.
-  const uint8_t* xsrc = Xq + (int64_t)(tm * 8 + 2 * wave) * KT * tile_step + loff;
-  const uint8_t* xssrc = Xs + (int64_t)(tm * 8 + 2 * wave) * KT * 256 + soff;
+  const uint8_t* xsrc = Xq + (int64_t)(tm * 8 + 2 * wave) * KT * tile_step;
+  const uint8_t* xssrc = Xs + (int64_t)(tm * 8 + 2 * wave) * KT * 256;
   // W fragments and scales of this wave's two column blocks.
-  const uint8_t* wsrc = Wq + (int64_t)(tn * 8 + 2 * wave) * KT * tile_step + loff;
-  const uint8_t* wssrc = Ws + (int64_t)(tn * 8 + 2 * wave) * KT * 256 + soff;
+  const uint8_t* wsrc = Wq + (int64_t)(tn * 8 + 2 * wave) * KT * tile_step;
+  const uint8_t* wssrc = Ws + (int64_t)(tn * 8 + 2 * wave) * KT * 256;
 
   // direct-to-LDS loads of tile kt: fragment f (0..7) of this wave's two row
   // blocks, and their two scale dwords
@@ -103,16 +105,23 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   // (they wait for more than needed, never for less) and the explicit wait in
   // front of the barrier covers the LDS data.  m0 has no other user in this kernel.
   const uint32_t lds_base = (uint32_t)(uintptr_t)smem;   // LDS byte address of the ring
-  auto dma16 = [&](const uint8_t* src, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr));
+  // The four fragments (kk) of one (row block, K tile) are 4 KiB contiguous both in
+  // memory and in the ring stage; the instruction's immediate offset is added to
+  // the global AND to the LDS address, so they share one base and one m0 value.
+  auto dma16 = [&](const uint8_t* src, uint32_t lds_addr, int kk) {
+    switch (kk) {
+      case 0: asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(loff), "s"(src), "s"(lds_addr)); break;
+      case 1: asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024" ::"v"(loff), "s"(src), "s"(lds_addr)); break;
+      case 2: asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:2048" ::"v"(loff), "s"(src), "s"(lds_addr)); break;
+      default: asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:3072" ::"v"(loff), "s"(src), "s"(lds_addr)); break;
+    }
   };
   auto dma4 = [&](const uint8_t* src, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_addr));
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1" ::"v"(soff), "s"(src), "s"(lds_addr));
   };
   auto dma_x_frag = [&](int kt, int f) {
     const int u = f >> 2, kk = f & 3;
-    dma16(xsrc + ((int64_t)u * KT + kt) * tile_step + kk * kFragB,
-          lds_base + (kt % kStages) * kXStageB + ((2 * wave + u) * 4 + kk) * kFragB);
+    dma16(xsrc + ((int64_t)u * KT + kt) * tile_step, lds_base + (kt % kStages) * kXStageB + (2 * wave + u) * 4 * kFragB, kk);
   };
   auto dma_x_scale = [&](int kt, int u) {
     dma4(xssrc + ((int64_t)u * KT + kt) * 256, lds_base + kXsBase + (kt % kStages) * kXsStageB + (2 * wave + u) * 256);
@@ -133,12 +142,17 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const uint8_t* p = wssrc + ((int64_t)j * KT + kt) * 256;
-      asm volatile("global_load_dword %0, %1, off" : "=v"(w.s[j]) : "v"(p));
+      asm volatile("global_load_dword %0, %1, %2" : "=v"(w.s[j]) : "v"(soff), "s"(p));
     }
   };
   auto load_w_frag = [&](WSet& w, int kt, int kk, int j) {
-    const uint8_t* p = wsrc + ((int64_t)j * KT + kt) * tile_step + kk * kFragB;
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(w.f[j][kk]) : "v"(p));
+    const uint8_t* p = wsrc + ((int64_t)j * KT + kt) * tile_step;
+    switch (kk) {
+      case 0: asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
+      case 1: asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024" : "=v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
+      case 2: asm volatile("global_load_dwordx4 %0, %1, %2 offset:2048" : "=v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
+      default: asm volatile("global_load_dwordx4 %0, %1, %2 offset:3072" : "=v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
+    }
   };
   auto read_x_frag = [&](int kt, int kk, int i) {
     return *reinterpret_cast<const v4i*>(smem + (kt % kStages) * kXStageB + (i * 4 + kk) * kFragB + loff);
@@ -272,6 +286,11 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   };
   using T = std::true_type;
   using F = std::false_type;
+  // Pull the epilogue's kernel arguments into SGPRs now.  A scalar load still
+  // pending at the loop entry shares its counter with the LDS reads and can
+  // return out of order, for which the compiler answers with lgkmcnt(0) at the
+  // loop top, i.e. a full LDS drain on every trip.
+  asm volatile("" ::"s"(Y), "s"(ldy), "s"(M), "s"(N), "s"(vec_store));
   int kt = 0;
   const int n_main = KT - 3;                   // iterations with every stream active
   if (n_main > 0 && (n_main & 1)) {            // odd count: one iteration on set 1 first
