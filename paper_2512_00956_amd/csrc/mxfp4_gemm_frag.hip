@@ -174,28 +174,32 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   int xsc[2][8];
   v4i af0[8], af1[8];
   const int p0 = (KT - 1) & 1;                 // set of iteration 0
+  // Issue order X0, X1, W(tile 0), X2, W(tile 1) -- the steady-state order (10 ring
+  // loads, then 10 W loads per iteration) -- so that the first barrier has to wait
+  // for ring stages 0 and 1 only and the first MFMA for W(tile 0) only, with the
+  // same in-order counts as in the loop; the rest of the lookahead lands during
+  // iteration 0.  K < 768 takes no shortcut.
+  auto load_w = [&](WSet& w, int kt) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) { load_w_frag(w, kt, kk, 0); load_w_frag(w, kt, kk, 1); }
+    load_w_scales(w, kt);
+  };
   dma_x(0);
   if (KT > 1) dma_x(1);
-  if (KT > 2) dma_x(2);
   if (p0 == 0) {
-    load_w_scales(wset[0], 0);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) { load_w_frag(wset[0], 0, kk, 0); load_w_frag(wset[0], 0, kk, 1); }
-    if (KT > 1) {
-      load_w_scales(wset[1], 1);
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) { load_w_frag(wset[1], 1, kk, 0); load_w_frag(wset[1], 1, kk, 1); }
-    }
+    load_w(wset[0], 0);
+    if (KT > 2) dma_x(2);
+    if (KT > 1) load_w(wset[1], 1);
   } else {
-    load_w_scales(wset[1], 0);
-    load_w_scales(wset[0], 1);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) { load_w_frag(wset[1], 0, kk, 0); load_w_frag(wset[1], 0, kk, 1); }
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) { load_w_frag(wset[0], 1, kk, 0); load_w_frag(wset[0], 1, kk, 1); }
+    load_w(wset[1], 0);
+    if (KT > 2) dma_x(2);
+    load_w(wset[0], 1);
   }
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-  __syncthreads();
+  if (KT > 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmemPerIter - kDmaPerIter + kVmemPerIter));
+  else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_barrier");
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     af0[i] = read_x_frag(0, 0, i);
@@ -219,8 +223,8 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
     const v8i A_ = {AF[i][0], AF[i][1], AF[i][2], AF[i][3], 0, 0, 0, 0};                                       \
     const v8i B0_ = {w.f[0][KK][0], w.f[0][KK][1], w.f[0][KK][2], w.f[0][KK][3], 0, 0, 0, 0};                  \
     const v8i B1_ = {w.f[1][KK][0], w.f[1][KK][1], w.f[1][KK][2], w.f[1][KK][3], 0, 0, 0, 0};                  \
-    acc[i][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A_, B0_, acc[i][0], 4, 4, KK, xs[i], KK, w.s[0]); \
-    acc[i][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A_, B1_, acc[i][1], 4, 4, KK, xs[i], KK, w.s[1]); \
+    acc[i][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B0_, A_, acc[i][0], 4, 4, KK, w.s[0], KK, xs[i]); \
+    acc[i][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B1_, A_, acc[i][1], 4, 4, KK, w.s[1], KK, xs[i]); \
   }
 #define WUSH_FENCE __builtin_amdgcn_sched_barrier(0);
   auto iteration = [&](int kt, WSet& w, const int (&xs)[8], int (&xs_next)[8], auto pfx_tag, auto pfw_tag,
@@ -309,46 +313,44 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
 #undef WUSH_FENCE
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- epilogue.  Accumulator e of lane (r, kh) in MFMA tile (i, j) is output
-  // row 32*i + 8*(e/4) + 4*kh + e%4, column 64*wave + 32*j + r of the tile.
+  // ---- epilogue.  The W fragment is the MFMA's first operand, so a tile of D is
+  // (32 output columns) x (32 tokens): lane (r, kh) of MFMA tile (i, j) holds token
+  // row 32*i + r, and its accumulator e is output column
+  // 64*wave + 32*j + 8*(e/4) + 4*kh + e%4 -- four consecutive columns per e/4.
   if (!OUT_F32 && vec_store) {
-    // BF16, 16-byte-aligned rows: transpose through LDS so that every lane
-    // stores 8 consecutive columns and a store instruction writes 8 full
-    // 128-byte row segments.  The ring is free after the last barrier; each wave
-    // uses a private 2 x 4 KiB area (32 rows x 64 BF16), so no barrier is needed.
-    // Adjacent lanes hold adjacent columns: a DPP swap pairs them so each lane
-    // writes one packed dword (two columns of one row).  Rows with bit 2 set keep
-    // their two 64-byte halves swapped, which spreads the two lane halves over
-    // all banks on the write and is a permutation within the row on the read.
+    // BF16, 16-byte-aligned rows.  Four consecutive columns = two packed converts =
+    // one 8-byte LDS write; a wave-private LDS image of 32 rows x 64 columns is read
+    // back as 16 bytes per lane so that a store instruction writes 8 full 128-byte
+    // row segments.  Row pitch 144 B: the 8-byte writes of a wave (pitch 36 dwords,
+    // +2 dwords for the upper lane half) hit every bank 4 times and the 16-byte
+    // reads every 4-bank group 8 times, both the minimum.  The ring is free after
+    // the last barrier; each wave uses a private double buffer, so no barrier.
     typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
     typedef float v2f __attribute__((ext_vector_type(2)));
-    uint8_t* area = smem + wave * 8192;
-    const bool odd_lane = lane & 1;
+    constexpr int kPitch = 144, kBuf = 32 * kPitch;
+    uint8_t* area = smem + wave * (2 * kBuf);
     uint16_t* Yb = reinterpret_cast<uint16_t*>(Y);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_barrier(0);
-      uint8_t* buf = area + (i & 1) * 4096;
+      uint8_t* buf = area + (i & 1) * kBuf;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
 #pragma unroll
-        for (int e = 0; e < 16; e += 2) {
-          const float lo = acc[i][j][e], hi = acc[i][j][e + 1];
-          const float keep = odd_lane ? hi : lo;
-          const float send = odd_lane ? lo : hi;
-          const float recv = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), 0xB1, 0xF, 0xF, true));
-          const v2f pair = odd_lane ? (v2f){recv, keep} : (v2f){keep, recv};
-          const v2bf packed = __builtin_convertvector(pair, v2bf);
-          const int row_l = 8 * (e >> 2) + 4 * kh + (e & 3) + (odd_lane ? 1 : 0);
-          const int d = (16 * j + (r >> 1)) ^ (16 * kh);
-          *reinterpret_cast<v2bf*>(buf + row_l * 128 + 4 * d) = packed;
+        for (int q = 0; q < 4; ++q) {
+          const v2bf lo = __builtin_convertvector((v2f){acc[i][j][4 * q], acc[i][j][4 * q + 1]}, v2bf);
+          const v2bf hi = __builtin_convertvector((v2f){acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]}, v2bf);
+          v2u two;
+          two[0] = __builtin_bit_cast(uint32_t, lo);
+          two[1] = __builtin_bit_cast(uint32_t, hi);
+          *reinterpret_cast<v2u*>(buf + r * kPitch + 2 * (32 * j + 8 * q + 4 * kh)) = two;
         }
       }
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const int row_l = (lane >> 3) + 8 * p;
         const int chunk = lane & 7;
-        const v4i v = *reinterpret_cast<const v4i*>(buf + row_l * 128 + 16 * (chunk ^ (4 * ((row_l >> 2) & 1))));
+        const v4i v = *reinterpret_cast<const v4i*>(buf + row_l * kPitch + 16 * chunk);
         const int row = m0 + 32 * i + row_l;
         const int col = n0 + 64 * wave + 8 * chunk;
         if (row < M && col < N) *reinterpret_cast<v4i*>(Yb + (int64_t)row * ldy + col) = v;
@@ -361,12 +363,12 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       __builtin_amdgcn_sched_barrier(0);   // one MFMA tile at a time: keeps the epilogue out of scratch
-      const int col = n0 + 64 * wave + 32 * j + r;
-      if (col < N) {
+      const int row = m0 + 32 * i + r;
+      if (row < M) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int row = m0 + 32 * i + 8 * (e >> 2) + 4 * kh + (e & 3);
-          if (row < M) {
+          const int col = n0 + 64 * wave + 32 * j + 8 * (e >> 2) + 4 * kh + (e & 3);
+          if (col < N) {
             if (OUT_F32) reinterpret_cast<float*>(Y)[(int64_t)row * ldy + col] = acc[i][j][e];
             else reinterpret_cast<uint16_t*>(Y)[(int64_t)row * ldy + col] = f32_to_bf16_bits(acc[i][j][e]);
           }
