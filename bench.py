@@ -36,7 +36,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM traffic per launch of the dominant kernel, bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this script scaled by a plain copy of known size (commands, raw counters and factors: profiles/*.md).
 MEASURED_TRAFFIC = {
-    ("c2", "tiled"): (48316 + 24576) * 1024,    # wush_linear
+    ("c2", "tiled"): (48194 + 24587) * 1024,    # wush_linear
     ("c4", "tiled"): (133280 + 34816) * 1024,   # wush_quantize_act, --cold 4
 }
 

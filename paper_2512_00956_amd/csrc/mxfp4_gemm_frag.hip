@@ -25,6 +25,16 @@
 //     the 4 MFMA issues of the iteration, selected with op_sel.
 // vmcnt completes in order, so the wait in front of the per-iteration barrier
 // is a fixed count: everything issued after the ring stage about to be read.
+// The W fragment is the MFMA's first operand: a lane then holds four consecutive
+// output columns of one token per accumulator quad, which the BF16 epilogue packs
+// with two converts and writes to its LDS transpose buffer as one 8-byte store.
+//
+// The main-loop loads are issued from inline asm (see below), so their
+// destination registers are invisible to the compiler's dependency tracking.
+// The build is only valid while every W register set keeps one physical
+// register assignment over the whole kernel (no copy of a register whose load
+// is still in flight) and nothing spills; tests/test_build_invariants.py
+// checks both on the generated code.
 #include <type_traits>
 
 #include "wush_device.hpp"
@@ -217,13 +227,18 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   // hold its issue-0 and issue-1 operands).  Flags say which streams still have
   // work: PFX = tile kt+3 exists (X ring), PFW = tile kt+2 exists (W registers),
   // NEXT = tile kt+1 exists (its first operands and scales are read here).
-  // Each slot = 2 MFMAs + at most one LDS read + at most one global load.
-#define WUSH_MMA2(KK, AF, i)                                                                                   \
+  // Each slot = MFMA, one LDS read, MFMA, at most one global load: the read sits
+  // in the shadow of the first MFMA and the load in the shadow of the second.
+#define WUSH_MMA_A(KK, AF, i)                                                                                  \
   {                                                                                                            \
     const v8i A_ = {AF[i][0], AF[i][1], AF[i][2], AF[i][3], 0, 0, 0, 0};                                       \
     const v8i B0_ = {w.f[0][KK][0], w.f[0][KK][1], w.f[0][KK][2], w.f[0][KK][3], 0, 0, 0, 0};                  \
-    const v8i B1_ = {w.f[1][KK][0], w.f[1][KK][1], w.f[1][KK][2], w.f[1][KK][3], 0, 0, 0, 0};                  \
     acc[i][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B0_, A_, acc[i][0], 4, 4, KK, w.s[0], KK, xs[i]); \
+  }
+#define WUSH_MMA_B(KK, AF, i)                                                                                  \
+  {                                                                                                            \
+    const v8i A_ = {AF[i][0], AF[i][1], AF[i][2], AF[i][3], 0, 0, 0, 0};                                       \
+    const v8i B1_ = {w.f[1][KK][0], w.f[1][KK][1], w.f[1][KK][2], w.f[1][KK][3], 0, 0, 0, 0};                  \
     acc[i][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B1_, A_, acc[i][1], 4, 4, KK, w.s[1], KK, xs[i]); \
   }
 #define WUSH_FENCE __builtin_amdgcn_sched_barrier(0);
@@ -237,34 +252,48 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
     WUSH_FENCE
 #pragma unroll
     for (int i = 0; i < 8; ++i) {            // issue 0: X ring refill, operands of issue 2
-      WUSH_MMA2(0, af0, i)
+      WUSH_MMA_A(0, af0, i)
+      const v4i nx_ = read_x_frag(kt, 2, i);
+      WUSH_FENCE
+      WUSH_MMA_B(0, af0, i)
       if (PFX) dma_x_frag(kt + 3, i);
-      af0[i] = read_x_frag(kt, 2, i);
+      af0[i] = nx_;
       WUSH_FENCE
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {            // issue 1: X scales, W fragments of issue 0, operands of issue 3
-      WUSH_MMA2(1, af1, i)
+      WUSH_MMA_A(1, af1, i)
+      const v4i nx_ = read_x_frag(kt, 3, i);
+      WUSH_FENCE
+      WUSH_MMA_B(1, af1, i)
       if (PFX && i < 2) dma_x_scale(kt + 3, i);
       if (PFW && (i == 2 || i == 3)) load_w_frag(w, kt + 2, 0, i - 2);
-      af1[i] = read_x_frag(kt, 3, i);
+      af1[i] = nx_;
       WUSH_FENCE
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {            // issue 2: W fragments of issue 1, next tile's issue-0 operands
-      WUSH_MMA2(2, af0, i)
+      WUSH_MMA_A(2, af0, i)
+      v4i nx_ = af0[i];
+      if (NEXT) nx_ = read_x_frag(kt + 1, 0, i);
+      WUSH_FENCE
+      WUSH_MMA_B(2, af0, i)
       if (PFW && i < 2) load_w_frag(w, kt + 2, 1, i);
-      if (NEXT) af0[i] = read_x_frag(kt + 1, 0, i);
+      af0[i] = nx_;
       WUSH_FENCE
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {            // issue 3: W fragments of issue 2, next tile's issue-1 operands, scales
-      WUSH_MMA2(3, af1, i)
-      if (PFW && i < 2) load_w_frag(w, kt + 2, 2, i);
+      WUSH_MMA_A(3, af1, i)
+      v4i nx_ = af1[i];
       if (NEXT) {
-        af1[i] = read_x_frag(kt + 1, 1, i);
+        nx_ = read_x_frag(kt + 1, 1, i);
         xs_next[i] = read_x_scale(kt + 1, i);
       }
+      WUSH_FENCE
+      WUSH_MMA_B(3, af1, i)
+      if (PFW && i < 2) load_w_frag(w, kt + 2, 2, i);
+      af1[i] = nx_;
       WUSH_FENCE
     }
     if (PFW) {
@@ -309,7 +338,8 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   if (KT >= 3) iteration(KT - 3, wset[0], xsc[0], xsc[1], F{}, T{}, T{});
   if (KT >= 2) iteration(KT - 2, wset[1], xsc[1], xsc[0], F{}, F{}, T{});
   iteration(KT - 1, wset[0], xsc[0], xsc[1], F{}, F{}, F{});
-#undef WUSH_MMA2
+#undef WUSH_MMA_A
+#undef WUSH_MMA_B
 #undef WUSH_FENCE
   __builtin_amdgcn_sched_barrier(0);
 
@@ -353,7 +383,9 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
         const v4i v = *reinterpret_cast<const v4i*>(buf + row_l * kPitch + 16 * chunk);
         const int row = m0 + 32 * i + row_l;
         const int col = n0 + 64 * wave + 8 * chunk;
-        if (row < M && col < N) *reinterpret_cast<v4i*>(Yb + (int64_t)row * ldy + col) = v;
+        // streaming store: the output is not read again by this kernel, and lines that
+        // leave the L2 as they are written shorten the write-back at the kernel's end
+        if (row < M && col < N) __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(Yb + (int64_t)row * ldy + col));
       }
     }
     return;

@@ -1,0 +1,67 @@
+"""Invariants of the generated code of the MXFP4 GEMM that the source cannot
+express: its main-loop global loads are issued from inline asm with explicit
+vmcnt waits, so the compiler does not know that their destination registers are
+written asynchronously.  That is only safe while (a) nothing in the kernel
+spills to scratch and (b) every register of the two W sets has ONE physical
+assignment in the whole kernel (16 fragment tuples + 4 scale registers, each
+loaded at the same number of code sites) -- a second assignment would mean a
+register copy that may read a tuple whose load is still in flight.
+The test compiles the kernel to gfx950 assembly (no GPU needed) and checks both.
+"""
+import os
+import re
+import shutil
+import subprocess
+import tempfile
+from collections import Counter
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "paper_2512_00956_amd", "csrc", "mxfp4_gemm_frag.hip")
+
+
+@pytest.fixture(scope="module")
+def asm_text():
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not available")
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "k.s")
+        cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", os.path.dirname(SRC), "-S",
+               "--cuda-device-only", SRC, "-o", out]
+        subprocess.run(cmd, check=True, capture_output=True)
+        return open(out).read()
+
+
+def _kernels(text):
+    """Split the assembly into {kernel symbol: body} for the two instantiations."""
+    parts = re.split(r"^(_ZN4wush\S*gemm_frag_kernel\S*):.*$", text, flags=re.M)
+    return {parts[i]: parts[i + 1].split("s_endpgm")[0] for i in range(1, len(parts) - 1, 2)}
+
+
+def test_no_scratch_and_single_register_assignment(asm_text):
+    kernels = _kernels(asm_text)
+    assert len(kernels) == 2, list(kernels)
+    for name, body in kernels.items():
+        assert "scratch_" not in body, f"{name}: spills to scratch"
+        frag = Counter(re.findall(r"global_load_dwordx4 (v\[\d+:\d+\])", body))
+        scale = Counter(re.findall(r"global_load_dword (v\d+),", body))
+        assert len(frag) == 16, (name, sorted(frag))
+        assert len(scale) == 4, (name, sorted(scale))
+        assert len(set(frag.values())) == 1 and len(set(scale.values())) == 1, (name, frag, scale)
+        # the 16 tuples are disjoint
+        regs = [r for t in frag for r in range(*map(int, re.match(r"v\[(\d+):(\d+)\]", t).groups()))]
+        assert len(regs) == len(set(regs))
+
+
+def test_main_loop_waits_are_explicit(asm_text):
+    """No compiler-made full drain (vmcnt(0)) inside the pipelined loop."""
+    for name, body in _kernels(asm_text).items():
+        m = re.search(r"Inner Loop Header.*?s_cbranch_scc1", body, flags=re.S)
+        assert m, name
+        loop = m.group(0)
+        assert loop.count("v_mfma_scale_f32_32x32x64_f8f6f4") == 128, name     # two K iterations
+        assert "vmcnt(0)" not in loop and "lgkmcnt(0)" not in loop, name
+        assert loop.count("s_barrier") == 2, name
