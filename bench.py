@@ -13,7 +13,11 @@ Prints ONE JSON line:
              average launch duration measured by HIP events on the launch stream
   cpu_baseline  the CPU oracle's layer forward timed on this machine's host cores
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|d2|d5]
+
+The decode workloads d2/d5 time wush_layer_decode (16 tokens) by replaying a
+captured graph of the steps, so that the host's launch cost is not what is
+measured; their roofline is HBM (the weights are streamed once per step).
 """
 from __future__ import annotations
 
@@ -45,7 +49,11 @@ WORKLOADS = {
     "c3": "Llama-3.1-8B MLP down projection, M=4096 K=14336 N=4096, MXFP4 W4A4, 448 WUSH blocks",
     "c4": "activation path only (wush_quantize_act), M=16384 K=4096",
     "c5": "Llama-70B MLP gate+up projection, M=8192 K=8192 N=57344, MXFP4 W4A4, 256 WUSH blocks",
+    "d2": "decode-sized batch on the c2 layer (wush_layer_decode), M=16 K=4096 N=6144",
+    "d5": "decode-sized batch on the c5 layer (wush_layer_decode), M=16 K=8192 N=57344",
 }
+DECODE = {"d2": "c2", "d5": "c5"}
+DECODE_TOKENS = 16
 
 
 def quant_bytes(M, K):
@@ -82,6 +90,81 @@ def cpu_baseline(cfg, T_bits, L, budget_rows):
             "seconds": dt, "sample": f"oracle transform+quantize on the first {rows} of {cfg.M} tokens"}
 
 
+def decode_bench(args, P, torch, dev):
+    """d2 / d5: one step = one wush_layer_decode call on M = 16 tokens."""
+    base = DECODE[args.workload]
+    cfg = I.scaled(I.CONFIGS[base], M=DECODE_TOKENS)
+    L = I.make_layer(I.CONFIGS[base])
+    M, K, N = cfg.M, cfg.K, cfg.N
+
+    def bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    Td = torch.empty((K // 32, 32, 32), dtype=torch.bfloat16, device=dev)
+    bws = torch.empty(P.wush_build_transforms_workspace(K), dtype=torch.uint8, device=dev)
+    Wd = bf16(L["W"])
+    P.wush_build_transforms(Wd, bf16(L["X_cal"]), 1e-2, Td, bws)
+    P.wush_build_transforms_status(bws, K)
+    T_bits = Td.view(torch.int16).cpu().numpy().view(np.uint16)
+    fmt = P.default_fmt(layout=1)
+    wcb, wsb = P.wush_packed_sizes(N, K, fmt)
+    Wq = torch.empty(wcb, dtype=torch.uint8, device=dev)
+    Ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    wsp = torch.empty(P.wush_prepare_weight_workspace(N, K), dtype=torch.uint8, device=dev)
+    P.wush_prepare_weight(Wd, Td, Wq, Ws, wsp, fmt)
+    P.wush_workspace_status(wsp, K)
+    del Wd, wsp, bws
+    Xd = bf16(L["X"][:M])
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    dws = torch.empty(P.wush_layer_decode_workspace(K), dtype=torch.uint8, device=dev)
+    P.wush_layer_decode_init(dws, K)
+    KT = K // 256
+    Xq, Xs = dws[:KT * 8192], dws[KT * 8192:KT * 8192 + KT * 512]   # where the call keeps the quantized activations
+
+    def replay_ms(fn, calls):
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            for _ in range(max(3, args.warmup)):
+                fn()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                for _ in range(calls):
+                    fn()
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            g.replay()
+            e1.record(st)
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / calls
+
+    ms_per_step = replay_ms(lambda: P.wush_layer_decode(Xd, Td, Wq, Ws, Y, dws, fmt), args.steps)
+    P.wush_layer_decode_status(dws, K)
+    g_ms = replay_ms(lambda: P.wush_linear(Xq, Xs, Wq, Ws, Y, fmt, K=K), args.steps)
+    gemm_bytes = N * K * (0.5 + 1 / 32) + M * K * (0.5 + 1 / 32) + M * N * 2
+    layer_bytes = N * K * (0.5 + 1 / 32) + quant_bytes(M, K) + M * K * (0.5 + 1 / 32) + M * N * 2
+    flops = 2.0 * M * N * K
+    out = {
+        "metric": "W4A4 layer TFLOP/s (transform+quant+MXFP4 GEMM); % of MXFP4 MFMA & HBM peak",
+        "value": flops / ms_per_step / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "mxfp4 (e2m1 x e8m0), bf16 in/out, f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
+                   "launch": "graph replay of the timed steps", "packed_layout": "tiled"},
+        "roofline": {"bound": "hbm", "kernel": "wush_linear for M <= 64 (weight-streaming MXFP4 GEMM)",
+                     "achieved": gemm_bytes / g_ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gemm_bytes / g_ms / 1e6 / PEAK_HBM_GBS, "traffic": None, "avg_launch_ms": g_ms},
+        "kernels": {"wush_layer_decode": {"ms": ms_per_step, "GB/s": layer_bytes / ms_per_step / 1e6,
+                                          "algorithmic_bytes": layer_bytes},
+                    "wush_linear": {"ms": g_ms, "GB/s": gemm_bytes / g_ms / 1e6, "algorithmic_bytes": gemm_bytes}},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, T_bits, L, M)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +192,9 @@ def main():
     P.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload in DECODE:
+        decode_bench(args, P, torch, dev)
+        return
 
     cfg = I.CONFIGS[args.workload]
     L = I.make_layer(cfg)          # c4 keeps its weights: they are only used to build the transforms

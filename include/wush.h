@@ -70,7 +70,8 @@ typedef enum {
   WUSH_ERR_FMT = 4,       /* unsupported format descriptor */
   WUSH_ERR_WORKSPACE = 5, /* workspace missing or too small */
   WUSH_ERR_DEVICE = 6,    /* the HIP runtime reported a launch error */
-  WUSH_ERR_SINGULAR = 7   /* a transform block is singular / a moment not positive definite */
+  WUSH_ERR_SINGULAR = 7,  /* a transform block is singular / a moment not positive definite */
+  WUSH_ERR_TIMEOUT = 8    /* wush_layer_decode: a workgroup gave up waiting at the grid-wide barrier */
 } wush_status;
 
 enum { WUSH_E2M1 = 1 };
@@ -170,11 +171,49 @@ wush_status wush_build_transforms_status(const void* workspace, int64_t K, void*
  *                 nearest even from the FP32 accumulator) or f32
  * ldy >= N (elements); Y aligned to its element size.  The tiled kernel needs
  * Y 16-byte aligned and ldy a multiple of 8; other layouts take a slower
- * general kernel.
+ * general kernel.  In the tiled layout M <= 64 takes a weight-streaming kernel
+ * (one workgroup per 32 output channels) instead of 256 x 256 tiles.
  */
 wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
                         int64_t M, int64_t N, int64_t K, wush_fmt fmt,
                         void* Y, int64_t ldy, void* stream);
+
+/*
+ * Decode-sized layer forward in one call (M <= 64 tokens): the whole layer
+ * forward-pass equation  Y = sum_i Wq(i)^T q(T(i) X(i))  -- activation transform,
+ * MXFP4 quantization and MXFP4 GEMM.  Results are those of wush_quantize_act
+ * followed by wush_linear: identical codes and scales, identical FP32
+ * accumulation order per output.  The quantized activations live only in the
+ * workspace, and the GEMM is the weight-streaming kernel for few tokens.
+ * Two forms exist.  The default enqueues two kernels (quantizer, GEMM).  With the
+ * environment variable WUSH_DECODE_FUSED=1 the call is ONE kernel launch:
+ * quantization, a grid-wide barrier, then the GEMM, with the weight stream
+ * started before the barrier.  On MI355X the barrier across the eight XCDs costs
+ * more (4-6 us) than the gap between two kernels of one stream (1.5-2 us), so
+ * the single launch only pays where launches are expensive for the caller.
+ *   X        in   bf16 [M][ldx] (device), 1 <= M <= 64
+ *   T_blocks in   bf16 [K/32][32][32] (device)
+ *   Wq, Ws   in   prepared weights in WUSH_LAYOUT_TILED (fmt.layout must say so;
+ *                 K % 256 == 0), as written by wush_prepare_weight
+ *   Y        out  [M][ldy] bf16 or f32 (fmt.out_dtype), ldy >= N
+ *   workspace     device memory, >= wush_layer_decode_workspace(K) bytes, 256-byte
+ *                 aligned: the quantized activations and the barrier words.
+ *                 wush_layer_decode_init must have run on it once (and again
+ *                 after a WUSH_ERR_TIMEOUT); one call at a time per workspace.
+ * The single-launch form holds all its workgroups resident (one per CU) and
+ * synchronizes them once through the workspace; every wait is bounded.  If a wait
+ * expires (the GPU was shared with work that kept this kernel's workgroups from
+ * running together) the workgroup sets a flag, Y is left incomplete, and
+ * wush_layer_decode_status (which synchronizes the stream) returns
+ * WUSH_ERR_TIMEOUT; otherwise WUSH_OK.
+ */
+size_t wush_layer_decode_workspace(int64_t K);
+wush_status wush_layer_decode_init(void* workspace, size_t workspace_bytes, int64_t K, void* stream);
+wush_status wush_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx,
+                              const void* T_blocks, const void* Wq, const void* Ws, int64_t N,
+                              wush_fmt fmt, void* Y, int64_t ldy,
+                              void* workspace, size_t workspace_bytes, void* stream);
+wush_status wush_layer_decode_status(const void* workspace, int64_t K, void* stream);
 
 /*
  * Test tap: the quantizer alone on FP32 values (same device function the fused

@@ -14,6 +14,10 @@ from .binding import (  # noqa: F401
     wush_build_transforms,
     wush_build_transforms_status,
     wush_build_transforms_workspace,
+    wush_layer_decode,
+    wush_layer_decode_init,
+    wush_layer_decode_status,
+    wush_layer_decode_workspace,
     wush_linear,
     wush_packed_sizes,
     wush_unpack_tiled,
@@ -29,5 +33,6 @@ __all__ = [
     "WushError", "WushFmt", "default_fmt", "lib", "lib_path", "wush_linear", "wush_prepare_weight",
     "wush_prepare_weight_workspace", "wush_quantize_act", "wush_quantize_f32", "wush_status_string",
     "wush_workspace_status", "wush_packed_sizes", "wush_unpack_tiled", "wush_build_transforms",
-    "wush_build_transforms_status", "wush_build_transforms_workspace",
+    "wush_build_transforms_status", "wush_build_transforms_workspace", "wush_layer_decode",
+    "wush_layer_decode_init", "wush_layer_decode_status", "wush_layer_decode_workspace",
 ]

@@ -21,7 +21,7 @@ WUSH_LAYOUT_CANONICAL, WUSH_LAYOUT_TILED = 0, 1
 
 STATUS_NAMES = {
     0: "WUSH_OK", 1: "WUSH_ERR_NULL", 2: "WUSH_ERR_SHAPE", 3: "WUSH_ERR_ALIGN", 4: "WUSH_ERR_FMT",
-    5: "WUSH_ERR_WORKSPACE", 6: "WUSH_ERR_DEVICE", 7: "WUSH_ERR_SINGULAR",
+    5: "WUSH_ERR_WORKSPACE", 6: "WUSH_ERR_DEVICE", 7: "WUSH_ERR_SINGULAR", 8: "WUSH_ERR_TIMEOUT",
 }
 
 # every symbol include/wush.h declares
@@ -30,6 +30,7 @@ EXPORTS = (
     "wush_workspace_status", "wush_linear", "wush_quantize_f32", "wush_status_string", "wush_version",
     "wush_packed_sizes", "wush_unpack_tiled",
     "wush_build_transforms", "wush_build_transforms_workspace", "wush_build_transforms_status",
+    "wush_layer_decode", "wush_layer_decode_workspace", "wush_layer_decode_init", "wush_layer_decode_status",
 )
 
 
@@ -93,6 +94,15 @@ def lib() -> ctypes.CDLL:
         L.wush_packed_sizes.argtypes = [c_int64, c_int64, WushFmt, POINTER(c_size_t), POINTER(c_size_t)]
         L.wush_unpack_tiled.restype = c_int32
         L.wush_unpack_tiled.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
+        L.wush_layer_decode_workspace.restype = c_size_t
+        L.wush_layer_decode_workspace.argtypes = [c_int64]
+        L.wush_layer_decode_init.restype = c_int32
+        L.wush_layer_decode_init.argtypes = [c_void_p, c_size_t, c_int64, c_void_p]
+        L.wush_layer_decode.restype = c_int32
+        L.wush_layer_decode.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_int64,
+                                        WushFmt, c_void_p, c_int64, c_void_p, c_size_t, c_void_p]
+        L.wush_layer_decode_status.restype = c_int32
+        L.wush_layer_decode_status.argtypes = [c_void_p, c_int64, c_void_p]
         _lib = L
     return _lib
 
@@ -201,3 +211,31 @@ def wush_quantize_f32(Yt, q, s, fmt: WushFmt | None = None, stream=None):
     M, K = Yt.shape
     _check(lib().wush_quantize_f32(_ptr(Yt), M, K, fmt or default_fmt(), _ptr(q), _ptr(s), _stream(stream)),
            "wush_quantize_f32")
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def wush_layer_decode_workspace(K: int) -> int:
+    return int(lib().wush_layer_decode_workspace(K))
+
+
+def wush_layer_decode_init(workspace, K: int, stream=None):
+    """Zero the barrier words of a wush_layer_decode workspace (once after allocation)."""
+    _check(lib().wush_layer_decode_init(_ptr(workspace), _nbytes(workspace), K, _stream(stream)),
+           "wush_layer_decode_init")
+
+
+def wush_layer_decode(X, T_blocks, Wq, Ws, Y, workspace, fmt: WushFmt | None = None, stream=None):
+    """One-launch layer forward for M <= 64 tokens: X bf16 [M][K], prepared tiled
+    weights Wq/Ws -> Y [M][N] (N from Y)."""
+    M, K = X.shape
+    N = Y.shape[1]
+    _check(lib().wush_layer_decode(_ptr(X), M, K, X.stride(0), _ptr(T_blocks), _ptr(Wq), _ptr(Ws), N,
+                                   fmt or default_fmt(layout=WUSH_LAYOUT_TILED), _ptr(Y), Y.stride(0),
+                                   _ptr(workspace), _nbytes(workspace), _stream(stream)), "wush_layer_decode")
+
+
+def wush_layer_decode_status(workspace, K: int, stream=None):
+    _check(lib().wush_layer_decode_status(_ptr(workspace), K, _stream(stream)), "wush_layer_decode_status")

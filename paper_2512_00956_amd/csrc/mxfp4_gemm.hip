@@ -256,7 +256,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
 hipError_t launch_mxfp4_gemm(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
                              int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y, int64_t ldy,
                              hipStream_t stream) {
-  if (tiled) return launch_mxfp4_gemm_frag(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
+  if (tiled) {
+    // Decode-sized batches stream the weights once instead of padding M to a 256-row tile.
+    if (M <= 64) return launch_mxfp4_gemm_skinny(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
+    return launch_mxfp4_gemm_frag(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
+  }
   // Debug knob: WUSH_GEMM=simple forces the general kernel.
   static const bool force_simple = [] {
     const char* e = getenv("WUSH_GEMM");

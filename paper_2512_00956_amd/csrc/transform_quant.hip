@@ -18,31 +18,17 @@
 //     codes in canonical nibble order.
 // Codes of two blocks are exchanged between the wave halves so every lane
 // stores 32 contiguous bytes; the 4 scale bytes of a token go out as one dword.
-#include "wush_device.hpp"
+#include "transform_quant_core.hpp"
 #include "wush_kernels.hpp"
 
 namespace wush {
 
 namespace {
 
-constexpr int kNB = 4;       // blocks per wave
+using tq::kNB;
+using tq::kTileM;
+using tq::XFrag;
 constexpr int kWaves = 4;    // waves per workgroup
-constexpr int kTileM = 32;   // tokens per MFMA tile
-
-struct XFrag {
-  v8bf lo, hi;  // channels 16h..16h+7 and 16h+8..16h+15 of one token, one block
-};
-
-__device__ __forceinline__ void load_tile(XFrag (&x)[kNB], const uint16_t* __restrict__ X,
-                                          int64_t ldx, int row, int bfirst, int C, int h) {
-#pragma unroll
-  for (int bb = 0; bb < kNB; ++bb) {
-    const int b = min(bfirst + bb, C - 1);  // clamped: out-of-range blocks reload a valid one
-    const uint16_t* p = X + (int64_t)row * ldx + 32 * b + 16 * h;
-    x[bb].lo = *reinterpret_cast<const v8bf*>(p);
-    x[bb].hi = *reinterpret_cast<const v8bf*>(p + 8);
-  }
-}
 
 template <bool DBG, bool TILED>
 __global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
@@ -57,17 +43,8 @@ __global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
   if (bfirst >= C) return;  // wave-uniform
   const int nb = min(kNB, C - bfirst);
 
-  // A operand: MFMA row position i carries output channel c(i), chosen so that
-  // accumulator r of lane half h is channel 16h + r.
-  const int crow = 16 * ((tok >> 2) & 1) + 4 * (tok >> 3) + (tok & 3);
   v8bf ta[kNB][2];
-#pragma unroll
-  for (int bb = 0; bb < kNB; ++bb) {
-    const int b = min(bfirst + bb, C - 1);
-    const uint16_t* p = T + ((int64_t)b * 32 + crow) * 32 + 16 * h;
-    ta[bb][0] = *reinterpret_cast<const v8bf*>(p);
-    ta[bb][1] = *reinterpret_cast<const v8bf*>(p + 8);
-  }
+  tq::load_transforms(ta, T, bfirst, C, tok, h);
 
   const int ntiles = (M + kTileM - 1) / kTileM;
   int t = blockIdx.x * tiles_per_wg;
@@ -75,70 +52,19 @@ __global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
   if (t >= tend) return;
 
   XFrag cur[kNB], nxt[kNB];
-  load_tile(cur, X, ldx, min(t * kTileM + tok, M - 1), bfirst, C, h);
+  tq::load_tile(cur, X, ldx, min(t * kTileM + tok, M - 1), bfirst, C, h);
 
   for (; t < tend; ++t) {
     const int m = t * kTileM + tok;
     const bool row_ok = m < M;
-    if (t + 1 < tend) load_tile(nxt, X, ldx, min((t + 1) * kTileM + tok, M - 1), bfirst, C, h);
+    if (t + 1 < tend) tq::load_tile(nxt, X, ldx, min((t + 1) * kTileM + tok, M - 1), bfirst, C, h);
 
-    uint32_t w[kNB][2];
-    uint32_t sbytes = 0;
-#pragma unroll
-    for (int bb = 0; bb < kNB; ++bb) {
-      v16f acc = {0};
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta[bb][0], cur[bb].lo, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta[bb][1], cur[bb].hi, acc, 0, 0, 0);
-      float v[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) v[r] = acc[r];
-      if (DBG) {
-        if (row_ok && bb < nb) {
-          float* d = dbg + (int64_t)m * K + 32 * (bfirst + bb) + 16 * h;
-#pragma unroll
-          for (int r = 0; r < 16; r += 4)
-            *reinterpret_cast<v4f*>(d + r) = (v4f){v[r], v[r + 1], v[r + 2], v[r + 3]};
-        }
-      }
-      float amax = fabsf(v[0]);
-#pragma unroll
-      for (int r = 1; r < 16; ++r) amax = fmaxf(amax, fabsf(v[r]));
-      // other half of the group lives in lane ^ 32
-      const uint32_t ab = __float_as_uint(amax);
-      const auto sw = __builtin_amdgcn_permlane32_swap(ab, ab, false, false);
-      amax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-      const int byte = scale_byte_f32(amax, rule);
-      const float sc = scale_as_f32(byte);
-      w[bb][0] = pack8_e2m1(v, sc);
-      w[bb][1] = pack8_e2m1(v + 8, sc);
-      sbytes |= (uint32_t)byte << (8 * bb);
-    }
-
-    // Exchange halves: lanes 0..31 end up with the full 16 bytes of blocks 0
-    // and 1 of their token, lanes 32..63 with blocks 2 and 3.
     v4u out[2];
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const auto s0 = __builtin_amdgcn_permlane32_swap(w[p][0], w[p + 2][0], false, false);
-      const auto s1 = __builtin_amdgcn_permlane32_swap(w[p][1], w[p + 2][1], false, false);
-      out[p] = (v4u){s0[0], s1[0], s0[1], s1[1]};
-    }
+    uint32_t sbytes;
+    float* dbg_row = (DBG && row_ok) ? dbg + (int64_t)m * K + 32 * bfirst + 16 * h : nullptr;
+    tq::transform_quantize<DBG>(ta, cur, rule, out, sbytes, dbg_row, nb);
     if (TILED) {
-      // fragment-order layout: K % 256 == 0, so nb == 4 and bfirst % 4 == 0.
-      // Lanes 0..31 hold blocks bfirst, bfirst+1 of their token (kk = 0, 1),
-      // lanes 32..63 blocks bfirst+2, bfirst+3 (kk = 2, 3); per instruction the
-      // 32 tokens of a half write 512 contiguous bytes.
-      if (row_ok) {
-        const int KT = K >> 8;
-        const int kt = bfirst >> 3, khg = (bfirst >> 2) & 1;
-        const int64_t frag = ((int64_t)t * KT + kt) * 4;   // row block = token tile t
-        uint8_t* q = Xq + ((frag + 2 * h) * 64 + khg * 32 + tok) * 16;
-        // streaming output: non-temporal stores keep it from displacing X in the caches
-        __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(q));
-        __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(q + 1024));
-        if (h == 0)
-          __builtin_nontemporal_store(sbytes, reinterpret_cast<uint32_t*>(Xs + ((((int64_t)t * KT + kt) * 64) + khg * 32 + tok) * 4));
-      }
+      if (row_ok) tq::store_tile_tiled<true>(out, sbytes, Xq, Xs, t, K >> 8, bfirst, tok, h);
     } else if (row_ok) {
       uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
       if (nb == kNB && (C & 3) == 0) {

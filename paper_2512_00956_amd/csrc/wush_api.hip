@@ -4,6 +4,7 @@
 #include "../../include/wush.h"
 
 #include <hip/hip_runtime.h>
+#include <stdlib.h>
 
 #include "wush_kernels.hpp"
 
@@ -141,6 +142,67 @@ wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const vo
                                           static_cast<hipStream_t>(stream)));
 }
 
+size_t wush_layer_decode_workspace(int64_t K) {
+  if (K <= 0 || K % 256 != 0 || K > kMaxDim) return 0;
+  return wush::layer_decode_workspace_bytes(K);
+}
+
+wush_status wush_layer_decode_init(void* workspace, size_t workspace_bytes, int64_t K, void* stream) {
+  if (!workspace) return WUSH_ERR_NULL;
+  if (K <= 0 || K % 256 != 0 || K > kMaxDim) return WUSH_ERR_SHAPE;
+  if (workspace_bytes < wush::layer_decode_workspace_bytes(K)) return WUSH_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_layer_decode_init(workspace, K, static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T_blocks,
+                              const void* Wq, const void* Ws, int64_t N, wush_fmt fmt, void* Y, int64_t ldy,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!X || !T_blocks || !Wq || !Ws || !Y) return WUSH_ERR_NULL;
+  if (wush_status s = check_fmt(fmt)) return s;
+  if (fmt.layout != WUSH_LAYOUT_TILED) return WUSH_ERR_FMT;
+  if (wush_status s = check_rows(M, K, ldx)) return s;
+  if (M > 64 || K % 256 != 0 || N <= 0 || N > kMaxDim || ldy < N) return WUSH_ERR_SHAPE;
+  if (!aligned16(X) || !aligned16(T_blocks) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
+  const uintptr_t elem = fmt.out_dtype == WUSH_OUT_F32 ? 4 : 2;
+  if (reinterpret_cast<uintptr_t>(Y) % elem != 0) return WUSH_ERR_ALIGN;
+  if (!workspace || workspace_bytes < wush::layer_decode_workspace_bytes(K)) return WUSH_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return WUSH_ERR_ALIGN;
+  // WUSH_DECODE_TEST_TIMEOUT=1 (tests only): make every workgroup's barrier wait expire at once.
+  const char* hook = getenv("WUSH_DECODE_TEST_TIMEOUT");
+  const int test_timeout = hook && hook[0] == '1';
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int out_f32 = fmt.out_dtype == WUSH_OUT_F32;
+  // Two launches by default.  With the host's launch cost out of the picture (graph
+  // replay) two back-to-back kernels are 1.5-2 us apart, while the single-launch
+  // form pays 4-6 us for its grid-wide barrier across the eight XCDs: measured
+  // 6.4 against 9.5 us on 4096 x 6144, 40 against 55 us on 8192 x 57344 (M = 1).
+  // WUSH_DECODE_FUSED=1 selects the single launch.
+  const char* f = getenv("WUSH_DECODE_FUSED");
+  const bool fused = f && f[0] == '1';
+  if (fused || test_timeout)
+    return from_hip(wush::launch_layer_decode(X, M, K, ldx, T_blocks, Wq, Ws, N, fmt.scale_rule, out_f32, Y, ldy,
+                                              workspace, test_timeout, st));
+  // two launches through the same workspace (same Xq/Xs layout and positions)
+  char* wsb = static_cast<char*>(workspace);
+  void* Xq = wsb;
+  void* Xs = wsb + wush::layer_decode_scales_offset(K);
+  if (hipError_t e = wush::launch_transform_quant(X, M, K, ldx, T_blocks, fmt.scale_rule, 1, Xq, Xs, nullptr, st))
+    return from_hip(e);
+  return from_hip(wush::launch_mxfp4_gemm_skinny(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, st));
+}
+
+wush_status wush_layer_decode_status(const void* workspace, int64_t K, void* stream) {
+  if (!workspace) return WUSH_ERR_NULL;
+  if (K <= 0 || K % 256 != 0 || K > kMaxDim) return WUSH_ERR_SHAPE;
+  unsigned flag = 0;
+  const char* p = static_cast<const char*>(workspace) + wush::layer_decode_error_offset(K);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&flag, p, sizeof(flag), hipMemcpyDeviceToHost, st) != hipSuccess) return WUSH_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return WUSH_ERR_DEVICE;
+  return flag ? WUSH_ERR_TIMEOUT : WUSH_OK;
+}
+
 wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fmt, void* q, void* s,
                               void* stream) {
   if (!Yt || !q || !s) return WUSH_ERR_NULL;
@@ -181,10 +243,11 @@ const char* wush_status_string(wush_status st) {
     case WUSH_ERR_WORKSPACE: return "workspace missing or too small";
     case WUSH_ERR_DEVICE: return "HIP runtime error";
     case WUSH_ERR_SINGULAR: return "singular transform block";
+    case WUSH_ERR_TIMEOUT: return "grid barrier wait expired";
   }
   return "unknown status";
 }
 
-const char* wush_version(void) { return "0.3"; }
+const char* wush_version(void) { return "0.4"; }
 
 }  // extern "C"

@@ -39,4 +39,18 @@ hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq
                                   int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
                                   hipStream_t stream);
 
+// Decode-sized paths (M <= 64, fragment-order operands).
+hipError_t launch_mxfp4_gemm_skinny(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M,
+                                    int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy, hipStream_t stream);
+// workspace layout: Xq for 64 tokens | Xs | barrier words (generation, error flag, arrival and release slots).
+size_t layer_decode_workspace_bytes(int64_t K);
+size_t layer_decode_scales_offset(int64_t K);
+size_t layer_decode_state_offset(int64_t K);
+size_t layer_decode_error_offset(int64_t K);
+hipError_t launch_layer_decode_init(void* workspace, int64_t K, hipStream_t stream);
+// test_timeout != 0: the barrier expects one workgroup more than launched and gives up after a few polls.
+hipError_t launch_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T, const void* Wq,
+                               const void* Ws, int64_t N, int rule, int out_f32, void* Y, int64_t ldy,
+                               void* workspace, int test_timeout, hipStream_t stream);
+
 }  // namespace wush

@@ -28,14 +28,14 @@ def test_header_symbols_are_exported(L):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(L, name) is not None
-    assert L.wush_version() == b"0.3"
+    assert L.wush_version() == b"0.4"
 
 
 def test_default_fmt_and_status_strings(L):
     f = P.default_fmt()
     assert (f.block, f.elem, f.scale, f.scale_rule, f.out_dtype, f.layout) == (32, 1, 1, 0, 0, 0)
-    names = {P.wush_status_string(c) for c in range(8)}
-    assert len(names) == 8 and "ok" in names
+    names = {P.wush_status_string(c) for c in range(9)}
+    assert len(names) == 9 and "ok" in names
     assert P.wush_status_string(99) == "unknown status"
 
 
@@ -134,3 +134,23 @@ def test_build_transforms_validation(L):
     assert bt(A, 8, 64, A, 16, 64, 64, 0.01, A, None, A, need - 1, None) == 5
     assert bt(A, 8, 64, A, 16, 64, 64, 0.01, A, None, None, need, None) == 5
     assert L.wush_build_transforms_status(None, 64, None) == 1
+
+
+def test_layer_decode_validation(L):
+    t = P.default_fmt(layout=1)
+    need = L.wush_layer_decode_workspace(512)
+    assert need >= 2 * (2 * 4096 + 2 * 256) + 64
+    assert L.wush_layer_decode_workspace(288) == 0                # K % 256
+    B = 0x10000                                                   # 256-byte aligned fake address
+    dec = lambda *a: L.wush_layer_decode(*a)
+    assert dec(None, 4, 512, 512, A, A, A, 64, t, A, 64, B, need, None) == 1
+    assert dec(A, 4, 512, 512, A, A, A, 64, P.default_fmt(), A, 64, B, need, None) == 4   # canonical weights
+    assert dec(A, 65, 512, 512, A, A, A, 64, t, A, 64, B, need, None) == 2                # M > 64
+    assert dec(A, 4, 480, 480, A, A, A, 64, t, A, 64, B, need, None) == 2                 # K % 256
+    assert dec(A, 4, 512, 512, A, A, A, 64, t, A, 60, B, need, None) == 2                 # ldy < N
+    assert dec(A, 4, 512, 512, A, A + 8, A, 64, t, A, 64, B, need, None) == 3
+    assert dec(A, 4, 512, 512, A, A, A, 64, t, A, 64, B, need - 1, None) == 5
+    assert dec(A, 4, 512, 512, A, A, A, 64, t, A, 64, B + 16, need, None) == 3            # workspace alignment
+    assert L.wush_layer_decode_init(None, need, 512, None) == 1
+    assert L.wush_layer_decode_init(B, need - 1, 512, None) == 5
+    assert L.wush_layer_decode_status(None, 512, None) == 1
