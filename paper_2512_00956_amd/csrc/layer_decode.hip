@@ -13,8 +13,9 @@
 // 33..64 tokens) partial tiles on the scaled 32x32x64 MFMA, and reduce the four
 // partials through LDS in a fixed order.  The W fragment is the first MFMA
 // operand, so a lane's accumulator quad is four consecutive output channels of one
-// token.  Latency is hidden by occupancy (several workgroups per CU), not by a
-// software pipeline: a wave only keeps the next W tile in flight.
+// token.  A wave issues the loads of 4 K tiles (2 for 33..64 tokens) of W and X
+// together and then consumes them; beyond that, latency is hidden by occupancy
+// (several workgroups per CU), not by a software pipeline.
 //
 // Fused form.  Phase 1: the (token tile, 4 blocks) units of the activation
 // quantizer are dealt out one per wave over the grid and write Xq/Xs (fragment
@@ -33,9 +34,10 @@
 // dropped: one release slot per workgroup, and every workgroup polling the slot
 // array itself -- both slower.  Device-scope release/acquire fences bracket the
 // stores and loads.  From the last arrival to the last workgroup leaving the
-// barrier takes 3-5 us: each hop is a trip to the memory side of the fabric.  The barrier needs all workgroups resident: the grid is capped at what
-// the occupancy query says fits, and every wait is bounded -- on expiry the
-// workgroup records an error and exits without touching Y.
+// barrier takes 3-5 us: each hop is a trip to the memory side of the fabric.
+// The barrier needs all workgroups resident: the grid is capped at one workgroup
+// per CU, and every wait is bounded -- on expiry the workgroup records an error
+// and exits without touching Y.
 #include "transform_quant_core.hpp"
 #include "wush_kernels.hpp"
 
@@ -48,7 +50,7 @@ constexpr uint32_t kSpinLimit = 1u << 21;   // polls of about 0.5 us each
 constexpr int kMaxGrid = 1024;              // barrier slots in the workspace
 
 // Barrier words in the workspace (uint32 index): generation of the last completed
-// launch, error flag, arrival slots (dense), release slots (one per 128 bytes).
+// launch, error flag (each on its own 128-byte line), arrival slots (dense).
 constexpr int kGenWord = 0, kErrWord = 32, kArriveWord = 64;
 constexpr int kStateWords = kArriveWord + kMaxGrid;
 
