@@ -163,6 +163,39 @@ wush_status wush_build_transforms(const void* W, int64_t N, int64_t ldw,
 wush_status wush_build_transforms_status(const void* workspace, int64_t K, void* stream);
 
 /*
+ * Offline weight preparation, GPTQ case of Alg. 2: the transforms are built
+ * block after block from the second moment of the UPDATED weight block and the
+ * diagonal block of the activation Hessian H = M_cal^-1 X_cal^T X_cal (Alg. 1),
+ * the transformed block is quantized by the GPTQ subroutine (intra-block error
+ * propagation under the transformed block Hessian) and the error, mapped back
+ * to the original space, is propagated to the remaining blocks through the
+ * Cholesky factor of inv(H + lambda tr(H)/K I).  All in FP64 on the device.
+ * Readings of what the paper leaves open: T_i is rounded to BF16 before it is
+ * used; the MXFP4 group of an output channel is the block itself and its scale
+ * is taken from the transformed weights before any intra-block update (later
+ * values saturate); channels of a block are processed in index order.
+ *   W        in   bf16 [N][ldw] (device)
+ *   X_cal    in   bf16 [M_cal][ldx] (device), calibration tokens
+ *   lambda        damping ratio of both the Hessian and Alg. 1
+ *   transform_given  0: T_blocks is an OUTPUT (the algorithm above);
+ *                 1: T_blocks is an INPUT (e.g. Hadamard or identity blocks) and
+ *                 only the GPTQ schedule runs -- the baselines of the paper's tables
+ *   T_blocks      bf16 [K/32][32][32]
+ *   Wq, Ws   out  packed codes / scales in fmt.layout, as wush_prepare_weight writes
+ *   workspace     device scratch, >= wush_prepare_weight_gptq_workspace(N, K)
+ *                 bytes (two K x K and one N x K FP64 matrices), 256-byte aligned
+ * A Hessian or moment that is not positive definite, or a singular T_i, sets a
+ * flag that wush_prepare_weight_gptq_status reads back (it synchronizes).
+ */
+size_t wush_prepare_weight_gptq_workspace(int64_t N, int64_t K);
+wush_status wush_prepare_weight_gptq(const void* W, int64_t N, int64_t K, int64_t ldw,
+                                     const void* X_cal, int64_t M_cal, int64_t ldx,
+                                     double lambda, int32_t transform_given, wush_fmt fmt,
+                                     void* T_blocks, void* Wq, void* Ws,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+wush_status wush_prepare_weight_gptq_status(const void* workspace, int64_t N, int64_t K, void* stream);
+
+/*
  * MXFP4 x MXFP4 GEMM with FP32 accumulation: the sum over blocks of the layer
  * forward-pass equation, Y = deq(Xq,Xs) . deq(Wq,Ws)^T, on block-scaled MFMA.
  *   Xq, Xs   in   u8 [M][K/2], u8 [M][K/32]

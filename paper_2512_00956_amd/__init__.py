@@ -22,6 +22,9 @@ from .binding import (  # noqa: F401
     wush_packed_sizes,
     wush_unpack_tiled,
     wush_prepare_weight,
+    wush_prepare_weight_gptq,
+    wush_prepare_weight_gptq_status,
+    wush_prepare_weight_gptq_workspace,
     wush_prepare_weight_workspace,
     wush_quantize_act,
     wush_quantize_f32,
@@ -35,4 +38,5 @@ __all__ = [
     "wush_workspace_status", "wush_packed_sizes", "wush_unpack_tiled", "wush_build_transforms",
     "wush_build_transforms_status", "wush_build_transforms_workspace", "wush_layer_decode",
     "wush_layer_decode_init", "wush_layer_decode_status", "wush_layer_decode_workspace",
+    "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_status", "wush_prepare_weight_gptq_workspace",
 ]

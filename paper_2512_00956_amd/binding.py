@@ -31,6 +31,7 @@ EXPORTS = (
     "wush_packed_sizes", "wush_unpack_tiled",
     "wush_build_transforms", "wush_build_transforms_workspace", "wush_build_transforms_status",
     "wush_layer_decode", "wush_layer_decode_workspace", "wush_layer_decode_init", "wush_layer_decode_status",
+    "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_workspace", "wush_prepare_weight_gptq_status",
 )
 
 
@@ -103,6 +104,14 @@ def lib() -> ctypes.CDLL:
                                         WushFmt, c_void_p, c_int64, c_void_p, c_size_t, c_void_p]
         L.wush_layer_decode_status.restype = c_int32
         L.wush_layer_decode_status.argtypes = [c_void_p, c_int64, c_void_p]
+        L.wush_prepare_weight_gptq_workspace.restype = c_size_t
+        L.wush_prepare_weight_gptq_workspace.argtypes = [c_int64, c_int64]
+        L.wush_prepare_weight_gptq.restype = c_int32
+        L.wush_prepare_weight_gptq.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int64, c_int64, c_double,
+                                               c_int32, WushFmt, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
+                                               c_void_p]
+        L.wush_prepare_weight_gptq_status.restype = c_int32
+        L.wush_prepare_weight_gptq_status.argtypes = [c_void_p, c_int64, c_int64, c_void_p]
         _lib = L
     return _lib
 
@@ -239,3 +248,23 @@ def wush_layer_decode(X, T_blocks, Wq, Ws, Y, workspace, fmt: WushFmt | None = N
 
 def wush_layer_decode_status(workspace, K: int, stream=None):
     _check(lib().wush_layer_decode_status(_ptr(workspace), K, _stream(stream)), "wush_layer_decode_status")
+
+
+def wush_prepare_weight_gptq_workspace(N: int, K: int) -> int:
+    return int(lib().wush_prepare_weight_gptq_workspace(N, K))
+
+
+def wush_prepare_weight_gptq(W, X_cal, lam: float, T_blocks, Wq, Ws, workspace, fmt: WushFmt | None = None,
+                             transform_given: bool = False, stream=None):
+    """Alg. 2, GPTQ case: W bf16 [N][K], X_cal bf16 [M_cal][K] -> T_blocks (output unless
+    transform_given), Wq, Ws."""
+    N, K = W.shape
+    _check(lib().wush_prepare_weight_gptq(_ptr(W), N, K, W.stride(0), _ptr(X_cal), X_cal.shape[0], X_cal.stride(0),
+                                          float(lam), int(bool(transform_given)), fmt or default_fmt(), _ptr(T_blocks),
+                                          _ptr(Wq), _ptr(Ws), _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "wush_prepare_weight_gptq")
+
+
+def wush_prepare_weight_gptq_status(workspace, N: int, K: int, stream=None):
+    _check(lib().wush_prepare_weight_gptq_status(_ptr(workspace), N, K, _stream(stream)),
+           "wush_prepare_weight_gptq_status")

@@ -142,6 +142,41 @@ wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const vo
                                           static_cast<hipStream_t>(stream)));
 }
 
+size_t wush_prepare_weight_gptq_workspace(int64_t N, int64_t K) {
+  if (N <= 0 || K <= 0 || K % 32 != 0 || N > kMaxDim || K > kMaxDim) return 0;
+  return wush::gptq_prep_workspace_bytes(N, K);
+}
+
+wush_status wush_prepare_weight_gptq(const void* W, int64_t N, int64_t K, int64_t ldw, const void* X_cal,
+                                     int64_t M_cal, int64_t ldx, double lambda, int32_t transform_given,
+                                     wush_fmt fmt, void* T_blocks, void* Wq, void* Ws, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  if (!W || !X_cal || !T_blocks || !Wq || !Ws) return WUSH_ERR_NULL;
+  if (wush_status s = check_fmt(fmt)) return s;
+  if (wush_status s = check_rows(N, K, ldw)) return s;
+  if (wush_status s = check_rows(M_cal, K, ldx)) return s;
+  if (wush_status s = check_layout(fmt, K)) return s;
+  if (!(lambda >= 0.0) || !(lambda < 1e6)) return WUSH_ERR_SHAPE;
+  if (transform_given != 0 && transform_given != 1) return WUSH_ERR_FMT;
+  if (!aligned16(W) || !aligned16(X_cal) || !aligned16(T_blocks) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
+  if (!workspace || workspace_bytes < wush::gptq_prep_workspace_bytes(N, K)) return WUSH_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_gptq_prep(W, N, K, ldw, X_cal, M_cal, ldx, lambda, transform_given, fmt.scale_rule,
+                                         fmt.layout == WUSH_LAYOUT_TILED, T_blocks, Wq, Ws, workspace,
+                                         static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_prepare_weight_gptq_status(const void* workspace, int64_t N, int64_t K, void* stream) {
+  if (!workspace) return WUSH_ERR_NULL;
+  if (N <= 0 || K <= 0 || K % 32 != 0 || N > kMaxDim || K > kMaxDim) return WUSH_ERR_SHAPE;
+  int flag = 0;
+  const char* p = static_cast<const char*>(workspace) + wush::gptq_prep_status_offset(N, K);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&flag, p, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess) return WUSH_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return WUSH_ERR_DEVICE;
+  return flag ? WUSH_ERR_SINGULAR : WUSH_OK;
+}
+
 size_t wush_layer_decode_workspace(int64_t K) {
   if (K <= 0 || K % 256 != 0 || K > kMaxDim) return 0;
   return wush::layer_decode_workspace_bytes(K);
@@ -248,6 +283,6 @@ const char* wush_status_string(wush_status st) {
   return "unknown status";
 }
 
-const char* wush_version(void) { return "0.4"; }
+const char* wush_version(void) { return "0.5"; }
 
 }  // extern "C"

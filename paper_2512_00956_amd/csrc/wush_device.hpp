@@ -56,6 +56,32 @@ __device__ __forceinline__ uint32_t pack8_e2m1(const float* v, float scale) {
   return w;
 }
 
+// Scale byte from an FP64 AbsMax; same rule as scale_byte_f32 on the 11-bit
+// exponent (re-biased to E8M0) and the 52-bit fraction.
+__device__ __forceinline__ int scale_byte_f64(double amax, int rule) {
+  const uint64_t bits = (uint64_t)__double_as_longlong(amax);
+  if (amax == 0.0) return 0;
+  const int e11 = (int)(bits >> 52);
+  const uint64_t frac = bits & 0xFFFFFFFFFFFFFull;
+  int biased = e11 - 1023 + 127 - 2;
+  if (rule == 0 && frac > 0x8000000000000ull) biased += 1;
+  return min(max(biased, 0), 254);
+}
+
+// |v| (already divided by the group scale) -> E2M1 magnitude code, nearest,
+// ties to the even code, saturating.
+__device__ __forceinline__ uint32_t e2m1_code_f64(double a) {
+  uint32_t c = 0;
+  c += a > 0.25;
+  c += a >= 0.75;
+  c += a > 1.25;
+  c += a >= 1.75;
+  c += a > 2.5;
+  c += a >= 3.5;
+  c += a > 5.0;
+  return c;
+}
+
 // ---------------------------------------------------------------------------
 // Tiled ("MFMA fragment order") layout of packed codes and scales, used between
 // the quantizers and the tiled GEMM.  Needs K % 256 == 0; buffers are padded to a

@@ -39,6 +39,14 @@ hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq
                                   int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
                                   hipStream_t stream);
 
+// Alg. 2, GPTQ case: transforms (unless given) and pre-quantized weights.  Workspace: FP64 Hessian factor,
+// its inverse, a working copy of W, per-block scratch, status word.
+size_t gptq_prep_workspace_bytes(int64_t N, int64_t K);
+size_t gptq_prep_status_offset(int64_t N, int64_t K);
+hipError_t launch_gptq_prep(const void* W, int64_t N, int64_t K, int64_t ldw, const void* Xc, int64_t Mc, int64_t ldx,
+                            double lambda, int transform_given, int rule, int tiled, void* T_blocks, void* Wq, void* Ws,
+                            void* workspace, hipStream_t stream);
+
 // Decode-sized paths (M <= 64, fragment-order operands).
 hipError_t launch_mxfp4_gemm_skinny(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M,
                                     int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy, hipStream_t stream);
