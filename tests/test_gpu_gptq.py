@@ -151,3 +151,19 @@ def test_gptq_layer_runs_through_the_online_path(P, G):
     l_rh = O.layer_loss(O.layer_forward(X, W, O.round_to_bf16(O.hadamard_transforms(K // 32))), exact)
     print(f"W4A4 layer loss: RTN-H {l_rh:.4e}  GPTQ-WUSH (GPU) {l_gw:.4e}")
     assert l_gw < l_rh
+
+
+def test_gptq_c2_full_size(P, G):
+    """The c2 layer in full (K=4096, N=6144, 4096 calibration tokens): the oracle redoes the whole schedule."""
+    import time
+    cfg = I.CONFIGS["c2"]
+    L = I.make_layer(cfg)
+    W, Xc = O.bf16_bits_to_f64(L["W"]), O.bf16_bits_to_f64(L["X_cal"])
+    X = O.bf16_bits_to_f64(L["X"][:256])
+    t0 = time.perf_counter()
+    T_gpu, c_gpu, s_gpu = _run_gpu(P, G, W, Xc, 1e-2, 1)
+    t1 = time.perf_counter()
+    T_ref, c_ref, s_ref = Q.gptq_wush_layer(W, Xc, 1e-2)
+    t2 = time.perf_counter()
+    print(f"c2 GPTQ case: GPU call incl. transfers {t1 - t0:.2f} s, oracle {t2 - t1:.1f} s")
+    _compare(T_gpu, c_gpu, s_gpu, T_ref, c_ref, s_ref, W, X, "c2")
