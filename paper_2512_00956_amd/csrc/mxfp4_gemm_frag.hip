@@ -2,9 +2,12 @@
 // wush_device.hpp: Y = deq(Xq,Xs) . deq(Wq,Ws)^T (the layer forward-pass
 // equation summed over all blocks), v_mfma_scale_f32_32x32x64_f8f6f4.
 //
-// Workgroup tile 256 (M) x 256 (N), K advances 256 elements per iteration.
-// The four wavefronts split N: each owns all 256 rows and 64 columns
-// (8 x 2 MFMA tiles, 256 accumulator registers), so one wave per SIMD.
+// Workgroup tile 256 (M) x 256 (N) or 128 x 384, K advances 256 elements per
+// iteration.  The four wavefronts split N: each owns all rows of the tile and 64
+// (96) columns -- 8 x 2 (4 x 3) MFMA tiles, 256 (192) accumulator registers -- so
+// one wave per SIMD.  The second shape has 3/4 of the area; the launcher takes it
+// when it needs fewer rounds of the 256 CUs (2048 x 6144: 256 tiles instead of 192
+// on 256 CUs).  RB = row blocks of the tile, CB = column blocks per wave.
 // With a single wave per SIMD nothing hides memory or LDS latency but the
 // software pipeline.  Every stream runs two K iterations ahead, and the loads
 // of an iteration are spread one by one between its 64 MFMAs so that no burst
@@ -35,6 +38,8 @@
 // register assignment over the whole kernel (no copy of a register whose load
 // is still in flight) and nothing spills; tests/test_build_invariants.py
 // checks both on the generated code.
+#include <stdlib.h>
+
 #include <type_traits>
 
 #include "wush_device.hpp"
@@ -44,32 +49,32 @@ namespace wush {
 
 namespace {
 
-constexpr int kTM = 256, kTN = 256;
 constexpr int kFragB = 1024;                 // one 32-row x 64-element fragment
-constexpr int kXStageB = 8 * 4 * kFragB;     // 8 row blocks x 4 issues = 32 KiB
-constexpr int kXsStageB = 8 * 256;           // 8 row blocks x 64 lanes x 4 B
 constexpr int kStages = 4;
-constexpr int kXsBase = kStages * kXStageB;
-constexpr int kLds = kStages * (kXStageB + kXsStageB);   // 136 KiB
+// ring: per stage RB row blocks x 4 issues of 1 KiB, plus RB x 64 lanes x 4 B of scales
+constexpr int lds_bytes(int RB) { return kStages * (RB * 4 * kFragB + RB * 256); }   // 136 KiB for RB = 8
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-struct WSet { v4i f[2][4]; int s[2]; };      // W fragments [column block][issue] and scale dwords
+template <int CB>
+struct WSet { v4i f[CB][4]; int s[CB]; };    // W fragments [column block][issue] and scale dwords
 
 // s_waitcnt immediate (gfx9 encoding) waiting only on vmcnt <= n.
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }
 
-// VMEM instructions one wave issues per pipelined iteration: 8 X fragment DMAs,
-// 2 X scale DMAs, 2 W scale loads, 8 W fragment loads.
-constexpr int kDmaPerIter = 10, kVmemPerIter = 20;
-
-template <bool OUT_F32>
+template <bool OUT_F32, int RB, int CB>
 __global__ __launch_bounds__(256) void gemm_frag_kernel(
     const uint8_t* __restrict__ Xq, const uint8_t* __restrict__ Xs,
     const uint8_t* __restrict__ Wq, const uint8_t* __restrict__ Ws,
-    int M, int N, int K, void* __restrict__ Y, int64_t ldy, int tiles_m, int tiles_n, int vec_store) {
+    int M, int N, int K, void* __restrict__ Y, int64_t ldy, int tiles_m, int tiles_n, int vec_store, int w_blocks) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+  constexpr int kTM = 32 * RB, kTN = 4 * 32 * CB;
+  constexpr int kUB = RB / 4;                          // row blocks of the ring each wave fills
+  constexpr int kXStageB = RB * 4 * kFragB, kXsStageB = RB * 256, kXsBase = kStages * kXStageB;
+  // VMEM instructions one wave issues per pipelined iteration: its share of the X
+  // fragments and X scales (direct to LDS), then CB x 4 W fragments and CB W scales.
+  constexpr int kDmaPerIter = 5 * kUB, kWPerIter = 5 * CB, kVmemPerIter = kDmaPerIter + kWPerIter;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps bases in SGPRs
   const int r = lane & 31, kh = lane >> 5;
@@ -97,12 +102,16 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   // Every global address is "wave-uniform 64-bit base (SGPR pair) + per-lane 32-bit
   // offset (one constant VGPR) + immediate": no vector ALU work per load.
   const int loff = 16 * lane, soff = 4 * lane;
-  // X: this wave fills row blocks 2*wave, 2*wave+1 of every ring stage.
-  const uint8_t* xsrc = Xq + (int64_t)(tm * 8 + 2 * wave) * KT * tile_step;
-  const uint8_t* xssrc = Xs + (int64_t)(tm * 8 + 2 * wave) * KT * 256;
-  // W fragments and scales of this wave's two column blocks.
-  const uint8_t* wsrc = Wq + (int64_t)(tn * 8 + 2 * wave) * KT * tile_step;
-  const uint8_t* wssrc = Ws + (int64_t)(tn * 8 + 2 * wave) * KT * 256;
+  // X: this wave fills row blocks kUB*wave .. of every ring stage.
+  const uint8_t* xsrc = Xq + (int64_t)(tm * RB + kUB * wave) * KT * tile_step;
+  const uint8_t* xssrc = Xs + (int64_t)(tm * RB + kUB * wave) * KT * 256;
+  // W fragments and scales of this wave's CB column blocks.  The packed buffers are
+  // padded to 256 rows (w_blocks blocks of 32); a 384-wide tile can reach past that,
+  // so every block index is clamped to the last block of the buffer: the load stays
+  // in bounds and the columns it feeds lie past N, which are never stored.
+  int64_t wblk[CB];
+#pragma unroll
+  for (int j = 0; j < CB; ++j) wblk[j] = min(tn * 4 * CB + CB * wave + j, w_blocks - 1);
 
   // direct-to-LDS loads of tile kt: fragment f (0..7) of this wave's two row
   // blocks, and their two scale dwords
@@ -131,16 +140,16 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   };
   auto dma_x_frag = [&](int kt, int f) {
     const int u = f >> 2, kk = f & 3;
-    dma16(xsrc + ((int64_t)u * KT + kt) * tile_step, lds_base + (kt % kStages) * kXStageB + (2 * wave + u) * 4 * kFragB, kk);
+    dma16(xsrc + ((int64_t)u * KT + kt) * tile_step, lds_base + (kt % kStages) * kXStageB + (kUB * wave + u) * 4 * kFragB, kk);
   };
   auto dma_x_scale = [&](int kt, int u) {
-    dma4(xssrc + ((int64_t)u * KT + kt) * 256, lds_base + kXsBase + (kt % kStages) * kXsStageB + (2 * wave + u) * 256);
+    dma4(xssrc + ((int64_t)u * KT + kt) * 256, lds_base + kXsBase + (kt % kStages) * kXsStageB + (kUB * wave + u) * 256);
   };
   auto dma_x = [&](int kt) {
 #pragma unroll
-    for (int f = 0; f < 8; ++f) dma_x_frag(kt, f);
-    dma_x_scale(kt, 0);
-    dma_x_scale(kt, 1);
+    for (int f = 0; f < 4 * kUB; ++f) dma_x_frag(kt, f);
+#pragma unroll
+    for (int u = 0; u < kUB; ++u) dma_x_scale(kt, u);
   };
   // W register loads are issued from asm as well, so that NO global load of the
   // main loop is visible to the compiler's vmcnt bookkeeping and every vmcnt wait
@@ -148,15 +157,15 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   // asynchronously; nothing may read them before the explicit wait at the start
   // of the iteration that consumes them (the generated code is checked for that:
   // no spill and no register copy in the loop).
-  auto load_w_scales = [&](WSet& w, int kt) {
+  auto load_w_scales = [&](WSet<CB>& w, int kt) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const uint8_t* p = wssrc + ((int64_t)j * KT + kt) * 256;
+    for (int j = 0; j < CB; ++j) {
+      const uint8_t* p = Ws + (wblk[j] * KT + kt) * 256;
       asm volatile("global_load_dword %0, %1, %2" : "=v"(w.s[j]) : "v"(soff), "s"(p));
     }
   };
-  auto load_w_frag = [&](WSet& w, int kt, int kk, int j) {
-    const uint8_t* p = wsrc + ((int64_t)j * KT + kt) * tile_step;
+  auto load_w_frag = [&](WSet<CB>& w, int kt, int kk, int j) {
+    const uint8_t* p = Wq + (wblk[j] * KT + kt) * tile_step;
     switch (kk) {
       case 0: asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
       case 1: asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024" : "=v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
@@ -171,27 +180,29 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
     return *reinterpret_cast<const int*>(smem + kXsBase + (kt % kStages) * kXsStageB + i * 256 + soff);
   };
 
-  v16f acc[8][2];
+  v16f acc[RB][CB];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < RB; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = (v16f){0};
+    for (int j = 0; j < CB; ++j) acc[i][j] = (v16f){0};
 
   // ---- prologue.  The two W register sets (and X scale sets) alternate by
   // iteration, chosen so that the LAST iteration always runs on set 0: the
   // drain code then exists in a single version.
-  WSet wset[2];
-  int xsc[2][8];
-  v4i af0[8], af1[8];
+  WSet<CB> wset[2];
+  int xsc[2][RB];
+  v4i af0[RB], af1[RB];
   const int p0 = (KT - 1) & 1;                 // set of iteration 0
-  // Issue order X0, X1, W(tile 0), X2, W(tile 1) -- the steady-state order (10 ring
-  // loads, then 10 W loads per iteration) -- so that the first barrier has to wait
+  // Issue order X0, X1, W(tile 0), X2, W(tile 1) -- the steady-state order (the
+  // ring loads, then the W loads of an iteration) -- so that the first barrier has to wait
   // for ring stages 0 and 1 only and the first MFMA for W(tile 0) only, with the
   // same in-order counts as in the loop; the rest of the lookahead lands during
   // iteration 0.  K < 768 takes no shortcut.
-  auto load_w = [&](WSet& w, int kt) {
+  auto load_w = [&](WSet<CB>& w, int kt) {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) { load_w_frag(w, kt, kk, 0); load_w_frag(w, kt, kk, 1); }
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int j = 0; j < CB; ++j) load_w_frag(w, kt, kk, j);
     load_w_scales(w, kt);
   };
   dma_x(0);
@@ -205,107 +216,110 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
     if (KT > 2) dma_x(2);
     load_w(wset[0], 1);
   }
-  if (KT > 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmemPerIter - kDmaPerIter + kVmemPerIter));
+  if (KT > 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kWPerIter + kVmemPerIter));
   else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   __builtin_amdgcn_sched_barrier(0);
   asm volatile("s_barrier");
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
+  for (int i = 0; i < RB; ++i) {
     af0[i] = read_x_frag(0, 0, i);
     af1[i] = read_x_frag(0, 1, i);
   }
   if (p0 == 0) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) xsc[0][i] = read_x_scale(0, i);
+    for (int i = 0; i < RB; ++i) xsc[0][i] = read_x_scale(0, i);
   } else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) xsc[1][i] = read_x_scale(0, i);
+    for (int i = 0; i < RB; ++i) xsc[1][i] = read_x_scale(0, i);
   }
 
   // One K iteration on tile kt with W set w and X scales xs (af0, af1 already
   // hold its issue-0 and issue-1 operands).  Flags say which streams still have
   // work: PFX = tile kt+3 exists (X ring), PFW = tile kt+2 exists (W registers),
   // NEXT = tile kt+1 exists (its first operands and scales are read here).
-  // Each slot = MFMA, one LDS read, MFMA, at most one global load: the read sits
-  // in the shadow of the first MFMA and the load in the shadow of the second.
-#define WUSH_MMA_A(KK, AF, i)                                                                                  \
+  // Each slot = MFMA, one LDS read, MFMA, at most one global load (, MFMA): the read
+  // sits in the shadow of the first MFMA and the load in the shadow of the second.
+#define WUSH_MMA(KK, AF, i, j)                                                                                 \
   {                                                                                                            \
     const v8i A_ = {AF[i][0], AF[i][1], AF[i][2], AF[i][3], 0, 0, 0, 0};                                       \
-    const v8i B0_ = {w.f[0][KK][0], w.f[0][KK][1], w.f[0][KK][2], w.f[0][KK][3], 0, 0, 0, 0};                  \
-    acc[i][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B0_, A_, acc[i][0], 4, 4, KK, w.s[0], KK, xs[i]); \
+    const v8i B_ = {w.f[j][KK][0], w.f[j][KK][1], w.f[j][KK][2], w.f[j][KK][3], 0, 0, 0, 0};                   \
+    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B_, A_, acc[i][j], 4, 4, KK, w.s[j], KK, xs[i]); \
   }
-#define WUSH_MMA_B(KK, AF, i)                                                                                  \
-  {                                                                                                            \
-    const v8i A_ = {AF[i][0], AF[i][1], AF[i][2], AF[i][3], 0, 0, 0, 0};                                       \
-    const v8i B1_ = {w.f[1][KK][0], w.f[1][KK][1], w.f[1][KK][2], w.f[1][KK][3], 0, 0, 0, 0};                  \
-    acc[i][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B1_, A_, acc[i][1], 4, 4, KK, w.s[1], KK, xs[i]); \
+#define WUSH_MMA_REST(KK, AF, i)                   \
+  if (CB > 2) {                                    \
+    WUSH_FENCE                                     \
+    WUSH_MMA(KK, AF, i, CB - 1)                    \
   }
 #define WUSH_FENCE __builtin_amdgcn_sched_barrier(0);
-  auto iteration = [&](int kt, WSet& w, const int (&xs)[8], int (&xs_next)[8], auto pfx_tag, auto pfw_tag,
+  auto iteration = [&](int kt, WSet<CB>& w, const int (&xs)[RB], int (&xs_next)[RB], auto pfx_tag, auto pfw_tag,
                        auto next_tag) {
     constexpr bool PFX = decltype(pfx_tag)::value, PFW = decltype(pfw_tag)::value, NEXT = decltype(next_tag)::value;
     // W fragments and scales of tile kt were issued two iterations ago; the last of
     // them (the scales) is followed by exactly the operations of the previous
-    // iteration: 20 when that one prefetched X and W, 10 when only W, else 0.
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(PFW ? kVmemPerIter : (NEXT ? kVmemPerIter - kDmaPerIter : 0)));
+    // iteration: its ring loads if tile kt+2 exists, its W loads if tile kt+1 exists.
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(PFW ? kVmemPerIter : (NEXT ? kWPerIter : 0)));
     WUSH_FENCE
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {            // issue 0: X ring refill, operands of issue 2
-      WUSH_MMA_A(0, af0, i)
+    for (int i = 0; i < RB; ++i) {           // issue 0: X ring refill, operands of issue 2
+      WUSH_MMA(0, af0, i, 0)
       const v4i nx_ = read_x_frag(kt, 2, i);
       WUSH_FENCE
-      WUSH_MMA_B(0, af0, i)
-      if (PFX) dma_x_frag(kt + 3, i);
+      WUSH_MMA(0, af0, i, 1)
+      if (PFX && i < 4 * kUB) dma_x_frag(kt + 3, i);
+      WUSH_MMA_REST(0, af0, i)
       af0[i] = nx_;
       WUSH_FENCE
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {            // issue 1: X scales, W fragments of issue 0, operands of issue 3
-      WUSH_MMA_A(1, af1, i)
+    for (int i = 0; i < RB; ++i) {           // issue 1: X scales, W fragments of issue 0, operands of issue 3
+      WUSH_MMA(1, af1, i, 0)
       const v4i nx_ = read_x_frag(kt, 3, i);
       WUSH_FENCE
-      WUSH_MMA_B(1, af1, i)
-      if (PFX && i < 2) dma_x_scale(kt + 3, i);
-      if (PFW && (i == 2 || i == 3)) load_w_frag(w, kt + 2, 0, i - 2);
+      WUSH_MMA(1, af1, i, 1)
+      if (PFX && i < kUB) dma_x_scale(kt + 3, i);
+      if (PFW && i >= kUB && i < kUB + CB) load_w_frag(w, kt + 2, 0, i - kUB);
+      WUSH_MMA_REST(1, af1, i)
       af1[i] = nx_;
       WUSH_FENCE
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {            // issue 2: W fragments of issue 1, next tile's issue-0 operands
-      WUSH_MMA_A(2, af0, i)
+    for (int i = 0; i < RB; ++i) {           // issue 2: W fragments of issue 1, next tile's issue-0 operands
+      WUSH_MMA(2, af0, i, 0)
       v4i nx_ = af0[i];
       if (NEXT) nx_ = read_x_frag(kt + 1, 0, i);
       WUSH_FENCE
-      WUSH_MMA_B(2, af0, i)
-      if (PFW && i < 2) load_w_frag(w, kt + 2, 1, i);
+      WUSH_MMA(2, af0, i, 1)
+      if (PFW && i < CB) load_w_frag(w, kt + 2, 1, i);
+      WUSH_MMA_REST(2, af0, i)
       af0[i] = nx_;
       WUSH_FENCE
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {            // issue 3: W fragments of issue 2, next tile's issue-1 operands, scales
-      WUSH_MMA_A(3, af1, i)
+    for (int i = 0; i < RB; ++i) {           // issue 3: W fragments of issue 2, next tile's issue-1 operands, scales
+      WUSH_MMA(3, af1, i, 0)
       v4i nx_ = af1[i];
       if (NEXT) {
         nx_ = read_x_frag(kt + 1, 1, i);
         xs_next[i] = read_x_scale(kt + 1, i);
       }
       WUSH_FENCE
-      WUSH_MMA_B(3, af1, i)
-      if (PFW && i < 2) load_w_frag(w, kt + 2, 2, i);
+      WUSH_MMA(3, af1, i, 1)
+      if (PFW && i < CB) load_w_frag(w, kt + 2, 2, i);
+      WUSH_MMA_REST(3, af1, i)
       af1[i] = nx_;
       WUSH_FENCE
     }
     if (PFW) {
-      load_w_frag(w, kt + 2, 3, 0);
-      load_w_frag(w, kt + 2, 3, 1);
+#pragma unroll
+      for (int j = 0; j < CB; ++j) load_w_frag(w, kt + 2, 3, j);
       load_w_scales(w, kt + 2);
     }
     // Ring stage kt+2 (this wave's share, issued during iteration kt-1) must have
     // landed before the barrier publishes it; vmcnt retires in order, and since
-    // that share the wave issued the 10 W loads of iteration kt-1 and all 20
+    // that share the wave issued the W loads of iteration kt-1 and all the
     // memory instructions of this one.
-    if (PFX) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmemPerIter - kDmaPerIter + kVmemPerIter));
+    if (PFX) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kWPerIter + kVmemPerIter));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     WUSH_FENCE
     // A bare s_barrier: __syncthreads() carries a workgroup fence for which the
@@ -338,34 +352,36 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   if (KT >= 3) iteration(KT - 3, wset[0], xsc[0], xsc[1], F{}, T{}, T{});
   if (KT >= 2) iteration(KT - 2, wset[1], xsc[1], xsc[0], F{}, F{}, T{});
   iteration(KT - 1, wset[0], xsc[0], xsc[1], F{}, F{}, F{});
-#undef WUSH_MMA_A
-#undef WUSH_MMA_B
+#undef WUSH_MMA
+#undef WUSH_MMA_REST
 #undef WUSH_FENCE
   __builtin_amdgcn_sched_barrier(0);
 
   // ---- epilogue.  The W fragment is the MFMA's first operand, so a tile of D is
   // (32 output columns) x (32 tokens): lane (r, kh) of MFMA tile (i, j) holds token
   // row 32*i + r, and its accumulator e is output column
-  // 64*wave + 32*j + 8*(e/4) + 4*kh + e%4 -- four consecutive columns per e/4.
+  // 32*CB*wave + 32*j + 8*(e/4) + 4*kh + e%4 -- four consecutive columns per e/4.
   if (!OUT_F32 && vec_store) {
     // BF16, 16-byte-aligned rows.  Four consecutive columns = two packed converts =
-    // one 8-byte LDS write; a wave-private LDS image of 32 rows x 64 columns is read
-    // back as 16 bytes per lane so that a store instruction writes 8 full 128-byte
-    // row segments.  Row pitch 144 B: the 8-byte writes of a wave (pitch 36 dwords,
-    // +2 dwords for the upper lane half) hit every bank 4 times and the 16-byte
-    // reads every 4-bank group 8 times, both the minimum.  The ring is free after
-    // the last barrier; each wave uses a private double buffer, so no barrier.
+    // one 8-byte LDS write; a wave-private LDS image of 32 rows x 32*CB columns is
+    // read back as 16 bytes per lane so that the stores cover whole row segments
+    // (128 or 192 bytes).  Row pitch = segment + 16 B (144 / 208): the 8-byte writes
+    // of a wave (pitch 36 / 52 dwords, +2 dwords for the upper lane half) hit every
+    // bank 4 times, the minimum.  The ring is free after the last barrier; each wave
+    // uses a private double buffer, so no barrier.
     typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
     typedef float v2f __attribute__((ext_vector_type(2)));
-    constexpr int kPitch = 144, kBuf = 32 * kPitch;
+    constexpr int kChunks = 4 * CB;                       // 16-byte chunks per row segment
+    constexpr int kPitch = 16 * kChunks + 16, kBuf = 32 * kPitch;
+    static_assert(4 * 2 * kBuf <= lds_bytes(RB), "transpose buffers must fit in the ring");
     uint8_t* area = smem + wave * (2 * kBuf);
     uint16_t* Yb = reinterpret_cast<uint16_t*>(Y);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < RB; ++i) {
       __builtin_amdgcn_sched_barrier(0);
       uint8_t* buf = area + (i & 1) * kBuf;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < CB; ++j) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const v2bf lo = __builtin_convertvector((v2f){acc[i][j][4 * q], acc[i][j][4 * q + 1]}, v2bf);
@@ -377,12 +393,13 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
         }
       }
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const int row_l = (lane >> 3) + 8 * p;
-        const int chunk = lane & 7;
+      for (int p = 0; p < 2 * CB; ++p) {                  // 32 rows x kChunks chunks, 64 per round
+        const int idx = 64 * p + lane;
+        const int row_l = idx / kChunks;
+        const int chunk = idx % kChunks;
         const v4i v = *reinterpret_cast<const v4i*>(buf + row_l * kPitch + 16 * chunk);
         const int row = m0 + 32 * i + row_l;
-        const int col = n0 + 64 * wave + 8 * chunk;
+        const int col = n0 + 32 * CB * wave + 8 * chunk;
         // streaming store: the output is not read again by this kernel, and lines that
         // leave the L2 as they are written shorten the write-back at the kernel's end
         if (row < M && col < N) __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(Yb + (int64_t)row * ldy + col));
@@ -391,15 +408,15 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
     return;
   }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
+  for (int i = 0; i < RB; ++i) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < CB; ++j) {
       __builtin_amdgcn_sched_barrier(0);   // one MFMA tile at a time: keeps the epilogue out of scratch
       const int row = m0 + 32 * i + r;
       if (row < M) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int col = n0 + 64 * wave + 32 * j + 8 * (e >> 2) + 4 * kh + (e & 3);
+          const int col = n0 + 32 * CB * wave + 32 * j + 8 * (e >> 2) + 4 * kh + (e & 3);
           if (col < N) {
             if (OUT_F32) reinterpret_cast<float*>(Y)[(int64_t)row * ldy + col] = acc[i][j][e];
             else reinterpret_cast<uint16_t*>(Y)[(int64_t)row * ldy + col] = f32_to_bf16_bits(acc[i][j][e]);
@@ -410,30 +427,52 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   }
 }
 
+template <bool OUT_F32, int RB, int CB>
+hipError_t launch_shape(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M, int64_t N, int64_t K,
+                        void* Y, int64_t ldy, hipStream_t stream) {
+  constexpr int kLds = lds_bytes(RB);
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_frag_kernel<OUT_F32, RB, CB>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  if (attr != hipSuccess) return attr;
+  constexpr int kTM = 32 * RB, kTN = 4 * 32 * CB;
+  const int tiles_m = (int)((M + kTM - 1) / kTM), tiles_n = (int)((N + kTN - 1) / kTN);
+  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+  // 128-bit stores need whole 8-column chunks at 16-byte aligned addresses
+  const int vec_store = (N % 8 == 0) && (ldy % 8 == 0) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
+  const int w_blocks = (int)((N + 255) / 256 * 8);   // 32-row blocks the packed W buffers hold
+  gemm_frag_kernel<OUT_F32, RB, CB><<<grid, block, kLds, stream>>>(
+      (const uint8_t*)Xq, (const uint8_t*)Xs, (const uint8_t*)Wq, (const uint8_t*)Ws, (int)M, (int)N, (int)K, Y, ldy,
+      tiles_m, tiles_n, vec_store, w_blocks);
+  return hipGetLastError();
+}
+
+// Rounds of the chip a tile shape needs, weighted by the MFMAs one of its K iterations
+// issues per wave (64 for 256 x 256, 48 for 128 x 384).
+int64_t shape_cost(int64_t M, int64_t N, int tm, int tn, int mfma_per_iter, int cus) {
+  const int64_t tiles = ((M + tm - 1) / tm) * ((N + tn - 1) / tn);
+  return (tiles + cus - 1) / cus * mfma_per_iter;
+}
+
 }  // namespace
 
 hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
                                   int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
                                   hipStream_t stream) {
-  static const hipError_t attr = [] {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_frag_kernel<false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_frag_kernel<true>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  static const int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
+    return n;
   }();
-  if (attr != hipSuccess) return attr;
-  const int tiles_m = (int)((M + kTM - 1) / kTM), tiles_n = (int)((N + kTN - 1) / kTN);
-  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
-  // 128-bit stores need whole 8-column chunks at 16-byte aligned addresses
-  const int vec_store = (N % 8 == 0) && (ldy % 8 == 0) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
-  if (out_f32)
-    gemm_frag_kernel<true><<<grid, block, kLds, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, (const uint8_t*)Wq,
-                                                      (const uint8_t*)Ws, (int)M, (int)N, (int)K, Y, ldy, tiles_m, tiles_n, vec_store);
-  else
-    gemm_frag_kernel<false><<<grid, block, kLds, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, (const uint8_t*)Wq,
-                                                       (const uint8_t*)Ws, (int)M, (int)N, (int)K, Y, ldy, tiles_m, tiles_n, vec_store);
-  return hipGetLastError();
+  // WUSH_GEMM_TILE=256x256 / 128x384 forces a shape (debug knob).
+  bool narrow = shape_cost(M, N, 128, 384, 48, cus) < shape_cost(M, N, 256, 256, 64, cus);
+  if (const char* e = getenv("WUSH_GEMM_TILE")) narrow = e[0] == '1';
+  if (narrow) {
+    if (out_f32) return launch_shape<true, 4, 3>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
+    return launch_shape<false, 4, 3>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
+  }
+  if (out_f32) return launch_shape<true, 8, 2>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
+  return launch_shape<false, 8, 2>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
 }
 
 }  // namespace wush

@@ -3,8 +3,9 @@ express: its main-loop global loads are issued from inline asm with explicit
 vmcnt waits, so the compiler does not know that their destination registers are
 written asynchronously.  That is only safe while (a) nothing in the kernel
 spills to scratch and (b) every register of the two W sets has ONE physical
-assignment in the whole kernel (16 fragment tuples + 4 scale registers, each
-loaded at the same number of code sites) -- a second assignment would mean a
+assignment in the whole kernel (2 sets x CB x 4 fragment tuples + 2 x CB scale
+registers for the tile shape with CB column blocks per wave, each loaded at the
+same number of code sites) -- a second assignment would mean a
 register copy that may read a tuple whose load is still in flight.
 The test compiles the kernel to gfx950 assembly (no GPU needed) and checks both.
 """
@@ -41,15 +42,22 @@ def _kernels(text):
     return {parts[i]: parts[i + 1].split("s_endpgm")[0] for i in range(1, len(parts) - 1, 2)}
 
 
+def _shape(name):
+    """(RB, CB) from the mangled template arguments ...ILb<f32>ELi<RB>ELi<CB>E..."""
+    m = re.search(r"ILb[01]ELi(\d+)ELi(\d+)E", name)
+    return int(m.group(1)), int(m.group(2))
+
+
 def test_no_scratch_and_single_register_assignment(asm_text):
     kernels = _kernels(asm_text)
-    assert len(kernels) == 2, list(kernels)
+    assert len(kernels) == 4, list(kernels)
     for name, body in kernels.items():
+        RB, CB = _shape(name)
         assert "scratch_" not in body, f"{name}: spills to scratch"
         frag = Counter(re.findall(r"global_load_dwordx4 (v\[\d+:\d+\])", body))
         scale = Counter(re.findall(r"global_load_dword (v\d+),", body))
-        assert len(frag) == 16, (name, sorted(frag))
-        assert len(scale) == 4, (name, sorted(scale))
+        assert len(frag) == 2 * CB * 4, (name, sorted(frag))
+        assert len(scale) == 2 * CB, (name, sorted(scale))
         assert len(set(frag.values())) == 1 and len(set(scale.values())) == 1, (name, frag, scale)
         # the 16 tuples are disjoint
         regs = [r for t in frag for r in range(*map(int, re.match(r"v\[(\d+):(\d+)\]", t).groups()))]
@@ -62,6 +70,7 @@ def test_main_loop_waits_are_explicit(asm_text):
         m = re.search(r"Inner Loop Header.*?s_cbranch_scc1", body, flags=re.S)
         assert m, name
         loop = m.group(0)
-        assert loop.count("v_mfma_scale_f32_32x32x64_f8f6f4") == 128, name     # two K iterations
+        RB, CB = _shape(name)
+        assert loop.count("v_mfma_scale_f32_32x32x64_f8f6f4") == 2 * 4 * RB * CB, name     # two K iterations
         assert "vmcnt(0)" not in loop and "lgkmcnt(0)" not in loop, name
         assert loop.count("s_barrier") == 2, name
