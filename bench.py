@@ -12,6 +12,9 @@ Prints ONE JSON line:
              the transform+quantize kernel) against the MI355X peak, with its
              average launch duration measured by HIP events on the launch stream
   cpu_baseline  the CPU oracle's layer forward timed on this machine's host cores
+  ceilings   measured on the spot: the GEMM's MFMA instruction alone on all CUs (with the
+             workload's own operand bits, and with all-equal operands), the shader clock
+             under each, and a plain 1 GiB device copy
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|d2|d5]
 
@@ -88,6 +91,41 @@ def cpu_baseline(cfg, T_bits, L, budget_rows):
                           f"{cfg.N} output channels, full K, weights pre-quantized"}
     return {"value": quant_bytes(rows, cfg.K) / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
             "seconds": dt, "sample": f"oracle transform+quantize on the first {rows} of {cfg.M} tokens"}
+
+
+def measured_ceilings(P, torch, dev, x_bits, w_bits):
+    """What this machine sustains, measured now: the GEMM's MFMA instruction in a register-only loop on all
+    CUs (wush_probe_mfma) with the workload's own operand bits and with all-equal operands, the shader
+    clock during each, and a plain 1 GiB device copy."""
+    props = torch.cuda.get_device_properties(dev)
+    cus = props.multi_processor_count
+    out = {"compute_units": cus}
+    ticks = torch.zeros((cus, 2), dtype=torch.int64, device=dev)
+    iters = 2000
+    flop_per_wg = 4.0 * iters * 64 * 2 * 32 * 32 * 64
+    real = torch.cat([x_bits[:8192], w_bits[:8192]]).contiguous()
+    equal = torch.full((16384,), 0x22, dtype=torch.uint8, device=dev)
+    for name, bits in (("workload_bits", real), ("equal_operands", equal)):
+        for _ in range(2):
+            P.wush_probe_mfma(bits, iters, cus, ticks)
+        torch.cuda.synchronize()
+        t = ticks.cpu().numpy().astype(np.float64)
+        ns = t[:, 1].mean() * 10.0
+        out[f"mfma_only_{name}_tflops"] = cus * flop_per_wg / ns / 1e3
+        out[f"sclk_ghz_{name}"] = float((t[:, 0] / (t[:, 1] * 10.0)).mean())
+        out[f"cycles_per_mfma_{name}"] = float(t[:, 0].mean() / (iters * 64))
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    out["copy_1gib_gbs"] = 5 * 2.0 * (1 << 30) / e0.elapsed_time(e1) / 1e6
+    del src, dst
+    return out
 
 
 def decode_bench(args, P, torch, dev):
@@ -180,6 +218,8 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured graph of the timed steps instead of launching every step from the host "
                          "(measured slower for c2: 40.1 against 38.0 us per step)")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the live measurement of the MFMA-only and copy ceilings of this box")
     ap.add_argument("--cold", type=int, default=0,
                     help="rotate over this many input/output buffer sets (>1 defeats the 256 MB last-level cache)")
     args = ap.parse_args()
@@ -321,6 +361,11 @@ def main():
                    "launch": "graph replay of the timed steps" if args.graph else "host loop"},
         "roofline": roof, "kernels": kernels,
     }
+    if not args.no_ceilings:
+        ceil = measured_ceilings(P, torch, dev, Xq[0], Wq if N else Xq[0])
+        out["ceilings"] = ceil
+        if N:
+            roof["frac_of_measured_mfma_ceiling"] = roof["achieved"] / ceil["mfma_only_workload_bits_tflops"]
     if not args.no_cpu_baseline:
         rows = {"c2": 2048, "c3": 256, "c4": 2048, "c5": 64}[args.workload]
         out["cpu_baseline"] = cpu_baseline(cfg, T_bits, L, rows)

@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     wush_prepare_weight_gptq_status,
     wush_prepare_weight_gptq_workspace,
     wush_prepare_weight_workspace,
+    wush_probe_mfma,
     wush_quantize_act,
     wush_quantize_f32,
     wush_status_string,
@@ -39,4 +40,5 @@ __all__ = [
     "wush_build_transforms_status", "wush_build_transforms_workspace", "wush_layer_decode",
     "wush_layer_decode_init", "wush_layer_decode_status", "wush_layer_decode_workspace",
     "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_status", "wush_prepare_weight_gptq_workspace",
+    "wush_probe_mfma",
 ]

@@ -32,6 +32,7 @@ EXPORTS = (
     "wush_build_transforms", "wush_build_transforms_workspace", "wush_build_transforms_status",
     "wush_layer_decode", "wush_layer_decode_workspace", "wush_layer_decode_init", "wush_layer_decode_status",
     "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_workspace", "wush_prepare_weight_gptq_status",
+    "wush_probe_mfma",
 )
 
 
@@ -112,6 +113,8 @@ def lib() -> ctypes.CDLL:
                                                c_void_p]
         L.wush_prepare_weight_gptq_status.restype = c_int32
         L.wush_prepare_weight_gptq_status.argtypes = [c_void_p, c_int64, c_int64, c_void_p]
+        L.wush_probe_mfma.restype = c_int32
+        L.wush_probe_mfma.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
         _lib = L
     return _lib
 
@@ -268,3 +271,9 @@ def wush_prepare_weight_gptq(W, X_cal, lam: float, T_blocks, Wq, Ws, workspace, 
 def wush_prepare_weight_gptq_status(workspace, N: int, K: int, stream=None):
     _check(lib().wush_prepare_weight_gptq_status(_ptr(workspace), N, K, _stream(stream)),
            "wush_prepare_weight_gptq_status")
+
+
+def wush_probe_mfma(operand_bits, iters: int, blocks: int, cycles_ticks, stream=None):
+    """MFMA-only ceiling probe: operand_bits u8 [16384], cycles_ticks int64 [blocks][2] (both on the GPU)."""
+    _check(lib().wush_probe_mfma(_ptr(operand_bits), iters, blocks, _ptr(cycles_ticks), _stream(stream)),
+           "wush_probe_mfma")

@@ -238,6 +238,13 @@ wush_status wush_layer_decode_status(const void* workspace, int64_t K, void* str
   return flag ? WUSH_ERR_TIMEOUT : WUSH_OK;
 }
 
+wush_status wush_probe_mfma(const void* operand_bits, int32_t iters, int32_t blocks, void* cycles_ticks, void* stream) {
+  if (!operand_bits || !cycles_ticks) return WUSH_ERR_NULL;
+  if (iters <= 0 || iters > (1 << 20) || blocks <= 0 || blocks > 4096) return WUSH_ERR_SHAPE;
+  if (!aligned16(operand_bits) || !aligned16(cycles_ticks)) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_mfma_probe(operand_bits, iters, blocks, cycles_ticks, static_cast<hipStream_t>(stream)));
+}
+
 wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fmt, void* q, void* s,
                               void* stream) {
   if (!Yt || !q || !s) return WUSH_ERR_NULL;

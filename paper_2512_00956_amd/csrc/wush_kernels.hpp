@@ -61,4 +61,7 @@ hipError_t launch_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx,
                                const void* Ws, int64_t N, int rule, int out_f32, void* Y, int64_t ldy,
                                void* workspace, int test_timeout, hipStream_t stream);
 
+// Measurement aid: register-only loop of the block-scaled FP4 MFMA (4 waves per workgroup, 64 MFMAs per trip).
+hipError_t launch_mfma_probe(const void* operand_bits, int iters, int blocks, void* out, hipStream_t stream);
+
 }  // namespace wush

@@ -154,3 +154,10 @@ def test_layer_decode_validation(L):
     assert L.wush_layer_decode_init(None, need, 512, None) == 1
     assert L.wush_layer_decode_init(B, need - 1, 512, None) == 5
     assert L.wush_layer_decode_status(None, 512, None) == 1
+
+
+def test_probe_validation(L):
+    assert L.wush_probe_mfma(None, 10, 4, A, None) == 1
+    assert L.wush_probe_mfma(A, 0, 4, A, None) == 2
+    assert L.wush_probe_mfma(A, 10, 5000, A, None) == 2
+    assert L.wush_probe_mfma(A + 4, 10, 4, A, None) == 3
