@@ -204,7 +204,8 @@ wush_status wush_prepare_weight_gptq_status(const void* workspace, int64_t N, in
  *                 nearest even from the FP32 accumulator) or f32
  * ldy >= N (elements); Y aligned to its element size.  The tiled kernel needs
  * Y 16-byte aligned and ldy a multiple of 8; other layouts take a slower
- * general kernel.  In the tiled layout M <= 64 takes a weight-streaming kernel
+ * general kernel.  In the tiled layout M <= 64 (and M <= 128 unless the layer is
+ * very large) takes a weight-streaming kernel
  * (one workgroup per 32 output channels) instead of 256 x 256 tiles.
  */
 wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const void* Ws,

@@ -1,7 +1,7 @@
 // Decode-sized layer forward (at most 64 tokens) for gfx950:
 //   Y = sum_i Wq(i)^T q(T(i) X(i))      (layer forward-pass equation)
 // with the weights already transformed and quantized, in two forms:
-//   * gemm_skinny_kernel: the MXFP4 GEMM alone for M <= 64 (wush_linear);
+//   * gemm_skinny_kernel: the MXFP4 GEMM alone for M <= 128 (wush_linear);
 //   * layer_decode_kernel: activation transform + quantization + GEMM in ONE
 //     launch (wush_layer_decode).
 // At these sizes the layer is bound by streaming the weights once (K/2 + K/32
@@ -68,7 +68,7 @@ __device__ __forceinline__ void load_frag_tile(FragTile& t, const uint8_t* __res
 }
 
 // K tiles a wave keeps in flight at once (its loads are issued together, then
-// consumed): 4 for up to 32 tokens, 2 for 33..64 (twice the X registers).
+// consumed): 4 for up to 32 tokens, 2 beyond (the X registers grow with the token blocks).
 template <int RB>
 struct Depth { static constexpr int U = RB == 1 ? 4 : 2; };
 
@@ -342,8 +342,10 @@ hipError_t launch_mxfp4_gemm_skinny(const void* Xq, const void* Xs, const void* 
                                                           (int)N, (int)K, Y, ldy, vec)
   if (M <= 32) {
     if (out_f32) WUSH_SKINNY_LAUNCH(1, true); else WUSH_SKINNY_LAUNCH(1, false);
-  } else {
+  } else if (M <= 64) {
     if (out_f32) WUSH_SKINNY_LAUNCH(2, true); else WUSH_SKINNY_LAUNCH(2, false);
+  } else {
+    if (out_f32) WUSH_SKINNY_LAUNCH(4, true); else WUSH_SKINNY_LAUNCH(4, false);
   }
 #undef WUSH_SKINNY_LAUNCH
   return hipGetLastError();

@@ -257,8 +257,20 @@ hipError_t launch_mxfp4_gemm(const void* Xq, const void* Xs, const void* Wq, con
                              int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y, int64_t ldy,
                              hipStream_t stream) {
   if (tiled) {
-    // Decode-sized batches stream the weights once instead of padding M to a 256-row tile.
-    if (M <= 64) return launch_mxfp4_gemm_skinny(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
+    // Small batches stream the weights once instead of padding M to a 128- or 256-row tile.
+    // Up to 64 tokens always; for 65..128 the streaming kernel runs at about 3.1 TB/s of packed
+    // weights (it re-reads four token blocks of activations per weight tile), so a layer big
+    // enough to fill the CUs with 128 x 384 tiles in one round is faster there
+    // (8192 x 57344: 57 against 79 us; 4096 x 6144: 17.6 against 7.2 us).
+    bool skinny = M <= 64;
+    if (!skinny && M <= 128) {
+      const double weight_mib = (double)N * (double)K * (17.0 / 32.0) / 1048576.0;
+      const double skinny_us = weight_mib / 3.1 + 4.0;
+      const double rounds = (double)(((N + 383) / 384 + 255) / 256);
+      const double tiled_us = rounds * (double)(K / 256) * 1.45 + 8.0;
+      skinny = skinny_us < tiled_us;
+    }
+    if (skinny) return launch_mxfp4_gemm_skinny(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
     return launch_mxfp4_gemm_frag(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
   }
   // Debug knob: WUSH_GEMM=simple forces the general kernel.

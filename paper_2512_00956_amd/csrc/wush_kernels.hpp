@@ -47,7 +47,7 @@ hipError_t launch_gptq_prep(const void* W, int64_t N, int64_t K, int64_t ldw, co
                             double lambda, int transform_given, int rule, int tiled, void* T_blocks, void* Wq, void* Ws,
                             void* workspace, hipStream_t stream);
 
-// Decode-sized paths (M <= 64, fragment-order operands).
+// Decode-sized paths (GEMM: M <= 128; fused layer: M <= 64; fragment-order operands).
 hipError_t launch_mxfp4_gemm_skinny(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M,
                                     int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy, hipStream_t stream);
 // workspace layout: Xq for 64 tokens | Xs | barrier words (generation, error flag, arrival and release slots).

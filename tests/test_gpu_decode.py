@@ -85,6 +85,19 @@ def test_skinny_gemm_against_oracle(P, G, M, K, N):
     assert O.rel_fro(O.bf16_bits_to_f64(G.host(Yb)), ref) <= 2e-3
 
 
+@pytest.mark.parametrize("M,K,N", [(65, 512, 96), (100, 1280, 200), (128, 4096, 6144)])
+def test_skinny_gemm_up_to_128_tokens(P, G, M, K, N):
+    """65..128 tokens still take the weight-streaming kernel (four token blocks per workgroup)."""
+    S = _prepared_layer(P, G, M, K, N)
+    Yf, xq, xs = _two_call(P, G, S, M, K, N, 1)
+    Yb, _, _ = _two_call(P, G, S, M, K, N, 0)
+    ref = O.dequantize(O.unpack_codes(xq), xs) @ O.dequantize(O.unpack_codes(S["wq"]), S["ws"]).T
+    yf = G.host(Yf).astype(np.float64)
+    assert np.isfinite(yf).all()
+    assert O.rel_fro(yf, ref) <= 1e-5
+    assert np.array_equal(O.bf16_bits_to_f64(G.host(Yb)), O.round_to_bf16(yf))
+
+
 def test_skinny_gemm_every_m(P, G):
     """Every M from 1 to 64 gives the rows of the M = 64 result (each token is independent)."""
     import torch
