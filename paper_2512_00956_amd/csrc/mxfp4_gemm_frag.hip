@@ -2,7 +2,7 @@
 // wush_device.hpp: Y = deq(Xq,Xs) . deq(Wq,Ws)^T (the layer forward-pass
 // equation summed over all blocks), v_mfma_scale_f32_32x32x64_f8f6f4.
 //
-// Workgroup tile 256 (M) x 256 (N) or 128 x 384, K advances 256 elements per
+// Workgroup tile 256 (M) x 256 (N), 128 x 384 or 128 x 256, K advances 256 elements per
 // iteration.  The four wavefronts split N: each owns all rows of the tile and 64
 // (96) columns -- 8 x 2 (4 x 3) MFMA tiles, 256 (192) accumulator registers -- so
 // one wave per SIMD.  The second shape has 3/4 of the area; the launcher takes it
@@ -464,12 +464,22 @@ hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
     return n;
   }();
-  // WUSH_GEMM_TILE=256x256 / 128x384 forces a shape (debug knob).
-  bool narrow = shape_cost(M, N, 128, 384, 48, cus) < shape_cost(M, N, 256, 256, 64, cus);
-  if (const char* e = getenv("WUSH_GEMM_TILE")) narrow = e[0] == '1';
-  if (narrow) {
+  // Three instantiations: 256 x 256 (8 x 2 MFMA tiles per wave), 128 x 384 (4 x 3) and 128 x 256 (4 x 2).
+  // The cheapest by "rounds of the CUs x MFMAs per K iteration" wins, ties go to the larger tile
+  // (less operand traffic).  WUSH_GEMM_TILE=0 / 1 / 2 forces one of them (debug knob).
+  const int64_t cost[3] = {shape_cost(M, N, 256, 256, 64, cus), shape_cost(M, N, 128, 384, 48, cus),
+                           shape_cost(M, N, 128, 256, 32, cus)};
+  int shape = 0;
+  if (cost[1] < cost[shape]) shape = 1;
+  if (cost[2] < cost[shape]) shape = 2;
+  if (const char* e = getenv("WUSH_GEMM_TILE")) shape = e[0] == '1' ? 1 : (e[0] == '2' ? 2 : 0);
+  if (shape == 1) {
     if (out_f32) return launch_shape<true, 4, 3>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
     return launch_shape<false, 4, 3>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
+  }
+  if (shape == 2) {
+    if (out_f32) return launch_shape<true, 4, 2>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
+    return launch_shape<false, 4, 2>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
   }
   if (out_f32) return launch_shape<true, 8, 2>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
   return launch_shape<false, 8, 2>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
