@@ -2,8 +2,8 @@
 // wush_device.hpp: Y = deq(Xq,Xs) . deq(Wq,Ws)^T (the layer forward-pass
 // equation summed over all blocks), v_mfma_scale_f32_32x32x64_f8f6f4.
 //
-// Workgroup tile 256 (M) x 256 (N), 128 x 384 or 128 x 256, K advances 256 elements per
-// iteration.  The four wavefronts split N: each owns all rows of the tile and 64
+// Workgroup tile 256 (M) x 256 (N), 128 x 384, 128 x 256 or 128 x 128, K advances 256
+// elements per iteration.  The four wavefronts split N: each owns all rows of the tile and 64
 // (96) columns -- 8 x 2 (4 x 3) MFMA tiles, 256 (192) accumulator registers -- so
 // one wave per SIMD.  The second shape has 3/4 of the area; the launcher takes it
 // when it needs fewer rounds of the 256 CUs (2048 x 6144: 256 tiles instead of 192
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
       WUSH_MMA(0, af0, i, 0)
       const v4i nx_ = read_x_frag(kt, 2, i);
       WUSH_FENCE
-      WUSH_MMA(0, af0, i, 1)
+      if (CB > 1) WUSH_MMA(0, af0, i, 1)
       if (PFX && i < 4 * kUB) dma_x_frag(kt + 3, i);
       WUSH_MMA_REST(0, af0, i)
       af0[i] = nx_;
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
       WUSH_MMA(1, af1, i, 0)
       const v4i nx_ = read_x_frag(kt, 3, i);
       WUSH_FENCE
-      WUSH_MMA(1, af1, i, 1)
+      if (CB > 1) WUSH_MMA(1, af1, i, 1)
       if (PFX && i < kUB) dma_x_scale(kt + 3, i);
       if (PFW && i >= kUB && i < kUB + CB) load_w_frag(w, kt + 2, 0, i - kUB);
       WUSH_MMA_REST(1, af1, i)
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
       v4i nx_ = af0[i];
       if (NEXT) nx_ = read_x_frag(kt + 1, 0, i);
       WUSH_FENCE
-      WUSH_MMA(2, af0, i, 1)
+      if (CB > 1) WUSH_MMA(2, af0, i, 1)
       if (PFW && i < CB) load_w_frag(w, kt + 2, 1, i);
       WUSH_MMA_REST(2, af0, i)
       af0[i] = nx_;
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
         xs_next[i] = read_x_scale(kt + 1, i);
       }
       WUSH_FENCE
-      WUSH_MMA(3, af1, i, 1)
+      if (CB > 1) WUSH_MMA(3, af1, i, 1)
       if (PFW && i < CB) load_w_frag(w, kt + 2, 2, i);
       WUSH_MMA_REST(3, af1, i)
       af1[i] = nx_;
@@ -464,15 +464,16 @@ hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
     return n;
   }();
-  // Three instantiations: 256 x 256 (8 x 2 MFMA tiles per wave), 128 x 384 (4 x 3) and 128 x 256 (4 x 2).
+  // Four instantiations: 256 x 256 (8 x 2 MFMA tiles per wave), 128 x 384 (4 x 3), 128 x 256 (4 x 2)
+  // and 128 x 128 (4 x 1).
   // The cheapest by "rounds of the CUs x MFMAs per K iteration" wins, ties go to the larger tile
-  // (less operand traffic).  WUSH_GEMM_TILE=0 / 1 / 2 forces one of them (debug knob).
-  const int64_t cost[3] = {shape_cost(M, N, 256, 256, 64, cus), shape_cost(M, N, 128, 384, 48, cus),
-                           shape_cost(M, N, 128, 256, 32, cus)};
+  // (less operand traffic).  WUSH_GEMM_TILE=0..3 forces one of them (debug knob).
+  const int64_t cost[4] = {shape_cost(M, N, 256, 256, 64, cus), shape_cost(M, N, 128, 384, 48, cus),
+                           shape_cost(M, N, 128, 256, 32, cus), shape_cost(M, N, 128, 128, 16, cus)};
   int shape = 0;
-  if (cost[1] < cost[shape]) shape = 1;
-  if (cost[2] < cost[shape]) shape = 2;
-  if (const char* e = getenv("WUSH_GEMM_TILE")) shape = e[0] == '1' ? 1 : (e[0] == '2' ? 2 : 0);
+  for (int c = 1; c < 4; ++c)
+    if (cost[c] < cost[shape]) shape = c;
+  if (const char* e = getenv("WUSH_GEMM_TILE")) shape = (e[0] >= '0' && e[0] <= '3') ? e[0] - '0' : 0;
   if (shape == 1) {
     if (out_f32) return launch_shape<true, 4, 3>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
     return launch_shape<false, 4, 3>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
@@ -480,6 +481,10 @@ hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq
   if (shape == 2) {
     if (out_f32) return launch_shape<true, 4, 2>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
     return launch_shape<false, 4, 2>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
+  }
+  if (shape == 3) {
+    if (out_f32) return launch_shape<true, 4, 1>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
+    return launch_shape<false, 4, 1>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
   }
   if (out_f32) return launch_shape<true, 8, 2>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
   return launch_shape<false, 8, 2>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);

@@ -50,7 +50,7 @@ def _shape(name):
 
 def test_no_scratch_and_single_register_assignment(asm_text):
     kernels = _kernels(asm_text)
-    assert len(kernels) == 6, list(kernels)
+    assert len(kernels) == 8, list(kernels)
     for name, body in kernels.items():
         RB, CB = _shape(name)
         assert "scratch_" not in body, f"{name}: spills to scratch"

@@ -365,10 +365,10 @@ def test_tiled_quantizer_tap(P, G):
     assert torch.equal(q, q2) and torch.equal(s, s2)
 
 
-@pytest.mark.parametrize("shape", ["0", "1", "2"], ids=["256x256", "128x384", "128x256"])
+@pytest.mark.parametrize("shape", ["0", "1", "2", "3"], ids=["256x256", "128x384", "128x256", "128x128"])
 @pytest.mark.parametrize("M,N,K", [(130, 1000, 512), (300, 392, 1024), (257, 4096, 768)])
 def test_linear_both_tile_shapes(P, G, M, N, K, shape):
-    """The tiled GEMM has three workgroup tile shapes and picks one by the size of the problem; each
+    """The tiled GEMM has four workgroup tile shapes and picks one by the size of the problem; each
     is forced in turn (WUSH_GEMM_TILE).  N that is not a multiple of 384 makes the last 128 x 384
     tile reach past the 256-row padding of the packed weights, which the kernel has to survive."""
     import os
