@@ -377,9 +377,13 @@ hipError_t launch_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx,
   dim3 block(kWaves * 64);
 #define WUSH_DECODE_LAUNCH(RB, F32)                                                                          \
   {                                                                                                          \
-    int limit = 0;                                                                                           \
-    hipError_t e = resident_limit(layer_decode_kernel<RB, F32>, &limit);                                     \
-    if (e != hipSuccess) return e;                                                                           \
+    static int limit = 0; /* queried once per instantiation */                                               \
+    if (limit == 0) {                                                                                        \
+      int l = 0;                                                                                             \
+      hipError_t e = resident_limit(layer_decode_kernel<RB, F32>, &l);                                       \
+      if (e != hipSuccess) return e;                                                                         \
+      limit = l;                                                                                             \
+    }                                                                                                        \
     const unsigned g = (unsigned)(NB < limit ? NB : limit);                                                  \
     /* test hook: expect one workgroup more than launched and give up after a few polls */                   \
     const uint32_t expected = test_timeout ? g + 1 : g;                                                      \
