@@ -250,6 +250,82 @@ wush_status wush_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx,
 wush_status wush_layer_decode_status(const void* workspace, int64_t K, void* stream);
 
 /*
+ * ---------------------------------------------------------------------------
+ * NVFP4 variant (paper: "Layerwise Quantization Loss" and the accuracy tables run
+ * the method with NVFP4 as well: group size 16, transform block size matched to
+ * the group size).  Format: E2M1 elements; one FP8 E4M3 scale byte (bias 7, no
+ * infinities, largest value 448 = 0x7E, never negative) per 16 consecutive
+ * channels; one FP32 scale per tensor.  A stored element is worth
+ *   E2M1(code) * E4M3(byte) * tensor_scale.
+ * Transforms are T16 bf16 [K/16][16][16], T16[b][j][k] as for the 32-blocks.
+ * Packed layout (canonical only): codes u8 [rows][K/2] (even k = low nibble),
+ * scales u8 [rows][K/16].  Tensor scales live in DEVICE memory (one float) so
+ * that no call has to synchronize.
+ * Quantizer (readings of what the paper leaves open): group scale byte =
+ * nearest E4M3 (ties to even, saturating) of AbsMax / (6 * tensor_scale);
+ * elements = nearest E2M1 (ties to even, saturating) of
+ * value / (E4M3(byte) * tensor_scale); the input's sign bit is kept; scale byte 0
+ * or tensor scale 0 give magnitude 0.  Each step is one IEEE operation, in FP32
+ * for activations and FP64 for weights:
+ *   c = 1/(6 ts), r = AbsMax c, d = E4M3(byte) ts, rcp = 1/d, code = E2M1(v rcp).
+ * Requirements as above (K % 32 == 0 for the quantizers, K % 64 == 0 for
+ * wush_linear_nvfp4, 16-byte aligned data pointers, 4-byte aligned scales).
+ * ---------------------------------------------------------------------------
+ */
+
+/*
+ * Fused activation transform (16 x 16 blocks) + NVFP4 quantization: q(T X) of the
+ * layer forward-pass equation.
+ *   X            in   bf16 [M][ldx] (device)
+ *   T16          in   bf16 [K/16][16][16] (device)
+ *   tensor_scale in   float (device): the activation tensor's second-level scale,
+ *                     e.g. AbsMax of T X over calibration data / (6 * 448)
+ *   Xq, Xs       out  u8 [M][K/2], u8 [M][K/16]
+ *   dbg_Yt       out  optional: f32 [M][K], the transformed values as quantized
+ */
+wush_status wush_quantize_act_nvfp4(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16,
+                                    const float* tensor_scale, void* Xq, void* Xs, float* dbg_Yt,
+                                    void* stream);
+
+/*
+ * Offline weight side in NVFP4 (Alg. 2, RTN case, d = 16): FP64 inverse of every
+ * block of T16, W_blk inv(T_b) in FP64, tensor scale = AbsMax of the transformed
+ * weights / (6 * 448) rounded to FP32, then the quantizer above in FP64.
+ *   W            in   bf16 [N][ldw] (device)
+ *   Wq, Ws       out  u8 [N][K/2], u8 [N][K/16]
+ *   tensor_scale out  float (device)
+ *   workspace         device scratch, >= wush_prepare_weight_nvfp4_workspace(K) bytes,
+ *                     16-byte aligned
+ * A singular block sets a flag that wush_prepare_weight_nvfp4_status reads back
+ * (it synchronizes the stream): WUSH_OK or WUSH_ERR_SINGULAR.
+ */
+size_t wush_prepare_weight_nvfp4_workspace(int64_t K);
+wush_status wush_prepare_weight_nvfp4(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T16,
+                                      void* Wq, void* Ws, float* tensor_scale,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+wush_status wush_prepare_weight_nvfp4_status(const void* workspace, int64_t K, void* stream);
+
+/*
+ * NVFP4 x NVFP4 GEMM, FP32 accumulation: Y = tsx tsw deq(Xq,Xs) . deq(Wq,Ws)^T.
+ * CDNA4's block-scaled MFMA has no E4M3-per-16 scale path; element * group scale
+ * is exact in FP16, so the kernel dequantizes into LDS and contracts on the FP16
+ * MFMA (FP32 accumulators): results differ from the exact product only by the
+ * FP32 accumulation order.
+ *   Xq, Xs, tsx  in   u8 [M][K/2], u8 [M][K/16], float (device)
+ *   Wq, Ws, tsw  in   u8 [N][K/2], u8 [N][K/16], float (device)
+ *   out_dtype         WUSH_OUT_BF16 or WUSH_OUT_F32
+ *   Y            out  [M][ldy], ldy >= N, aligned to its element size
+ */
+wush_status wush_linear_nvfp4(const void* Xq, const void* Xs, const float* tsx,
+                              const void* Wq, const void* Ws, const float* tsw,
+                              int64_t M, int64_t N, int64_t K, int32_t out_dtype,
+                              void* Y, int64_t ldy, void* stream);
+
+/* Test tap: the NVFP4 quantizer alone on FP32 values. Yt f32 [M][K] -> q, s. */
+wush_status wush_quantize_f32_nvfp4(const float* Yt, int64_t M, int64_t K, const float* tensor_scale,
+                                    void* q, void* s, void* stream);
+
+/*
  * Measurement aid for the roofline of wush_linear (for benchmark harnesses: it
  * computes nothing of the layer): `blocks` workgroups of four waves run `iters`
  * trips of 64 independent block-scaled FP4 MFMAs (32x32x64) on registers only.

@@ -95,7 +95,7 @@ def quantize_nvfp4(Y: np.ndarray, ts, prec=np.float32):
     Gr = Y.reshape(*lead, K // G, G)
     with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
         amax = np.max(np.abs(Gr), axis=-1)
-        c = prec(1) / (prec(6) * ts)
+        c = prec(0) if ts == 0 else prec(1) / (prec(6) * ts)   # ts = 0: an all-zero tensor
         r = (amax * c).astype(prec)
         sb = round_e4m3(r)
         d = (e4m3_value(sb).astype(prec) * ts).astype(prec)

@@ -19,16 +19,22 @@ from .binding import (  # noqa: F401
     wush_layer_decode_status,
     wush_layer_decode_workspace,
     wush_linear,
+    wush_linear_nvfp4,
     wush_packed_sizes,
     wush_unpack_tiled,
     wush_prepare_weight,
     wush_prepare_weight_gptq,
     wush_prepare_weight_gptq_status,
     wush_prepare_weight_gptq_workspace,
+    wush_prepare_weight_nvfp4,
+    wush_prepare_weight_nvfp4_status,
+    wush_prepare_weight_nvfp4_workspace,
     wush_prepare_weight_workspace,
     wush_probe_mfma,
     wush_quantize_act,
+    wush_quantize_act_nvfp4,
     wush_quantize_f32,
+    wush_quantize_f32_nvfp4,
     wush_status_string,
     wush_workspace_status,
 )
@@ -40,5 +46,6 @@ __all__ = [
     "wush_build_transforms_status", "wush_build_transforms_workspace", "wush_layer_decode",
     "wush_layer_decode_init", "wush_layer_decode_status", "wush_layer_decode_workspace",
     "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_status", "wush_prepare_weight_gptq_workspace",
-    "wush_probe_mfma",
+    "wush_probe_mfma", "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_status",
+    "wush_prepare_weight_nvfp4_workspace", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
 ]

@@ -245,6 +245,69 @@ wush_status wush_probe_mfma(const void* operand_bits, int32_t iters, int32_t blo
   return from_hip(wush::launch_mfma_probe(operand_bits, iters, blocks, cycles_ticks, static_cast<hipStream_t>(stream)));
 }
 
+wush_status wush_quantize_act_nvfp4(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16,
+                                    const float* tensor_scale, void* Xq, void* Xs, float* dbg_Yt, void* stream) {
+  if (!X || !T16 || !tensor_scale || !Xq || !Xs) return WUSH_ERR_NULL;
+  if (wush_status s = check_rows(M, K, ldx)) return s;
+  if (!aligned16(X) || !aligned16(T16) || !aligned16(Xq) || !aligned16(Xs) || !aligned16(dbg_Yt)) return WUSH_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(tensor_scale) % 4 != 0) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_nvfp4_transform_quant(X, M, K, ldx, T16, tensor_scale, Xq, Xs, dbg_Yt,
+                                                     static_cast<hipStream_t>(stream)));
+}
+
+size_t wush_prepare_weight_nvfp4_workspace(int64_t K) {
+  if (K <= 0 || K % 32 != 0 || K > kMaxDim) return 0;
+  return wush::nvfp4_weight_prep_workspace_bytes(K);
+}
+
+wush_status wush_prepare_weight_nvfp4(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T16, void* Wq,
+                                      void* Ws, float* tensor_scale, void* workspace, size_t workspace_bytes,
+                                      void* stream) {
+  if (!W || !T16 || !Wq || !Ws || !tensor_scale) return WUSH_ERR_NULL;
+  if (wush_status s = check_rows(N, K, ldw)) return s;
+  if (!aligned16(W) || !aligned16(T16) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(tensor_scale) % 4 != 0) return WUSH_ERR_ALIGN;
+  if (!workspace || workspace_bytes < wush::nvfp4_weight_prep_workspace_bytes(K)) return WUSH_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_nvfp4_weight_prep(W, N, K, ldw, T16, Wq, Ws, tensor_scale, workspace,
+                                                 static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_prepare_weight_nvfp4_status(const void* workspace, int64_t K, void* stream) {
+  if (!workspace) return WUSH_ERR_NULL;
+  if (K <= 0 || K % 32 != 0 || K > kMaxDim) return WUSH_ERR_SHAPE;
+  int flag = 0;
+  const char* p = static_cast<const char*>(workspace) + wush::nvfp4_weight_prep_status_offset(K);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&flag, p, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess) return WUSH_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return WUSH_ERR_DEVICE;
+  return flag ? WUSH_ERR_SINGULAR : WUSH_OK;
+}
+
+wush_status wush_linear_nvfp4(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
+                              const float* tsw, int64_t M, int64_t N, int64_t K, int32_t out_dtype, void* Y,
+                              int64_t ldy, void* stream) {
+  if (!Xq || !Xs || !tsx || !Wq || !Ws || !tsw || !Y) return WUSH_ERR_NULL;
+  if (out_dtype != WUSH_OUT_BF16 && out_dtype != WUSH_OUT_F32) return WUSH_ERR_FMT;
+  if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim || K % 64 != 0) return WUSH_ERR_SHAPE;
+  if (ldy < N) return WUSH_ERR_SHAPE;
+  if (!aligned16(Xq) || !aligned16(Xs) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(tsx) % 4 != 0 || reinterpret_cast<uintptr_t>(tsw) % 4 != 0) return WUSH_ERR_ALIGN;
+  const uintptr_t elem = out_dtype == WUSH_OUT_F32 ? 4 : 2;
+  if (reinterpret_cast<uintptr_t>(Y) % elem != 0) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_nvfp4_gemm(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, out_dtype == WUSH_OUT_F32, Y, ldy,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_quantize_f32_nvfp4(const float* Yt, int64_t M, int64_t K, const float* tensor_scale, void* q, void* s,
+                                    void* stream) {
+  if (!Yt || !tensor_scale || !q || !s) return WUSH_ERR_NULL;
+  if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (!aligned16(Yt) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(tensor_scale) % 4 != 0) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_nvfp4_quantize_f32(Yt, M, K, tensor_scale, q, s, static_cast<hipStream_t>(stream)));
+}
+
 wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fmt, void* q, void* s,
                               void* stream) {
   if (!Yt || !q || !s) return WUSH_ERR_NULL;
@@ -290,6 +353,6 @@ const char* wush_status_string(wush_status st) {
   return "unknown status";
 }
 
-const char* wush_version(void) { return "0.5"; }
+const char* wush_version(void) { return "0.6"; }
 
 }  // extern "C"

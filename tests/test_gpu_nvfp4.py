@@ -1,0 +1,291 @@
+"""GPU parity of the NVFP4 variant (16 x 16 transforms, E2M1 elements, E4M3 scale per
+16, FP32 tensor scale) against oracle/wush_nvfp4_oracle.py, through the C ABI.
+Bars: quantizer bit-exact when both sides see the same FP32 values; transformed
+values within 1e-5 of the group AbsMax; codes against the all-FP64 path differ only
+next to a decision boundary; GEMM relative Frobenius error <= 2e-3 (BF16 output) and
+<= 1e-5 (FP32 output)."""
+import numpy as np
+import pytest
+
+import wush_inputs as I
+from oracle import wush_nvfp4_oracle as NV
+from oracle import wush_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2512_00956_amd as P
+    P.lib()
+    return P
+
+
+@pytest.fixture(scope="module")
+def G():
+    from tests import gpu_util
+    return gpu_util
+
+
+def _f32_dev(x):
+    import torch
+    return torch.tensor([float(x)], dtype=torch.float32, device="cuda")
+
+
+def _wush16(W, Xc, lam=1e-2):
+    K = W.shape[1]
+    T = np.empty((K // 16, 16, 16))
+    for b in range(K // 16):
+        sl = slice(16 * b, 16 * b + 16)
+        T[b] = O.wush_block(O.second_moment(W[:, sl]), O.second_moment(Xc[:, sl]), lam)
+    return O.round_to_bf16(T)
+
+
+SHAPES = {
+    "c1": I.CONFIGS["c1"],
+    "ragged": I.scaled(I.CONFIGS["c1"], M=77, K=32 * 13, N=45, calib_tokens=256, n_outlier=3),
+    "tiles": I.scaled(I.CONFIGS["c2"], M=300, K=1024, N=520, calib_tokens=1024, n_outlier=5),
+    "one_token": I.scaled(I.CONFIGS["c1"], M=1, K=128, N=32, calib_tokens=256, n_outlier=1),
+}
+_cache = {}
+
+
+def _layer(name):
+    if name not in _cache:
+        cfg = SHAPES[name]
+        L = I.make_layer(cfg)
+        X, Xc, W = (O.bf16_bits_to_f64(L[k]) for k in ("X", "X_cal", "W"))
+        _cache[name] = (cfg, L, X, W, _wush16(W, Xc))
+    return _cache[name]
+
+
+def _pack(codes):
+    return O.pack_codes(codes)
+
+
+def _explained(vals64, ts, codes_gpu, sb_gpu, codes_ref, sb_ref, tol):
+    """Counts differing elements that do NOT sit within tol (relative to the group
+    AbsMax) of an E2M1 midpoint and whose group is NOT within tol of an E4M3 midpoint."""
+    R, K = vals64.shape
+    Gr = vals64.reshape(R, K // 16, 16)
+    amax = np.max(np.abs(Gr), axis=-1)
+    cg, cr = codes_gpu.reshape(R, K // 16, 16), codes_ref.reshape(R, K // 16, 16)
+    same = (cg == cr) | (((cg & 7) == 0) & ((cr & 7) == 0))
+    bad = ~same | (sb_gpu != sb_ref)[..., None]
+    if not bad.any():
+        return 0.0, 0
+    r = amax / (6.0 * float(ts))
+    grid = NV.e4m3_value(np.arange(127))
+    mids = (grid[1:] + grid[:-1]) / 2
+    near_scale = np.min(np.abs(r[..., None] - mids), axis=-1) <= tol * np.maximum(r, 2.0 ** -9)
+    d = NV.e4m3_value(sb_ref) * float(ts)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        v = np.abs(Gr) / d[..., None]
+        a = amax / d
+    emid = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+    near_mid = np.min(np.abs(v[..., None] - emid), axis=-1) <= tol * a[..., None]
+    unexplained = bad & ~near_mid & ~near_scale[..., None]
+    return float(np.mean(bad)), int(unexplained.sum())
+
+
+def _adversarial_groups():
+    """Groups on every E2M1 midpoint, with AbsMax on E4M3 midpoints and thresholds."""
+    pts = []
+    for mpt in (0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0):
+        f = np.float32(mpt)
+        pts += [f, -np.nextafter(f, np.float32(0)), np.nextafter(f, np.float32(10))]
+    pts = np.array(pts[:15], dtype=np.float32)
+    rows = []
+    grid = NV.e4m3_value(np.arange(127))
+    mids = ((grid[1:] + grid[:-1]) / 2)[::7]
+    for top in list(mids) + [448.0, 464.0, 500.0, 2.0 ** -10, 2.0 ** -9, 3 * 2.0 ** -10, 1e-4, 0.0]:
+        g = np.zeros(16, dtype=np.float32)
+        g[:15] = pts * np.float32(top / 6.0 if top > 0 else 0.0)
+        g[15] = -np.float32(6.0 * top)
+        rows.append(g)
+    z = np.zeros(16, dtype=np.float32)
+    z[2] = -0.0
+    rows.append(z)
+    return np.stack(rows)
+
+
+@pytest.mark.parametrize("ts", [1.0, 0.0123, 3.7e-5])
+def test_quantizer_tap_bit_exact(P, G, ts):
+    import torch
+    adv = _adversarial_groups() * np.float32(ts)
+    rnd = I.random_f32((257, 16 * 9), seed=12, spread=6.0) * np.float32(ts)
+    pad = (-adv.shape[0]) % 9
+    adv = np.concatenate([adv, np.zeros((pad, 16), np.float32)]).reshape(-1, 16 * 9)
+    Y = np.concatenate([rnd, adv]).astype(np.float32)
+    # rows must be a multiple of 32 channels wide for the entry point: 144 = 4.5 * 32 -> widen to 288
+    Y = np.concatenate([Y, Y[::-1]], axis=1)
+    M, K = Y.shape
+    q, s = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    P.wush_quantize_f32_nvfp4(torch.from_numpy(Y).cuda(), _f32_dev(ts), q, s)
+    torch.cuda.synchronize()
+    cr, sr = NV.quantize_nvfp4(Y, np.float32(ts), prec=np.float32)
+    assert np.array_equal(G.host(s), sr)
+    assert np.array_equal(G.host(q), _pack(cr))
+
+
+def test_quantizer_tap_zero_tensor_scale(P, G):
+    import torch
+    Y = I.random_f32((4, 64), seed=3, spread=2.0)
+    q, s = G.empty_u8(4, 32), G.empty_u8(4, 4)
+    P.wush_quantize_f32_nvfp4(torch.from_numpy(Y).cuda(), _f32_dev(0.0), q, s)
+    torch.cuda.synchronize()
+    cr, sr = NV.quantize_nvfp4(Y, np.float32(0.0), prec=np.float32)
+    assert not sr.any() and np.array_equal(G.host(s), sr) and np.array_equal(G.host(q), _pack(cr))
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_transform_quant(P, G, name):
+    import torch
+    cfg, L, X, W, T = _layer(name)
+    M, K = cfg.M, cfg.K
+    Yt = NV.transform_act(X, T)
+    ts = NV.tensor_scale(Yt)
+    Xd, Td = G.bf16_dev(L["X"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    dbg = torch.full((M, K), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_quantize_act_nvfp4(Xd, Td, _f32_dev(ts), Xq, Xs, dbg_Yt=dbg)
+    Xq2, Xs2 = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    P.wush_quantize_act_nvfp4(Xd, Td, _f32_dev(ts), Xq2, Xs2)
+    torch.cuda.synchronize()
+    xq, xs, yt = G.host(Xq), G.host(Xs), G.host(dbg)
+    assert np.array_equal(xq, G.host(Xq2)) and np.array_equal(xs, G.host(Xs2))
+    # (1) quantizer bit-exact on the kernel's own FP32 values
+    assert np.isfinite(yt).all()
+    cr, sr = NV.quantize_nvfp4(yt, ts, prec=np.float32)
+    assert np.array_equal(xs, sr)
+    assert np.array_equal(xq, _pack(cr))
+    # (2) transformed values against FP64
+    amax = np.max(np.abs(Yt.reshape(M, K // 16, 16)), axis=-1)
+    err = np.max(np.abs(yt.astype(np.float64) - Yt).reshape(M, K // 16, 16), axis=-1)
+    assert np.max(err / amax) <= 1e-5
+    # (3) codes against the all-FP64 path: differences only next to a decision boundary
+    c64, s64 = NV.quantize_nvfp4(Yt, np.float64(ts), prec=np.float64)
+    rate, unexplained = _explained(Yt, ts, O.unpack_codes(xq), xs, c64, s64, tol=1e-5)
+    assert rate <= 2e-4 and unexplained == 0, (rate, unexplained)
+
+
+def test_transform_quant_strided_rows(P, G):
+    import torch
+    cfg, L, X, W, T = _layer("ragged")
+    M, K = cfg.M, cfg.K
+    ts = _f32_dev(NV.tensor_scale(NV.transform_act(X, T)))
+    wide = torch.zeros((M, K + 64), dtype=torch.bfloat16, device="cuda")
+    wide[:, :K] = G.bf16_dev(L["X"])
+    Td = G.bf16_dev(O.bf16_values_to_bits(T))
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    Xq2, Xs2 = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    P.wush_quantize_act_nvfp4(wide[:, :K], Td, ts, Xq, Xs)
+    P.wush_quantize_act_nvfp4(G.bf16_dev(L["X"]), Td, ts, Xq2, Xs2)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.host(Xq), G.host(Xq2)) and np.array_equal(G.host(Xs), G.host(Xs2))
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_prepare_weight(P, G, name):
+    import torch
+    cfg, L, X, W, T = _layer(name)
+    N, K = cfg.N, cfg.K
+    Wd, Td = G.bf16_dev(L["W"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    Wq, Ws = G.empty_u8(N, K // 2), G.empty_u8(N, K // 16)
+    tsw = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = G.empty_u8(P.wush_prepare_weight_nvfp4_workspace(K))
+    P.wush_prepare_weight_nvfp4(Wd, Td, Wq, Ws, tsw, ws)
+    P.wush_prepare_weight_nvfp4_status(ws, K)
+    cr, sr, ts_ref = NV.prepare_weight(W, T)
+    ts_gpu = np.float32(tsw.cpu().numpy()[0])
+    assert abs(float(ts_gpu) - float(ts_ref)) <= 1.2e-7 * float(ts_ref)      # at most one FP32 ulp
+    Wt = NV.transform_weight(W, T)
+    if ts_gpu != ts_ref:
+        cr, sr = NV.quantize_nvfp4(Wt, np.float64(ts_gpu), prec=np.float64)
+    rate, unexplained = _explained(Wt, ts_gpu, O.unpack_codes(G.host(Wq)), G.host(Ws), cr, sr, tol=1e-9)
+    assert rate <= 1e-4 and unexplained == 0, (rate, unexplained)
+
+
+def test_prepare_weight_flags_singular_block(P, G):
+    import torch
+    K, N = 64, 40
+    T = np.stack([np.eye(16)] * 4)
+    T[2, 5, :] = 0.0                                   # rank-deficient third block
+    Wd = G.bf16_dev(I.f32_to_bf16_bits(I.random_f32((N, K), 5, 1.0)))
+    Wq, Ws = G.empty_u8(N, K // 2), G.empty_u8(N, K // 16)
+    tsw = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = G.empty_u8(P.wush_prepare_weight_nvfp4_workspace(K))
+    P.wush_prepare_weight_nvfp4(Wd, G.bf16_dev(O.bf16_values_to_bits(T)), Wq, Ws, tsw, ws)
+    with pytest.raises(P.WushError) as e:
+        P.wush_prepare_weight_nvfp4_status(ws, K)
+    assert e.value.code == 7
+    # a good tensor clears the flag again
+    P.wush_prepare_weight_nvfp4(Wd, G.bf16_dev(O.bf16_values_to_bits(np.stack([np.eye(16)] * 4))), Wq, Ws, tsw, ws)
+    P.wush_prepare_weight_nvfp4_status(ws, K)
+
+
+GEMM_SHAPES = [(16, 256, 64), (77, 45, 128), (300, 520, 192), (257, 256, 1024), (512, 768, 4096), (1, 32, 256)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("out", ["bf16", "f32"])
+def test_linear_against_oracle(P, G, M, N, K, out):
+    """GEMM alone: both sides start from the same codes, scale bytes and tensor scales."""
+    import torch
+    rng = np.random.default_rng(1000 + M + N + K)
+    xc = rng.integers(0, 16, (M, K), dtype=np.uint8)
+    wc = rng.integers(0, 16, (N, K), dtype=np.uint8)
+    xs = rng.integers(0, 127, (M, K // 16), dtype=np.uint8)       # every finite E4M3 byte, subnormals included
+    ws_ = rng.integers(40, 80, (N, K // 16), dtype=np.uint8)
+    tsx, tsw = np.float32(0.0371), np.float32(2.4e-4)
+    ref = NV.linear_dequant(xc, xs, tsx, wc, ws_, tsw)
+    f32 = out == "f32"
+    Y = torch.full((M, N + 8), float("nan"), dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
+    P.wush_linear_nvfp4(G.u8_dev(_pack(xc)), G.u8_dev(xs), _f32_dev(tsx), G.u8_dev(_pack(wc)), G.u8_dev(ws_),
+                        _f32_dev(tsw), Y[:, :N], out_dtype=1 if f32 else 0)
+    torch.cuda.synchronize()
+    y = Y.float().cpu().numpy().astype(np.float64)
+    assert np.isnan(y[:, N:]).all()                      # nothing written past N
+    assert O.rel_fro(y[:, :N], ref) <= (1e-5 if f32 else 2e-3)
+
+
+@pytest.mark.parametrize("name", ["c1", "tiles"])
+def test_layer_end_to_end(P, G, name):
+    import torch
+    cfg, L, X, W, T = _layer(name)
+    M, N, K = cfg.M, cfg.N, cfg.K
+    if K % 64:
+        pytest.skip("GEMM needs K % 64 == 0")
+    Yt = NV.transform_act(X, T)
+    ts = NV.tensor_scale(Yt)
+    Xd, Wd, Td = G.bf16_dev(L["X"]), G.bf16_dev(L["W"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    Wq, Ws = G.empty_u8(N, K // 2), G.empty_u8(N, K // 16)
+    tsx, tsw = _f32_dev(ts), torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = G.empty_u8(P.wush_prepare_weight_nvfp4_workspace(K))
+    P.wush_prepare_weight_nvfp4(Wd, Td, Wq, Ws, tsw, ws)
+    P.wush_quantize_act_nvfp4(Xd, Td, tsx, Xq, Xs)
+    Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    P.wush_linear_nvfp4(Xq, Xs, tsx, Wq, Ws, tsw, Y, out_dtype=1)
+    torch.cuda.synchronize()
+    ref = NV.layer_forward(X, W, T, tsx=ts)
+    # a handful of boundary codes may differ; their effect on the output is far below the bar
+    assert O.rel_fro(Y.cpu().numpy().astype(np.float64), ref) <= 2e-3
+    # and the quantized layer approximates the unquantized product as the oracle's does
+    exact = X @ W.T
+    assert abs(O.rel_fro(Y.cpu().numpy().astype(np.float64), exact) - O.rel_fro(ref, exact)) <= 1e-3
+
+
+def test_argument_validation(P, G):
+    import torch
+    Xq, Xs = G.empty_u8(4, 48), G.empty_u8(4, 6)     # K = 96: not a multiple of 64
+    Y = torch.empty((4, 4), dtype=torch.bfloat16, device="cuda")
+    one = _f32_dev(1.0)
+    with pytest.raises(P.WushError) as e:
+        P.wush_linear_nvfp4(Xq, Xs, one, Xq, Xs, one, Y)
+    assert e.value.code == 2
+    with pytest.raises(P.WushError) as e:
+        P.wush_linear_nvfp4(G.empty_u8(4, 64), G.empty_u8(4, 8), None, G.empty_u8(4, 64), G.empty_u8(4, 8), one, Y)
+    assert e.value.code == 1
