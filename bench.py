@@ -16,7 +16,7 @@ Prints ONE JSON line:
              workload's own operand bits, and with all-equal operands), the shader clock
              under each, and a plain 1 GiB device copy
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|d2|d5|fig3]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|d2|d5|fig3|n2|n5]
 
 The decode workloads d2/d5 time wush_layer_decode (16 tokens) by replaying a
 captured graph of the steps, so that the host's launch cost is not what is
@@ -38,6 +38,7 @@ sys.path.insert(0, ROOT)
 import wush_inputs as I  # noqa: E402
 
 PEAK_FP4_TFLOPS = 10100.0   # MI355X dense MXFP4 MFMA
+PEAK_F16_TFLOPS = 2500.0    # MI355X dense FP16 / BF16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # HBM traffic per launch of the dominant kernel, bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
@@ -63,6 +64,9 @@ FIG3_LAYERS = [  # (name, K, N)
     ("llama-3.1-70b qkv", 8192, 10240), ("llama-3.1-70b o", 8192, 8192), ("llama-3.1-70b gate+up", 8192, 57344),
     ("llama-3.1-70b down", 28672, 8192),
 ]
+WORKLOADS["n2"] = "the c2 layer in the NVFP4 variant (E4M3 scale per 16, 16 x 16 transforms), M=2048 K=4096 N=6144"
+WORKLOADS["n5"] = "the c5 layer in the NVFP4 variant, M=8192 K=8192 N=57344"
+NVFP4 = {"n2": "c2", "n5": "c5"}
 DECODE = {"d2": "c2", "d5": "c5"}
 DECODE_TOKENS = 16
 
@@ -281,6 +285,107 @@ def decode_bench(args, P, torch, dev):
     print(json.dumps(out))
 
 
+def nvfp4_bench(args, P, torch, dev):
+    """The layer forward in the NVFP4 variant: wush_quantize_act_nvfp4 + wush_linear_nvfp4 per step.
+    CDNA4 has no scaled-MFMA path for E4M3-per-16 scales; the GEMM dequantizes (exactly) to FP16 and is
+    priced against the FP16 MFMA peak."""
+    cfg = I.CONFIGS[NVFP4[args.workload]]
+    L = I.make_layer(cfg)
+    M, K, N = cfg.M, cfg.K, cfg.N
+
+    def bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    # Timing does not depend on the transform values: random well-conditioned 16 x 16 blocks.
+    T_bits = I.make_transforms_random(K // 16, seed=95700, block=16)
+    Td, Xd = bf16(T_bits), bf16(L["X"])
+    # The activation tensor scale is an input of the quantizer (a calibrated constant): AbsMax of the
+    # transformed calibration-sized batch / (6 * 448), taken here from the batch itself.
+    Yt = torch.einsum("mbk,bjk->mbj", Xd.float().view(M, K // 16, 16), Td.float())
+    tsx = (Yt.abs().max() / 2688.0).reshape(1).float().contiguous()
+    del Yt
+    lay = 1 if args.layout == "tiled" else 0
+    (xcb, xsb), (wcb, wsb) = P.wush_packed_sizes_nvfp4(M, K, lay), P.wush_packed_sizes_nvfp4(N, K, lay)
+    Xq = torch.empty(xcb, dtype=torch.uint8, device=dev)
+    Xs = torch.empty(xsb, dtype=torch.uint8, device=dev)
+    Wq = torch.empty(wcb, dtype=torch.uint8, device=dev)
+    Ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    tsw = torch.zeros(1, dtype=torch.float32, device=dev)
+    wsp = torch.empty(P.wush_prepare_weight_nvfp4_workspace(K), dtype=torch.uint8, device=dev)
+    Wd = bf16(L["W"])
+    P.wush_prepare_weight_nvfp4(Wd, Td, Wq, Ws, tsw, wsp, layout=lay)
+    P.wush_prepare_weight_nvfp4_status(wsp, K)
+    del Wd
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+
+    def quant(i):
+        P.wush_quantize_act_nvfp4(Xd, Td, tsx, Xq, Xs, layout=lay)
+
+    def gemm(i):
+        P.wush_linear_nvfp4(Xq, Xs, tsx, Wq, Ws, tsw, Y, layout=lay, K=K)
+
+    def step(i):
+        quant(i)
+        gemm(i)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    def kernel_ms(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    q_ms, g_ms = kernel_ms(quant), kernel_ms(gemm)
+    qb = M * K * (2 + 0.5 + 1 / 16) + (K // 16) * 512
+    flops = 2.0 * M * N * K
+    out = {
+        "metric": "W4A4 layer TFLOP/s (transform+quant+NVFP4 GEMM); % of FP16 MFMA peak",
+        "value": flops / ms_per_step / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "nvfp4 (e2m1 x e4m3 per 16 x f32 per tensor), bf16 in/out, f16 MFMA operands, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
+                   "packed_layout": args.layout, "launch": "host loop"},
+        "roofline": {"bound": "mfma", "kernel": "wush_linear_nvfp4 (dequantize to FP16 in LDS + FP16 MFMA)",
+                     "achieved": flops / g_ms / 1e9, "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops / g_ms / 1e9 / PEAK_F16_TFLOPS, "traffic": None, "avg_launch_ms": g_ms},
+        "kernels": {"wush_quantize_act_nvfp4": {"ms": q_ms, "GB/s": qb / q_ms / 1e6,
+                                                "frac_hbm": qb / q_ms / 1e6 / PEAK_HBM_GBS, "algorithmic_bytes": qb},
+                    "wush_linear_nvfp4": {"ms": g_ms, "TFLOP/s": flops / g_ms / 1e9}},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import wush_nvfp4_oracle as NV
+        from oracle import wush_oracle as O
+        rows, n_out = min(M, {"n2": 1024, "n5": 64}[args.workload]), min(N, 8192)
+        T = O.bf16_bits_to_f64(T_bits)
+        wc, wsb, tw = NV.prepare_weight(O.bf16_bits_to_f64(L["W"][:n_out]), T)
+        X = O.bf16_bits_to_f64(L["X"][:rows])
+        ts_host = float(tsx.cpu()[0])
+        t0 = time.perf_counter()
+        xc, xsb = NV.quantize_nvfp4(NV.transform_act(X, T).astype(np.float32), ts_host)
+        NV.linear_dequant(xc, xsb, ts_host, wc, wsb, tw)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2.0 * rows * n_out * K / dt / 1e12, "unit": "TFLOP/s",
+                               "cores": len(os.sched_getaffinity(0)), "kind": "oracle", "seconds": dt,
+                               "sample": f"NVFP4 oracle layer forward on the first {rows} of {M} tokens and the first "
+                                         f"{n_out} of {N} output channels, full K, weights pre-quantized"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -318,6 +423,9 @@ def main():
         return
     if args.workload == "fig3":
         fig3_bench(args, P, torch, dev)
+        return
+    if args.workload in NVFP4:
+        nvfp4_bench(args, P, torch, dev)
         return
 
     cfg = I.CONFIGS[args.workload]

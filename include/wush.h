@@ -258,9 +258,13 @@ wush_status wush_layer_decode_status(const void* workspace, int64_t K, void* str
  * channels; one FP32 scale per tensor.  A stored element is worth
  *   E2M1(code) * E4M3(byte) * tensor_scale.
  * Transforms are T16 bf16 [K/16][16][16], T16[b][j][k] as for the 32-blocks.
- * Packed layout (canonical only): codes u8 [rows][K/2] (even k = low nibble),
- * scales u8 [rows][K/16].  Tensor scales live in DEVICE memory (one float) so
- * that no call has to synchronize.
+ * Packed layouts (argument `layout`): WUSH_LAYOUT_CANONICAL: codes u8 [rows][K/2]
+ * (even k = low nibble), scales u8 [rows][K/16].  WUSH_LAYOUT_TILED (opaque, fast;
+ * K % 64 == 0; buffers hold a multiple of 32 rows, wush_packed_sizes_nvfp4 gives the
+ * sizes): the same 16-byte chunks and scale dwords, ordered [row block of 32][K step
+ * of 64][half][row] so that a GEMM tile reads contiguous runs; both operands of one
+ * wush_linear_nvfp4 call use the same layout; wush_unpack_tiled_nvfp4 converts back.
+ * Tensor scales live in DEVICE memory (one float) so that no call has to synchronize.
  * Quantizer (readings of what the paper leaves open): group scale byte =
  * nearest E4M3 (ties to even, saturating) of AbsMax / (6 * tensor_scale);
  * elements = nearest E2M1 (ties to even, saturating) of
@@ -284,8 +288,8 @@ wush_status wush_layer_decode_status(const void* workspace, int64_t K, void* str
  *   dbg_Yt       out  optional: f32 [M][K], the transformed values as quantized
  */
 wush_status wush_quantize_act_nvfp4(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16,
-                                    const float* tensor_scale, void* Xq, void* Xs, float* dbg_Yt,
-                                    void* stream);
+                                    const float* tensor_scale, int32_t layout, void* Xq, void* Xs,
+                                    float* dbg_Yt, void* stream);
 
 /*
  * Offline weight side in NVFP4 (Alg. 2, RTN case, d = 16): FP64 inverse of every
@@ -301,7 +305,7 @@ wush_status wush_quantize_act_nvfp4(const void* X, int64_t M, int64_t K, int64_t
  */
 size_t wush_prepare_weight_nvfp4_workspace(int64_t K);
 wush_status wush_prepare_weight_nvfp4(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T16,
-                                      void* Wq, void* Ws, float* tensor_scale,
+                                      int32_t layout, void* Wq, void* Ws, float* tensor_scale,
                                       void* workspace, size_t workspace_bytes, void* stream);
 wush_status wush_prepare_weight_nvfp4_status(const void* workspace, int64_t K, void* stream);
 
@@ -311,18 +315,28 @@ wush_status wush_prepare_weight_nvfp4_status(const void* workspace, int64_t K, v
  * is exact in FP16, so the kernel dequantizes into LDS and contracts on the FP16
  * MFMA (FP32 accumulators): results differ from the exact product only by the
  * FP32 accumulation order.
- *   Xq, Xs, tsx  in   u8 [M][K/2], u8 [M][K/16], float (device)
- *   Wq, Ws, tsw  in   u8 [N][K/2], u8 [N][K/16], float (device)
+ *   Xq, Xs, tsx  in   u8 [M][K/2], u8 [M][K/16] (or tiled), float (device)
+ *   Wq, Ws, tsw  in   u8 [N][K/2], u8 [N][K/16] (or tiled), float (device)
+ *   layout            of all four packed buffers; the tiled one is about a quarter faster
+ *                     (a 256-row tile of a row-major operand touches 256 cache lines per load)
  *   out_dtype         WUSH_OUT_BF16 or WUSH_OUT_F32
  *   Y            out  [M][ldy], ldy >= N, aligned to its element size
  */
 wush_status wush_linear_nvfp4(const void* Xq, const void* Xs, const float* tsx,
                               const void* Wq, const void* Ws, const float* tsw,
-                              int64_t M, int64_t N, int64_t K, int32_t out_dtype,
+                              int64_t M, int64_t N, int64_t K, int32_t layout, int32_t out_dtype,
                               void* Y, int64_t ldy, void* stream);
 
-/* Test tap: the NVFP4 quantizer alone on FP32 values. Yt f32 [M][K] -> q, s. */
+/* Test tap: the NVFP4 quantizer alone on FP32 values. Yt f32 [M][K] -> q, s in `layout`. */
 wush_status wush_quantize_f32_nvfp4(const float* Yt, int64_t M, int64_t K, const float* tensor_scale,
+                                    int32_t layout, void* q, void* s, void* stream);
+
+/* Buffer sizes (bytes) of a packed NVFP4 [rows][K] operand in `layout`.  Host pointers out. */
+wush_status wush_packed_sizes_nvfp4(int64_t rows, int64_t K, int32_t layout,
+                                    size_t* code_bytes, size_t* scale_bytes);
+
+/* Tiled -> canonical copy of one packed NVFP4 operand (device pointers); for inspection and tests. */
+wush_status wush_unpack_tiled_nvfp4(const void* q_tiled, const void* s_tiled, int64_t rows, int64_t K,
                                     void* q, void* s, void* stream);
 
 /*

@@ -21,7 +21,9 @@ from .binding import (  # noqa: F401
     wush_linear,
     wush_linear_nvfp4,
     wush_packed_sizes,
+    wush_packed_sizes_nvfp4,
     wush_unpack_tiled,
+    wush_unpack_tiled_nvfp4,
     wush_prepare_weight,
     wush_prepare_weight_gptq,
     wush_prepare_weight_gptq_status,
@@ -48,4 +50,5 @@ __all__ = [
     "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_status", "wush_prepare_weight_gptq_workspace",
     "wush_probe_mfma", "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_status",
     "wush_prepare_weight_nvfp4_workspace", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
+    "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4",
 ]

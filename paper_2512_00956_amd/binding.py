@@ -35,6 +35,7 @@ EXPORTS = (
     "wush_probe_mfma",
     "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_workspace",
     "wush_prepare_weight_nvfp4_status", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
+    "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4",
 )
 
 
@@ -118,20 +119,24 @@ def lib() -> ctypes.CDLL:
         L.wush_probe_mfma.restype = c_int32
         L.wush_probe_mfma.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
         L.wush_quantize_act_nvfp4.restype = c_int32
-        L.wush_quantize_act_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
-                                              c_void_p, c_void_p]
+        L.wush_quantize_act_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_int32, c_void_p,
+                                              c_void_p, c_void_p, c_void_p]
         L.wush_prepare_weight_nvfp4_workspace.restype = c_size_t
         L.wush_prepare_weight_nvfp4_workspace.argtypes = [c_int64]
         L.wush_prepare_weight_nvfp4.restype = c_int32
-        L.wush_prepare_weight_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p,
+        L.wush_prepare_weight_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_void_p, c_void_p,
                                                 c_void_p, c_void_p, c_size_t, c_void_p]
         L.wush_prepare_weight_nvfp4_status.restype = c_int32
         L.wush_prepare_weight_nvfp4_status.argtypes = [c_void_p, c_int64, c_void_p]
         L.wush_linear_nvfp4.restype = c_int32
         L.wush_linear_nvfp4.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64,
-                                        c_int64, c_int32, c_void_p, c_int64, c_void_p]
+                                        c_int64, c_int32, c_int32, c_void_p, c_int64, c_void_p]
         L.wush_quantize_f32_nvfp4.restype = c_int32
-        L.wush_quantize_f32_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p]
+        L.wush_quantize_f32_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
+        L.wush_packed_sizes_nvfp4.restype = c_int32
+        L.wush_packed_sizes_nvfp4.argtypes = [c_int64, c_int64, c_int32, POINTER(c_size_t), POINTER(c_size_t)]
+        L.wush_unpack_tiled_nvfp4.restype = c_int32
+        L.wush_unpack_tiled_nvfp4.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
         _lib = L
     return _lib
 
@@ -298,12 +303,15 @@ def wush_probe_mfma(operand_bits, iters: int, blocks: int, cycles_ticks, stream=
 
 # ---------------------------------------------------------------------------
 # NVFP4 variant (E2M1, E4M3 scale per 16, FP32 tensor scale held in a 1-element
-# float tensor on the GPU; transforms bf16 [K/16][16][16])
+# float tensor on the GPU; transforms bf16 [K/16][16][16]).  `layout`:
+# WUSH_LAYOUT_CANONICAL (default) or WUSH_LAYOUT_TILED.
 # ---------------------------------------------------------------------------
-def wush_quantize_act_nvfp4(X, T16, tensor_scale, Xq, Xs, dbg_Yt=None, stream=None):
-    """X bf16 [M][K] -> Xq u8 [M][K/2], Xs u8 [M][K/16]; tensor_scale: float32 tensor (1 element, GPU)."""
+def wush_quantize_act_nvfp4(X, T16, tensor_scale, Xq, Xs, layout: int = WUSH_LAYOUT_CANONICAL, dbg_Yt=None,
+                            stream=None):
+    """X bf16 [M][K] -> Xq u8 [M][K/2], Xs u8 [M][K/16] (canonical shapes); tensor_scale: float32 tensor
+    (1 element, GPU)."""
     M, K = X.shape
-    _check(lib().wush_quantize_act_nvfp4(_ptr(X), M, K, X.stride(0), _ptr(T16), _ptr(tensor_scale), _ptr(Xq),
+    _check(lib().wush_quantize_act_nvfp4(_ptr(X), M, K, X.stride(0), _ptr(T16), _ptr(tensor_scale), layout, _ptr(Xq),
                                          _ptr(Xs), _ptr(dbg_Yt), _stream(stream)), "wush_quantize_act_nvfp4")
 
 
@@ -311,10 +319,11 @@ def wush_prepare_weight_nvfp4_workspace(K: int) -> int:
     return int(lib().wush_prepare_weight_nvfp4_workspace(K))
 
 
-def wush_prepare_weight_nvfp4(W, T16, Wq, Ws, tensor_scale, workspace, stream=None):
-    """W bf16 [N][K] -> Wq u8 [N][K/2], Ws u8 [N][K/16], tensor_scale (float32 tensor, 1 element, written)."""
+def wush_prepare_weight_nvfp4(W, T16, Wq, Ws, tensor_scale, workspace, layout: int = WUSH_LAYOUT_CANONICAL,
+                              stream=None):
+    """W bf16 [N][K] -> Wq, Ws in `layout`, tensor_scale (float32 tensor, 1 element, written)."""
     N, K = W.shape
-    _check(lib().wush_prepare_weight_nvfp4(_ptr(W), N, K, W.stride(0), _ptr(T16), _ptr(Wq), _ptr(Ws),
+    _check(lib().wush_prepare_weight_nvfp4(_ptr(W), N, K, W.stride(0), _ptr(T16), layout, _ptr(Wq), _ptr(Ws),
                                            _ptr(tensor_scale), _ptr(workspace),
                                            0 if workspace is None else workspace.numel() * workspace.element_size(),
                                            _stream(stream)), "wush_prepare_weight_nvfp4")
@@ -325,15 +334,31 @@ def wush_prepare_weight_nvfp4_status(workspace, K: int, stream=None):
            "wush_prepare_weight_nvfp4_status")
 
 
-def wush_linear_nvfp4(Xq, Xs, tsx, Wq, Ws, tsw, Y, out_dtype: int = WUSH_OUT_BF16, stream=None):
-    """Y [M][N] = tsx tsw deq(Xq, Xs) . deq(Wq, Ws)^T; K = 2 * Xq.shape[-1]."""
+def wush_linear_nvfp4(Xq, Xs, tsx, Wq, Ws, tsw, Y, layout: int = WUSH_LAYOUT_CANONICAL,
+                      out_dtype: int = WUSH_OUT_BF16, stream=None, K: int | None = None):
+    """Y [M][N] = tsx tsw deq(Xq, Xs) . deq(Wq, Ws)^T; K from the canonical shape of Xq unless given."""
     M, N = Y.shape
-    K = 2 * Xq.shape[-1]
-    _check(lib().wush_linear_nvfp4(_ptr(Xq), _ptr(Xs), _ptr(tsx), _ptr(Wq), _ptr(Ws), _ptr(tsw), M, N, K, out_dtype,
-                                   _ptr(Y), Y.stride(0), _stream(stream)), "wush_linear_nvfp4")
+    if K is None:
+        K = 2 * Xq.shape[-1]
+    _check(lib().wush_linear_nvfp4(_ptr(Xq), _ptr(Xs), _ptr(tsx), _ptr(Wq), _ptr(Ws), _ptr(tsw), M, N, K, layout,
+                                   out_dtype, _ptr(Y), Y.stride(0), _stream(stream)), "wush_linear_nvfp4")
 
 
-def wush_quantize_f32_nvfp4(Yt, tensor_scale, q, s, stream=None):
+def wush_quantize_f32_nvfp4(Yt, tensor_scale, q, s, layout: int = WUSH_LAYOUT_CANONICAL, stream=None):
     M, K = Yt.shape
-    _check(lib().wush_quantize_f32_nvfp4(_ptr(Yt), M, K, _ptr(tensor_scale), _ptr(q), _ptr(s), _stream(stream)),
-           "wush_quantize_f32_nvfp4")
+    _check(lib().wush_quantize_f32_nvfp4(_ptr(Yt), M, K, _ptr(tensor_scale), layout, _ptr(q), _ptr(s),
+                                         _stream(stream)), "wush_quantize_f32_nvfp4")
+
+
+def wush_packed_sizes_nvfp4(rows: int, K: int, layout: int = WUSH_LAYOUT_CANONICAL):
+    """(code_bytes, scale_bytes) of a packed NVFP4 [rows][K] operand in `layout`."""
+    cb, sb = c_size_t(0), c_size_t(0)
+    _check(lib().wush_packed_sizes_nvfp4(rows, K, layout, ctypes.byref(cb), ctypes.byref(sb)),
+           "wush_packed_sizes_nvfp4")
+    return cb.value, sb.value
+
+
+def wush_unpack_tiled_nvfp4(q_tiled, s_tiled, rows: int, K: int, q, s, stream=None):
+    """Tiled -> canonical copy (q u8 [rows][K/2], s u8 [rows][K/16])."""
+    _check(lib().wush_unpack_tiled_nvfp4(_ptr(q_tiled), _ptr(s_tiled), rows, K, _ptr(q), _ptr(s), _stream(stream)),
+           "wush_unpack_tiled_nvfp4")

@@ -7,15 +7,24 @@
 // E4M3 scale per 16 has no hardware path.  The product element * group-scale,
 // however, has at most 2 + 4 significant bits and lies in [2^-10, 2688], so it is
 // EXACT in FP16.  The kernel therefore dequantizes while staging: packed codes and
-// scale bytes travel HBM -> registers, become FP16 (hardware fp4 -> f16 convert,
+// scale bytes (row-major, or tiled so that a tile's K step is a few contiguous runs:
+// a 256-row tile otherwise pulls 16 bytes out of 256 different cache lines per load)
+// travel HBM -> registers, become FP16 (hardware fp4 -> f16 convert,
 // one packed multiply by the group scale), land in LDS in MFMA operand order, and
 // the contraction runs on v_mfma_f32_32x32x16_f16.  Nothing but the FP32
 // accumulation order separates the result from the exact one.
 //
-// Tiling: one workgroup (4 waves, 2 x 2) per 256 x 256 output tile, K in steps of
-// 64 (= 4 scale groups); each thread converts one X row and one W row of the step
-// (interleaved with the MFMAs of the previous step); two LDS stages (2 x 64 KiB),
-// two register stages for the packed loads.
+// Tiling: one workgroup (4 waves, 2 x 2) per 256 x 64*CB output tile (CB = 4, 3 or 2:
+// 256, 192 or 128 output channels, chosen per problem so that the last round of tiles
+// leaves few CUs idle), K in steps of 64 (= 4 scale groups); each thread converts one X
+// row (and one W row) of the next step after the MFMAs of the current one; two LDS
+// stages.  On this GPU a SIMD does not overlap VALU issue with MFMA execution (measured:
+// n VALU operations between two 32-cycle MFMAs cost 4n cycles more, for one wave per
+// SIMD and for two), so the conversion is priced in issue slots and nothing is gained by
+// interleaving it; it runs as one block per K step.
+#include <stdlib.h>
+
+#include "nvfp4_layout.hpp"
 #include "wush_device.hpp"
 #include "wush_kernels.hpp"
 
@@ -26,29 +35,54 @@ namespace {
 typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
-constexpr int kBM = 256, kBN = 256, kBK = 64;
-constexpr int kOperandBytes = 8 * 256 * 16;      // [k chunk of 8][row][16 B]
-constexpr int kStageBytes = 2 * kOperandBytes;   // X part, then W part
-constexpr int kLdsBytes = 2 * kStageBytes;       // 128 KiB
+constexpr int kBM = 256, kBK = 64;
+constexpr int kXBytes = 8 * 256 * 16;            // X part of a stage: [k chunk of 8][256 rows][16 B]
+constexpr int stage_bytes(int CB) { return kXBytes + 8 * 64 * CB * 16; }   // then the W part, 64*CB rows
+constexpr int lds_bytes(int CB) { return 2 * stage_bytes(CB); }           // 128 KiB at CB = 4
 
 struct Raw {
   v4u q[2];    // 64 codes of one row
   uint32_t s;  // their 4 scale bytes
 };
 
-__device__ __forceinline__ void load_raw(Raw& r, const uint8_t* __restrict__ q, const uint8_t* __restrict__ s,
-                                         int64_t row, int K, int kt) {
-  const uint8_t* p = q + row * (K / 2) + kt * 32;
-  r.q[0] = *reinterpret_cast<const v4u*>(p);
-  r.q[1] = *reinterpret_cast<const v4u*>(p + 16);
-  r.s = *reinterpret_cast<const uint32_t*>(s + row * (K / 16) + kt * 4);
+// Where a row's K steps live: byte offset of step 0 plus a stride per step, for the
+// codes (two 16-byte halves, `half` bytes apart) and for the scale dword.  Covers
+// the canonical row-major layout and the tiled one (nvfp4_layout.hpp).
+struct RowAddr {
+  const uint8_t* q;
+  const uint8_t* s;
+  int q_step, q_half, s_step;
+};
+
+__device__ __forceinline__ RowAddr row_addr(const uint8_t* __restrict__ q, const uint8_t* __restrict__ s, int64_t row,
+                                            int K, int tiled) {
+  RowAddr a;
+  if (tiled) {
+    const int KT = K >> 6;
+    a.q = q + nv_tiled_chunk_offset(row, 0, 0, KT);
+    a.s = s + nv_tiled_scale_offset(row, 0, KT);
+    a.q_step = 1024; a.q_half = 512; a.s_step = 128;
+  } else {
+    a.q = q + row * (K / 2);
+    a.s = s + row * (K / 16);
+    a.q_step = 32; a.q_half = 16; a.s_step = 4;
+  }
+  return a;
 }
 
-// E4M3 byte (non-negative, finite) -> FP16; every such value is an FP16 normal.
-__device__ __forceinline__ _Float16 e4m3_to_f16(uint32_t byte) {
-  const float f = byte < 8 ? (float)byte * 0.001953125f
-                           : __uint_as_float(((byte >> 3) + 120u) << 23 | (byte & 7u) << 20);
-  return (_Float16)f;
+__device__ __forceinline__ void load_raw(Raw& r, const RowAddr& a, int kt) {
+  const uint8_t* p = a.q + (int64_t)kt * a.q_step;
+  r.q[0] = *reinterpret_cast<const v4u*>(p);
+  r.q[1] = *reinterpret_cast<const v4u*>(p + a.q_half);
+  r.s = *reinterpret_cast<const uint32_t*>(a.s + (int64_t)kt * a.s_step);
+}
+
+// Two E4M3 scale bytes (word `HI` of the row's scale dword) -> two FP16 values, by the
+// hardware FP8 convert (gfx950 reads FP8 as OCP E4M3); every finite E4M3 value is an
+// FP16 normal, so the conversion is exact.
+template <bool HI>
+__device__ __forceinline__ v2h e4m3x2_to_f16(uint32_t scales) {
+  return __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(scales, 1.0f, HI);
 }
 
 // Eight codes (one dword, element i in nibble i) times the group scale -> 8 FP16.
@@ -63,22 +97,26 @@ __device__ __forceinline__ v4u dequant8(uint32_t w, v2h s) {
 }
 
 // Group g (16 elements) of a row's K step: two 16-byte LDS chunks, k = 16g + 8hh + 0..7.
-__device__ __forceinline__ void convert_group(const Raw& r, int g, char* operand, int row) {
-  const _Float16 sc = e4m3_to_f16((r.s >> (8 * g)) & 0xFFu);
+// `operand` = the X or W part of a stage, `rows` = its row count.
+__device__ __forceinline__ void convert_group(const Raw& r, int g, char* operand, int rows, int row) {
+  const v2h pair = g < 2 ? e4m3x2_to_f16<false>(r.s) : e4m3x2_to_f16<true>(r.s);
+  const _Float16 sc = pair[g & 1];
   const v2h s = {sc, sc};
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh) {
     const uint32_t w = r.q[g >> 1][(g & 1) * 2 + hh];
-    *reinterpret_cast<v4u*>(operand + ((2 * g + hh) * 256 + row) * 16) = dequant8(w, s);
+    *reinterpret_cast<v4u*>(operand + ((2 * g + hh) * rows + row) * 16) = dequant8(w, s);
   }
 }
 
-template <bool OUT_F32>
+template <bool OUT_F32, int CB>
 __global__ __launch_bounds__(256) void nvfp4_gemm_kernel(
     const uint8_t* __restrict__ Xq, const uint8_t* __restrict__ Xs, const float* __restrict__ tsx,
     const uint8_t* __restrict__ Wq, const uint8_t* __restrict__ Ws, const float* __restrict__ tsw,
-    void* __restrict__ Yv, int64_t ldy, int M, int N, int K, int tiles_m, int tiles_n) {
+    void* __restrict__ Yv, int64_t ldy, int M, int N, int K, int tiles_m, int tiles_n, int tiled) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
+  constexpr int kBN = 64 * CB;         // output channels per tile
+  constexpr int kStage = stage_bytes(CB);
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -93,78 +131,70 @@ __global__ __launch_bounds__(256) void nvfp4_gemm_kernel(
   const int m0 = tm * kBM, n0 = tn * kBN;
 
   const int64_t rowX = min(m0 + tid, M - 1);  // rows past the end re-read the last valid row
-  const int64_t rowW = min(n0 + tid, N - 1);
+  const int64_t rowW = min(n0 + min(tid, kBN - 1), N - 1);
+  const bool w_thread = tid < kBN;            // wave-uniform: kBN is a multiple of 64
   const int KT = K / kBK;
 
-  Raw rx[2], rw[2];
-  load_raw(rx[0], Xq, Xs, rowX, K, 0);
-  load_raw(rw[0], Wq, Ws, rowW, K, 0);
-  if (KT > 1) {
-    load_raw(rx[1], Xq, Xs, rowX, K, 1);
-    load_raw(rw[1], Wq, Ws, rowW, K, 1);
-  }
+  auto convert = [&](const Raw& x, const Raw& w, char* stage) {
 #pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    convert_group(rx[0], g, lds, tid);
-    convert_group(rw[0], g, lds + kOperandBytes, tid);
-  }
-  if (KT > 2) {
-    load_raw(rx[0], Xq, Xs, rowX, K, 2);
-    load_raw(rw[0], Wq, Ws, rowW, K, 2);
-  }
+    for (int g = 0; g < 4; ++g) convert_group(x, g, stage, 256, tid);
+    if (w_thread) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) convert_group(w, g, stage + kXBytes, kBN, tid);
+    }
+  };
+
+  // Packed operands of the step after the one being converted are in flight for one
+  // whole MFMA phase.  Step numbers are clamped (surplus loads re-read the last step).
+  const RowAddr ax = row_addr(Xq, Xs, rowX, K, tiled), aw = row_addr(Wq, Ws, rowW, K, tiled);
+  Raw rx, rw;
+  load_raw(rx, ax, 0);
+  load_raw(rw, aw, 0);
+  convert(rx, rw, lds);
+  load_raw(rx, ax, min(1, KT - 1));
+  load_raw(rw, aw, min(1, KT - 1));
   __syncthreads();
 
-  v16f acc[4][4];
+  v16f acc[4][CB];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = (v16f){0};
+    for (int j = 0; j < CB; ++j) acc[i][j] = (v16f){0};
 
-  // One K step: MFMAs on stage `cur`; meanwhile convert step kt+1 (registers set
-  // (kt+1)&1) into the other stage and refill that register set with step kt+3.
-  auto step = [&](int kt, Raw& nx, Raw& nw) {
-    const char* cur = lds + (kt & 1) * kStageBytes;
-    char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
-    const bool have_next = kt + 1 < KT;
+  auto mma_step = [&](const char* cur) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      v8h a[4], b[4];
+      v8h a[4], b[CB];
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         a[i] = *reinterpret_cast<const v8h*>(cur + ((2 * g + h) * 256 + wm * 128 + 32 * i + l32) * 16);
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        b[j] = *reinterpret_cast<const v8h*>(cur + kOperandBytes + ((2 * g + h) * 256 + wn * 128 + 32 * j + l32) * 16);
-      if (have_next) {
-        convert_group(nx, g, nxt, tid);
-        convert_group(nw, g, nxt + kOperandBytes, tid);
-      }
+      for (int j = 0; j < CB; ++j)
+        b[j] = *reinterpret_cast<const v8h*>(cur + kXBytes + ((2 * g + h) * kBN + wn * (32 * CB) + 32 * j + l32) * 16);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < CB; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 3 < KT) {
-      load_raw(nx, Xq, Xs, rowX, K, kt + 3);
-      load_raw(nw, Wq, Ws, rowW, K, kt + 3);
-    }
-    __syncthreads();
   };
 
-  int kt = 0;
-  for (; kt + 1 < KT; kt += 2) {
-    step(kt, rx[1], rw[1]);
-    step(kt + 1, rx[0], rw[0]);
+  for (int kt = 0; kt + 1 < KT; ++kt) {
+    mma_step(lds + (kt & 1) * kStage);
+    convert(rx, rw, lds + ((kt + 1) & 1) * kStage);   // the other stage: last read before the previous barrier
+    const int kl = min(kt + 2, KT - 1);
+    load_raw(rx, ax, kl);
+    load_raw(rw, aw, kl);
+    __syncthreads();
   }
-  if (kt < KT) step(kt, rx[1], rw[1]);
+  mma_step(lds + ((KT - 1) & 1) * kStage);
 
   const float scale = *tsx * *tsw;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = n0 + wn * 128 + 32 * j + l32;
+    for (int j = 0; j < CB; ++j) {
+      const int n = n0 + wn * (32 * CB) + 32 * j + l32;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = m0 + wm * 128 + 32 * i + 8 * (r >> 2) + 4 * h + (r & 3);
@@ -178,32 +208,58 @@ __global__ __launch_bounds__(256) void nvfp4_gemm_kernel(
   }
 }
 
-}  // namespace
-
-hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
-                             const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
-                             hipStream_t stream) {
-  static bool configured = false;
+template <bool OUT_F32, int CB>
+hipError_t launch_shape(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
+                        const float* tsw, int64_t M, int64_t N, int64_t K, int tiled, void* Y, int64_t ldy,
+                        hipStream_t stream) {
+  static bool configured = false;  // per instantiation
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nvfp4_gemm_kernel<false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(nvfp4_gemm_kernel<true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nvfp4_gemm_kernel<OUT_F32, CB>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(CB));
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + kBN - 1) / kBN);
-  const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
-  if (out_f32)
-    nvfp4_gemm_kernel<true><<<grid, block, kLdsBytes, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, tsx,
-                                                                (const uint8_t*)Wq, (const uint8_t*)Ws, tsw, Y, ldy,
-                                                                (int)M, (int)N, (int)K, tiles_m, tiles_n);
-  else
-    nvfp4_gemm_kernel<false><<<grid, block, kLdsBytes, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, tsx,
-                                                                 (const uint8_t*)Wq, (const uint8_t*)Ws, tsw, Y, ldy,
-                                                                 (int)M, (int)N, (int)K, tiles_m, tiles_n);
+  const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + 64 * CB - 1) / (64 * CB));
+  nvfp4_gemm_kernel<OUT_F32, CB><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds_bytes(CB), stream>>>(
+      (const uint8_t*)Xq, (const uint8_t*)Xs, tsx, (const uint8_t*)Wq, (const uint8_t*)Ws, tsw, Y, ldy, (int)M, (int)N,
+      (int)K, tiles_m, tiles_n, tiled);
   return hipGetLastError();
+}
+
+// Cost of a tile width in issue cycles per K step and SIMD, times the number of rounds the
+// tiles take on `cus` CUs: 16*CB MFMAs of 32 cycles plus about 150 conversion / LDS slots of 4.
+int64_t width_cost(int64_t M, int64_t N, int CB, int cus) {
+  const int64_t tiles = ((M + kBM - 1) / kBM) * ((N + 64 * CB - 1) / (64 * CB));
+  return ((tiles + cus - 1) / cus) * (512 * CB + 600);
+}
+
+int device_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
+    cus = n;
+  }
+  return cus;
+}
+
+}  // namespace
+
+hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
+                             const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y,
+                             int64_t ldy, hipStream_t stream) {
+  const int cus = device_cus();
+  int best = 4;
+  for (int cb = 3; cb >= 2; --cb)
+    if (width_cost(M, N, cb, cus) < width_cost(M, N, best, cus)) best = cb;   // ties keep the wider tile
+  if (const char* f = getenv("WUSH_NVFP4_WIDTH")) {  // tests: force a tile width (output channels / 64)
+    if (f[0] >= '2' && f[0] <= '4' && f[1] == 0) best = f[0] - '0';
+  }
+#define WUSH_NV_LAUNCH(F32, CB) launch_shape<F32, CB>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, tiled, Y, ldy, stream)
+  if (out_f32) return best == 4 ? WUSH_NV_LAUNCH(true, 4) : best == 3 ? WUSH_NV_LAUNCH(true, 3) : WUSH_NV_LAUNCH(true, 2);
+  return best == 4 ? WUSH_NV_LAUNCH(false, 4) : best == 3 ? WUSH_NV_LAUNCH(false, 3) : WUSH_NV_LAUNCH(false, 2);
+#undef WUSH_NV_LAUNCH
 }
 
 }  // namespace wush

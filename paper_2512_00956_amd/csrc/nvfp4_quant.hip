@@ -18,6 +18,7 @@
 // two 16 x 16 blocks presented to the 32x32x16 BF16 MFMA as one block-diagonal
 // 32 x 32 operand -- the zero half costs nothing (the kernel is bound by HBM
 // traffic, and the accumulator layout then gives every lane exactly one group of 16).
+#include "nvfp4_layout.hpp"
 #include "transform_quant_core.hpp"
 #include "wush_kernels.hpp"
 
@@ -135,7 +136,7 @@ __device__ __forceinline__ void transform_quantize16(const v8bf (&ta)[kNB][2], c
   scales[1] = (g0 >> 16 & 0xFFu) | (g1 >> 16 & 0xFFu) << 8 | (g0 >> 24) << 16 | (g1 >> 24) << 24;
 }
 
-template <bool DBG>
+template <bool DBG, bool TILED>
 __global__ __launch_bounds__(kWaves * 64) void nvfp4_transform_quant_kernel(
     const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ T16, const float* __restrict__ tscale,
     uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs, float* __restrict__ dbg, int M, int K, int C32,
@@ -170,7 +171,16 @@ __global__ __launch_bounds__(kWaves * 64) void nvfp4_transform_quant_kernel(
     v2u scales;
     float* dbg_row = (DBG && row_ok) ? dbg + (int64_t)m * K + 32 * bfirst + 16 * h : nullptr;
     transform_quantize16<DBG>(ta, cur, c, ts, out, scales, dbg_row, nb);
-    if (row_ok) {
+    if (row_ok && TILED) {
+      // K % 64 == 0: this lane's chunks 2h, 2h+1 are the two halves of K step bfirst/2 + h
+      const int KT = K >> 6, kt = (bfirst >> 1) + h;
+      if (2 * h < nb) {
+        __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(Xq + nv_tiled_chunk_offset(m, kt, 0, KT)));
+        __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(Xq + nv_tiled_chunk_offset(m, kt, 1, KT)));
+        // every lane holds all 8 scale bytes of its token; each half writes its own step's four
+        __builtin_nontemporal_store(scales[h], reinterpret_cast<uint32_t*>(Xs + nv_tiled_scale_offset(m, kt, KT)));
+      }
+    } else if (row_ok) {
       uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
       uint8_t* sp = Xs + (int64_t)m * (K / 16) + 2 * bfirst;
       if (nb == kNB && (C32 & 3) == 0) {
@@ -195,7 +205,7 @@ __global__ __launch_bounds__(kWaves * 64) void nvfp4_transform_quant_kernel(
 __global__ __launch_bounds__(256) void nvfp4_quantize_f32_kernel(const float* __restrict__ Y,
                                                                  const float* __restrict__ tscale,
                                                                  uint8_t* __restrict__ q, uint8_t* __restrict__ s,
-                                                                 int64_t groups) {
+                                                                 int64_t groups, int C16, int tiled) {
   const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (g >= groups) return;
   float v[16];
@@ -213,8 +223,15 @@ __global__ __launch_bounds__(256) void nvfp4_quantize_f32_kernel(const float* __
   float rcp;
   const int byte = group_scale_f32(amax, c, ts, rcp);
   const v2u out = {pack8_scaled(v, rcp), pack8_scaled(v + 8, rcp)};
-  *reinterpret_cast<v2u*>(q + g * 8) = out;
-  s[g] = (uint8_t)byte;
+  if (tiled) {
+    const int64_t row = g / C16;
+    const int b = (int)(g % C16), kt = b >> 2, gi = b & 3;
+    *reinterpret_cast<v2u*>(q + nv_tiled_chunk_offset(row, kt, gi >> 1, C16 >> 2) + 8 * (gi & 1)) = out;
+    s[nv_tiled_scale_offset(row, kt, C16 >> 2) + gi] = (uint8_t)byte;
+  } else {
+    *reinterpret_cast<v2u*>(q + g * 8) = out;
+    s[g] = (uint8_t)byte;
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -310,7 +327,7 @@ __global__ __launch_bounds__(256) void nvfp4_weight_kernel(const uint16_t* __res
                                                            const double* __restrict__ Tinv,
                                                            unsigned long long* __restrict__ amax_bits,
                                                            uint8_t* __restrict__ Wq, uint8_t* __restrict__ Ws,
-                                                           float* __restrict__ ts_out, int N, int K) {
+                                                           float* __restrict__ ts_out, int N, int K, int tiled) {
   __shared__ double ti[16][16];
   __shared__ unsigned long long wg_max;
   const int b = blockIdx.y;
@@ -354,14 +371,37 @@ __global__ __launch_bounds__(256) void nvfp4_weight_kernel(const uint16_t* __res
     }
     words[g] = wd;
   }
-  *reinterpret_cast<v2u*>(Wq + (int64_t)n * (K / 2) + 8 * b) = (v2u){words[0], words[1]};
-  Ws[(int64_t)n * (K / 16) + b] = (uint8_t)byte;
+  if (tiled) {
+    const int kt = b >> 2, gi = b & 3, KT = K >> 6;
+    *reinterpret_cast<v2u*>(Wq + nv_tiled_chunk_offset(n, kt, gi >> 1, KT) + 8 * (gi & 1)) = (v2u){words[0], words[1]};
+    Ws[nv_tiled_scale_offset(n, kt, KT) + gi] = (uint8_t)byte;
+  } else {
+    *reinterpret_cast<v2u*>(Wq + (int64_t)n * (K / 2) + 8 * b) = (v2u){words[0], words[1]};
+    Ws[(int64_t)n * (K / 16) + b] = (uint8_t)byte;
+  }
+}
+
+// Tiled -> canonical copy of packed codes and scales (inspection / tests): one thread per (row, K step).
+__global__ __launch_bounds__(256) void nvfp4_unpack_tiled_kernel(const uint8_t* __restrict__ qt,
+                                                                 const uint8_t* __restrict__ st,
+                                                                 uint8_t* __restrict__ q, uint8_t* __restrict__ s,
+                                                                 int64_t rows, int KT) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * KT) return;
+  const int64_t row = idx / KT;
+  const int kt = (int)(idx % KT);
+  uint8_t* dst = q + row * KT * 32 + kt * 32;
+  *reinterpret_cast<v4u*>(dst) = *reinterpret_cast<const v4u*>(qt + nv_tiled_chunk_offset(row, kt, 0, KT));
+  *reinterpret_cast<v4u*>(dst + 16) = *reinterpret_cast<const v4u*>(qt + nv_tiled_chunk_offset(row, kt, 1, KT));
+  *reinterpret_cast<uint32_t*>(s + row * KT * 4 + kt * 4) =
+      *reinterpret_cast<const uint32_t*>(st + nv_tiled_scale_offset(row, kt, KT));
 }
 
 }  // namespace
 
 hipError_t launch_nvfp4_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16,
-                                        const float* tscale, void* Xq, void* Xs, float* dbg, hipStream_t stream) {
+                                        const float* tscale, int tiled, void* Xq, void* Xs, float* dbg,
+                                        hipStream_t stream) {
   const int C32 = (int)(K / 32);
   const int col_groups = (C32 + kWaves * kNB - 1) / (kWaves * kNB);
   const int ntiles = (int)((M + kTileM - 1) / kTileM);
@@ -369,22 +409,32 @@ hipError_t launch_nvfp4_transform_quant(const void* X, int64_t M, int64_t K, int
   while (tiles_per_wg > 1 && (int64_t)col_groups * ((ntiles + tiles_per_wg - 1) / tiles_per_wg) < 1024) tiles_per_wg >>= 1;
   dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
   dim3 block(kWaves * 64);
-  if (dbg)
-    nvfp4_transform_quant_kernel<true><<<grid, block, 0, stream>>>((const uint16_t*)X, ldx, (const uint16_t*)T16, tscale,
-                                                                   (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M, (int)K, C32,
-                                                                   tiles_per_wg);
-  else
-    nvfp4_transform_quant_kernel<false><<<grid, block, 0, stream>>>((const uint16_t*)X, ldx, (const uint16_t*)T16,
-                                                                    tscale, (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M,
-                                                                    (int)K, C32, tiles_per_wg);
+#define WUSH_NVQ_LAUNCH(DBG, TILED)                                                                          \
+  nvfp4_transform_quant_kernel<DBG, TILED><<<grid, block, 0, stream>>>(                                      \
+      (const uint16_t*)X, ldx, (const uint16_t*)T16, tscale, (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M, (int)K, \
+      C32, tiles_per_wg)
+  if (dbg) {
+    if (tiled) WUSH_NVQ_LAUNCH(true, true); else WUSH_NVQ_LAUNCH(true, false);
+  } else {
+    if (tiled) WUSH_NVQ_LAUNCH(false, true); else WUSH_NVQ_LAUNCH(false, false);
+  }
+#undef WUSH_NVQ_LAUNCH
   return hipGetLastError();
 }
 
-hipError_t launch_nvfp4_quantize_f32(const float* Y, int64_t M, int64_t K, const float* tscale, void* q, void* s,
-                                     hipStream_t stream) {
+hipError_t launch_nvfp4_quantize_f32(const float* Y, int64_t M, int64_t K, const float* tscale, int tiled, void* q,
+                                     void* s, hipStream_t stream) {
   const int64_t groups = M * (K / 16);
   nvfp4_quantize_f32_kernel<<<dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream>>>(
-      Y, tscale, (uint8_t*)q, (uint8_t*)s, groups);
+      Y, tscale, (uint8_t*)q, (uint8_t*)s, groups, (int)(K / 16), tiled);
+  return hipGetLastError();
+}
+
+hipError_t launch_nvfp4_unpack_tiled(const void* qt, const void* st, int64_t rows, int64_t K, void* q, void* s,
+                                     hipStream_t stream) {
+  const int64_t n = rows * (K / 64);
+  nvfp4_unpack_tiled_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(
+      (const uint8_t*)qt, (const uint8_t*)st, (uint8_t*)q, (uint8_t*)s, rows, (int)(K / 64));
   return hipGetLastError();
 }
 
@@ -393,8 +443,8 @@ size_t nvfp4_weight_prep_amax_offset(int64_t K) { return (size_t)(K / 16) * 256 
 size_t nvfp4_weight_prep_status_offset(int64_t K) { return nvfp4_weight_prep_amax_offset(K) + 8; }
 size_t nvfp4_weight_prep_workspace_bytes(int64_t K) { return nvfp4_weight_prep_amax_offset(K) + 16; }
 
-hipError_t launch_nvfp4_weight_prep(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T16, void* Wq,
-                                    void* Ws, float* ts_out, void* workspace, hipStream_t stream) {
+hipError_t launch_nvfp4_weight_prep(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T16, int tiled,
+                                    void* Wq, void* Ws, float* ts_out, void* workspace, hipStream_t stream) {
   double* tinv = reinterpret_cast<double*>(workspace);
   char* base = reinterpret_cast<char*>(workspace);
   unsigned long long* amax = reinterpret_cast<unsigned long long*>(base + nvfp4_weight_prep_amax_offset(K));
@@ -407,11 +457,11 @@ hipError_t launch_nvfp4_weight_prep(const void* W, int64_t N, int64_t K, int64_t
   if (e != hipSuccess) return e;
   dim3 grid((unsigned)((N + 255) / 256), (unsigned)(K / 16));
   nvfp4_weight_kernel<false><<<grid, dim3(256), 0, stream>>>((const uint16_t*)W, ldw, tinv, amax, nullptr, nullptr,
-                                                             nullptr, (int)N, (int)K);
+                                                             nullptr, (int)N, (int)K, tiled);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   nvfp4_weight_kernel<true><<<grid, dim3(256), 0, stream>>>((const uint16_t*)W, ldw, tinv, amax, (uint8_t*)Wq,
-                                                            (uint8_t*)Ws, ts_out, (int)N, (int)K);
+                                                            (uint8_t*)Ws, ts_out, (int)N, (int)K, tiled);
   return hipGetLastError();
 }
 

@@ -245,14 +245,21 @@ wush_status wush_probe_mfma(const void* operand_bits, int32_t iters, int32_t blo
   return from_hip(wush::launch_mfma_probe(operand_bits, iters, blocks, cycles_ticks, static_cast<hipStream_t>(stream)));
 }
 
+static inline wush_status check_nv_layout(int32_t layout, int64_t K) {
+  if (layout != WUSH_LAYOUT_CANONICAL && layout != WUSH_LAYOUT_TILED) return WUSH_ERR_FMT;
+  return (layout == WUSH_LAYOUT_TILED && K % 64 != 0) ? WUSH_ERR_SHAPE : WUSH_OK;
+}
+
 wush_status wush_quantize_act_nvfp4(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16,
-                                    const float* tensor_scale, void* Xq, void* Xs, float* dbg_Yt, void* stream) {
+                                    const float* tensor_scale, int32_t layout, void* Xq, void* Xs, float* dbg_Yt,
+                                    void* stream) {
   if (!X || !T16 || !tensor_scale || !Xq || !Xs) return WUSH_ERR_NULL;
   if (wush_status s = check_rows(M, K, ldx)) return s;
+  if (wush_status s = check_nv_layout(layout, K)) return s;
   if (!aligned16(X) || !aligned16(T16) || !aligned16(Xq) || !aligned16(Xs) || !aligned16(dbg_Yt)) return WUSH_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(tensor_scale) % 4 != 0) return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_nvfp4_transform_quant(X, M, K, ldx, T16, tensor_scale, Xq, Xs, dbg_Yt,
-                                                     static_cast<hipStream_t>(stream)));
+  return from_hip(wush::launch_nvfp4_transform_quant(X, M, K, ldx, T16, tensor_scale, layout == WUSH_LAYOUT_TILED, Xq,
+                                                     Xs, dbg_Yt, static_cast<hipStream_t>(stream)));
 }
 
 size_t wush_prepare_weight_nvfp4_workspace(int64_t K) {
@@ -260,17 +267,18 @@ size_t wush_prepare_weight_nvfp4_workspace(int64_t K) {
   return wush::nvfp4_weight_prep_workspace_bytes(K);
 }
 
-wush_status wush_prepare_weight_nvfp4(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T16, void* Wq,
-                                      void* Ws, float* tensor_scale, void* workspace, size_t workspace_bytes,
-                                      void* stream) {
+wush_status wush_prepare_weight_nvfp4(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T16,
+                                      int32_t layout, void* Wq, void* Ws, float* tensor_scale, void* workspace,
+                                      size_t workspace_bytes, void* stream) {
   if (!W || !T16 || !Wq || !Ws || !tensor_scale) return WUSH_ERR_NULL;
   if (wush_status s = check_rows(N, K, ldw)) return s;
+  if (wush_status s = check_nv_layout(layout, K)) return s;
   if (!aligned16(W) || !aligned16(T16) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(tensor_scale) % 4 != 0) return WUSH_ERR_ALIGN;
   if (!workspace || workspace_bytes < wush::nvfp4_weight_prep_workspace_bytes(K)) return WUSH_ERR_WORKSPACE;
   if (!aligned16(workspace)) return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_nvfp4_weight_prep(W, N, K, ldw, T16, Wq, Ws, tensor_scale, workspace,
-                                                 static_cast<hipStream_t>(stream)));
+  return from_hip(wush::launch_nvfp4_weight_prep(W, N, K, ldw, T16, layout == WUSH_LAYOUT_TILED, Wq, Ws, tensor_scale,
+                                                 workspace, static_cast<hipStream_t>(stream)));
 }
 
 wush_status wush_prepare_weight_nvfp4_status(const void* workspace, int64_t K, void* stream) {
@@ -285,27 +293,48 @@ wush_status wush_prepare_weight_nvfp4_status(const void* workspace, int64_t K, v
 }
 
 wush_status wush_linear_nvfp4(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
-                              const float* tsw, int64_t M, int64_t N, int64_t K, int32_t out_dtype, void* Y,
-                              int64_t ldy, void* stream) {
+                              const float* tsw, int64_t M, int64_t N, int64_t K, int32_t layout, int32_t out_dtype,
+                              void* Y, int64_t ldy, void* stream) {
   if (!Xq || !Xs || !tsx || !Wq || !Ws || !tsw || !Y) return WUSH_ERR_NULL;
   if (out_dtype != WUSH_OUT_BF16 && out_dtype != WUSH_OUT_F32) return WUSH_ERR_FMT;
+  if (layout != WUSH_LAYOUT_CANONICAL && layout != WUSH_LAYOUT_TILED) return WUSH_ERR_FMT;
   if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim || K % 64 != 0) return WUSH_ERR_SHAPE;
   if (ldy < N) return WUSH_ERR_SHAPE;
   if (!aligned16(Xq) || !aligned16(Xs) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(tsx) % 4 != 0 || reinterpret_cast<uintptr_t>(tsw) % 4 != 0) return WUSH_ERR_ALIGN;
   const uintptr_t elem = out_dtype == WUSH_OUT_F32 ? 4 : 2;
   if (reinterpret_cast<uintptr_t>(Y) % elem != 0) return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_nvfp4_gemm(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, out_dtype == WUSH_OUT_F32, Y, ldy,
-                                          static_cast<hipStream_t>(stream)));
+  return from_hip(wush::launch_nvfp4_gemm(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, out_dtype == WUSH_OUT_F32,
+                                          layout == WUSH_LAYOUT_TILED, Y, ldy, static_cast<hipStream_t>(stream)));
 }
 
-wush_status wush_quantize_f32_nvfp4(const float* Yt, int64_t M, int64_t K, const float* tensor_scale, void* q, void* s,
-                                    void* stream) {
+wush_status wush_quantize_f32_nvfp4(const float* Yt, int64_t M, int64_t K, const float* tensor_scale, int32_t layout,
+                                    void* q, void* s, void* stream) {
   if (!Yt || !tensor_scale || !q || !s) return WUSH_ERR_NULL;
   if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (wush_status st = check_nv_layout(layout, K)) return st;
   if (!aligned16(Yt) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(tensor_scale) % 4 != 0) return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_nvfp4_quantize_f32(Yt, M, K, tensor_scale, q, s, static_cast<hipStream_t>(stream)));
+  return from_hip(wush::launch_nvfp4_quantize_f32(Yt, M, K, tensor_scale, layout == WUSH_LAYOUT_TILED, q, s,
+                                                  static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_packed_sizes_nvfp4(int64_t rows, int64_t K, int32_t layout, size_t* code_bytes, size_t* scale_bytes) {
+  if (!code_bytes || !scale_bytes) return WUSH_ERR_NULL;
+  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (wush_status st = check_nv_layout(layout, K)) return st;
+  const int64_t r = layout == WUSH_LAYOUT_TILED ? (rows + 31) / 32 * 32 : rows;
+  *code_bytes = (size_t)r * (size_t)(K / 2);
+  *scale_bytes = (size_t)r * (size_t)(K / 16);
+  return WUSH_OK;
+}
+
+wush_status wush_unpack_tiled_nvfp4(const void* q_tiled, const void* s_tiled, int64_t rows, int64_t K, void* q, void* s,
+                                    void* stream) {
+  if (!q_tiled || !s_tiled || !q || !s) return WUSH_ERR_NULL;
+  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxDim || K % 64 != 0) return WUSH_ERR_SHAPE;
+  if (!aligned16(q_tiled) || !aligned16(s_tiled) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_nvfp4_unpack_tiled(q_tiled, s_tiled, rows, K, q, s, static_cast<hipStream_t>(stream)));
 }
 
 wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fmt, void* q, void* s,

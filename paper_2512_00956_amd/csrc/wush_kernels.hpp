@@ -62,19 +62,23 @@ hipError_t launch_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx,
                                void* workspace, int test_timeout, hipStream_t stream);
 
 // NVFP4 variant (E2M1, E4M3 scale per 16, FP32 tensor scale in device memory; 16 x 16 transforms).
+// `tiled` != 0 selects the layout of nvfp4_layout.hpp (K % 64 == 0, buffers of a multiple of 32 rows).
 hipError_t launch_nvfp4_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16,
-                                        const float* tscale, void* Xq, void* Xs, float* dbg, hipStream_t stream);
-hipError_t launch_nvfp4_quantize_f32(const float* Y, int64_t M, int64_t K, const float* tscale, void* q, void* s,
+                                        const float* tscale, int tiled, void* Xq, void* Xs, float* dbg,
+                                        hipStream_t stream);
+hipError_t launch_nvfp4_quantize_f32(const float* Y, int64_t M, int64_t K, const float* tscale, int tiled, void* q,
+                                     void* s, hipStream_t stream);
+hipError_t launch_nvfp4_unpack_tiled(const void* qt, const void* st, int64_t rows, int64_t K, void* q, void* s,
                                      hipStream_t stream);
 // workspace: [K/16][16][16] FP64 inverses | u64 AbsMax bits | int32 status
 size_t nvfp4_weight_prep_workspace_bytes(int64_t K);
 size_t nvfp4_weight_prep_status_offset(int64_t K);
-hipError_t launch_nvfp4_weight_prep(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T16, void* Wq,
-                                    void* Ws, float* ts_out, void* workspace, hipStream_t stream);
+hipError_t launch_nvfp4_weight_prep(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T16, int tiled,
+                                    void* Wq, void* Ws, float* ts_out, void* workspace, hipStream_t stream);
 // K % 64 == 0
 hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
-                             const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
-                             hipStream_t stream);
+                             const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y,
+                             int64_t ldy, hipStream_t stream);
 
 // Measurement aid: register-only loop of the block-scaled FP4 MFMA (4 waves per workgroup, 64 MFMAs per trip).
 hipError_t launch_mfma_probe(const void* operand_bits, int iters, int blocks, void* out, hipStream_t stream);

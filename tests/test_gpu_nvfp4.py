@@ -251,6 +251,27 @@ def test_linear_against_oracle(P, G, M, N, K, out):
     assert O.rel_fro(y[:, :N], ref) <= (1e-5 if f32 else 2e-3)
 
 
+@pytest.mark.parametrize("width", ["2", "3", "4"])
+def test_linear_every_tile_width(P, G, width, monkeypatch):
+    """The three tile widths (128, 192, 256 output channels) on a shape with several
+    tiles and ragged edges in both directions; the library normally chooses by cost."""
+    import torch
+    monkeypatch.setenv("WUSH_NVFP4_WIDTH", width)
+    M, N, K = 300, 700, 320
+    rng = np.random.default_rng(77)
+    xc = rng.integers(0, 16, (M, K), dtype=np.uint8)
+    wc = rng.integers(0, 16, (N, K), dtype=np.uint8)
+    xs = rng.integers(30, 100, (M, K // 16), dtype=np.uint8)
+    ws_ = rng.integers(0, 127, (N, K // 16), dtype=np.uint8)
+    tsx, tsw = np.float32(1.7), np.float32(3.1e-3)
+    ref = NV.linear_dequant(xc, xs, tsx, wc, ws_, tsw)
+    Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_linear_nvfp4(G.u8_dev(_pack(xc)), G.u8_dev(xs), _f32_dev(tsx), G.u8_dev(_pack(wc)), G.u8_dev(ws_),
+                        _f32_dev(tsw), Y, out_dtype=1)
+    torch.cuda.synchronize()
+    assert O.rel_fro(Y.cpu().numpy().astype(np.float64), ref) <= 1e-5
+
+
 @pytest.mark.parametrize("name", ["c1", "tiles"])
 def test_layer_end_to_end(P, G, name):
     import torch
@@ -278,6 +299,76 @@ def test_layer_end_to_end(P, G, name):
     assert abs(O.rel_fro(Y.cpu().numpy().astype(np.float64), exact) - O.rel_fro(ref, exact)) <= 1e-3
 
 
+def test_tiled_layout_is_a_permutation_of_canonical(P, G):
+    """Both quantizers and the tap write the tiled layout; unpacking it gives the canonical bytes."""
+    import torch
+    cfg, L, X, W, T = _layer("tiles")
+    M, N, K = cfg.M, cfg.N, cfg.K
+    ts = _f32_dev(NV.tensor_scale(NV.transform_act(X, T)))
+    Xd, Wd, Td = G.bf16_dev(L["X"]), G.bf16_dev(L["W"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    for rows, run in ((M, "act"), (N, "weight"), (M, "tap")):
+        cb, sb = P.wush_packed_sizes_nvfp4(rows, K, 1)
+        assert cb == (rows + 31) // 32 * 32 * K // 2 and sb == (rows + 31) // 32 * 32 * K // 16
+        qt = torch.full((cb,), 0xEE, dtype=torch.uint8, device="cuda")
+        st = torch.full((sb,), 0xEE, dtype=torch.uint8, device="cuda")
+        qc, sc = G.empty_u8(rows, K // 2), G.empty_u8(rows, K // 16)
+        if run == "act":
+            P.wush_quantize_act_nvfp4(Xd, Td, ts, qt, st, layout=1)
+            P.wush_quantize_act_nvfp4(Xd, Td, ts, qc, sc)
+        elif run == "weight":
+            tsw = torch.zeros(1, dtype=torch.float32, device="cuda")
+            ws = G.empty_u8(P.wush_prepare_weight_nvfp4_workspace(K))
+            P.wush_prepare_weight_nvfp4(Wd, Td, qt, st, tsw, ws, layout=1)
+            P.wush_prepare_weight_nvfp4(Wd, Td, qc, sc, tsw, ws)
+        else:
+            Y = torch.from_numpy(I.random_f32((rows, K), seed=5, spread=3.0)).cuda()
+            P.wush_quantize_f32_nvfp4(Y, ts, qt, st, layout=1)
+            P.wush_quantize_f32_nvfp4(Y, ts, qc, sc)
+        qu, su = G.empty_u8(rows, K // 2), G.empty_u8(rows, K // 16)
+        P.wush_unpack_tiled_nvfp4(qt, st, rows, K, qu, su)
+        torch.cuda.synchronize()
+        assert np.array_equal(G.host(qu), G.host(qc)), run
+        assert np.array_equal(G.host(su), G.host(sc)), run
+        # an independent statement of the layout: chunk (row, kt, hh) and scale dword (row, kt)
+        qh, sh, qch, sch = G.host(qt), G.host(st), G.host(qc), G.host(sc)
+        KT = K // 64
+        for row, kt, hh in ((0, 0, 0), (rows - 1, KT - 1, 1), (min(37, rows - 1), 3, 1), (rows // 2, 5, 0)):
+            off = ((((row // 32) * KT + kt) * 2 + hh) * 32 + row % 32) * 16
+            assert np.array_equal(qh[off:off + 16], qch[row, kt * 32 + hh * 16: kt * 32 + hh * 16 + 16])
+            so = (((row // 32) * KT + kt) * 32 + row % 32) * 4
+            assert np.array_equal(sh[so:so + 4], sch[row, kt * 4: kt * 4 + 4])
+
+
+@pytest.mark.parametrize("width", ["2", "3", "4"])
+def test_layer_end_to_end_tiled(P, G, width, monkeypatch):
+    """The path the benchmark times: tiled buffers from both quantizers into the GEMM."""
+    import torch
+    monkeypatch.setenv("WUSH_NVFP4_WIDTH", width)
+    cfg, L, X, W, T = _layer("tiles")
+    M, N, K = cfg.M, cfg.N, cfg.K
+    Yt = NV.transform_act(X, T)
+    ts = NV.tensor_scale(Yt)
+    Xd, Wd, Td = G.bf16_dev(L["X"]), G.bf16_dev(L["W"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    xcb, xsb = P.wush_packed_sizes_nvfp4(M, K, 1)
+    wcb, wsb = P.wush_packed_sizes_nvfp4(N, K, 1)
+    Xq, Xs, Wq, Ws = G.empty_u8(xcb), G.empty_u8(xsb), G.empty_u8(wcb), G.empty_u8(wsb)
+    tsx, tsw = _f32_dev(ts), torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = G.empty_u8(P.wush_prepare_weight_nvfp4_workspace(K))
+    P.wush_prepare_weight_nvfp4(Wd, Td, Wq, Ws, tsw, ws, layout=1)
+    P.wush_quantize_act_nvfp4(Xd, Td, tsx, Xq, Xs, layout=1)
+    Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_linear_nvfp4(Xq, Xs, tsx, Wq, Ws, tsw, Y, layout=1, out_dtype=1, K=K)
+    # the same through the canonical layout: identical accumulation order, identical bits
+    Xq2, Xs2, Wq2, Ws2 = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16), G.empty_u8(N, K // 2), G.empty_u8(N, K // 16)
+    P.wush_prepare_weight_nvfp4(Wd, Td, Wq2, Ws2, tsw, ws)
+    P.wush_quantize_act_nvfp4(Xd, Td, tsx, Xq2, Xs2)
+    Y2 = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    P.wush_linear_nvfp4(Xq2, Xs2, tsx, Wq2, Ws2, tsw, Y2, out_dtype=1)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)
+    assert O.rel_fro(Y.cpu().numpy().astype(np.float64), NV.layer_forward(X, W, T, tsx=ts)) <= 2e-3
+
+
 def test_argument_validation(P, G):
     import torch
     Xq, Xs = G.empty_u8(4, 48), G.empty_u8(4, 6)     # K = 96: not a multiple of 64
@@ -289,3 +380,7 @@ def test_argument_validation(P, G):
     with pytest.raises(P.WushError) as e:
         P.wush_linear_nvfp4(G.empty_u8(4, 64), G.empty_u8(4, 8), None, G.empty_u8(4, 64), G.empty_u8(4, 8), one, Y)
     assert e.value.code == 1
+    with pytest.raises(P.WushError) as e:       # the tiled layout needs K % 64 == 0
+        P.wush_quantize_f32_nvfp4(torch.zeros((4, 96), device="cuda"), one, G.empty_u8(32 * 48), G.empty_u8(32 * 6),
+                                  layout=1)
+    assert e.value.code == 2

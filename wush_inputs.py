@@ -137,8 +137,9 @@ def make_layer(cfg: LayerConfig, *, want_weight: bool = True) -> dict:
     return out
 
 
-def make_transforms_random(C: int, seed: int) -> np.ndarray:
-    """Well-conditioned random 32x32 blocks as BF16 bits, shape [C][32][32].
+def make_transforms_random(C: int, seed: int, block: int = BLOCK) -> np.ndarray:
+    """Well-conditioned random block x block transforms as BF16 bits, shape [C][block][block]
+    (block = 32, or 16 for the NVFP4 variant).
 
     Timing of the path does not depend on the values of the transforms; the
     benchmark uses these when it only needs a tensor of the right shape whose
@@ -146,10 +147,10 @@ def make_transforms_random(C: int, seed: int) -> np.ndarray:
     matrix (QR of a Gaussian) with its rows rescaled by log-normal factors.
     """
     rng = np.random.Generator(np.random.PCG64(seed))
-    T = np.empty((C, BLOCK, BLOCK), dtype=np.float32)
+    T = np.empty((C, block, block), dtype=np.float32)
     for b in range(C):
-        q, _ = np.linalg.qr(rng.standard_normal((BLOCK, BLOCK)))
-        s = rng.lognormal(0.0, 0.5, size=BLOCK)
+        q, _ = np.linalg.qr(rng.standard_normal((block, block)))
+        s = rng.lognormal(0.0, 0.5, size=block)
         T[b] = (s[:, None] * q).astype(np.float32)
     return f32_to_bf16_bits(T)
 
