@@ -233,23 +233,12 @@ int64_t width_cost(int64_t M, int64_t N, int CB, int cus) {
   return ((tiles + cus - 1) / cus) * (512 * CB + 600);
 }
 
-int device_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
-    cus = n;
-  }
-  return cus;
-}
-
 }  // namespace
 
 hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
                              const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y,
                              int64_t ldy, hipStream_t stream) {
-  const int cus = device_cus();
+  const int cus = device_cu_count();
   int best = 4;
   for (int cb = 3; cb >= 2; --cb)
     if (width_cost(M, N, cb, cus) < width_cost(M, N, best, cus)) best = cb;   // ties keep the wider tile

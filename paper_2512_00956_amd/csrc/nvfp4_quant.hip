@@ -34,34 +34,38 @@ constexpr int kWaves = 4;
 // ---------------------------------------------------------------------------
 // E4M3 (finite-only FP8, bias 7): rounding and decoding
 // ---------------------------------------------------------------------------
-// Byte of the E4M3 value nearest to r >= 0 (ties to even, saturating at 448).
-__device__ __forceinline__ int e4m3_byte_f32(float r) {
-  if (r < 0.015625f) return (int)rintf(r * 512.0f);  // subnormal range: multiples of 2^-9 (8 -> 2^-6)
-  uint32_t bits = __float_as_uint(r);
-  bits += 0x7FFFFu + ((bits >> 20) & 1u);             // round the fraction to 3 bits, carry into the exponent
-  const int byte = (int)(((bits >> 23) - 120u) << 3 | ((bits >> 20) & 7u));
-  return r >= 464.0f ? 126 : min(byte, 126);          // 464 = midpoint past 448
+// r >= 0 rounded to the E4M3 grid (nearest, ties to even, saturating at 448), branch-free:
+// adding and subtracting 2^(e-3+23), with e the exponent of r floored at -6 (below 2^-6 the
+// grid is the multiples of 2^-9), leaves r rounded to 3 fraction bits.  Returns the value;
+// `byte` gets its encoding (for a subnormal k * 2^-9 the fraction of k * 2^-9 + 2^-6 is k / 8).
+__device__ __forceinline__ float round_e4m3_f32(float r, int& byte) {
+  r = fminf(r, 448.0f);                                   // anything above rounds or saturates to 448
+  const uint32_t eb = max(__float_as_uint(r) >> 23, 121u);
+  const float magic = __uint_as_float((eb + 20u) << 23);
+  const float t = (r + magic) - magic;
+  const bool sub = t < 0.015625f;
+  const float u = sub ? t + 0.015625f : t;
+  byte = (int)(__float_as_uint(u) >> 20) - (sub ? (121 << 3) : (120 << 3));
+  return t;
 }
 
-__device__ __forceinline__ int e4m3_byte_f64(double r) {
-  if (r < 0.015625) return (int)rint(r * 512.0);
-  if (r >= 464.0) return 126;
-  uint64_t bits = (uint64_t)__double_as_longlong(r);
-  bits += 0xFFFFFFFFFFFFull + ((bits >> 49) & 1ull);
-  const int byte = (int)((((bits >> 52) - 1016ull) << 3) | ((bits >> 49) & 7ull));
-  return min(byte, 126);
-}
-
-__device__ __forceinline__ float e4m3_value_f32(int byte) {
-  return byte < 8 ? (float)byte * 0.001953125f
-                  : __uint_as_float((uint32_t)((byte >> 3) + 120) << 23 | (uint32_t)(byte & 7) << 20);
+__device__ __forceinline__ double round_e4m3_f64(double r, int& byte) {
+  r = fmin(r, 448.0);
+  const uint64_t eb = max((uint64_t)__double_as_longlong(r) >> 52, (uint64_t)1017);
+  const double magic = __longlong_as_double((long long)((eb + 49ull) << 52));
+  const double t = (r + magic) - magic;
+  const bool sub = t < 0.015625;
+  const double u = sub ? t + 0.015625 : t;
+  byte = (int)((uint64_t)__double_as_longlong(u) >> 49) - (sub ? (1017 << 3) : (1016 << 3));
+  return t;
 }
 
 // Scale byte and element multiplier of one group (FP32 decision arithmetic).
 __device__ __forceinline__ int group_scale_f32(float amax, float c, float ts, float& rcp) {
-  const int byte = e4m3_byte_f32(amax * c);
-  const float d = e4m3_value_f32(byte) * ts;
-  rcp = byte == 0 ? 0.0f : 1.0f / d;
+  int byte;
+  const float d = round_e4m3_f32(amax * c, byte) * ts;
+  const float q = 1.0f / d;             // IEEE division; d = 0 only with byte 0 (or ts = 0)
+  rcp = byte == 0 ? 0.0f : q;
   return byte;
 }
 
@@ -137,7 +141,7 @@ __device__ __forceinline__ void transform_quantize16(const v8bf (&ta)[kNB][2], c
 }
 
 template <bool DBG, bool TILED>
-__global__ __launch_bounds__(kWaves * 64) void nvfp4_transform_quant_kernel(
+__global__ __launch_bounds__(kWaves * 64, 3) void nvfp4_transform_quant_kernel(
     const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ T16, const float* __restrict__ tscale,
     uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs, float* __restrict__ dbg, int M, int K, int C32,
     int tiles_per_wg) {
@@ -353,11 +357,8 @@ __global__ __launch_bounds__(256) void nvfp4_weight_kernel(const uint16_t* __res
   if (n >= N) return;
   const double ts = (double)tsf;
   const double c = ts == 0.0 ? 0.0 : 1.0 / (6.0 * ts);
-  const int byte = e4m3_byte_f64(amax * c);
-  const double sv = byte < 8 ? (double)byte * 0.001953125
-                             : __longlong_as_double((long long)((uint64_t)((byte >> 3) + 1016) << 52 |
-                                                                (uint64_t)(byte & 7) << 49));
-  const double d = sv * ts;
+  int byte;
+  const double d = round_e4m3_f64(amax * c, byte) * ts;
   const double rcp = byte == 0 ? 0.0 : 1.0 / d;
   uint32_t words[2];
 #pragma unroll
@@ -405,8 +406,7 @@ hipError_t launch_nvfp4_transform_quant(const void* X, int64_t M, int64_t K, int
   const int C32 = (int)(K / 32);
   const int col_groups = (C32 + kWaves * kNB - 1) / (kWaves * kNB);
   const int ntiles = (int)((M + kTileM - 1) / kTileM);
-  int tiles_per_wg = 4;
-  while (tiles_per_wg > 1 && (int64_t)col_groups * ((ntiles + tiles_per_wg - 1) / tiles_per_wg) < 1024) tiles_per_wg >>= 1;
+  const int tiles_per_wg = token_walk(ntiles, col_groups);
   dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
   dim3 block(kWaves * 64);
 #define WUSH_NVQ_LAUNCH(DBG, TILED)                                                                          \

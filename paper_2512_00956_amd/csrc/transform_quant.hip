@@ -87,15 +87,35 @@ __global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
 
 }  // namespace
 
+int device_cu_count() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
+    cus = n;
+  }
+  return cus;
+}
+
+// Token tiles each workgroup walks down (the register-resident transforms are loaded once per
+// workgroup).  Measured on 2048..32768 tokens x 4096..14336 channels: a grid of at most one
+// workgroup per CU, all of them busy from start to end, streams at 6.0-7.2 TB/s, while grids of
+// 2-4 workgroups per CU lose up to a third to the uneven last round (8192 x 8192: 42 -> 28 us).
+// Small inputs are latency bound and take the shortest walk.
+int token_walk(int ntiles, int col_groups) {
+  const int cus = device_cu_count();
+  if ((int64_t)ntiles * col_groups <= 2 * cus) return 1;
+  const int wg_rows = cus / col_groups > 0 ? cus / col_groups : 1;
+  return (ntiles + wg_rows - 1) / wg_rows;
+}
+
 hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T,
                                   int rule, int tiled, void* Xq, void* Xs, float* dbg, hipStream_t stream) {
   const int C = (int)(K / 32);
   const int col_groups = (C + kWaves * kNB - 1) / (kWaves * kNB);
   const int ntiles = (int)((M + kTileM - 1) / kTileM);
-  // Token walk per workgroup: 4 tiles amortize the register-resident T_b (measured
-  // best on 16384 x 4096); shorter walks when that would leave CUs without work.
-  int tiles_per_wg = 4;
-  while (tiles_per_wg > 1 && (int64_t)col_groups * ((ntiles + tiles_per_wg - 1) / tiles_per_wg) < 1024) tiles_per_wg >>= 1;
+  const int tiles_per_wg = token_walk(ntiles, col_groups);
   dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
   dim3 block(kWaves * 64);
 #define WUSH_TQ_LAUNCH(DBG, TILED)                                                                   \

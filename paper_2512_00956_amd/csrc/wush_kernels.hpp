@@ -7,6 +7,12 @@
 
 namespace wush {
 
+// Compute units of the current device (queried once).
+int device_cu_count();
+// Token tiles per workgroup of the fused transform + quantize kernels (ntiles 32-token tiles,
+// col_groups workgroups across the channels).
+int token_walk(int ntiles, int col_groups);
+
 // `tiled` != 0 selects the fragment-order layout of wush_device.hpp (K % 256 == 0).
 hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T,
                                   int rule, int tiled, void* Xq, void* Xs, float* dbg, hipStream_t stream);
