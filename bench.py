@@ -367,6 +367,41 @@ def nvfp4_bench(args, P, torch, dev):
                                                 "frac_hbm": qb / q_ms / 1e6 / PEAK_HBM_GBS, "algorithmic_bytes": qb},
                     "wush_linear_nvfp4": {"ms": g_ms, "TFLOP/s": flops / g_ms / 1e9}},
     }
+    if not args.no_ceilings:
+        # What this machine sustains now: the GEMM's FP16 MFMA in a register-only loop on all CUs, fed with the
+        # FP16 images of the workload's own packed operands (first 4096 elements of X and of W) and with
+        # all-equal operands; the shader clock during each.
+        def f16_image(q, s, rows):
+            qc = torch.empty((rows, K // 2), dtype=torch.uint8, device=dev)
+            sc = torch.empty((rows, K // 16), dtype=torch.uint8, device=dev)
+            if lay:
+                P.wush_unpack_tiled_nvfp4(q, s, rows, K, qc, sc)
+            else:
+                qc, sc = q.view(rows, K // 2), s.view(rows, K // 16)
+            b = qc[0, :2048].to(torch.int64)
+            codes = torch.stack([b & 15, b >> 4], dim=1).reshape(-1)
+            grid = torch.tensor([0, .5, 1, 1.5, 2, 3, 4, 6], device=dev)
+            val = grid[codes & 7] * (1.0 - 2.0 * (codes >> 3).float())
+            sv = sc[0, :256].view(torch.float8_e4m3fn).float().repeat_interleave(16)
+            return (val * sv).half()
+        cus = torch.cuda.get_device_properties(dev).multi_processor_count
+        ticks = torch.zeros((cus, 2), dtype=torch.int64, device=dev)
+        iters = 4000
+        flop_per_wg = 4.0 * iters * 64 * 2 * 32 * 32 * 16
+        real = torch.cat([f16_image(Xq, Xs, M), f16_image(Wq, Ws, N)]).contiguous()
+        equal = torch.ones(8192, dtype=torch.float16, device=dev)
+        ceil = {"compute_units": cus}
+        for name, bits in (("workload_bits", real), ("equal_operands", equal)):
+            for _ in range(2):
+                P.wush_probe_mfma_f16(bits, iters, cus, ticks)
+            torch.cuda.synchronize()
+            t = ticks.cpu().numpy().astype(np.float64)
+            ns = t[:, 1].mean() * 10.0
+            ceil[f"mfma_f16_only_{name}_tflops"] = cus * flop_per_wg / ns / 1e3
+            ceil[f"sclk_ghz_{name}"] = float((t[:, 0] / (t[:, 1] * 10.0)).mean())
+            ceil[f"cycles_per_mfma_{name}"] = float(t[:, 0].mean() / (iters * 64))
+        out["ceilings"] = ceil
+        out["roofline"]["frac_of_measured_mfma_ceiling"] = out["roofline"]["achieved"] / ceil["mfma_f16_only_workload_bits_tflops"]
     if not args.no_cpu_baseline:
         from oracle import wush_nvfp4_oracle as NV
         from oracle import wush_oracle as O

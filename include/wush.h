@@ -354,6 +354,16 @@ wush_status wush_probe_mfma(const void* operand_bits, int32_t iters, int32_t blo
                             void* cycles_ticks, void* stream);
 
 /*
+ * The same measurement for the FP16 MFMA (32x32x16) that wush_linear_nvfp4 contracts
+ * on: 64 independent MFMAs per trip.
+ *   operand_f16   in   16 KiB (device) of FP16 values: 8 KiB X-side + 8 KiB W-side
+ *   cycles_ticks  out  u64 [blocks][2] as above
+ * FLOP per workgroup = 4 waves * iters * 64 * 2*32*32*16.
+ */
+wush_status wush_probe_mfma_f16(const void* operand_f16, int32_t iters, int32_t blocks,
+                                void* cycles_ticks, void* stream);
+
+/*
  * Test tap: the quantizer alone on FP32 values (same device function the fused
  * kernel uses).  Yt f32 [M][K] (device) -> q u8 [M][K/2], s u8 [M][K/32].
  */

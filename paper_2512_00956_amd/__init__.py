@@ -33,6 +33,7 @@ from .binding import (  # noqa: F401
     wush_prepare_weight_nvfp4_workspace,
     wush_prepare_weight_workspace,
     wush_probe_mfma,
+    wush_probe_mfma_f16,
     wush_quantize_act,
     wush_quantize_act_nvfp4,
     wush_quantize_f32,
@@ -50,5 +51,5 @@ __all__ = [
     "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_status", "wush_prepare_weight_gptq_workspace",
     "wush_probe_mfma", "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_status",
     "wush_prepare_weight_nvfp4_workspace", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
-    "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4",
+    "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", "wush_probe_mfma_f16",
 ]

@@ -35,7 +35,7 @@ EXPORTS = (
     "wush_probe_mfma",
     "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_workspace",
     "wush_prepare_weight_nvfp4_status", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
-    "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4",
+    "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", "wush_probe_mfma_f16",
 )
 
 
@@ -118,6 +118,8 @@ def lib() -> ctypes.CDLL:
         L.wush_prepare_weight_gptq_status.argtypes = [c_void_p, c_int64, c_int64, c_void_p]
         L.wush_probe_mfma.restype = c_int32
         L.wush_probe_mfma.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
+        L.wush_probe_mfma_f16.restype = c_int32
+        L.wush_probe_mfma_f16.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
         L.wush_quantize_act_nvfp4.restype = c_int32
         L.wush_quantize_act_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_int32, c_void_p,
                                               c_void_p, c_void_p, c_void_p]
@@ -362,3 +364,9 @@ def wush_unpack_tiled_nvfp4(q_tiled, s_tiled, rows: int, K: int, q, s, stream=No
     """Tiled -> canonical copy (q u8 [rows][K/2], s u8 [rows][K/16])."""
     _check(lib().wush_unpack_tiled_nvfp4(_ptr(q_tiled), _ptr(s_tiled), rows, K, _ptr(q), _ptr(s), _stream(stream)),
            "wush_unpack_tiled_nvfp4")
+
+
+def wush_probe_mfma_f16(operand_f16, iters: int, blocks: int, cycles_ticks, stream=None):
+    """FP16 MFMA in a register-only loop; cycles_ticks: int64 tensor [blocks][2] (shader cycles, 100 MHz ticks)."""
+    _check(lib().wush_probe_mfma_f16(_ptr(operand_f16), iters, blocks, _ptr(cycles_ticks), _stream(stream)),
+           "wush_probe_mfma_f16")

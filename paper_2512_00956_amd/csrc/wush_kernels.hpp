@@ -88,5 +88,7 @@ hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, c
 
 // Measurement aid: register-only loop of the block-scaled FP4 MFMA (4 waves per workgroup, 64 MFMAs per trip).
 hipError_t launch_mfma_probe(const void* operand_bits, int iters, int blocks, void* out, hipStream_t stream);
+// The same for the FP16 MFMA of the NVFP4 GEMM (operands: 16 KiB of FP16 values).
+hipError_t launch_mfma_f16_probe(const void* operand_bits, int iters, int blocks, void* out, hipStream_t stream);
 
 }  // namespace wush

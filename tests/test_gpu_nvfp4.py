@@ -369,6 +369,21 @@ def test_layer_end_to_end_tiled(P, G, width, monkeypatch):
     assert O.rel_fro(Y.cpu().numpy().astype(np.float64), NV.layer_forward(X, W, T, tsx=ts)) <= 2e-3
 
 
+def test_f16_mfma_probe_reports_the_instruction_rate(P, G):
+    """The measurement aid of the NVFP4 GEMM's roofline: one 32x32x16 FP16 MFMA issues every 32 shader
+    cycles per wave, whatever the operand values; only the clock depends on them."""
+    import torch
+    vals = (torch.randn(8192, device="cuda") * 3).half()
+    out = torch.zeros((8, 2), dtype=torch.int64, device="cuda")
+    P.wush_probe_mfma_f16(vals, 200, 8, out)
+    torch.cuda.synchronize()
+    t = out.cpu().numpy().astype(np.float64)
+    per_mfma = t[:, 0] / (200 * 64)
+    assert np.all((per_mfma > 31.5) & (per_mfma < 36.0)), per_mfma
+    ghz = t[:, 0] / (t[:, 1] * 10.0)
+    assert np.all((ghz > 0.5) & (ghz < 3.0)), ghz
+
+
 def test_argument_validation(P, G):
     import torch
     Xq, Xs = G.empty_u8(4, 48), G.empty_u8(4, 6)     # K = 96: not a multiple of 64
