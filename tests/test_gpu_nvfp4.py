@@ -369,6 +369,64 @@ def test_layer_end_to_end_tiled(P, G, width, monkeypatch):
     assert O.rel_fro(Y.cpu().numpy().astype(np.float64), NV.layer_forward(X, W, T, tsx=ts)) <= 2e-3
 
 
+def test_c2_shape_full_size(P, G):
+    """The configuration bench.py times for workload n2 (2048 x 4096 -> 6144, tiled layout, BF16
+    output): sampled token rows, weight rows and output entries against the oracle."""
+    import torch
+    L = I.make_layer(I.CONFIGS["c2"])
+    cfg = L["cfg"]
+    M, K, N = cfg.M, cfg.K, cfg.N
+    T = np.empty((K // 16, 16, 16))
+    for b in range(K // 16):
+        sl = slice(16 * b, 16 * b + 16)
+        T[b] = O.wush_block(O.second_moment(O.bf16_bits_to_f64(L["W"][:, sl])),
+                            O.second_moment(O.bf16_bits_to_f64(L["X_cal"][:, sl])), 1e-2)
+    T = O.round_to_bf16(T)
+    rng = np.random.default_rng(22)
+    rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 48)]))
+    cols = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 256)]))
+    X = O.bf16_bits_to_f64(L["X"][rows])
+    Yt = NV.transform_act(X, T)
+    ts = np.float32(np.max(np.abs(Yt)) / 2688.0 * 1.5)      # a calibrated constant, not the exact batch maximum
+    Xd, Wd, Td = G.bf16_dev(L["X"]), G.bf16_dev(L["W"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    (xcb, xsb), (wcb, wsb) = P.wush_packed_sizes_nvfp4(M, K, 1), P.wush_packed_sizes_nvfp4(N, K, 1)
+    Xq, Xs, Wq, Ws = G.empty_u8(xcb), G.empty_u8(xsb), G.empty_u8(wcb), G.empty_u8(wsb)
+    tsx, tsw = _f32_dev(ts), torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = G.empty_u8(P.wush_prepare_weight_nvfp4_workspace(K))
+    P.wush_prepare_weight_nvfp4(Wd, Td, Wq, Ws, tsw, ws, layout=1)
+    P.wush_prepare_weight_nvfp4_status(ws, K)
+    P.wush_quantize_act_nvfp4(Xd, Td, tsx, Xq, Xs, layout=1)
+    Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    P.wush_linear_nvfp4(Xq, Xs, tsx, Wq, Ws, tsw, Y, layout=1, K=K)
+    Xqc, Xsc, Wqc, Wsc = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16), G.empty_u8(N, K // 2), G.empty_u8(N, K // 16)
+    P.wush_unpack_tiled_nvfp4(Xq, Xs, M, K, Xqc, Xsc)
+    P.wush_unpack_tiled_nvfp4(Wq, Ws, N, K, Wqc, Wsc)
+    torch.cuda.synchronize()
+    assert not bool(Y.isnan().any())
+    # activation rows against the all-FP64 path
+    xq, xs = Xqc[rows.tolist()].cpu().numpy(), Xsc[rows.tolist()].cpu().numpy()
+    c64, s64 = NV.quantize_nvfp4(Yt, np.float64(ts), prec=np.float64)
+    rate, unexplained = _explained(Yt, ts, O.unpack_codes(xq), xs, c64, s64, tol=1e-5)
+    assert rate <= 2e-4 and unexplained == 0, ("activation codes", rate, unexplained)
+    # weight rows (= output columns): the tensor scale needs the whole tensor, so take the GPU's
+    # (checked against the oracle's on the small shapes) and verify it bounds the sampled rows
+    ts_w = np.float32(tsw.cpu().numpy()[0])
+    Wt = NV.transform_weight(O.bf16_bits_to_f64(L["W"][cols]), T)
+    assert np.max(np.abs(Wt)) <= float(ts_w) * 2688.0 * (1 + 1e-6)
+    cw, sw = NV.quantize_nvfp4(Wt, np.float64(ts_w), prec=np.float64)
+    wq, wsb_ = Wqc[cols.tolist()].cpu().numpy(), Wsc[cols.tolist()].cpu().numpy()
+    rate, unexplained = _explained(Wt, ts_w, O.unpack_codes(wq), wsb_, cw, sw, tol=1e-9)
+    assert rate <= 1e-4 and unexplained == 0, ("weight codes", rate, unexplained)
+    # output entries: the GEMM on the GPU's own codes, and the oracle's whole forward
+    y = O.bf16_bits_to_f64(G.host(Y[rows.tolist()][:, cols.tolist()].contiguous()))
+    own = NV.linear_dequant(O.unpack_codes(xq), xs, ts, O.unpack_codes(wq), wsb_, ts_w)
+    assert O.rel_fro(y, own) <= 2e-3
+    ref = NV.linear_dequant(c64, s64, ts, cw, sw, ts_w)
+    exact = X @ O.bf16_bits_to_f64(L["W"][cols]).T
+    q_err = O.rel_fro(ref, exact)
+    assert O.rel_fro(y, ref) <= max(2e-3, 0.05 * q_err) and q_err < 0.25, (O.rel_fro(y, ref), q_err)
+
+
 def test_f16_mfma_probe_reports_the_instruction_rate(P, G):
     """The measurement aid of the NVFP4 GEMM's roofline: one 32x32x16 FP16 MFMA issues every 32 shader
     cycles per wave, whatever the operand values; only the clock depends on them."""
