@@ -1,0 +1,179 @@
+"""Pins of the INT4 oracle (oracle/wush_int4_oracle.py) to things other than itself:
+numerical integration and the textbook optimum of the Gaussian quantizer, exact
+rational brute force, error bounds, and the directions the paper's Table 1 reports."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy import integrate, optimize
+
+from oracle import wush_int4_oracle as Q
+from oracle import wush_oracle as O
+
+
+# ---------------------------------------------------------------- the clipping constant
+def test_gaussian_mse_closed_form_matches_numerical_integration():
+    for step in (0.2, 0.3386, 0.5):
+        def integrand(x):
+            q = min(max(round(x / step), -8), 7)       # Python's round is half-to-even
+            return (x - q * step) ** 2 * np.exp(-0.5 * x * x) / np.sqrt(2 * np.pi)
+        edges = [-12.0] + [(k + 0.5) * step for k in range(-8, 7)] + [12.0]
+        num = sum(integrate.quad(integrand, a, b, epsabs=1e-13)[0] for a, b in zip(edges[:-1], edges[1:]))
+        assert abs(Q.gaussian_mse(step) - num) < 1e-9
+
+
+def test_textbook_optimum_of_the_16_level_uniform_quantizer():
+    """Max's table for the Gaussian: the 16-level uniform (mid-rise) quantizer has its
+    minimum distortion 0.01154 at step 0.3352."""
+    def mse(step):
+        return Q.gaussian_mse(step, levels=[(k + 0.5) * step for k in range(-8, 8)])
+    r = optimize.minimize_scalar(mse, bounds=(0.1, 0.6), method="bounded", options={"xatol": 1e-10})
+    assert abs(r.x - 0.3352) < 5e-5 and abs(r.fun - 0.01154) < 5e-6
+
+
+def test_step_constant_is_the_minimizer_for_the_int4_grid():
+    r = optimize.minimize_scalar(Q.gaussian_mse, bounds=(0.1, 0.6), method="bounded", options={"xatol": 1e-12})
+    assert abs(r.x - Q.STEP) < 2e-7
+    assert Q.gaussian_mse(Q.STEP) - r.fun < 1e-14
+    # a brute-force scan agrees (no local minimum elsewhere in a wide bracket)
+    grid = np.linspace(0.05, 1.5, 2901)
+    assert abs(grid[np.argmin([Q.gaussian_mse(s) for s in grid])] - Q.STEP) <= 5e-4
+
+
+def test_measured_error_on_gaussian_data_matches_the_theory():
+    rng = np.random.default_rng(0)
+    y = rng.standard_normal((4096, 32 * 8)).astype(np.float32) * 3.0
+    q, s = Q.quantize_int4(y)
+    err = np.mean((y - Q.dequantize_int4(q, s)) ** 2) / 9.0
+    # sigma is the RMS of the very 32 samples that are quantized, which gains a little on the 0.011864
+    # of a fixed step on a unit Gaussian (a group with a large sample gets a larger step)
+    assert 0.0100 < err < 0.0119
+    # a step 20 % off in either direction loses (the constant is at the minimum, not merely near it)
+    for f in (0.8, 1.25):
+        gr = y.reshape(4096, 8, 32).astype(np.float64)
+        sc = f * Q.STEP * np.sqrt(np.mean(gr ** 2, axis=-1, keepdims=True))
+        assert np.mean((gr - np.clip(np.rint(gr / sc), -8, 7) * sc) ** 2) / 9.0 > err
+
+
+# ---------------------------------------------------------------- quantizer
+def _exact_reference(y):
+    """Scale and codes from exact arithmetic (sigma via a 60-digit square root)."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    qs = np.zeros(y.shape, dtype=np.int8)
+    sc = np.zeros(y.shape[0])
+    for g in range(y.shape[0]):
+        vals = [Fraction(float(v)) for v in y[g]]
+        ss = sum(v * v for v in vals) / 32
+        sigma = (Decimal(ss.numerator) / Decimal(ss.denominator)).sqrt()
+        s_real = float(Decimal(repr(float(np.float32(Q.STEP)))) * sigma)
+        s = float(O.round_to_bf16(np.array([s_real]))[0])
+        sc[g] = s
+        for i, v in enumerate(vals):
+            if s == 0:
+                continue
+            r = v / Fraction(s)
+            k = min(range(-8, 8), key=lambda c: (abs(c - r), c % 2))        # nearest, ties to even
+            qs[g, i] = k
+    return qs, sc
+
+
+@pytest.mark.parametrize("prec", [np.float32, np.float64])
+def test_quantizer_against_exact_rational_brute_force(prec):
+    rng = np.random.default_rng(5)
+    y = (rng.standard_normal((300, 32)) * np.exp(rng.uniform(-6, 6, (300, 1)))).astype(np.float32)
+    q, sb = Q.quantize_int4(y, prec=prec)
+    qe, se = _exact_reference(y)
+    s = O.bf16_bits_to_f64(sb)[:, 0]
+    # rounded sums may move STEP * sigma across a BF16 rounding boundary: rare, and then by one BF16 step
+    assert np.mean(s != se) <= 0.02
+    assert np.all(np.abs(s - se) <= se * 2.0 ** -7)
+    same = s == se
+    assert np.mean(q[same] != qe[same]) <= (1e-3 if prec == np.float32 else 1e-9)
+    assert np.all(np.abs(q[same].astype(int) - qe[same]) <= 1)
+
+
+def test_error_bound_and_clipping():
+    rng = np.random.default_rng(3)
+    y = (rng.standard_normal((64, 256)) * np.exp(rng.uniform(-3, 3, (64, 1)))).astype(np.float32)
+    q, sb = Q.quantize_int4(y)
+    s = np.repeat(O.bf16_bits_to_f64(sb), 32, axis=-1)
+    deq = Q.dequantize_int4(q, sb)
+    inside = (y / s >= -8.5) & (y / s <= 7.5)
+    assert np.all(np.abs(y - deq)[inside] <= 0.5 * s[inside] * (1 + 1e-6))
+    assert np.all(q[y / s > 7.5] == 7) and np.all(q[y / s < -8.5] == -8)
+    # with STEP * sigma as the step about 1 % of Gaussian samples are clipped (beyond 7.5 * 0.3386 = 2.54 sigma)
+    assert 0.002 < np.mean(~inside) < 0.03
+    assert q.min() >= -8 and q.max() <= 7
+
+
+def test_worked_group_and_zero_group():
+    # all entries +-a: sigma = a, scale = BF16(STEP * a), every |v| / scale = 1 / STEP = 2.95 -> |q| = 3
+    y = np.full((1, 32), 2.0, dtype=np.float32)
+    y[0, ::2] *= -1
+    q, sb = Q.quantize_int4(y)
+    assert O.bf16_bits_to_f64(sb)[0, 0] == float(O.round_to_bf16(np.array([np.float32(Q.STEP) * np.float32(2.0)]))[0])
+    assert np.array_equal(q[0], np.where(np.arange(32) % 2 == 0, -3, 3))
+    q0, s0 = Q.quantize_int4(np.zeros((1, 32), dtype=np.float32))
+    assert not q0.any() and not s0.any()
+
+
+def test_power_of_two_invariance_and_packing():
+    rng = np.random.default_rng(9)
+    y = rng.standard_normal((8, 64)).astype(np.float32)
+    q0, s0 = Q.quantize_int4(y)
+    q1, s1 = Q.quantize_int4(y * np.float32(2.0 ** 7))
+    assert np.array_equal(q0, q1)
+    assert np.array_equal(O.bf16_bits_to_f64(s1), O.bf16_bits_to_f64(s0) * 2.0 ** 7)
+    p = Q.pack_codes(q0)
+    assert p.shape == (8, 32) and np.array_equal(Q.unpack_codes(p), q0)
+    assert Q.pack_codes(np.array([[-8, 7]]))[0, 0] == 0x78 and Q.pack_codes(np.array([[-1, 1]]))[0, 0] == 0x1F
+
+
+# ---------------------------------------------------------------- layer
+def _heavy_tailed_layer(seed, M=256, K=256, N=128):
+    rng = np.random.default_rng(seed)
+    ch = np.exp(rng.standard_normal(K))
+    ch[rng.choice(K, 4, replace=False)] *= 30
+    X = O.round_to_bf16(rng.standard_normal((M, K)) * ch)
+    Xc = O.round_to_bf16(rng.standard_normal((4 * M, K)) * ch)
+    W = O.round_to_bf16(rng.standard_normal((N, K)) * 0.02 * np.exp(0.5 * rng.standard_normal((N, 1))))
+    return X, Xc, W
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_table1_directions_on_synthetic_data(seed):
+    """Table 1, INT4 rows: the Hadamard transform loses less than the identity, WUSH less than Hadamard."""
+    X, Xc, W = _heavy_tailed_layer(seed)
+    Y = X @ W.T
+    C = X.shape[1] // 32
+    eye = np.broadcast_to(np.eye(32), (C, 32, 32)).copy()
+    had = O.round_to_bf16(O.hadamard_transforms(C))
+    wush = O.round_to_bf16(O.build_transforms(W, Xc, 1e-2))
+    l_i, l_h, l_w = (O.layer_loss(Q.layer_forward(X, W, T), Y) for T in (eye, had, wush))
+    assert l_w < l_h < l_i
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_table1_pattern_across_formats(seed):
+    """What identifies the scale rule in Table 1: with the identity transform INT4 loses an order of
+    magnitude more than MXFP4 (the RMS-based step clips the outlier channels: 170 against 11.1 in the
+    paper's first column), while behind a Hadamard or WUSH transform it loses less than MXFP4 (5.57 / 7.24
+    and 2.39 / 3.34).  An AbsMax-based step would show neither."""
+    X, Xc, W = _heavy_tailed_layer(seed)
+    Y = X @ W.T
+    C = X.shape[1] // 32
+    eye = np.broadcast_to(np.eye(32), (C, 32, 32)).copy()
+    had = O.round_to_bf16(O.hadamard_transforms(C))
+    wush = O.round_to_bf16(O.build_transforms(W, Xc, 1e-2))
+    ratio = [O.layer_loss(Q.layer_forward(X, W, T), Y) / O.layer_loss(O.layer_forward(X, W, T), Y)
+             for T in (eye, had, wush)]
+    assert ratio[0] > 3.0
+    assert 0.6 < ratio[1] < 1.0 and 0.6 < ratio[2] < 1.0
+
+
+def test_forward_reproduces_the_unquantized_product_up_to_the_quantization_error():
+    X, Xc, W = _heavy_tailed_layer(4)
+    T = O.round_to_bf16(O.build_transforms(W, Xc, 1e-2))
+    Y = X @ W.T
+    assert O.rel_fro(Q.layer_forward(X, W, T), Y) < 0.2
