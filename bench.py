@@ -16,7 +16,7 @@ Prints ONE JSON line:
              workload's own operand bits, and with all-equal operands), the shader clock
              under each, and a plain 1 GiB device copy
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|d2|d5|fig3|n2|n5]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|d2|d5|fig3|n2|n5|i2|i5]
 
 The decode workloads d2/d5 time wush_layer_decode (16 tokens) by replaying a
 captured graph of the steps, so that the host's launch cost is not what is
@@ -66,7 +66,10 @@ FIG3_LAYERS = [  # (name, K, N)
 ]
 WORKLOADS["n2"] = "the c2 layer in the NVFP4 variant (E4M3 scale per 16, 16 x 16 transforms), M=2048 K=4096 N=6144"
 WORKLOADS["n5"] = "the c5 layer in the NVFP4 variant, M=8192 K=8192 N=57344"
+WORKLOADS["i2"] = "the c2 layer in the INT4 variant (BF16 scale per 32, Gaussian-MSE step), M=2048 K=4096 N=6144"
+WORKLOADS["i5"] = "the c5 layer in the INT4 variant, M=8192 K=8192 N=57344"
 NVFP4 = {"n2": "c2", "n5": "c5"}
+INT4 = {"i2": "c2", "i5": "c5"}
 DECODE = {"d2": "c2", "d5": "c5"}
 DECODE_TOKENS = 16
 
@@ -421,6 +424,103 @@ def nvfp4_bench(args, P, torch, dev):
     print(json.dumps(out))
 
 
+def int4_bench(args, P, torch, dev):
+    """The layer forward in the INT4 variant: wush_quantize_act_int4 + wush_linear_int4 per step; the GEMM is the
+    NVFP4 one with another dequantization and is priced against the FP16 MFMA peak."""
+    cfg = I.CONFIGS[INT4[args.workload]]
+    L = I.make_layer(cfg)
+    M, K, N = cfg.M, cfg.K, cfg.N
+
+    def bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    Td = torch.empty((K // 32, 32, 32), dtype=torch.bfloat16, device=dev)
+    bws = torch.empty(P.wush_build_transforms_workspace(K), dtype=torch.uint8, device=dev)
+    Wd = bf16(L["W"])
+    P.wush_build_transforms(Wd, bf16(L["X_cal"]), 1e-2, Td, bws)
+    P.wush_build_transforms_status(bws, K)
+    del bws
+    T_bits = Td.view(torch.int16).cpu().numpy().view(np.uint16)
+    Xd = bf16(L["X"])
+    lay = 1 if args.layout == "tiled" else 0
+    (xcb, xsb), (wcb, wsb) = P.wush_packed_sizes_nvfp4(M, K, lay), P.wush_packed_sizes_nvfp4(N, K, lay)
+    Xq = torch.empty(xcb, dtype=torch.uint8, device=dev)
+    Xs = torch.empty(xsb, dtype=torch.uint8, device=dev)
+    Wq = torch.empty(wcb, dtype=torch.uint8, device=dev)
+    Ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    wsp = torch.empty(P.wush_prepare_weight_workspace(N, K), dtype=torch.uint8, device=dev)
+    P.wush_prepare_weight_int4(Wd, Td, Wq, Ws, wsp, layout=lay)
+    P.wush_workspace_status(wsp, K)
+    del Wd
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+
+    def quant(i):
+        P.wush_quantize_act_int4(Xd, Td, Xq, Xs, layout=lay)
+
+    def gemm(i):
+        P.wush_linear_int4(Xq, Xs, Wq, Ws, Y, layout=lay, K=K)
+
+    def step(i):
+        quant(i)
+        gemm(i)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    def kernel_ms(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    q_ms, g_ms = kernel_ms(quant), kernel_ms(gemm)
+    qb = M * K * (2 + 0.5 + 1 / 16) + (K // 32) * 2048
+    flops = 2.0 * M * N * K
+    out = {
+        "metric": "W4A4 layer TFLOP/s (transform+quant+INT4 GEMM); % of FP16 MFMA peak",
+        "value": flops / ms_per_step / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4 (two's complement x bf16 per 32), bf16 in/out, f16 MFMA operands, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
+                   "packed_layout": args.layout, "launch": "host loop"},
+        "roofline": {"bound": "mfma", "kernel": "wush_linear_int4 (dequantize to FP16 in LDS + FP16 MFMA)",
+                     "achieved": flops / g_ms / 1e9, "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops / g_ms / 1e9 / PEAK_F16_TFLOPS, "traffic": None, "avg_launch_ms": g_ms},
+        "kernels": {"wush_quantize_act_int4": {"ms": q_ms, "GB/s": qb / q_ms / 1e6,
+                                               "frac_hbm": qb / q_ms / 1e6 / PEAK_HBM_GBS, "algorithmic_bytes": qb},
+                    "wush_linear_int4": {"ms": g_ms, "TFLOP/s": flops / g_ms / 1e9}},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import wush_int4_oracle as Q4
+        from oracle import wush_oracle as O
+        rows, n_out = min(M, {"i2": 1024, "i5": 64}[args.workload]), min(N, 8192)
+        T = O.bf16_bits_to_f64(T_bits)
+        wq, wsb_ = Q4.quantize_int4(O.transform_weight(O.bf16_bits_to_f64(L["W"][:n_out]), T), prec=np.float64)
+        X = O.bf16_bits_to_f64(L["X"][:rows])
+        t0 = time.perf_counter()
+        xq, xsb_ = Q4.quantize_int4(O.transform_act(X, T).astype(np.float32))
+        Q4.linear_dequant(xq, xsb_, wq, wsb_)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2.0 * rows * n_out * K / dt / 1e12, "unit": "TFLOP/s",
+                               "cores": len(os.sched_getaffinity(0)), "kind": "oracle", "seconds": dt,
+                               "sample": f"INT4 oracle layer forward on the first {rows} of {M} tokens and the first "
+                                         f"{n_out} of {N} output channels, full K, weights pre-quantized"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -461,6 +561,9 @@ def main():
         return
     if args.workload in NVFP4:
         nvfp4_bench(args, P, torch, dev)
+        return
+    if args.workload in INT4:
+        int4_bench(args, P, torch, dev)
         return
 
     cfg = I.CONFIGS[args.workload]

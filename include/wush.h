@@ -340,6 +340,52 @@ wush_status wush_unpack_tiled_nvfp4(const void* q_tiled, const void* s_tiled, in
                                     void* q, void* s, void* stream);
 
 /*
+ * ---------------------------------------------------------------------------
+ * INT4 variant (paper, "Layerwise Quantization Loss" / Table 1: "4-bit integers with
+ * Gaussian MSE clipping and BF16 scales of group size 32"; transform blocks of 32 as
+ * for MXFP4, same T_blocks tensor).  Codes: two's-complement nibbles -8 .. 7 (even k =
+ * low nibble); one BF16 scale per 32 consecutive channels; value = code * scale.
+ * Readings: scale = BF16(STEP * root-mean-square of the group), STEP = 0.33860793 = the
+ * step that minimizes the mean squared error of this 16-level grid on a unit Gaussian
+ * (values beyond -8.5 / 7.5 steps are clipped); code = clip(round-half-even(v / scale));
+ * a scale below BF16's normal range is stored as 0 and gives code 0.  One IEEE
+ * operation per step, FP32 for activations and FP64 for weights, no fused multiply-add
+ * in the sum of squares (channels 0..15 left to right, 16..31 left to right, the two
+ * sums added; sigma = sqrt(ss / 32); rcp = 1 / scale; v * rcp rounded).
+ * Packed layouts: canonical = codes u8 [rows][K/2], scales u16 [rows][K/32]; tiled = the
+ * NVFP4 tiled layout (the 4 scale bytes of a K step of 64 are its two BF16 scales;
+ * K % 64 == 0); wush_packed_sizes_nvfp4 / wush_unpack_tiled_nvfp4 serve both formats
+ * (same geometry: 4 bits per code, 4 scale bytes per 64 channels).
+ * ---------------------------------------------------------------------------
+ */
+wush_status wush_quantize_act_int4(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T_blocks,
+                                   int32_t layout, void* Xq, void* Xs, float* dbg_Yt, void* stream);
+
+/*
+ * Offline weight side in INT4 (Alg. 2, RTN case): as wush_prepare_weight (FP64 inverse
+ * of every block, W_blk inv(T_b) in FP64), then the quantizer above in FP64.  Workspace
+ * and status: wush_prepare_weight_workspace / wush_workspace_status.
+ */
+wush_status wush_prepare_weight_int4(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T_blocks,
+                                     int32_t layout, void* Wq, void* Ws,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * INT4 x INT4 GEMM, FP32 accumulation: Y = deq(Xq,Xs) . deq(Wq,Ws)^T, by the kernel of
+ * wush_linear_nvfp4 with another dequantization (code * scale is exact in FP16 while
+ * the scale lies in FP16's normal range, 2^-14 .. 8188; smaller scales lose bits below
+ * 2^-24, larger ones overflow: rescale the tensor by a power of two beforehand).
+ * K % 64 == 0.
+ */
+wush_status wush_linear_int4(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
+                             int64_t M, int64_t N, int64_t K, int32_t layout, int32_t out_dtype,
+                             void* Y, int64_t ldy, void* stream);
+
+/* Test tap: the INT4 quantizer alone on FP32 values. Yt f32 [M][K] -> q, s in `layout`. */
+wush_status wush_quantize_f32_int4(const float* Yt, int64_t M, int64_t K, int32_t layout,
+                                   void* q, void* s, void* stream);
+
+/*
  * Measurement aid for the roofline of wush_linear (for benchmark harnesses: it
  * computes nothing of the layer): `blocks` workgroups of four waves run `iters`
  * trips of 64 independent block-scaled FP4 MFMAs (32x32x64) on registers only.

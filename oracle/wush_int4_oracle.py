@@ -19,8 +19,8 @@ Readings of what the paper leaves open (listed in the design notes as well):
     what Table 1 shows: with the identity transform INT4 loses an order of
     magnitude more than MXFP4 (outlier channels are clipped), behind a Hadamard
     or WUSH transform it loses less -- a pattern an AbsMax-based step would not give.
-  * elements: q = clip(round-half-even(v / scale), -8, 7); scale 0 (an all-zero
-    group) gives q = 0.
+  * elements: q = clip(round-half-even(v / scale), -8, 7); a scale below BF16's
+    normal range (an all-zero group) is stored as 0 and gives q = 0.
   * arithmetic: every step is one IEEE operation in ONE working precision `prec`
     (FP32 for activations, the precision of the kernel's accumulators; FP64 for
     the offline weight path), in this order:
@@ -89,15 +89,17 @@ def quantize_int4(Y: np.ndarray, prec=np.float32):
     Y = np.asarray(Y, dtype=prec)
     *lead, K = Y.shape
     Gr = Y.reshape(-1, K // G, G)
-    t = (Gr * Gr).astype(prec)
-    s_lo = np.zeros(t.shape[:2], dtype=prec)
-    s_hi = np.zeros(t.shape[:2], dtype=prec)
-    for i in range(16):                                    # left to right, one rounding per addition
-        s_lo = (s_lo + t[..., i]).astype(prec)
-        s_hi = (s_hi + t[..., 16 + i]).astype(prec)
-    ss = (s_lo + s_hi).astype(prec)
-    sigma = np.sqrt((ss / prec(32)).astype(prec)).astype(prec)
-    sbits = round_to_bf16_bits((prec(STEP) * sigma).astype(prec))
+    with np.errstate(over="ignore"):                           # squares beyond the range of `prec` give an infinite scale
+        t = (Gr * Gr).astype(prec)
+        s_lo = np.zeros(t.shape[:2], dtype=prec)
+        s_hi = np.zeros(t.shape[:2], dtype=prec)
+        for i in range(16):                                    # left to right, one rounding per addition
+            s_lo = (s_lo + t[..., i]).astype(prec)
+            s_hi = (s_hi + t[..., 16 + i]).astype(prec)
+        ss = (s_lo + s_hi).astype(prec)
+        sigma = np.sqrt((ss / prec(32)).astype(prec)).astype(prec)
+        sbits = round_to_bf16_bits((prec(STEP) * sigma).astype(prec))
+    sbits = np.where(sbits < 0x80, 0, sbits).astype(np.uint16)      # below BF16's normal range: an empty group
     scale = O.bf16_bits_to_f64(sbits).astype(prec)
     with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
         rcp = (prec(1) / scale).astype(prec)

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     wush_layer_decode_status,
     wush_layer_decode_workspace,
     wush_linear,
+    wush_linear_int4,
     wush_linear_nvfp4,
     wush_packed_sizes,
     wush_packed_sizes_nvfp4,
@@ -28,6 +29,7 @@ from .binding import (  # noqa: F401
     wush_prepare_weight_gptq,
     wush_prepare_weight_gptq_status,
     wush_prepare_weight_gptq_workspace,
+    wush_prepare_weight_int4,
     wush_prepare_weight_nvfp4,
     wush_prepare_weight_nvfp4_status,
     wush_prepare_weight_nvfp4_workspace,
@@ -35,8 +37,10 @@ from .binding import (  # noqa: F401
     wush_probe_mfma,
     wush_probe_mfma_f16,
     wush_quantize_act,
+    wush_quantize_act_int4,
     wush_quantize_act_nvfp4,
     wush_quantize_f32,
+    wush_quantize_f32_int4,
     wush_quantize_f32_nvfp4,
     wush_status_string,
     wush_workspace_status,
@@ -52,4 +56,5 @@ __all__ = [
     "wush_probe_mfma", "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_status",
     "wush_prepare_weight_nvfp4_workspace", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
     "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", "wush_probe_mfma_f16",
+    "wush_quantize_act_int4", "wush_prepare_weight_int4", "wush_linear_int4", "wush_quantize_f32_int4",
 ]

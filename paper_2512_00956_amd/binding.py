@@ -36,6 +36,7 @@ EXPORTS = (
     "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_workspace",
     "wush_prepare_weight_nvfp4_status", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
     "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", "wush_probe_mfma_f16",
+    "wush_quantize_act_int4", "wush_prepare_weight_int4", "wush_linear_int4", "wush_quantize_f32_int4",
 )
 
 
@@ -118,6 +119,17 @@ def lib() -> ctypes.CDLL:
         L.wush_prepare_weight_gptq_status.argtypes = [c_void_p, c_int64, c_int64, c_void_p]
         L.wush_probe_mfma.restype = c_int32
         L.wush_probe_mfma.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
+        L.wush_quantize_act_int4.restype = c_int32
+        L.wush_quantize_act_int4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_void_p, c_void_p,
+                                             c_void_p, c_void_p]
+        L.wush_prepare_weight_int4.restype = c_int32
+        L.wush_prepare_weight_int4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_void_p, c_void_p,
+                                               c_void_p, c_size_t, c_void_p]
+        L.wush_linear_int4.restype = c_int32
+        L.wush_linear_int4.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int32,
+                                       c_int32, c_void_p, c_int64, c_void_p]
+        L.wush_quantize_f32_int4.restype = c_int32
+        L.wush_quantize_f32_int4.argtypes = [c_void_p, c_int64, c_int64, c_int32, c_void_p, c_void_p, c_void_p]
         L.wush_probe_mfma_f16.restype = c_int32
         L.wush_probe_mfma_f16.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
         L.wush_quantize_act_nvfp4.restype = c_int32
@@ -370,3 +382,39 @@ def wush_probe_mfma_f16(operand_f16, iters: int, blocks: int, cycles_ticks, stre
     """FP16 MFMA in a register-only loop; cycles_ticks: int64 tensor [blocks][2] (shader cycles, 100 MHz ticks)."""
     _check(lib().wush_probe_mfma_f16(_ptr(operand_f16), iters, blocks, _ptr(cycles_ticks), _stream(stream)),
            "wush_probe_mfma_f16")
+
+
+# ---------------------------------------------------------------------------
+# INT4 variant (two's-complement codes, BF16 scale per 32; transforms bf16 [K/32][32][32]).
+# Packed sizes / unpacking: wush_packed_sizes_nvfp4, wush_unpack_tiled_nvfp4 (same geometry).
+# ---------------------------------------------------------------------------
+def wush_quantize_act_int4(X, T_blocks, Xq, Xs, layout: int = WUSH_LAYOUT_CANONICAL, dbg_Yt=None, stream=None):
+    """X bf16 [M][K] -> Xq u8 [M][K/2], Xs: BF16 scales [M][K/32] (2 bytes each; canonical shapes)."""
+    M, K = X.shape
+    _check(lib().wush_quantize_act_int4(_ptr(X), M, K, X.stride(0), _ptr(T_blocks), layout, _ptr(Xq), _ptr(Xs),
+                                        _ptr(dbg_Yt), _stream(stream)), "wush_quantize_act_int4")
+
+
+def wush_prepare_weight_int4(W, T_blocks, Wq, Ws, workspace, layout: int = WUSH_LAYOUT_CANONICAL, stream=None):
+    """W bf16 [N][K] -> Wq, Ws in `layout`; workspace as for wush_prepare_weight."""
+    N, K = W.shape
+    _check(lib().wush_prepare_weight_int4(_ptr(W), N, K, W.stride(0), _ptr(T_blocks), layout, _ptr(Wq), _ptr(Ws),
+                                          _ptr(workspace),
+                                          0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                          _stream(stream)), "wush_prepare_weight_int4")
+
+
+def wush_linear_int4(Xq, Xs, Wq, Ws, Y, layout: int = WUSH_LAYOUT_CANONICAL, out_dtype: int = WUSH_OUT_BF16,
+                     stream=None, K: int | None = None):
+    """Y [M][N] = deq(Xq, Xs) . deq(Wq, Ws)^T; K from the canonical shape of Xq unless given."""
+    M, N = Y.shape
+    if K is None:
+        K = 2 * Xq.shape[-1]
+    _check(lib().wush_linear_int4(_ptr(Xq), _ptr(Xs), _ptr(Wq), _ptr(Ws), M, N, K, layout, out_dtype, _ptr(Y),
+                                  Y.stride(0), _stream(stream)), "wush_linear_int4")
+
+
+def wush_quantize_f32_int4(Yt, q, s, layout: int = WUSH_LAYOUT_CANONICAL, stream=None):
+    M, K = Yt.shape
+    _check(lib().wush_quantize_f32_int4(_ptr(Yt), M, K, layout, _ptr(q), _ptr(s), _stream(stream)),
+           "wush_quantize_f32_int4")

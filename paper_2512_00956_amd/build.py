@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwush.so")
-SOURCES = ["wush_api.hip", "transform_quant.hip", "weight_prep.hip", "mxfp4_gemm.hip", "mxfp4_gemm_frag.hip", "build_transforms.hip", "layer_decode.hip", "gptq_prep.hip", "probe.hip", "nvfp4_quant.hip", "nvfp4_gemm.hip"]
+SOURCES = ["wush_api.hip", "transform_quant.hip", "weight_prep.hip", "mxfp4_gemm.hip", "mxfp4_gemm_frag.hip", "build_transforms.hip", "layer_decode.hip", "gptq_prep.hip", "probe.hip", "nvfp4_quant.hip", "nvfp4_gemm.hip", "int4_quant.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

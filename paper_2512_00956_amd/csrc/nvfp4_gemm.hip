@@ -1,4 +1,6 @@
-// NVFP4 x NVFP4 GEMM with FP32 accumulation for gfx950:
+// GEMMs of the two 4-bit formats without a block-scaled MFMA path, NVFP4 and INT4 (BF16 scale per
+// 32; element * scale has at most 3 + 8 significant bits: exact in FP16 as long as the scale lies in
+// FP16's normal range), with FP32 accumulation for gfx950.  Written for NVFP4:
 //   Y = tsx tsw * deq(Xq, Xs) . deq(Wq, Ws)^T
 // (the sum over blocks of the layer forward-pass equation, in the NVFP4 variant
 // of the paper's experiments: E2M1 elements, E4M3 scale per 16, FP32 tensor scale).
@@ -96,21 +98,47 @@ __device__ __forceinline__ v4u dequant8(uint32_t w, v2h s) {
   return c.u;
 }
 
+// Eight two's-complement INT4 codes times the group scale -> 8 FP16.  A nibble n becomes the
+// FP16 number 1024 + (n ^ 8) by OR-ing it into the fraction of 0x6400; subtracting 1032 leaves
+// the signed code, exactly; code * scale has at most 3 + 8 significant bits: exact in FP16 too.
+__device__ __forceinline__ v4u dequant8_int4(uint32_t w, v2h s) {
+  const uint32_t x = w ^ 0x88888888u, y = x >> 4;
+  const v2h bias = {(_Float16)1032.0f, (_Float16)1032.0f};
+  union { v2h h[4]; v4u u; uint32_t d[4]; } c;
+  c.d[0] = (__builtin_amdgcn_perm(y, x, 0x0C040C00u) & 0x000F000Fu) | 0x64006400u;
+  c.d[1] = (__builtin_amdgcn_perm(y, x, 0x0C050C01u) & 0x000F000Fu) | 0x64006400u;
+  c.d[2] = (__builtin_amdgcn_perm(y, x, 0x0C060C02u) & 0x000F000Fu) | 0x64006400u;
+  c.d[3] = (__builtin_amdgcn_perm(y, x, 0x0C070C03u) & 0x000F000Fu) | 0x64006400u;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) c.h[i] = (c.h[i] - bias) * s;
+  return c.u;
+}
+
+constexpr int kNvfp4 = 0, kInt4 = 1;
+
 // Group g (16 elements) of a row's K step: two 16-byte LDS chunks, k = 16g + 8hh + 0..7.
-// `operand` = the X or W part of a stage, `rows` = its row count.
+// `operand` = the X or W part of a stage, `rows` = its row count.  The row's scale dword holds
+// four E4M3 bytes (NVFP4: one per 16 elements) or two BF16 numbers (INT4: one per 32).
+template <int FMT>
 __device__ __forceinline__ void convert_group(const Raw& r, int g, char* operand, int rows, int row) {
-  const v2h pair = g < 2 ? e4m3x2_to_f16<false>(r.s) : e4m3x2_to_f16<true>(r.s);
-  const _Float16 sc = pair[g & 1];
+  _Float16 sc;
+  if (FMT == kNvfp4) {
+    const v2h pair = g < 2 ? e4m3x2_to_f16<false>(r.s) : e4m3x2_to_f16<true>(r.s);
+    sc = pair[g & 1];
+  } else {
+    sc = (_Float16)__uint_as_float(g < 2 ? r.s << 16 : r.s & 0xFFFF0000u);
+  }
   const v2h s = {sc, sc};
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh) {
     const uint32_t w = r.q[g >> 1][(g & 1) * 2 + hh];
-    *reinterpret_cast<v4u*>(operand + ((2 * g + hh) * rows + row) * 16) = dequant8(w, s);
+    *reinterpret_cast<v4u*>(operand + ((2 * g + hh) * rows + row) * 16) =
+        FMT == kNvfp4 ? dequant8(w, s) : dequant8_int4(w, s);
   }
 }
 
-template <bool OUT_F32, int CB>
-__global__ __launch_bounds__(256) void nvfp4_gemm_kernel(
+template <bool OUT_F32, int CB, int FMT>
+__global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
     const uint8_t* __restrict__ Xq, const uint8_t* __restrict__ Xs, const float* __restrict__ tsx,
     const uint8_t* __restrict__ Wq, const uint8_t* __restrict__ Ws, const float* __restrict__ tsw,
     void* __restrict__ Yv, int64_t ldy, int M, int N, int K, int tiles_m, int tiles_n, int tiled) {
@@ -137,10 +165,10 @@ __global__ __launch_bounds__(256) void nvfp4_gemm_kernel(
 
   auto convert = [&](const Raw& x, const Raw& w, char* stage) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) convert_group(x, g, stage, 256, tid);
+    for (int g = 0; g < 4; ++g) convert_group<FMT>(x, g, stage, 256, tid);
     if (w_thread) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) convert_group(w, g, stage + kXBytes, kBN, tid);
+      for (int g = 0; g < 4; ++g) convert_group<FMT>(w, g, stage + kXBytes, kBN, tid);
     }
   };
 
@@ -189,7 +217,7 @@ __global__ __launch_bounds__(256) void nvfp4_gemm_kernel(
   }
   mma_step(lds + ((KT - 1) & 1) * kStage);
 
-  const float scale = *tsx * *tsw;
+  const float scale = FMT == kNvfp4 ? *tsx * *tsw : 1.0f;   // INT4 has no tensor scales (null pointers)
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -208,19 +236,19 @@ __global__ __launch_bounds__(256) void nvfp4_gemm_kernel(
   }
 }
 
-template <bool OUT_F32, int CB>
+template <bool OUT_F32, int CB, int FMT>
 hipError_t launch_shape(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
                         const float* tsw, int64_t M, int64_t N, int64_t K, int tiled, void* Y, int64_t ldy,
                         hipStream_t stream) {
   static bool configured = false;  // per instantiation
   if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nvfp4_gemm_kernel<OUT_F32, CB>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4_f16_gemm_kernel<OUT_F32, CB, FMT>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(CB));
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + 64 * CB - 1) / (64 * CB));
-  nvfp4_gemm_kernel<OUT_F32, CB><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds_bytes(CB), stream>>>(
+  w4_f16_gemm_kernel<OUT_F32, CB, FMT><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds_bytes(CB), stream>>>(
       (const uint8_t*)Xq, (const uint8_t*)Xs, tsx, (const uint8_t*)Wq, (const uint8_t*)Ws, tsw, Y, ldy, (int)M, (int)N,
       (int)K, tiles_m, tiles_n, tiled);
   return hipGetLastError();
@@ -235,9 +263,12 @@ int64_t width_cost(int64_t M, int64_t N, int CB, int cus) {
 
 }  // namespace
 
-hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
-                             const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y,
-                             int64_t ldy, hipStream_t stream) {
+namespace {
+
+template <int FMT>
+hipError_t launch_w4_f16_gemm(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
+                              const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y,
+                              int64_t ldy, hipStream_t stream) {
   const int cus = device_cu_count();
   int best = 4;
   for (int cb = 3; cb >= 2; --cb)
@@ -245,10 +276,23 @@ hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, c
   if (const char* f = getenv("WUSH_NVFP4_WIDTH")) {  // tests: force a tile width (output channels / 64)
     if (f[0] >= '2' && f[0] <= '4' && f[1] == 0) best = f[0] - '0';
   }
-#define WUSH_NV_LAUNCH(F32, CB) launch_shape<F32, CB>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, tiled, Y, ldy, stream)
+#define WUSH_NV_LAUNCH(F32, CB) launch_shape<F32, CB, FMT>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, tiled, Y, ldy, stream)
   if (out_f32) return best == 4 ? WUSH_NV_LAUNCH(true, 4) : best == 3 ? WUSH_NV_LAUNCH(true, 3) : WUSH_NV_LAUNCH(true, 2);
   return best == 4 ? WUSH_NV_LAUNCH(false, 4) : best == 3 ? WUSH_NV_LAUNCH(false, 3) : WUSH_NV_LAUNCH(false, 2);
 #undef WUSH_NV_LAUNCH
+}
+
+}  // namespace
+
+hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
+                             const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y,
+                             int64_t ldy, hipStream_t stream) {
+  return launch_w4_f16_gemm<kNvfp4>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, out_f32, tiled, Y, ldy, stream);
+}
+
+hipError_t launch_int4_gemm(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M, int64_t N,
+                            int64_t K, int out_f32, int tiled, void* Y, int64_t ldy, hipStream_t stream) {
+  return launch_w4_f16_gemm<kInt4>(Xq, Xs, nullptr, Wq, Ws, nullptr, M, N, K, out_f32, tiled, Y, ldy, stream);
 }
 
 }  // namespace wush

@@ -8,6 +8,7 @@
 //      rules as the activation kernel, evaluated on the FP64 values.
 // This path runs once per layer, offline; it is written for exactness against
 // an FP64 reference, not for speed.
+#include "nvfp4_layout.hpp"
 #include "wush_device.hpp"
 #include "wush_kernels.hpp"
 
@@ -135,6 +136,78 @@ __global__ __launch_bounds__(256) void weight_apply_quant_kernel(
   }
 }
 
+// INT4 variant (Table 1: 4-bit integers, BF16 scale per 32 = Gaussian-MSE-optimal step times the
+// group's root mean square): the same FP64 product, then the quantizer decided in FP64 with one IEEE
+// operation per step and no fused multiply-add in the sum of squares (channels 0..15 left to right,
+// channels 16..31 left to right, the two sums added).  Tiled layout: nvfp4_layout.hpp.
+__global__ __launch_bounds__(256) void weight_apply_quant_int4_kernel(
+    const uint16_t* __restrict__ W, int64_t ldw, const double* __restrict__ Tinv, uint8_t* __restrict__ Wq,
+    uint8_t* __restrict__ Ws, int N, int K, int C, int tiled) {
+  __shared__ double ti[32][32];  // inv(T_b)[k][j]
+  const int b = blockIdx.y;
+  for (int i = threadIdx.x; i < 1024; i += 256) ti[i >> 5][i & 31] = Tinv[(int64_t)b * 1024 + i];
+  __syncthreads();
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  double w[32];
+  const uint16_t* wp = W + (int64_t)n * ldw + 32 * b;
+#pragma unroll
+  for (int k = 0; k < 32; k += 8) {
+    const v4u raw = *reinterpret_cast<const v4u*>(wp + k);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      w[k + 2 * i] = (double)__uint_as_float(raw[i] << 16);
+      w[k + 2 * i + 1] = (double)__uint_as_float(raw[i] & 0xFFFF0000u);
+    }
+  }
+  double y[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    double acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) acc = fma(w[k], ti[k][j], acc);
+    y[j] = acc;
+  }
+  uint32_t bits;
+  double rcp;
+  {
+#pragma clang fp contract(off)
+    double lo = y[0] * y[0], hi = y[16] * y[16];
+#pragma unroll
+    for (int j = 1; j < 16; ++j) {
+      const double t0 = y[j] * y[j], t1 = y[16 + j] * y[16 + j];
+      lo = lo + t0;
+      hi = hi + t1;
+    }
+    const double ss = lo + hi;
+    const double sigma = sqrt(ss * 0.03125);
+    bits = f64_to_bf16_bits(0.33860793 * sigma);
+    bits = bits < 0x80u ? 0u : bits;
+    const double q = 1.0 / (double)__uint_as_float(bits << 16);
+    rcp = bits == 0 ? 0.0 : q;
+  }
+  uint32_t words[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    uint32_t wd = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const double t = fmin(fmax(y[8 * g + i] * rcp, -8.0), 7.0);
+      wd |= ((uint32_t)(int)rint(t) & 0xFu) << (4 * i);
+    }
+    words[g] = wd;
+  }
+  const v4u chunk = {words[0], words[1], words[2], words[3]};
+  if (tiled) {
+    const int KT = K >> 6;
+    *reinterpret_cast<v4u*>(Wq + nv_tiled_chunk_offset(n, b >> 1, b & 1, KT)) = chunk;
+    reinterpret_cast<uint16_t*>(Ws + nv_tiled_scale_offset(n, b >> 1, KT))[b & 1] = (uint16_t)bits;
+  } else {
+    *reinterpret_cast<v4u*>(Wq + (int64_t)n * (K / 2) + 16 * b) = chunk;
+    reinterpret_cast<uint16_t*>(Ws)[(int64_t)n * C + b] = (uint16_t)bits;
+  }
+}
+
 // Tiled -> canonical copy of packed codes and scales (inspection / tests).
 __global__ __launch_bounds__(256) void unpack_tiled_kernel(const uint8_t* __restrict__ qt,
                                                            const uint8_t* __restrict__ st,
@@ -201,6 +274,23 @@ hipError_t launch_weight_prep(const void* W, int64_t N, int64_t K, int64_t ldw, 
   dim3 grid((unsigned)((N + 255) / 256), (unsigned)C);
   weight_apply_quant_kernel<<<grid, dim3(256), 0, stream>>>((const uint16_t*)W, ldw, tinv, (uint8_t*)Wq,
                                                            (uint8_t*)Ws, (int)N, (int)K, C, rule, tiled);
+  return hipGetLastError();
+}
+
+hipError_t launch_int4_weight_prep(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T, int tiled, void* Wq,
+                                   void* Ws, void* workspace, hipStream_t stream) {
+  const int C = (int)(K / 32);
+  double* tinv = reinterpret_cast<double*>(workspace);
+  int* status = reinterpret_cast<int*>(reinterpret_cast<char*>(workspace) + weight_prep_status_offset(K));
+  reset_status_kernel<<<dim3(1), dim3(64), 0, stream>>>(status);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  invert_blocks_kernel<<<dim3(C), dim3(64), 0, stream>>>((const uint16_t*)T, tinv, status);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  dim3 grid((unsigned)((N + 255) / 256), (unsigned)C);
+  weight_apply_quant_int4_kernel<<<grid, dim3(256), 0, stream>>>((const uint16_t*)W, ldw, tinv, (uint8_t*)Wq,
+                                                                (uint8_t*)Ws, (int)N, (int)K, C, tiled);
   return hipGetLastError();
 }
 

@@ -346,6 +346,54 @@ wush_status wush_unpack_tiled_nvfp4(const void* q_tiled, const void* s_tiled, in
   return from_hip(wush::launch_nvfp4_unpack_tiled(q_tiled, s_tiled, rows, K, q, s, static_cast<hipStream_t>(stream)));
 }
 
+wush_status wush_quantize_act_int4(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T_blocks,
+                                   int32_t layout, void* Xq, void* Xs, float* dbg_Yt, void* stream) {
+  if (!X || !T_blocks || !Xq || !Xs) return WUSH_ERR_NULL;
+  if (wush_status s = check_rows(M, K, ldx)) return s;
+  if (wush_status s = check_nv_layout(layout, K)) return s;
+  if (!aligned16(X) || !aligned16(T_blocks) || !aligned16(Xq) || !aligned16(Xs) || !aligned16(dbg_Yt))
+    return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_int4_transform_quant(X, M, K, ldx, T_blocks, layout == WUSH_LAYOUT_TILED, Xq, Xs, dbg_Yt,
+                                                    static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_prepare_weight_int4(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T_blocks,
+                                     int32_t layout, void* Wq, void* Ws, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  if (!W || !T_blocks || !Wq || !Ws) return WUSH_ERR_NULL;
+  if (wush_status s = check_rows(N, K, ldw)) return s;
+  if (wush_status s = check_nv_layout(layout, K)) return s;
+  if (!aligned16(W) || !aligned16(T_blocks) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
+  if (!workspace || workspace_bytes < wush::weight_prep_workspace_bytes(N, K)) return WUSH_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_int4_weight_prep(W, N, K, ldw, T_blocks, layout == WUSH_LAYOUT_TILED, Wq, Ws, workspace,
+                                                static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_linear_int4(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M, int64_t N,
+                             int64_t K, int32_t layout, int32_t out_dtype, void* Y, int64_t ldy, void* stream) {
+  if (!Xq || !Xs || !Wq || !Ws || !Y) return WUSH_ERR_NULL;
+  if (out_dtype != WUSH_OUT_BF16 && out_dtype != WUSH_OUT_F32) return WUSH_ERR_FMT;
+  if (layout != WUSH_LAYOUT_CANONICAL && layout != WUSH_LAYOUT_TILED) return WUSH_ERR_FMT;
+  if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim || K % 64 != 0) return WUSH_ERR_SHAPE;
+  if (ldy < N) return WUSH_ERR_SHAPE;
+  if (!aligned16(Xq) || !aligned16(Xs) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
+  const uintptr_t elem = out_dtype == WUSH_OUT_F32 ? 4 : 2;
+  if (reinterpret_cast<uintptr_t>(Y) % elem != 0) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_int4_gemm(Xq, Xs, Wq, Ws, M, N, K, out_dtype == WUSH_OUT_F32,
+                                         layout == WUSH_LAYOUT_TILED, Y, ldy, static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_quantize_f32_int4(const float* Yt, int64_t M, int64_t K, int32_t layout, void* q, void* s,
+                                   void* stream) {
+  if (!Yt || !q || !s) return WUSH_ERR_NULL;
+  if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (wush_status st = check_nv_layout(layout, K)) return st;
+  if (!aligned16(Yt) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_int4_quantize_f32(Yt, M, K, layout == WUSH_LAYOUT_TILED, q, s,
+                                                 static_cast<hipStream_t>(stream)));
+}
+
 wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fmt, void* q, void* s,
                               void* stream) {
   if (!Yt || !q || !s) return WUSH_ERR_NULL;
@@ -391,6 +439,6 @@ const char* wush_status_string(wush_status st) {
   return "unknown status";
 }
 
-const char* wush_version(void) { return "0.6"; }
+const char* wush_version(void) { return "0.7"; }
 
 }  // extern "C"

@@ -5,22 +5,6 @@
 
 namespace wush {
 
-// FP64 -> BF16 bits, round to nearest even, for finite values in BF16's normal range.
-__device__ __forceinline__ uint16_t f64_to_bf16_bits(double v) {
-  const uint64_t u = (uint64_t)__double_as_longlong(v);
-  const uint32_t sign = (uint32_t)(u >> 63) << 15;
-  const int e11 = (int)((u >> 52) & 0x7FF);
-  if (e11 == 0) return (uint16_t)sign;               // zero (FP64 denormals flush)
-  const int e8 = e11 - 1023 + 127;
-  if (e8 <= 0) return (uint16_t)sign;                 // below BF16's normal range
-  if (e8 >= 255) return (uint16_t)(sign | 0x7F80);    // overflow -> inf
-  const uint64_t frac = u & 0xFFFFFFFFFFFFFull;       // 52 bits
-  uint32_t mag = ((uint32_t)e8 << 7) | (uint32_t)(frac >> 45);
-  const uint64_t rest = frac & ((1ull << 45) - 1), half = 1ull << 44;
-  if (rest > half || (rest == half && (mag & 1))) mag += 1;  // carry may bump the exponent: still correct
-  return (uint16_t)(sign | mag);
-}
-
 // Alg. 1 for one block, by ONE wavefront (64 lanes, all active):
 //   W' W'^T = M_W + lambda d^-1 tr(M_W) I,  X' X'^T likewise  (Cholesky, side by side)
 //   U S V^T = W'^T X'  (one-sided Jacobi on the columns; V never needed)

@@ -116,4 +116,20 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// FP64 -> BF16 bits, round to nearest even, for finite values in BF16's normal range.
+__device__ __forceinline__ uint16_t f64_to_bf16_bits(double v) {
+  const uint64_t u = (uint64_t)__double_as_longlong(v);
+  const uint32_t sign = (uint32_t)(u >> 63) << 15;
+  const int e11 = (int)((u >> 52) & 0x7FF);
+  if (e11 == 0) return (uint16_t)sign;               // zero (FP64 denormals flush)
+  const int e8 = e11 - 1023 + 127;
+  if (e8 <= 0) return (uint16_t)sign;                 // below BF16's normal range
+  if (e8 >= 255) return (uint16_t)(sign | 0x7F80);    // overflow -> inf
+  const uint64_t frac = u & 0xFFFFFFFFFFFFFull;       // 52 bits
+  uint32_t mag = ((uint32_t)e8 << 7) | (uint32_t)(frac >> 45);
+  const uint64_t rest = frac & ((1ull << 45) - 1), half = 1ull << 44;
+  if (rest > half || (rest == half && (mag & 1))) mag += 1;  // carry may bump the exponent: still correct
+  return (uint16_t)(sign | mag);
+}
+
 }  // namespace wush

@@ -86,6 +86,18 @@ hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, c
                              const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y,
                              int64_t ldy, hipStream_t stream);
 
+// INT4 variant (two's-complement codes, BF16 scale per 32, 32 x 32 transforms); layouts as for NVFP4
+// (the 4 scale bytes of a K step of 64 are two BF16 numbers).  Weight workspace: as launch_weight_prep.
+hipError_t launch_int4_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T, int tiled,
+                                       void* Xq, void* Xs, float* dbg, hipStream_t stream);
+hipError_t launch_int4_quantize_f32(const float* Y, int64_t M, int64_t K, int tiled, void* q, void* s,
+                                    hipStream_t stream);
+hipError_t launch_int4_weight_prep(const void* W, int64_t N, int64_t K, int64_t ldw, const void* T, int tiled, void* Wq,
+                                   void* Ws, void* workspace, hipStream_t stream);
+// K % 64 == 0
+hipError_t launch_int4_gemm(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M, int64_t N,
+                            int64_t K, int out_f32, int tiled, void* Y, int64_t ldy, hipStream_t stream);
+
 // Measurement aid: register-only loop of the block-scaled FP4 MFMA (4 waves per workgroup, 64 MFMAs per trip).
 hipError_t launch_mfma_probe(const void* operand_bits, int iters, int blocks, void* out, hipStream_t stream);
 // The same for the FP16 MFMA of the NVFP4 GEMM (operands: 16 KiB of FP16 values).

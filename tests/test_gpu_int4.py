@@ -1,0 +1,243 @@
+"""GPU parity of the INT4 variant (32 x 32 transforms, two's-complement codes, BF16 scale
+per 32 = Gaussian-MSE-optimal step times the group RMS) against oracle/wush_int4_oracle.py,
+through the C ABI.  Bars: quantizer bit-exact when both sides see the same FP32 values;
+transformed values within 1e-5 of the group AbsMax; codes against the all-FP64 path differ
+only next to a decision boundary; GEMM relative Frobenius error <= 2e-3 (BF16 output) and
+<= 1e-5 (FP32 output)."""
+import numpy as np
+import pytest
+
+import wush_inputs as I
+from oracle import wush_int4_oracle as Q
+from oracle import wush_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2512_00956_amd as P
+    P.lib()
+    return P
+
+
+@pytest.fixture(scope="module")
+def G():
+    from tests import gpu_util
+    return gpu_util
+
+
+SHAPES = {
+    "c1": I.CONFIGS["c1"],
+    "ragged": I.scaled(I.CONFIGS["c1"], M=77, K=32 * 13, N=45, calib_tokens=256, n_outlier=3),
+    "tiles": I.scaled(I.CONFIGS["c2"], M=300, K=1024, N=520, calib_tokens=1024, n_outlier=5),
+    "one_token": I.scaled(I.CONFIGS["c1"], M=1, K=128, N=32, calib_tokens=256, n_outlier=1),
+}
+_cache = {}
+
+
+def _layer(name):
+    if name not in _cache:
+        cfg = SHAPES[name]
+        L = I.make_layer(cfg)
+        X, Xc, W = (O.bf16_bits_to_f64(L[k]) for k in ("X", "X_cal", "W"))
+        _cache[name] = (cfg, L, X, W, O.round_to_bf16(O.build_transforms(W, Xc, 1e-2)))
+    return _cache[name]
+
+
+def _u16(t):
+    """GPU u8 tensor [rows][2 * groups] -> numpy uint16 [rows][groups]."""
+    return np.ascontiguousarray(t.cpu().numpy()).view(np.uint16)
+
+
+def _explained(vals64, q_gpu, s_gpu, q_ref, s_ref, tol):
+    """(mismatch rate, number of differing elements that sit neither within tol (relative to
+    the group's largest |v / scale|) of a rounding midpoint nor in a group whose STEP * sigma
+    is within tol of a BF16 rounding boundary)."""
+    R, K = vals64.shape
+    Gr = vals64.reshape(R, K // 32, 32)
+    qg, qr = q_gpu.reshape(R, K // 32, 32), q_ref.reshape(R, K // 32, 32)
+    sdiff = s_gpu != s_ref
+    bad = (qg != qr) | sdiff[..., None]
+    if not bad.any():
+        return 0.0, 0
+    s_real = Q.STEP * np.sqrt(np.mean(Gr * Gr, axis=-1))
+    sref = O.bf16_bits_to_f64(s_ref)
+    lo = np.minimum(O.bf16_bits_to_f64(s_gpu), sref)
+    hi = np.maximum(O.bf16_bits_to_f64(s_gpu), sref)
+    near_scale = sdiff & (np.abs(s_real - 0.5 * (lo + hi)) <= tol * s_real)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        v = Gr / sref[..., None]
+    frac = np.abs(v - np.floor(v) - 0.5)
+    near_mid = frac <= tol * np.maximum(np.max(np.abs(v), axis=-1, keepdims=True), 1.0)
+    unexplained = bad & ~near_mid & ~near_scale[..., None]
+    return float(np.mean(bad)), int(unexplained.sum())
+
+
+def _adversarial_groups():
+    rows = []
+    for scale in (1.0, 3.7e-3, 911.0):
+        s = np.float32(O.bf16_bits_to_f64(O.bf16_values_to_bits(O.round_to_bf16(np.array([scale]))))[0])
+        for shift in (0.0, 1e-3):
+            g = np.zeros(32, dtype=np.float32)
+            halves = (np.arange(-9, 8) + 0.5).astype(np.float32)         # every rounding midpoint, and past both ends
+            g[:17] = halves * s * np.float32(1 + shift)
+            g[17:] = np.float32(0.3) * s
+            rows.append(g)
+    rows.append(np.zeros(32, dtype=np.float32))
+    tiny = np.zeros(32, dtype=np.float32)
+    tiny[3], tiny[9] = np.float32(1e-40), -np.float32(3e-39)              # scale below BF16's normal range
+    rows.append(tiny)
+    big = np.full(32, 1e30, dtype=np.float32)
+    big[::3] *= -1
+    rows.append(big)
+    return np.stack(rows)
+
+
+def test_quantizer_tap_bit_exact(P, G):
+    import torch
+    adv = _adversarial_groups()
+    rnd = I.random_f32((257, 32 * 9), seed=21, spread=8.0)
+    pad = (-adv.shape[0]) % 9
+    adv = np.concatenate([adv, np.zeros((pad, 32), np.float32)]).reshape(-1, 32 * 9)
+    Y = np.concatenate([rnd, adv]).astype(np.float32)
+    M, K = Y.shape
+    q, s = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    P.wush_quantize_f32_int4(torch.from_numpy(Y).cuda(), q, s)
+    torch.cuda.synchronize()
+    qr, sr = Q.quantize_int4(Y, prec=np.float32)
+    assert np.array_equal(_u16(s), sr)
+    assert np.array_equal(G.host(q), Q.pack_codes(qr))
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_transform_quant(P, G, name):
+    import torch
+    cfg, L, X, W, T = _layer(name)
+    M, K = cfg.M, cfg.K
+    Xd, Td = G.bf16_dev(L["X"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    dbg = torch.full((M, K), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_quantize_act_int4(Xd, Td, Xq, Xs, dbg_Yt=dbg)
+    Xq2, Xs2 = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    P.wush_quantize_act_int4(Xd, Td, Xq2, Xs2)
+    torch.cuda.synchronize()
+    xq, xs, yt = G.host(Xq), _u16(Xs), G.host(dbg)
+    assert np.array_equal(xq, G.host(Xq2)) and np.array_equal(xs, _u16(Xs2))
+    # (1) quantizer bit-exact on the kernel's own FP32 values
+    assert np.isfinite(yt).all()
+    qr, sr = Q.quantize_int4(yt, prec=np.float32)
+    assert np.array_equal(xs, sr)
+    assert np.array_equal(xq, Q.pack_codes(qr))
+    # (2) transformed values against FP64
+    Yt = O.transform_act(X, T)
+    amax = np.max(np.abs(Yt.reshape(M, K // 32, 32)), axis=-1)
+    err = np.max(np.abs(yt.astype(np.float64) - Yt).reshape(M, K // 32, 32), axis=-1)
+    assert np.max(err / amax) <= 1e-5
+    # (3) codes against the all-FP64 path
+    q64, s64 = Q.quantize_int4(Yt, prec=np.float64)
+    rate, unexplained = _explained(Yt, Q.unpack_codes(xq), xs, q64, s64, tol=1e-5)
+    assert rate <= 1e-3 and unexplained == 0, (rate, unexplained)
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_prepare_weight(P, G, name):
+    cfg, L, X, W, T = _layer(name)
+    N, K = cfg.N, cfg.K
+    Wd, Td = G.bf16_dev(L["W"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    Wq, Ws = G.empty_u8(N, K // 2), G.empty_u8(N, K // 16)
+    ws = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+    P.wush_prepare_weight_int4(Wd, Td, Wq, Ws, ws)
+    P.wush_workspace_status(ws, K)
+    Wt = O.transform_weight(W, T)
+    qr, sr = Q.quantize_int4(Wt, prec=np.float64)
+    rate, unexplained = _explained(Wt, Q.unpack_codes(G.host(Wq)), _u16(Ws), qr, sr, tol=1e-9)
+    assert rate <= 1e-3 and unexplained == 0, (rate, unexplained)
+
+
+def test_prepare_weight_flags_singular_block(P, G):
+    K, N = 64, 40
+    T = np.stack([np.eye(32), np.eye(32)])
+    T[1, 5, :] = 0.0
+    Wd = G.bf16_dev(I.f32_to_bf16_bits(I.random_f32((N, K), 5, 1.0)))
+    Wq, Ws = G.empty_u8(N, K // 2), G.empty_u8(N, K // 16)
+    ws = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+    P.wush_prepare_weight_int4(Wd, G.bf16_dev(O.bf16_values_to_bits(T)), Wq, Ws, ws)
+    with pytest.raises(P.WushError) as e:
+        P.wush_workspace_status(ws, K)
+    assert e.value.code == 7
+
+
+def _random_operand(rng, rows, K, lo_exp, hi_exp):
+    q = rng.integers(-8, 8, (rows, K)).astype(np.int8)
+    s = O.round_to_bf16(np.exp2(rng.uniform(lo_exp, hi_exp, (rows, K // 32))) * rng.uniform(1, 2, (rows, K // 32)))
+    return q, O.bf16_values_to_bits(s)
+
+
+GEMM_SHAPES = [(16, 256, 64), (77, 45, 128), (300, 520, 192), (257, 256, 1024), (512, 768, 4096), (1, 32, 256)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("out", ["bf16", "f32"])
+def test_linear_against_oracle(P, G, M, N, K, out):
+    """GEMM alone: both sides start from the same codes and BF16 scales (spread over FP16's normal range)."""
+    import torch
+    rng = np.random.default_rng(2000 + M + N + K)
+    xq, xs = _random_operand(rng, M, K, -13, 9)
+    wq, ws_ = _random_operand(rng, N, K, -10, -2)
+    ref = Q.linear_dequant(xq, xs, wq, ws_)
+    f32 = out == "f32"
+    Y = torch.full((M, N + 8), float("nan"), dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
+    P.wush_linear_int4(G.u8_dev(Q.pack_codes(xq)), G.u8_dev(xs.view(np.uint8)), G.u8_dev(Q.pack_codes(wq)),
+                       G.u8_dev(ws_.view(np.uint8)), Y[:, :N], out_dtype=1 if f32 else 0)
+    torch.cuda.synchronize()
+    y = Y.float().cpu().numpy().astype(np.float64)
+    assert np.isnan(y[:, N:]).all()
+    assert O.rel_fro(y[:, :N], ref) <= (1e-5 if f32 else 2e-3)
+
+
+@pytest.mark.parametrize("width", ["2", "3", "4"])
+def test_layer_end_to_end_both_layouts(P, G, width, monkeypatch):
+    import torch
+    monkeypatch.setenv("WUSH_NVFP4_WIDTH", width)
+    cfg, L, X, W, T = _layer("tiles")
+    M, N, K = cfg.M, cfg.N, cfg.K
+    Xd, Wd, Td = G.bf16_dev(L["X"]), G.bf16_dev(L["W"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    ws = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+    outs = []
+    for lay in (0, 1):
+        (xcb, xsb), (wcb, wsb) = P.wush_packed_sizes_nvfp4(M, K, lay), P.wush_packed_sizes_nvfp4(N, K, lay)
+        Xq, Xs, Wq, Ws = G.empty_u8(xcb), G.empty_u8(xsb), G.empty_u8(wcb), G.empty_u8(wsb)
+        P.wush_prepare_weight_int4(Wd, Td, Wq, Ws, ws, layout=lay)
+        P.wush_quantize_act_int4(Xd, Td, Xq, Xs, layout=lay)
+        Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        P.wush_linear_int4(Xq, Xs, Wq, Ws, Y, layout=lay, out_dtype=1, K=K)
+        if lay:   # the tiled buffers are a permutation of the canonical ones
+            qu, su = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+            P.wush_unpack_tiled_nvfp4(Xq, Xs, M, K, qu, su)
+            torch.cuda.synchronize()
+            assert torch.equal(qu, outs[0][1].view(M, K // 2)) and torch.equal(su, outs[0][2].view(M, K // 16))
+        outs.append((Y, Xq, Xs))
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0][0], outs[1][0])
+    ref = Q.layer_forward(X, W, T)
+    y = outs[1][0].cpu().numpy().astype(np.float64)
+    assert O.rel_fro(y, ref) <= 2e-3
+    exact = X @ W.T
+    assert abs(O.rel_fro(y, exact) - O.rel_fro(ref, exact)) <= 1e-3
+
+
+def test_argument_validation(P, G):
+    import torch
+    Y = torch.empty((4, 4), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(P.WushError) as e:        # K = 96 is not a multiple of 64
+        P.wush_linear_int4(G.empty_u8(4, 48), G.empty_u8(4, 6), G.empty_u8(4, 48), G.empty_u8(4, 6), Y)
+    assert e.value.code == 2
+    with pytest.raises(P.WushError) as e:
+        P.wush_linear_int4(G.empty_u8(4, 64), None, G.empty_u8(4, 64), G.empty_u8(4, 8), Y)
+    assert e.value.code == 1
+    with pytest.raises(P.WushError) as e:        # unknown layout
+        P.wush_quantize_f32_int4(torch.zeros((4, 64), device="cuda"), G.empty_u8(4, 32), G.empty_u8(4, 4), layout=7)
+    assert e.value.code == 4
