@@ -292,6 +292,18 @@ wush_status wush_quantize_act_nvfp4(const void* X, int64_t M, int64_t K, int64_t
                                     float* dbg_Yt, void* stream);
 
 /*
+ * Calibration of the activation tensor scale (offline, on a calibration batch; or online, once
+ * before wush_quantize_act_nvfp4, when the batch's own maximum is wanted): AbsMax of T X over
+ * the batch / (6 * 448), with the quantizer's own transform arithmetic (BF16 MFMA, FP32
+ * accumulators).
+ *   X            in   bf16 [M][ldx] (device)
+ *   T16          in   bf16 [K/16][16][16] (device)
+ *   tensor_scale out  float (device)
+ */
+wush_status wush_calibrate_act_nvfp4(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16,
+                                     float* tensor_scale, void* stream);
+
+/*
  * Offline weight side in NVFP4 (Alg. 2, RTN case, d = 16): FP64 inverse of every
  * block of T16, W_blk inv(T_b) in FP64, tensor scale = AbsMax of the transformed
  * weights / (6 * 448) rounded to FP32, then the quantizer above in FP64.

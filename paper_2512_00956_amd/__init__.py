@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     wush_build_transforms,
     wush_build_transforms_status,
     wush_build_transforms_workspace,
+    wush_calibrate_act_nvfp4,
     wush_layer_decode,
     wush_layer_decode_init,
     wush_layer_decode_status,
@@ -56,5 +57,5 @@ __all__ = [
     "wush_probe_mfma", "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_status",
     "wush_prepare_weight_nvfp4_workspace", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
     "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", "wush_probe_mfma_f16",
-    "wush_quantize_act_int4", "wush_prepare_weight_int4", "wush_linear_int4", "wush_quantize_f32_int4",
+    "wush_calibrate_act_nvfp4", "wush_quantize_act_int4", "wush_prepare_weight_int4", "wush_linear_int4", "wush_quantize_f32_int4",
 ]

@@ -36,6 +36,7 @@ EXPORTS = (
     "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_workspace",
     "wush_prepare_weight_nvfp4_status", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
     "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", "wush_probe_mfma_f16",
+    "wush_calibrate_act_nvfp4",
     "wush_quantize_act_int4", "wush_prepare_weight_int4", "wush_linear_int4", "wush_quantize_f32_int4",
 )
 
@@ -130,6 +131,8 @@ def lib() -> ctypes.CDLL:
                                        c_int32, c_void_p, c_int64, c_void_p]
         L.wush_quantize_f32_int4.restype = c_int32
         L.wush_quantize_f32_int4.argtypes = [c_void_p, c_int64, c_int64, c_int32, c_void_p, c_void_p, c_void_p]
+        L.wush_calibrate_act_nvfp4.restype = c_int32
+        L.wush_calibrate_act_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
         L.wush_probe_mfma_f16.restype = c_int32
         L.wush_probe_mfma_f16.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
         L.wush_quantize_act_nvfp4.restype = c_int32
@@ -327,6 +330,13 @@ def wush_quantize_act_nvfp4(X, T16, tensor_scale, Xq, Xs, layout: int = WUSH_LAY
     M, K = X.shape
     _check(lib().wush_quantize_act_nvfp4(_ptr(X), M, K, X.stride(0), _ptr(T16), _ptr(tensor_scale), layout, _ptr(Xq),
                                          _ptr(Xs), _ptr(dbg_Yt), _stream(stream)), "wush_quantize_act_nvfp4")
+
+
+def wush_calibrate_act_nvfp4(X, T16, tensor_scale, stream=None):
+    """tensor_scale (float32 tensor, 1 element, written) = AbsMax of T X over the batch / (6 * 448)."""
+    M, K = X.shape
+    _check(lib().wush_calibrate_act_nvfp4(_ptr(X), M, K, X.stride(0), _ptr(T16), _ptr(tensor_scale), _stream(stream)),
+           "wush_calibrate_act_nvfp4")
 
 
 def wush_prepare_weight_nvfp4_workspace(K: int) -> int:

@@ -205,6 +205,52 @@ __global__ __launch_bounds__(kWaves * 64, 3) void nvfp4_transform_quant_kernel(
   }
 }
 
+// Calibration of the activation tensor scale: AbsMax of T X over a batch (same transform, same
+// FP32 accumulators as the quantizer), reduced with an atomic max on the bit pattern (non-negative
+// floats order like their bits); a second tiny kernel turns it into AbsMax / (6 * 448).
+__global__ __launch_bounds__(kWaves * 64, 3) void nvfp4_absmax_kernel(
+    const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ T16, unsigned int* __restrict__ amax_bits,
+    int M, int C32, int tiles_per_wg) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int tok = lane & 31;
+  const int h = lane >> 5;
+  const int bfirst = (blockIdx.y * kWaves + wave) * kNB;
+  if (bfirst >= C32) return;  // wave-uniform
+  const int nb = min(kNB, C32 - bfirst);
+  v8bf ta[kNB][2];
+  load_transforms16(ta, T16, bfirst, C32, tok, h);
+  const int ntiles = (M + kTileM - 1) / kTileM;
+  const int tend = min((int)(blockIdx.x + 1) * tiles_per_wg, ntiles);
+  float amax = 0.0f;
+  for (int t = blockIdx.x * tiles_per_wg; t < tend; ++t) {
+    XFrag cur[kNB];
+    // rows past M re-read row M - 1 (its maximum is counted twice, which changes nothing)
+    tq::load_tile(cur, X, ldx, min(t * kTileM + tok, M - 1), bfirst, C32, h);
+#pragma unroll
+    for (int bb = 0; bb < kNB; ++bb) {
+      v16f acc = {0};
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta[bb][0], cur[bb].lo, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta[bb][1], cur[bb].hi, acc, 0, 0, 0);
+      if (bb < nb) {  // blocks past the end were clamped to a valid one: harmless, but skip them
+#pragma unroll
+        for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(acc[r]));
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+  if (lane == 0) atomicMax(amax_bits, __float_as_uint(amax));
+}
+
+__global__ void nvfp4_reset_absmax_kernel(unsigned int* amax_bits) {
+  if (threadIdx.x == 0) *amax_bits = 0u;
+}
+
+__global__ void nvfp4_finish_scale_kernel(float* ts) {
+  if (threadIdx.x == 0) *ts = *ts / 2688.0f;  // the word holds the AbsMax (bit pattern of a float)
+}
+
 // Quantizer-only tap: one thread per group of 16 FP32 values.
 __global__ __launch_bounds__(256) void nvfp4_quantize_f32_kernel(const float* __restrict__ Y,
                                                                  const float* __restrict__ tscale,
@@ -419,6 +465,25 @@ hipError_t launch_nvfp4_transform_quant(const void* X, int64_t M, int64_t K, int
     if (tiled) WUSH_NVQ_LAUNCH(false, true); else WUSH_NVQ_LAUNCH(false, false);
   }
 #undef WUSH_NVQ_LAUNCH
+  return hipGetLastError();
+}
+
+// The output word doubles as the reduction target: zeroed, raised to the AbsMax, then scaled in place.
+hipError_t launch_nvfp4_calibrate(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16, float* ts_out,
+                                  hipStream_t stream) {
+  const int C32 = (int)(K / 32);
+  const int col_groups = (C32 + kWaves * kNB - 1) / (kWaves * kNB);
+  const int ntiles = (int)((M + kTileM - 1) / kTileM);
+  const int tiles_per_wg = token_walk(ntiles, col_groups);
+  unsigned int* word = reinterpret_cast<unsigned int*>(ts_out);
+  nvfp4_reset_absmax_kernel<<<dim3(1), dim3(64), 0, stream>>>(word);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  nvfp4_absmax_kernel<<<dim3((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups), dim3(kWaves * 64), 0, stream>>>(
+      (const uint16_t*)X, ldx, (const uint16_t*)T16, word, (int)M, C32, tiles_per_wg);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  nvfp4_finish_scale_kernel<<<dim3(1), dim3(64), 0, stream>>>(ts_out);
   return hipGetLastError();
 }
 

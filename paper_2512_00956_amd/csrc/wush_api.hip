@@ -271,6 +271,15 @@ wush_status wush_quantize_act_nvfp4(const void* X, int64_t M, int64_t K, int64_t
                                                      Xs, dbg_Yt, static_cast<hipStream_t>(stream)));
 }
 
+wush_status wush_calibrate_act_nvfp4(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16,
+                                     float* tensor_scale, void* stream) {
+  if (!X || !T16 || !tensor_scale) return WUSH_ERR_NULL;
+  if (wush_status s = check_rows(M, K, ldx)) return s;
+  if (!aligned16(X) || !aligned16(T16)) return WUSH_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(tensor_scale) % 4 != 0) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_nvfp4_calibrate(X, M, K, ldx, T16, tensor_scale, static_cast<hipStream_t>(stream)));
+}
+
 size_t wush_prepare_weight_nvfp4_workspace(int64_t K) {
   if (K <= 0 || K % 32 != 0 || K > kMaxDim) return 0;
   return wush::nvfp4_weight_prep_workspace_bytes(K);

@@ -72,6 +72,9 @@ hipError_t launch_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx,
 hipError_t launch_nvfp4_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16,
                                         const float* tscale, int tiled, void* Xq, void* Xs, float* dbg,
                                         hipStream_t stream);
+// AbsMax of T X over the batch / (6 * 448) -> *ts_out (device float).
+hipError_t launch_nvfp4_calibrate(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T16, float* ts_out,
+                                  hipStream_t stream);
 hipError_t launch_nvfp4_quantize_f32(const float* Y, int64_t M, int64_t K, const float* tscale, int tiled, void* q,
                                      void* s, hipStream_t stream);
 hipError_t launch_nvfp4_unpack_tiled(const void* qt, const void* st, int64_t rows, int64_t K, void* q, void* s,

@@ -171,6 +171,23 @@ def test_transform_quant(P, G, name):
     assert rate <= 2e-4 and unexplained == 0, (rate, unexplained)
 
 
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_calibrate_act(P, G, name):
+    """AbsMax of T X / (6 * 448) on the device against the oracle's (FP32 accumulators against FP64)."""
+    import torch
+    cfg, L, X, W, T = _layer(name)
+    ts = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_calibrate_act_nvfp4(G.bf16_dev(L["X"]), G.bf16_dev(O.bf16_values_to_bits(T)), ts)
+    torch.cuda.synchronize()
+    ref = float(NV.tensor_scale(NV.transform_act(X, T)))
+    assert abs(float(ts.cpu()[0]) - ref) <= 1e-5 * ref
+    # a second call on the same word starts from zero again
+    P.wush_calibrate_act_nvfp4(G.bf16_dev(L["X"][:1]), G.bf16_dev(O.bf16_values_to_bits(T)), ts)
+    torch.cuda.synchronize()
+    ref1 = float(NV.tensor_scale(NV.transform_act(X[:1], T)))
+    assert abs(float(ts.cpu()[0]) - ref1) <= 1e-5 * ref1
+
+
 def test_transform_quant_strided_rows(P, G):
     import torch
     cfg, L, X, W, T = _layer("ragged")
