@@ -74,3 +74,59 @@ def test_main_loop_waits_are_explicit(asm_text):
         assert loop.count("v_mfma_scale_f32_32x32x64_f8f6f4") == 2 * 4 * RB * CB, name     # two K iterations
         assert "vmcnt(0)" not in loop and "lgkmcnt(0)" not in loop, name
         assert loop.count("s_barrier") == 2, name
+
+
+# ---------------------------------------------------------------------------
+# The FP16-dequantizing GEMM of the NVFP4 / INT4 variants and the three fused quantizers: performance
+# invariants of the generated code -- nothing spills to scratch (the GEMM keeps up to 256 accumulator
+# registers per lane alive next to its conversion temporaries), and the GEMM's K loop holds exactly the
+# MFMAs of one K step and one workgroup barrier.
+# ---------------------------------------------------------------------------
+def _compile(src_name):
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not available")
+    src = os.path.join(ROOT, "paper_2512_00956_amd", "csrc", src_name)
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "k.s")
+        cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", os.path.dirname(src), "-S",
+               "--cuda-device-only", src, "-o", out]
+        subprocess.run(cmd, check=True, capture_output=True)
+        return open(out).read()
+
+
+def _bodies(text, pattern):
+    parts = re.split(rf"^(_ZN4wush\S*{pattern}\S*):.*$", text, flags=re.M)
+    return {parts[i]: parts[i + 1].split("s_endpgm")[0] for i in range(1, len(parts) - 1, 2)}
+
+
+def test_f16_gemm_has_no_scratch_and_a_tight_loop():
+    text = _compile("nvfp4_gemm.hip")
+    kernels = _bodies(text, "w4_f16_gemm_kernel")
+    assert len(kernels) == 12, list(kernels)          # {bf16, f32 output} x {4, 3, 2 column blocks} x {NVFP4, INT4}
+    for name, body in kernels.items():
+        cb = int(re.search(r"ILb[01]ELi(\d+)ELi[01]E", name).group(1))
+        assert "scratch_" not in body, f"{name}: spills to scratch"
+        # the K loop = the basic blocks the compiler annotates as the loop header or "in Loop"
+        blocks = re.split(r"^(\.LBB\d+_\d+:.*)$", body, flags=re.M)
+        loop = "".join(blocks[i + 1] for i in range(1, len(blocks) - 1, 2)
+                       if "Loop Header" in blocks[i] or "in Loop" in blocks[i])
+        assert loop, name
+        assert len(re.findall(r"v_mfma_f32_32x32x16_f16", loop)) == 16 * cb, name
+        assert len(re.findall(r"s_barrier", loop)) == 1, name
+
+
+@pytest.mark.parametrize("src,pattern,count", [("nvfp4_quant.hip", "nvfp4_transform_quant_kernel", 4),
+                                                ("int4_quant.hip", "int4_transform_quant_kernel", 4),
+                                                ("transform_quant.hip", "22transform_quant_kernel", 4)])
+def test_quantizers_do_not_spill_and_keep_three_waves_per_simd(src, pattern, count):
+    text = _compile(src)
+    kernels = _bodies(text, pattern)
+    assert len(kernels) == count, list(kernels)
+    for name, body in kernels.items():
+        assert "scratch_" not in body, f"{name}: spills to scratch"
+    # register budget from the kernel descriptors: at most 168 VGPRs = three waves per SIMD of 512
+    for m in re.finditer(r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.vgpr_count:\s+(\d+)", text):
+        if pattern in m.group(1):
+            assert int(m.group(2)) <= 176, (m.group(1), m.group(2))
