@@ -229,6 +229,56 @@ def test_layer_end_to_end_both_layouts(P, G, width, monkeypatch):
     assert abs(O.rel_fro(y, exact) - O.rel_fro(ref, exact)) <= 1e-3
 
 
+def test_c2_shape_full_size(P, G):
+    """The configuration bench.py times for workload i2 (2048 x 4096 -> 6144, tiled layout, BF16 output):
+    sampled token rows, weight rows and output entries against the oracle."""
+    import torch
+    L = I.make_layer(I.CONFIGS["c2"])
+    cfg = L["cfg"]
+    M, K, N = cfg.M, cfg.K, cfg.N
+    T = np.empty((K // 32, 32, 32))
+    for b in range(K // 32):
+        sl = slice(32 * b, 32 * b + 32)
+        T[b] = O.wush_block(O.second_moment(O.bf16_bits_to_f64(L["W"][:, sl])),
+                            O.second_moment(O.bf16_bits_to_f64(L["X_cal"][:, sl])), 1e-2)
+    T = O.round_to_bf16(T)
+    rng = np.random.default_rng(23)
+    rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 48)]))
+    cols = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 256)]))
+    Xd, Wd, Td = G.bf16_dev(L["X"]), G.bf16_dev(L["W"]), G.bf16_dev(O.bf16_values_to_bits(T))
+    (xcb, xsb), (wcb, wsb) = P.wush_packed_sizes_nvfp4(M, K, 1), P.wush_packed_sizes_nvfp4(N, K, 1)
+    Xq, Xs, Wq, Ws = G.empty_u8(xcb), G.empty_u8(xsb), G.empty_u8(wcb), G.empty_u8(wsb)
+    ws = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+    P.wush_prepare_weight_int4(Wd, Td, Wq, Ws, ws, layout=1)
+    P.wush_workspace_status(ws, K)
+    P.wush_quantize_act_int4(Xd, Td, Xq, Xs, layout=1)
+    Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    P.wush_linear_int4(Xq, Xs, Wq, Ws, Y, layout=1, K=K)
+    Xqc, Xsc, Wqc, Wsc = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16), G.empty_u8(N, K // 2), G.empty_u8(N, K // 16)
+    P.wush_unpack_tiled_nvfp4(Xq, Xs, M, K, Xqc, Xsc)
+    P.wush_unpack_tiled_nvfp4(Wq, Ws, N, K, Wqc, Wsc)
+    torch.cuda.synchronize()
+    assert not bool(Y.isnan().any())
+    X = O.bf16_bits_to_f64(L["X"][rows])
+    Yt = O.transform_act(X, T)
+    xq, xs = Q.unpack_codes(Xqc[rows.tolist()].cpu().numpy()), _u16(Xsc[rows.tolist()])
+    q64, s64 = Q.quantize_int4(Yt, prec=np.float64)
+    rate, unexplained = _explained(Yt, xq, xs, q64, s64, tol=1e-5)
+    assert rate <= 1e-3 and unexplained == 0, ("activation codes", rate, unexplained)
+    Wt = O.transform_weight(O.bf16_bits_to_f64(L["W"][cols]), T)
+    qw, sw = Q.quantize_int4(Wt, prec=np.float64)
+    wq, wsc = Q.unpack_codes(Wqc[cols.tolist()].cpu().numpy()), _u16(Wsc[cols.tolist()])
+    rate, unexplained = _explained(Wt, wq, wsc, qw, sw, tol=1e-9)
+    assert rate <= 1e-3 and unexplained == 0, ("weight codes", rate, unexplained)
+    y = O.bf16_bits_to_f64(G.host(Y[rows.tolist()][:, cols.tolist()].contiguous()))
+    own = Q.linear_dequant(xq, xs, wq, wsc)
+    assert O.rel_fro(y, own) <= 2e-3
+    ref = Q.linear_dequant(q64, s64, qw, sw)
+    exact = X @ O.bf16_bits_to_f64(L["W"][cols]).T
+    q_err = O.rel_fro(ref, exact)
+    assert O.rel_fro(y, ref) <= max(2e-3, 0.05 * q_err) and q_err < 0.25, (O.rel_fro(y, ref), q_err)
+
+
 def test_argument_validation(P, G):
     import torch
     Y = torch.empty((4, 4), dtype=torch.bfloat16, device="cuda")
