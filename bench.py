@@ -299,9 +299,15 @@ def nvfp4_bench(args, P, torch, dev):
     def bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
 
-    # Timing does not depend on the transform values: random well-conditioned 16 x 16 blocks.
-    T_bits = I.make_transforms_random(K // 16, seed=95700, block=16)
-    Td, Xd = bf16(T_bits), bf16(L["X"])
+    # The 16 x 16 transforms come from the library's own offline path (Alg. 1 on the device with d = 16)
+    # applied to the workload's weights and calibration tokens.
+    Td = torch.empty((K // 16, 16, 16), dtype=torch.bfloat16, device=dev)
+    bws = torch.empty(P.wush_build_transforms_workspace(K), dtype=torch.uint8, device=dev)
+    P.wush_build_transforms_nvfp4(bf16(L["W"]), bf16(L["X_cal"]), 1e-2, Td, bws)
+    P.wush_build_transforms_status(bws, K)
+    del bws
+    T_bits = Td.view(torch.int16).cpu().numpy().view(np.uint16)
+    Xd = bf16(L["X"])
     # The activation tensor scale is an input of the quantizer (a calibrated constant), taken here from
     # the batch itself, once, outside the timed steps.
     tsx = torch.zeros(1, dtype=torch.float32, device=dev)

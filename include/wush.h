@@ -292,6 +292,19 @@ wush_status wush_quantize_act_nvfp4(const void* X, int64_t M, int64_t K, int64_t
                                     float* dbg_Yt, void* stream);
 
 /*
+ * Offline construction of the 16 x 16 transforms on the device: wush_build_transforms with
+ * d = 16 (Alg. 1 per block of 16 channels, Hadamard matrix of order 16).  Same workspace size
+ * (wush_build_transforms_workspace) and status call (wush_build_transforms_status).
+ *   T16      out  bf16 [K/16][16][16]
+ *   T_f64    out  optional: f64 [K/16][16][16], T before rounding
+ */
+wush_status wush_build_transforms_nvfp4(const void* W, int64_t N, int64_t ldw,
+                                        const void* X_cal, int64_t M_cal, int64_t ldx,
+                                        int64_t K, double lambda,
+                                        void* T16, double* T_f64,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Calibration of the activation tensor scale (offline, on a calibration batch; or online, once
  * before wush_quantize_act_nvfp4, when the batch's own maximum is wanted): AbsMax of T X over
  * the batch / (6 * 448), with the quantizer's own transform arithmetic (BF16 MFMA, FP32

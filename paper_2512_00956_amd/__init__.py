@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     lib,
     lib_path,
     wush_build_transforms,
+    wush_build_transforms_nvfp4,
     wush_build_transforms_status,
     wush_build_transforms_workspace,
     wush_calibrate_act_nvfp4,
@@ -57,5 +58,5 @@ __all__ = [
     "wush_probe_mfma", "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_status",
     "wush_prepare_weight_nvfp4_workspace", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
     "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", "wush_probe_mfma_f16",
-    "wush_calibrate_act_nvfp4", "wush_quantize_act_int4", "wush_prepare_weight_int4", "wush_linear_int4", "wush_quantize_f32_int4",
+    "wush_calibrate_act_nvfp4", "wush_build_transforms_nvfp4", "wush_quantize_act_int4", "wush_prepare_weight_int4", "wush_linear_int4", "wush_quantize_f32_int4",
 ]

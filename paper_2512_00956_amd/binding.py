@@ -36,7 +36,7 @@ EXPORTS = (
     "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_workspace",
     "wush_prepare_weight_nvfp4_status", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
     "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", "wush_probe_mfma_f16",
-    "wush_calibrate_act_nvfp4",
+    "wush_calibrate_act_nvfp4", "wush_build_transforms_nvfp4",
     "wush_quantize_act_int4", "wush_prepare_weight_int4", "wush_linear_int4", "wush_quantize_f32_int4",
 )
 
@@ -131,6 +131,8 @@ def lib() -> ctypes.CDLL:
                                        c_int32, c_void_p, c_int64, c_void_p]
         L.wush_quantize_f32_int4.restype = c_int32
         L.wush_quantize_f32_int4.argtypes = [c_void_p, c_int64, c_int64, c_int32, c_void_p, c_void_p, c_void_p]
+        L.wush_build_transforms_nvfp4.restype = c_int32
+        L.wush_build_transforms_nvfp4.argtypes = L.wush_build_transforms.argtypes
         L.wush_calibrate_act_nvfp4.restype = c_int32
         L.wush_calibrate_act_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
         L.wush_probe_mfma_f16.restype = c_int32
@@ -251,6 +253,16 @@ def wush_build_transforms(W, X_cal, lam: float, T_blocks, workspace, T_f64=None,
                                        _ptr(T_blocks), _ptr(T_f64), _ptr(workspace),
                                        0 if workspace is None else workspace.numel() * workspace.element_size(),
                                        _stream(stream)), "wush_build_transforms")
+
+
+def wush_build_transforms_nvfp4(W, X_cal, lam: float, T16, workspace, T_f64=None, stream=None):
+    """The same with 16 x 16 blocks (NVFP4 variant): -> T16 bf16 [K/16][16][16]."""
+    N, K = W.shape
+    Mc = X_cal.shape[0]
+    _check(lib().wush_build_transforms_nvfp4(_ptr(W), N, W.stride(0), _ptr(X_cal), Mc, X_cal.stride(0), K, float(lam),
+                                             _ptr(T16), _ptr(T_f64), _ptr(workspace),
+                                             0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                             _stream(stream)), "wush_build_transforms_nvfp4")
 
 
 def wush_build_transforms_status(workspace, K: int, stream=None):

@@ -85,7 +85,24 @@ __global__ __launch_bounds__(64) void wush_block_kernel(const double* __restrict
     for (int s = 0; s < S; ++s) acc += p[(int64_t)s * C * 1024 + r * 32 + c];
     return acc * (1.0 / (double)(half ? Mc : N));
   };
-  wush_block_wave(moment, lambda, T_out + (int64_t)b * 1024, T_f64 ? T_f64 + (int64_t)b * 1024 : nullptr, nullptr, status);
+  wush_block_wave<32>(moment, lambda, T_out + (int64_t)b * 1024, T_f64 ? T_f64 + (int64_t)b * 1024 : nullptr, nullptr,
+                      status);
+}
+
+// The same for 16 x 16 blocks (the NVFP4 variant: transform block = quantization group of 16).  The
+// moments of block b are the diagonal 16 x 16 sub-block (b & 1) of the 32-channel moments of block b / 2.
+__global__ __launch_bounds__(64) void wush_block16_kernel(const double* __restrict__ partial, int S, int C, int N,
+                                                          int Mc, double lambda, uint16_t* __restrict__ T_out,
+                                                          double* __restrict__ T_f64, int* __restrict__ status) {
+  const int b = blockIdx.x, b32 = b >> 1, off = 16 * (b & 1);
+  auto moment = [&](int half, int r, int c) {
+    const double* p = partial + ((int64_t)half * S * C + b32) * 1024;
+    double acc = 0.0;
+    for (int s = 0; s < S; ++s) acc += p[(int64_t)s * C * 1024 + (off + r) * 32 + off + c];
+    return acc * (1.0 / (double)(half ? Mc : N));
+  };
+  wush_block_wave<16>(moment, lambda, T_out + (int64_t)b * 256, T_f64 ? T_f64 + (int64_t)b * 256 : nullptr, nullptr,
+                      status);
 }
 
 __global__ void reset_bt_status_kernel(int* status) {
@@ -109,7 +126,7 @@ size_t build_transforms_status_offset(int64_t K) {
 size_t build_transforms_workspace_bytes(int64_t K) { return build_transforms_status_offset(K) + 16; }
 
 hipError_t launch_build_transforms(const void* W, int64_t N, int64_t ldw, const void* X, int64_t Mc, int64_t ldx,
-                                   int64_t K, double lambda, void* T_out, double* T_f64, void* workspace,
+                                   int64_t K, double lambda, int block, void* T_out, double* T_f64, void* workspace,
                                    hipStream_t stream) {
   const int C = (int)(K / 32);
   const int S = splits_for(C);
@@ -123,8 +140,12 @@ hipError_t launch_build_transforms(const void* W, int64_t N, int64_t ldw, const 
                                                                ldx, (int)Mc, per(N), per(Mc), S, C, partial);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  wush_block_kernel<<<dim3(C), dim3(64), 0, stream>>>(partial, S, C, (int)N, (int)Mc, lambda, (uint16_t*)T_out, T_f64,
-                                                      status);
+  if (block == 16)
+    wush_block16_kernel<<<dim3(2 * C), dim3(64), 0, stream>>>(partial, S, C, (int)N, (int)Mc, lambda, (uint16_t*)T_out,
+                                                              T_f64, status);
+  else
+    wush_block_kernel<<<dim3(C), dim3(64), 0, stream>>>(partial, S, C, (int)N, (int)Mc, lambda, (uint16_t*)T_out, T_f64,
+                                                        status);
   return hipGetLastError();
 }
 

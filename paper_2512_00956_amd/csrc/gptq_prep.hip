@@ -309,7 +309,7 @@ __global__ __launch_bounds__(64) void gptq_wush_kernel(const double* __restrict_
     for (int s = 0; s < S; ++s) acc += partial[(int64_t)s * 1024 + r * 32 + c];
     return acc / (double)N;
   };
-  wush_block_wave(moment, lambda, T_bits_i, nullptr, Tb, status);
+  wush_block_wave<32>(moment, lambda, T_bits_i, nullptr, Tb, status);
 }
 
 // identity / fixed transforms for comparisons: T_i given, only widen it

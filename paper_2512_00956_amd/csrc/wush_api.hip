@@ -111,7 +111,21 @@ wush_status wush_build_transforms(const void* W, int64_t N, int64_t ldw, const v
   if (!aligned16(W) || !aligned16(X_cal) || !aligned16(T_blocks) || !aligned16(T_f64)) return WUSH_ERR_ALIGN;
   if (!workspace || workspace_bytes < wush::build_transforms_workspace_bytes(K)) return WUSH_ERR_WORKSPACE;
   if (!aligned16(workspace)) return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_build_transforms(W, N, ldw, X_cal, M_cal, ldx, K, lambda, T_blocks, T_f64, workspace,
+  return from_hip(wush::launch_build_transforms(W, N, ldw, X_cal, M_cal, ldx, K, lambda, 32, T_blocks, T_f64, workspace,
+                                                static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_build_transforms_nvfp4(const void* W, int64_t N, int64_t ldw, const void* X_cal, int64_t M_cal,
+                                        int64_t ldx, int64_t K, double lambda, void* T16, double* T_f64,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (!W || !X_cal || !T16) return WUSH_ERR_NULL;
+  if (wush_status s = check_rows(N, K, ldw)) return s;
+  if (wush_status s = check_rows(M_cal, K, ldx)) return s;
+  if (!(lambda >= 0.0) || !(lambda < 1e6)) return WUSH_ERR_SHAPE;
+  if (!aligned16(W) || !aligned16(X_cal) || !aligned16(T16) || !aligned16(T_f64)) return WUSH_ERR_ALIGN;
+  if (!workspace || workspace_bytes < wush::build_transforms_workspace_bytes(K)) return WUSH_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return WUSH_ERR_ALIGN;
+  return from_hip(wush::launch_build_transforms(W, N, ldw, X_cal, M_cal, ldx, K, lambda, 16, T16, T_f64, workspace,
                                                 static_cast<hipStream_t>(stream)));
 }
 

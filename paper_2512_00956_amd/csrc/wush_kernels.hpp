@@ -37,8 +37,8 @@ hipError_t launch_mxfp4_gemm(const void* Xq, const void* Xs, const void* Wq, con
 size_t build_transforms_workspace_bytes(int64_t K);
 size_t build_transforms_status_offset(int64_t K);
 hipError_t launch_build_transforms(const void* W, int64_t N, int64_t ldw, const void* X, int64_t Mc, int64_t ldx,
-                                   int64_t K, double lambda, void* T_out, double* T_f64, void* workspace,
-                                   hipStream_t stream);
+                                   int64_t K, double lambda, int block, void* T_out, double* T_f64, void* workspace,
+                                   hipStream_t stream);   // block = 32, or 16 for the NVFP4 variant
 
 // Operands in the fragment-order layout (K % 256 == 0).
 hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq, const void* Ws,

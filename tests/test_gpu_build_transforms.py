@@ -118,3 +118,38 @@ def test_build_transforms_flags_indefinite_moment(P, G):
     with pytest.raises(P.WushError) as ei:
         P.wush_build_transforms_status(ws, 64)
     assert ei.value.code == 7
+
+
+@pytest.mark.parametrize("name", ["c1", "c1_lam0", "ragged_rows", "c2_cut"])
+def test_build_transforms_16_matches_oracle(P, G, name):
+    """The same construction with 16 x 16 blocks (the NVFP4 variant)."""
+    import torch
+    cfg, lam = CASES[name]
+    L = I.make_layer(cfg)
+    W, Xc = O.bf16_bits_to_f64(L["W"]), O.bf16_bits_to_f64(L["X_cal"])
+    C16 = cfg.K // 16
+    T_ref = np.empty((C16, 16, 16))
+    for b in range(C16):
+        sl = slice(16 * b, 16 * b + 16)
+        T_ref[b] = O.wush_block(O.second_moment(W[:, sl]), O.second_moment(Xc[:, sl]), lam)
+    T = torch.empty((C16, 16, 16), dtype=torch.bfloat16, device="cuda")
+    T64 = torch.full((C16, 16, 16), float("nan"), dtype=torch.float64, device="cuda")
+    ws = G.empty_u8(P.wush_build_transforms_workspace(cfg.K))
+    P.wush_build_transforms_nvfp4(G.bf16_dev(L["W"]), G.bf16_dev(L["X_cal"]), lam, T, ws, T_f64=T64)
+    P.wush_build_transforms_status(ws, cfg.K)
+    t_bits, t64 = G.host(T), T64.cpu().numpy()
+    assert np.isfinite(t64).all()
+    scale = np.max(np.abs(T_ref), axis=(1, 2), keepdims=True)
+    assert np.max(np.abs(t64 - T_ref) / scale) <= 1e-9
+    ref_bits = O.bf16_values_to_bits(O.round_to_bf16(T_ref))
+    diff = t_bits != ref_bits
+    assert diff.mean() <= 1e-4
+    if diff.any():
+        assert np.all(np.abs(t64[diff] - T_ref[diff]) <= 1e-9 * scale.repeat(16, 1).repeat(16, 2)[diff])
+    # the identities of the construction hold for a 16-block as well
+    b = C16 // 2
+    sl = slice(16 * b, 16 * b + 16)
+    Wp, Xp, U, s, V = O.wush_factors(O.second_moment(W[:, sl]), O.second_moment(Xc[:, sl]), lam)
+    eq = t64[b] @ O.damped(O.second_moment(Xc[:, sl]), lam) @ t64[b].T
+    assert np.allclose(np.diag(eq), s.sum() / 16, rtol=1e-8)
+    assert O.fp_model_objective(t64[b], Wp, Xp) == pytest.approx(s.sum() ** 2 / 16, rel=1e-8)
