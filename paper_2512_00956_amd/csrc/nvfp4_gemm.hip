@@ -105,10 +105,14 @@ __device__ __forceinline__ v4u dequant8_int4(uint32_t w, v2h s) {
   const uint32_t x = w ^ 0x88888888u, y = x >> 4;
   const v2h bias = {(_Float16)1032.0f, (_Float16)1032.0f};
   union { v2h h[4]; v4u u; uint32_t d[4]; } c;
-  c.d[0] = (__builtin_amdgcn_perm(y, x, 0x0C040C00u) & 0x000F000Fu) | 0x64006400u;
-  c.d[1] = (__builtin_amdgcn_perm(y, x, 0x0C050C01u) & 0x000F000Fu) | 0x64006400u;
-  c.d[2] = (__builtin_amdgcn_perm(y, x, 0x0C060C02u) & 0x000F000Fu) | 0x64006400u;
-  c.d[3] = (__builtin_amdgcn_perm(y, x, 0x0C070C03u) & 0x000F000Fu) | 0x64006400u;
+  // (permuted & 0x000F000F) | 0x64006400 as one v_and_or_b32 each (the compiler emits an and and an or)
+  const uint32_t mask = 0x000F000Fu, magic = 0x64006400u;
+  const uint32_t p0 = __builtin_amdgcn_perm(y, x, 0x0C040C00u), p1 = __builtin_amdgcn_perm(y, x, 0x0C050C01u);
+  const uint32_t p2 = __builtin_amdgcn_perm(y, x, 0x0C060C02u), p3 = __builtin_amdgcn_perm(y, x, 0x0C070C03u);
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(c.d[0]) : "v"(p0), "s"(mask), "v"(magic));
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(c.d[1]) : "v"(p1), "s"(mask), "v"(magic));
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(c.d[2]) : "v"(p2), "s"(mask), "v"(magic));
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(c.d[3]) : "v"(p3), "s"(mask), "v"(magic));
 #pragma unroll
   for (int i = 0; i < 4; ++i) c.h[i] = (c.h[i] - bias) * s;
   return c.u;
