@@ -161,3 +161,59 @@ def test_probe_validation(L):
     assert L.wush_probe_mfma(A, 0, 4, A, None) == 2
     assert L.wush_probe_mfma(A, 10, 5000, A, None) == 2
     assert L.wush_probe_mfma(A + 4, 10, 4, A, None) == 3
+
+
+def test_nvfp4_validation(L):
+    q = lambda *a: L.wush_quantize_act_nvfp4(*a)
+    assert q(None, 4, 64, 64, A, A, 0, A, A, None, None) == 1          # null X
+    assert q(A, 4, 64, 64, A, None, 0, A, A, None, None) == 1          # null tensor scale
+    assert q(A, 4, 48, 48, A, A, 0, A, A, None, None) == 2             # K % 32
+    assert q(A, 4, 96, 96, A, A, 1, A, A, None, None) == 2             # tiled layout needs K % 64 == 0
+    assert q(A, 4, 64, 64, A, A, 3, A, A, None, None) == 4             # unknown layout
+    assert q(A, 4, 64, 64, A, A + 2, 0, A, A, None, None) == 3         # tensor scale not 4-byte aligned
+    assert q(A, 4, 64, 64, A + 8, A, 0, A, A, None, None) == 3
+    need = L.wush_prepare_weight_nvfp4_workspace(64)
+    assert need >= 4 * 256 * 8 + 12 and L.wush_prepare_weight_nvfp4_workspace(40) == 0
+    w = lambda *a: L.wush_prepare_weight_nvfp4(*a)
+    assert w(A, 8, 64, 64, A, 0, A, A, None, A, need, None) == 1       # null tensor scale (output)
+    assert w(A, 8, 64, 64, A, 0, A, A, A, None, need, None) == 5
+    assert w(A, 8, 64, 64, A, 0, A, A, A, A, need - 1, None) == 5
+    assert w(A, 8, 64, 64, A, 2, A, A, A, A, need, None) == 4
+    assert L.wush_prepare_weight_nvfp4_status(None, 64, None) == 1
+    lin = lambda *a: L.wush_linear_nvfp4(*a)
+    assert lin(A, A, None, A, A, A, 4, 8, 64, 0, 0, A, 8, None) == 1
+    assert lin(A, A, A, A, A, A, 4, 8, 96, 0, 0, A, 8, None) == 2      # K % 64
+    assert lin(A, A, A, A, A, A, 4, 9, 64, 0, 0, A, 8, None) == 2      # ldy < N
+    assert lin(A, A, A, A, A, A, 4, 8, 64, 0, 2, A, 8, None) == 4      # output type
+    assert lin(A, A, A, A, A, A, 4, 8, 64, 5, 0, A, 8, None) == 4      # layout
+    assert lin(A, A, A, A, A, A, 4, 8, 64, 0, 1, A + 2, 8, None) == 3  # f32 Y not 4-byte aligned
+    assert L.wush_calibrate_act_nvfp4(A, 4, 64, 64, A, None, None) == 1
+    assert L.wush_calibrate_act_nvfp4(A, 4, 64, 60, A, A, None) == 2
+    need_bt = L.wush_build_transforms_workspace(64)
+    assert L.wush_build_transforms_nvfp4(A, 8, 64, A, 16, 64, 64, 0.01, A, None, A, need_bt - 1, None) == 5
+    assert L.wush_build_transforms_nvfp4(A, 8, 64, None, 16, 64, 64, 0.01, A, None, A, need_bt, None) == 1
+    assert P.wush_packed_sizes_nvfp4(100, 512) == (100 * 256, 100 * 32)
+    assert P.wush_packed_sizes_nvfp4(100, 512, 1) == (128 * 256, 128 * 32)
+    with pytest.raises(P.WushError):
+        P.wush_packed_sizes_nvfp4(100, 96, 1)
+    assert L.wush_unpack_tiled_nvfp4(A, A, 4, 96, A, A, None) == 2
+    assert L.wush_probe_mfma_f16(None, 10, 1, A, None) == 1 and L.wush_probe_mfma_f16(A, 0, 1, A, None) == 2
+
+
+def test_int4_validation(L):
+    q = lambda *a: L.wush_quantize_act_int4(*a)
+    assert q(None, 4, 64, 64, A, 0, A, A, None, None) == 1
+    assert q(A, 4, 48, 48, A, 0, A, A, None, None) == 2
+    assert q(A, 4, 96, 96, A, 1, A, A, None, None) == 2                # tiled layout needs K % 64 == 0
+    assert q(A, 4, 64, 64, A, 9, A, A, None, None) == 4
+    assert q(A, 4, 64, 64, A, 0, A + 4, A, None, None) == 3
+    need = L.wush_prepare_weight_workspace(8, 64)
+    w = lambda *a: L.wush_prepare_weight_int4(*a)
+    assert w(A, 8, 64, 64, A, 0, A, A, A, need - 1, None) == 5
+    assert w(A, 8, 64, 64, None, 0, A, A, A, need, None) == 1
+    lin = lambda *a: L.wush_linear_int4(*a)
+    assert lin(A, A, A, None, 4, 8, 64, 0, 0, A, 8, None) == 1
+    assert lin(A, A, A, A, 4, 8, 32, 0, 0, A, 8, None) == 2            # K % 64
+    assert lin(A, A, A, A, 4, 8, 64, 0, 0, A + 1, 8, None) == 3
+    tap = lambda *a: L.wush_quantize_f32_int4(*a)
+    assert tap(A, 4, 64, 0, None, A, None) == 1 and tap(A, 4, 65, 0, A, A, None) == 2
