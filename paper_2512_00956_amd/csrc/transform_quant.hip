@@ -99,13 +99,20 @@ int device_cu_count() {
 }
 
 // Token tiles each workgroup walks down (the register-resident transforms are loaded once per
-// workgroup).  Measured on 2048..32768 tokens x 4096..14336 channels: a grid of at most one
-// workgroup per CU, all of them busy from start to end, streams at 6.0-7.2 TB/s, while grids of
-// 2-4 workgroups per CU lose up to a third to the uneven last round (8192 x 8192: 42 -> 28 us).
-// (2048 x 4096: 5.15 -> 4.86 us.)  Inputs with fewer tiles than CUs take the shortest walk.
+// workgroup).  Chosen from the number of (tile, channel group) units T against the CU count, after
+// sweeps of the walk on 512..32768 tokens x 4096..28672 channels (graph replay for the small ones):
+//   T <= 1.5 CUs : 1   (latency bound: 1024 x 4096 takes 3.7 us with a walk of 1, 4.6 with 2)
+//   T <= 6 CUs   : 2   (2048 x 4096: 4.9 us against 5.2; 2048 x 8192: 8.8 against 9.7)
+//   T < 16 CUs   : 4   (4096 x 8192: 15.8 us against 21.2 with 1 and 16.4 with 8)
+//   larger       : a grid of at most one workgroup per CU, all busy from start to end: 6.0-7.2 TB/s
+//                  cache resident, where grids of 2-4 workgroups per CU lose up to a third to an
+//                  uneven last round (8192 x 8192: 42 -> 28 us).
 int token_walk(int ntiles, int col_groups) {
   const int cus = device_cu_count();
-  if ((int64_t)ntiles * col_groups <= cus) return 1;
+  const int64_t units = (int64_t)ntiles * col_groups;
+  if (2 * units <= 3 * cus) return 1;
+  if (units <= 6 * cus) return 2;
+  if (units < 16 * cus) return 4;
   const int wg_rows = cus / col_groups > 0 ? cus / col_groups : 1;
   return (ntiles + wg_rows - 1) / wg_rows;
 }
