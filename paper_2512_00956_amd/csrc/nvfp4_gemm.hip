@@ -26,6 +26,9 @@
 // interleaving it; it runs as one block per K step.
 #include <stdlib.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "nvfp4_layout.hpp"
 #include "wush_device.hpp"
 #include "wush_kernels.hpp"
@@ -39,8 +42,11 @@ typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
 constexpr int kBM = 256, kBK = 64;
 constexpr int kXBytes = 8 * 256 * 16;            // X part of a stage: [k chunk of 8][256 rows][16 B]
-constexpr int stage_bytes(int CB) { return kXBytes + 8 * 64 * CB * 16; }   // then the W part, 64*CB rows
-constexpr int lds_bytes(int CB) { return 2 * stage_bytes(CB); }           // 128 KiB at CB = 4
+// The W part has the same geometry whatever the tile width (rows past 64*CB are written by the
+// threads that have no W row of their own -- a duplicate, never read -- so that the conversion
+// stream has no branch in it).
+constexpr int kStage = 2 * kXBytes;
+constexpr int kLdsBytes = 2 * kStage;            // 128 KiB
 
 struct Raw {
   v4u q[2];    // 64 codes of one row
@@ -141,6 +147,84 @@ __device__ __forceinline__ void convert_group(const Raw& r, int g, char* operand
   }
 }
 
+// ---------------------------------------------------------------------------
+// The K step as a hand-ordered instruction stream.  Measured on this GPU (FP16 MFMA 32x32x16,
+// one wave per SIMD): up to about four independent VALU operations issue in the shadow of each
+// 32-cycle MFMA for free (8 cost 10-14 cycles more, 16 double the time), while a block of 130
+// conversion operations with no MFMA between them simply adds its 500-1000 cycles to the step.
+// So the conversion of step kt+1 is cut into micro-operations (per 8 codes: 4 converts, 4
+// multiplies, one 16-byte LDS write; more for INT4) and dealt out over the MFMAs of step kt, a
+// few per MFMA, converts well ahead of the multiplies that use them; the LDS reads of the next
+// group of fragments and the global loads of step kt+2 go into the same slots.  A scheduling
+// barrier after every slot keeps the compiler from regrouping them.
+// ---------------------------------------------------------------------------
+template <int FMT>
+struct Conv {
+  static constexpr int kOpsPerTask = FMT == kNvfp4 ? 9 : 19;   // micro-operations per 8 codes
+  v2h h[4];
+  uint32_t x, y, p[4];
+};
+
+// Micro-operation U of the dword task (8 codes -> one 16-byte LDS chunk).  w = the 8 codes,
+// s = the group scale in both halves, dst = where the chunk goes.
+template <int FMT, int U>
+__device__ __forceinline__ void micro_op(Conv<FMT>& c, uint32_t w, v2h s, char* dst) {
+  if constexpr (FMT == kNvfp4) {
+    if constexpr (U < 4) c.h[U] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, U);
+    else if constexpr (U < 8) c.h[U - 4] = c.h[U - 4] * s;
+    else {
+      union { v2h h[4]; v4u u; } o;
+      o.h[0] = c.h[0]; o.h[1] = c.h[1]; o.h[2] = c.h[2]; o.h[3] = c.h[3];
+      *reinterpret_cast<v4u*>(dst) = o.u;
+    }
+  } else {
+    if constexpr (U == 0) c.x = w ^ 0x88888888u;
+    else if constexpr (U == 1) c.y = c.x >> 4;
+    else if constexpr (U < 6) c.p[U - 2] = __builtin_amdgcn_perm(c.y, c.x, 0x0C040C00u + 0x00010001u * (U - 2));
+    else if constexpr (U < 10) {
+      uint32_t d;
+      const uint32_t mask = 0x000F000Fu, magic = 0x64006400u;
+      asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(c.p[U - 6]), "s"(mask), "v"(magic));
+      union { uint32_t u; v2h h; } t;
+      t.u = d;
+      c.h[U - 6] = t.h;
+    } else if constexpr (U < 14) {
+      const v2h bias = {(_Float16)1032.0f, (_Float16)1032.0f};
+      c.h[U - 10] = c.h[U - 10] - bias;
+    } else if constexpr (U < 18) c.h[U - 14] = c.h[U - 14] * s;
+    else {
+      union { v2h h[4]; v4u u; } o;
+      o.h[0] = c.h[0]; o.h[1] = c.h[1]; o.h[2] = c.h[2]; o.h[3] = c.h[3];
+      *reinterpret_cast<v4u*>(dst) = o.u;
+    }
+  }
+}
+
+// The four group scales of a row's K step as FP16 (NVFP4: four E4M3 bytes; INT4: two BF16
+// numbers, each serving two groups of 16).
+template <int FMT>
+__device__ __forceinline__ void step_scales(uint32_t sdw, v2h (&sc)[2]) {
+  if constexpr (FMT == kNvfp4) {
+    sc[0] = e4m3x2_to_f16<false>(sdw);
+    sc[1] = e4m3x2_to_f16<true>(sdw);
+  } else {
+    const _Float16 s0 = (_Float16)__uint_as_float(sdw << 16), s1 = (_Float16)__uint_as_float(sdw & 0xFFFF0000u);
+    sc[0] = (v2h){s0, s0};
+    sc[1] = (v2h){s1, s1};
+  }
+}
+
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), unrolled at compile time.
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 template <bool OUT_F32, int CB, int FMT>
 __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
     const uint8_t* __restrict__ Xq, const uint8_t* __restrict__ Xs, const float* __restrict__ tsx,
@@ -148,7 +232,11 @@ __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
     void* __restrict__ Yv, int64_t ldy, int M, int N, int K, int tiles_m, int tiles_n, int tiled) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   constexpr int kBN = 64 * CB;         // output channels per tile
-  constexpr int kStage = stage_bytes(CB);
+  constexpr int kSlots = 16 * CB;      // MFMAs per K step and wave
+  constexpr int kGroup = 4 * CB;       // MFMAs per 16-element K group
+  // slots that carry conversion work; the workgroup barrier follows, then the first fragments of the next step
+  constexpr int kConvSlots = FMT == kNvfp4 ? 12 * CB : 16 * CB - 4;
+  constexpr int kOps = Conv<FMT>::kOpsPerTask;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -163,28 +251,25 @@ __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
   const int m0 = tm * kBM, n0 = tn * kBN;
 
   const int64_t rowX = min(m0 + tid, M - 1);  // rows past the end re-read the last valid row
-  const int64_t rowW = min(n0 + min(tid, kBN - 1), N - 1);
-  const bool w_thread = tid < kBN;            // wave-uniform: kBN is a multiple of 64
+  const int64_t rowW = min(n0 + min(tid, kBN - 1), N - 1);   // threads past the tile's W rows repeat its last row
   const int KT = K / kBK;
 
   auto convert = [&](const Raw& x, const Raw& w, char* stage) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) convert_group<FMT>(x, g, stage, 256, tid);
-    if (w_thread) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) convert_group<FMT>(w, g, stage + kXBytes, kBN, tid);
-    }
+    for (int g = 0; g < 4; ++g) convert_group<FMT>(w, g, stage + kXBytes, 256, tid);
   };
 
-  // Packed operands of the step after the one being converted are in flight for one
-  // whole MFMA phase.  Step numbers are clamped (surplus loads re-read the last step).
+  // Packed operands in flight: (ax_, aw_) = step kt+1, converted during step kt; (bx_, bw_) = step
+  // kt+2, loaded at the start of step kt.  Step numbers are clamped (surplus loads re-read the last step).
   const RowAddr ax = row_addr(Xq, Xs, rowX, K, tiled), aw = row_addr(Wq, Ws, rowW, K, tiled);
-  Raw rx, rw;
-  load_raw(rx, ax, 0);
-  load_raw(rw, aw, 0);
-  convert(rx, rw, lds);
-  load_raw(rx, ax, min(1, KT - 1));
-  load_raw(rw, aw, min(1, KT - 1));
+  Raw ax_, aw_, bx_, bw_;
+  load_raw(ax_, ax, 0);
+  load_raw(aw_, aw, 0);
+  convert(ax_, aw_, lds);
+  load_raw(ax_, ax, min(1, KT - 1));
+  load_raw(aw_, aw, min(1, KT - 1));
   __syncthreads();
 
   v16f acc[4][CB];
@@ -193,33 +278,73 @@ __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
 #pragma unroll
     for (int j = 0; j < CB; ++j) acc[i][j] = (v16f){0};
 
-  auto mma_step = [&](const char* cur) {
+  // Fragment registers of two K groups: group g of a step uses set g & 1.
+  v8h fa[2][4], fb[2][CB];
+  const int a_off = (h * 256 + wm * 128 + l32) * 16;                          // + 2g chunks, + 32 i rows
+  const int b_off = kXBytes + (h * 256 + wn * (32 * CB) + l32) * 16;
+  auto read_frag = [&](const char* stage, int g, int r, int set) {            // r: 0..3 = A rows, 4.. = B rows
+    if (r < 4) fa[set][r] = *reinterpret_cast<const v8h*>(stage + a_off + (2 * g * 256 + 32 * r) * 16);
+    else fb[set][r - 4] = *reinterpret_cast<const v8h*>(stage + b_off + (2 * g * 256 + 32 * (r - 4)) * 16);
+  };
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      v8h a[4], b[CB];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        a[i] = *reinterpret_cast<const v8h*>(cur + ((2 * g + h) * 256 + wm * 128 + 32 * i + l32) * 16);
-#pragma unroll
-      for (int j = 0; j < CB; ++j)
-        b[j] = *reinterpret_cast<const v8h*>(cur + kXBytes + ((2 * g + h) * kBN + wn * (32 * CB) + 32 * j + l32) * 16);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < CB; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+  for (int r = 0; r < 4 + CB; ++r) read_frag(lds, 0, r, 0);
+
+  // One K step.  NEXT: another step follows (convert it, synchronize, fetch its first fragments).
+  auto step = [&](int kt, auto next_tag) {
+    constexpr bool NEXT = decltype(next_tag)::value;
+    const char* cur = lds + (kt & 1) * kStage;
+    char* nxt = lds + ((kt + 1) & 1) * kStage;
+    char* xdst = nxt + tid * 16;                 // + chunk * 256 rows * 16
+    char* wdst = nxt + kXBytes + tid * 16;
+    Conv<FMT> cv;
+    v2h sx[2], sw[2];
+    if (NEXT) {
+      step_scales<FMT>(ax_.s, sx);
+      step_scales<FMT>(aw_.s, sw);
+      const int kl = min(kt + 2, KT - 1);
+      load_raw(bx_, ax, kl);
+      load_raw(bw_, aw, kl);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<kSlots>([&](auto slot) {
+      constexpr int S = decltype(slot)::value;
+      constexpr int g = S / kGroup, idx = S % kGroup, i = idx / CB, j = idx % CB;
+      if (NEXT && S == kConvSlots) __syncthreads();   // every conversion write of this step is behind us
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[g & 1][i], fb[g & 1][j], acc[i][j], 0, 0, 0);
+      // fragments of the next group: one LDS read per slot from the second slot of the group on
+      if constexpr (g < 3) {
+        if constexpr (idx >= 1 && idx - 1 < 4 + CB) read_frag(cur, g + 1, idx - 1, (g + 1) & 1);
+      }
+      if constexpr (NEXT && S >= kConvSlots) {
+        // behind the barrier: the first fragments of the next step, spread over the remaining slots
+        constexpr int left = kSlots - kConvSlots, r0 = (S - kConvSlots) * (4 + CB) / left,
+                      r1 = (S - kConvSlots + 1) * (4 + CB) / left;
+        static_for<r1 - r0>([&](auto q) { read_frag(nxt, 0, r0 + decltype(q)::value, 0); });
+      }
+      // conversion micro-operations of this slot: 8 X tasks, then 8 W tasks
+      if constexpr (NEXT && S < kConvSlots) {
+        constexpr int total = 16 * kOps, u0 = S * total / kConvSlots, u1 = (S + 1) * total / kConvSlots;
+        static_for<u1 - u0>([&](auto q) {
+          constexpr int u = u0 + decltype(q)::value, task = u / kOps, op = u % kOps, d = task & 7;
+          if constexpr (task < 8) {
+            micro_op<FMT, op>(cv, ax_.q[d >> 2][d & 3], (v2h){sx[d >> 2][(d >> 1) & 1], sx[d >> 2][(d >> 1) & 1]},
+                              xdst + d * 256 * 16);
+          } else {
+            micro_op<FMT, op>(cv, aw_.q[d >> 2][d & 3], (v2h){sw[d >> 2][(d >> 1) & 1], sw[d >> 2][(d >> 1) & 1]},
+                              wdst + d * 256 * 16);
+          }
+        });
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    if (NEXT) {
+      ax_ = bx_;
+      aw_ = bw_;
     }
   };
 
-  for (int kt = 0; kt + 1 < KT; ++kt) {
-    mma_step(lds + (kt & 1) * kStage);
-    convert(rx, rw, lds + ((kt + 1) & 1) * kStage);   // the other stage: last read before the previous barrier
-    const int kl = min(kt + 2, KT - 1);
-    load_raw(rx, ax, kl);
-    load_raw(rw, aw, kl);
-    __syncthreads();
-  }
-  mma_step(lds + ((KT - 1) & 1) * kStage);
+  for (int kt = 0; kt + 1 < KT; ++kt) step(kt, std::true_type{});
+  step(KT - 1, std::false_type{});
 
   const float scale = FMT == kNvfp4 ? *tsx * *tsw : 1.0f;   // INT4 has no tensor scales (null pointers)
 #pragma unroll
@@ -247,12 +372,12 @@ hipError_t launch_shape(const void* Xq, const void* Xs, const float* tsx, const 
   static bool configured = false;  // per instantiation
   if (!configured) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4_f16_gemm_kernel<OUT_F32, CB, FMT>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(CB));
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + 64 * CB - 1) / (64 * CB));
-  w4_f16_gemm_kernel<OUT_F32, CB, FMT><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds_bytes(CB), stream>>>(
+  w4_f16_gemm_kernel<OUT_F32, CB, FMT><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), kLdsBytes, stream>>>(
       (const uint8_t*)Xq, (const uint8_t*)Xs, tsx, (const uint8_t*)Wq, (const uint8_t*)Ws, tsw, Y, ldy, (int)M, (int)N,
       (int)K, tiles_m, tiles_n, tiled);
   return hipGetLastError();
