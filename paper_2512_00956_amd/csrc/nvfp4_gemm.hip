@@ -18,12 +18,16 @@
 //
 // Tiling: one workgroup (4 waves, 2 x 2) per 256 x 64*CB output tile (CB = 4, 3 or 2:
 // 256, 192 or 128 output channels, chosen per problem so that the last round of tiles
-// leaves few CUs idle), K in steps of 64 (= 4 scale groups); each thread converts one X
-// row (and one W row) of the next step after the MFMAs of the current one; two LDS
-// stages.  On this GPU a SIMD does not overlap VALU issue with MFMA execution (measured:
-// n VALU operations between two 32-cycle MFMAs cost 4n cycles more, for one wave per
-// SIMD and for two), so the conversion is priced in issue slots and nothing is gained by
-// interleaving it; it runs as one block per K step.
+// leaves few CUs idle), K in steps of 64 (= 4 scale groups), two LDS stages.  Two kernels:
+//   * w4_f16_gemm_kernel stages both operands in LDS (each thread converts one X row and one
+//     W row of the next step); it serves INT4 and any K;
+//   * nvfp4_wreg_gemm_kernel (NVFP4, K a multiple of 128) keeps W out of LDS: every wave
+//     converts the W fragments it multiplies in its own registers.
+// In both the conversion of the next step is cut into single instructions and dealt out over
+// the MFMAs of the current one: with one wave per SIMD the MFMA pipe is busy 32 cycles per
+// instruction and a handful of independent vector instructions issue in that shadow for free,
+// while anything issued as a block (conversions, register moves, global loads, address
+// arithmetic) stalls the pipe for its length.
 #include <stdlib.h>
 
 #include <type_traits>
@@ -365,6 +369,278 @@ __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------
+// NVFP4, K a multiple of 128: the W operand goes straight into registers.  Every wave loads the
+// packed W fragments it multiplies by itself and converts them in registers (the two waves that
+// share the columns each do it); only X passes through LDS.  The order of the 16 k of an MFMA is
+// free as long as both operands agree: MFMA group g of a K step takes, in lane half h, the eight
+// codes of dword 4h+g of the row's 32 bytes, so the four groups of a lane are ONE 16-byte load
+// and its two scale bytes are bytes 2h, 2h+1 of the row's scale dword.  Against the staged kernel:
+// half the LDS traffic and half the barriers' work for 40 % more conversion arithmetic, which
+// costs nothing as long as it sits in the shadow of the MFMAs.
+//
+// What the slots of a K step carry besides their MFMA (measured: arithmetic dealt out like this is
+// free, a global load costs its slot about 30 cycles, so there is one per slot at most, with a
+// scalar base and a 32-bit lane offset; a block of loads or register moves stalls the MFMA pipe
+// for its whole length, hence two K steps per loop trip with the register sets swapping roles
+// instead of being copied):
+//   every slot        two conversion operations of the W fragments of the next group
+//   group 0           the three loads of X for step kt+2        (its register set is free)
+//   group 1           the W scale dwords for step kt+2          (consumed in group 3 of step kt-1)
+//   group 2           the W codes for step kt+2, fragment by fragment as its last group is through
+//   slots < 16 CB - 4 the conversion of X for step kt+1 into the other LDS stage
+//   then the workgroup barrier and the first four A fragments of step kt+1
+// ---------------------------------------------------------------------------
+
+// Room a slot of the register-W kernel has for X conversion work, in instructions: about six issue
+// in the shadow of one MFMA; the slot's own fragment read, W conversion pair, scale conversion and
+// global load (which costs several) come off that.
+template <int CB>
+constexpr int wreg_slot_room(int S) {
+  constexpr int kRoom = 6, kLoadCost = 3;
+  const int kGroup = 4 * CB, g = S / kGroup, idx = S % kGroup;
+  int used = 2;                                              // the W conversion pair
+  if (g < 3 && idx >= 1 && idx <= 4) used += 1;              // A fragment read
+  if (g == 3 && idx < CB) used += 2;                         // W scale pair: shift and convert
+  if (g == 0 && idx >= kGroup - 3) used += kLoadCost;                // global loads
+  if (g == 1 && idx >= kGroup - CB) used += kLoadCost;
+  if (g == 2 && (idx & 3) == 3) used += kLoadCost;
+  return used >= kRoom ? 0 : kRoom - used;
+}
+// Conversion operations of X dealt to the slots before `S`, out of `total`, in proportion to the room.
+template <int CB>
+constexpr int wreg_x_ops_before(int S, int total, int conv_slots) {
+  int all = 0, before = 0;
+  for (int t = 0; t < conv_slots; ++t) {
+    all += wreg_slot_room<CB>(t);
+    if (t < S) before += wreg_slot_room<CB>(t);
+  }
+  return (int)((long long)total * before / all);
+}
+struct RawW {
+  v4u q;       // the lane's 32 codes of one row's K step (dwords 4h .. 4h+3)
+  uint32_t s;  // the row's 4 scale bytes
+};
+union Frag {
+  v2h h[4];
+  v8h v;
+};
+
+template <bool OUT_F32, int CB>
+__global__ __launch_bounds__(256) void nvfp4_wreg_gemm_kernel(
+    const uint8_t* __restrict__ Xq, const uint8_t* __restrict__ Xs, const float* __restrict__ tsx,
+    const uint8_t* __restrict__ Wq, const uint8_t* __restrict__ Ws, const float* __restrict__ tsw,
+    void* __restrict__ Yv, int64_t ldy, int M, int N, int K, int tiles_m, int tiles_n, int tiled) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  constexpr int FMT = kNvfp4;
+  constexpr int kBN = 64 * CB;
+  constexpr int kSlots = 16 * CB, kGroup = 4 * CB;
+  constexpr int kConvSlots = 16 * CB - 4;
+  constexpr int kXSlots = CB == 4 ? 48 : 16 * CB - 4;   // slots that carry X conversion work (measured)
+  constexpr int kOps = Conv<FMT>::kOpsPerTask;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, h = lane >> 5;
+
+  const int ntiles = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  if ((ntiles & 7) == 0) id = (id & 7) * (ntiles >> 3) + (id >> 3);
+  const int tm = id % tiles_m, tn = id / tiles_m;
+  const int m0 = tm * kBM, n0 = tn * kBN;
+  const int KT = K / kBK;   // even
+
+  // Addresses: a uniform 64-bit base per operand and K step (scalar registers) plus a 32-bit lane
+  // offset inside the tile.
+  int q_step = tiled ? 1024 : 32, q_half = tiled ? 512 : 16, s_step = tiled ? 128 : 4;
+  asm volatile("" : "+s"(q_step), "+s"(q_half), "+s"(s_step));   // plain numbers from here on: one loop, not one per layout
+  auto lane_off = [&](const int64_t row, const int64_t row0, int hh, uint32_t& oq, uint32_t& os) {
+    if (tiled) {
+      oq = (uint32_t)(nv_tiled_chunk_offset(row, 0, hh, KT) - nv_tiled_chunk_offset(row0, 0, 0, KT));
+      os = (uint32_t)(nv_tiled_scale_offset(row, 0, KT) - nv_tiled_scale_offset(row0, 0, KT));
+    } else {
+      oq = (uint32_t)((row - row0) * (K / 2) + hh * 16);
+      os = (uint32_t)((row - row0) * (K / 16));
+    }
+  };
+  const uint8_t* xq0 = Xq + (tiled ? nv_tiled_chunk_offset(m0, 0, 0, KT) : (int64_t)m0 * (K / 2));
+  const uint8_t* xs0 = Xs + (tiled ? nv_tiled_scale_offset(m0, 0, KT) : (int64_t)m0 * (K / 16));
+  const uint8_t* wq0 = Wq + (tiled ? nv_tiled_chunk_offset(n0, 0, 0, KT) : (int64_t)n0 * (K / 2));
+  const uint8_t* ws0 = Ws + (tiled ? nv_tiled_scale_offset(n0, 0, KT) : (int64_t)n0 * (K / 16));
+  uint32_t xoq, xos, woq[CB], wos[CB];
+  lane_off(min(m0 + tid, M - 1), m0, 0, xoq, xos);   // rows past the end re-read the last valid row
+  // W fragment j of this wave: rows n0 + 32 CB wn + 32 j + l32; lane half h takes the 16-byte half h of the K step
+#pragma unroll
+  for (int j = 0; j < CB; ++j) lane_off(min(n0 + wn * (32 * CB) + 32 * j + l32, N - 1), n0, h, woq[j], wos[j]);
+  const int sh = 16 * h;
+
+  // One load of K step `kt` at a time.  which = 0, 1: the two 16-byte halves of the X row, 2: its
+  // scale dword.  The empty asm keeps the 32-bit lane offset apart from the scalar base, so that the
+  // load takes the base from scalar registers and no vector instruction computes an address.
+  auto load_x = [&](Raw& r, int kt, int which) {
+    asm volatile("" : "+v"(xoq), "+v"(xos));
+    if (which < 2) r.q[which] = *reinterpret_cast<const v4u*>(xq0 + ((int64_t)kt * q_step + which * q_half) + xoq);
+    else r.s = *reinterpret_cast<const uint32_t*>(xs0 + (int64_t)kt * s_step + xos);
+  };
+  auto load_wq = [&](RawW& r, int kt, int j) {
+    asm volatile("" : "+v"(woq[j]));
+    r.q = *reinterpret_cast<const v4u*>(wq0 + (int64_t)kt * q_step + woq[j]);
+  };
+  auto load_ws = [&](RawW& r, int kt, int j) {
+    asm volatile("" : "+v"(wos[j]));
+    r.s = *reinterpret_cast<const uint32_t*>(ws0 + (int64_t)kt * s_step + wos[j]);
+  };
+
+  Raw xr[2];                  // X of step kt+1 lives in xr[(kt+1) & 1] during step kt; the other set receives step kt+2
+  RawW wr[2][CB];             // W of step kt in wr[kt & 1]; refilled with step kt+2 as its groups are converted
+  v2h wsc[2][CB];             // their scales as FP16 pairs: [group >> 1]
+  Frag fb[2][CB];
+  v8h fa[2][4];
+
+#pragma unroll
+  for (int w = 0; w < 3; ++w) load_x(xr[0], 0, w);
+#pragma unroll
+  for (int j = 0; j < CB; ++j) {
+    load_wq(wr[0][j], 0, j);
+    load_ws(wr[0][j], 0, j);
+  }
+#pragma unroll
+  for (int j = 0; j < CB; ++j) {
+    load_wq(wr[1][j], 1, j);
+    load_ws(wr[1][j], 1, j);
+  }
+#pragma unroll
+  for (int g = 0; g < 4; ++g) convert_group<FMT>(xr[0], g, lds, 256, tid);
+#pragma unroll
+  for (int w = 0; w < 3; ++w) load_x(xr[1], 1, w);
+#pragma unroll
+  for (int j = 0; j < CB; ++j) {
+    wsc[0][j] = e4m3x2_to_f16<false>(wr[0][j].s >> sh);
+    const v2h s = {wsc[0][j][0], wsc[0][j][0]};
+    fb[0][j].h[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(wr[0][j].q[0], 1.0f, 0) * s;
+    fb[0][j].h[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(wr[0][j].q[0], 1.0f, 1) * s;
+    fb[0][j].h[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(wr[0][j].q[0], 1.0f, 2) * s;
+    fb[0][j].h[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(wr[0][j].q[0], 1.0f, 3) * s;
+  }
+  __syncthreads();
+
+  v16f acc[4][CB];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+      acc[i][j] = (v16f){0};
+      asm volatile("" : "+a"(acc[i][j]));   // pins the accumulators to their registers from here to the epilogue
+    }
+
+  // A fragment of MFMA group g, lane half h: LDS chunk 4h + g (the dword order W is loaded in)
+  const int a_off = (4 * h * 256 + wm * 128 + l32) * 16;
+  auto read_frag = [&](const char* stage, int g, int r, int set) {
+    fa[set][r] = *reinterpret_cast<const v8h*>(stage + a_off + (g * 256 + 32 * r) * 16);
+  };
+#pragma unroll
+  for (int r = 0; r < 4; ++r) read_frag(lds, 0, r, 0);
+
+  // One K step of parity P = kt & 1 (LDS stage and register sets are compile-time choices).  Every
+  // step prepares a successor; behind the last one that is the last step again (clamped loads),
+  // converted into a stage and a fragment set nobody reads.
+  auto step = [&](int kt, auto parity) {
+    constexpr int P = decltype(parity)::value, Q = P ^ 1;
+    const char* cur = lds + P * kXBytes;
+    char* nxt = lds + Q * kXBytes;
+    char* xdst = nxt + tid * 16;
+    Conv<FMT> cv;
+    v2h sx[2];
+    step_scales<FMT>(xr[Q].s, sx);
+    const int kl = min(kt + 2, KT - 1);   // the step the free register sets are refilled with
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<kSlots>([&](auto slot) {
+      constexpr int S = decltype(slot)::value;
+      constexpr int g = S / kGroup, idx = S % kGroup, i = idx / CB, j = idx % CB;
+      if (S == kConvSlots) __syncthreads();
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[g & 1][i], fb[g & 1][j].v, acc[i][j], 0, 0, 0);
+      if constexpr (g < 3) {
+        if constexpr (idx >= 1 && idx <= 4) read_frag(cur, g + 1, idx - 1, (g + 1) & 1);
+      }
+      if constexpr (S >= kConvSlots) read_frag(nxt, 0, S - kConvSlots, 0);
+      // W fragments of the next group (group 0 of the next step behind group 3): two operations per slot
+      {
+        constexpr int tg = (g + 1) & 3, set = (g + 1) & 1, R = g == 3 ? Q : P;
+        if constexpr (g == 3 && idx < CB) wsc[Q][idx] = e4m3x2_to_f16<false>(wr[Q][idx].s >> sh);
+        static_for<2>([&](auto q) {
+          constexpr int u = 2 * idx + decltype(q)::value, task = u / 8, op = u % 8;
+          const RawW& r = wr[R][task];
+          const v2h& sp = wsc[R][task];
+          if constexpr (op < 4) fb[set][task].h[op] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(r.q[tg], 1.0f, op);
+          else fb[set][task].h[op - 4] = fb[set][task].h[op - 4] * (v2h){sp[tg >> 1], sp[tg >> 1]};
+        });
+      }
+      // refills, one load per slot, each once its registers are free
+      if constexpr (g == 0 && idx >= kGroup - 3) load_x(xr[P], kl, idx - (kGroup - 3));
+      if constexpr (g == 1 && idx >= kGroup - CB) load_ws(wr[P][idx - (kGroup - CB)], kl, idx - (kGroup - CB));
+      if constexpr (g == 2 && (idx & 3) == 3) load_wq(wr[P][idx >> 2], kl, idx >> 2);
+      if constexpr (S < kXSlots) {
+        constexpr int total = 8 * kOps, u0 = wreg_x_ops_before<CB>(S, total, kXSlots),
+                      u1 = wreg_x_ops_before<CB>(S + 1, total, kXSlots);
+        static_for<u1 - u0>([&](auto q) {
+          constexpr int u = u0 + decltype(q)::value, d = u / kOps, op = u % kOps;
+          micro_op<FMT, op>(cv, xr[Q].q[d >> 2][d & 3], (v2h){sx[d >> 2][(d >> 1) & 1], sx[d >> 2][(d >> 1) & 1]},
+                            xdst + d * 256 * 16);
+        });
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
+#pragma clang loop unroll(disable)
+  for (int kt = 0; kt < KT; kt += 2) {
+    step(kt, std::integral_constant<int, 0>{});
+    step(kt + 1, std::integral_constant<int, 1>{});
+  }
+
+  const float scale = *tsx * *tsw;
+  // Output coordinates from a fresh copy of the thread index: nothing of the prologue's index
+  // arithmetic has to stay in registers across the loop.
+  int te = threadIdx.x;
+  asm volatile("" : "+v"(te));
+  const int e_row = m0 + (te >> 7) * 128 + 4 * ((te >> 5) & 1), e_col = n0 + ((te >> 6) & 1) * (32 * CB) + (te & 31);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+      const int n = e_col + 32 * j;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = e_row + 32 * i + 8 * (r >> 2) + (r & 3);
+        if (m < M && n < N) {
+          const float v = acc[i][j][r] * scale;
+          if (OUT_F32) reinterpret_cast<float*>(Yv)[(int64_t)m * ldy + n] = v;
+          else reinterpret_cast<uint16_t*>(Yv)[(int64_t)m * ldy + n] = f32_to_bf16_bits(v);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);   // one 32 x 32 block at a time: the accumulators leave their registers block by block
+    }
+  }
+}
+
+template <bool OUT_F32, int CB>
+hipError_t launch_wreg(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
+                       const float* tsw, int64_t M, int64_t N, int64_t K, int tiled, void* Y, int64_t ldy,
+                       hipStream_t stream) {
+  static bool configured = false;
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nvfp4_wreg_gemm_kernel<OUT_F32, CB>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kXBytes);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + 64 * CB - 1) / (64 * CB));
+  nvfp4_wreg_gemm_kernel<OUT_F32, CB><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 2 * kXBytes, stream>>>(
+      (const uint8_t*)Xq, (const uint8_t*)Xs, tsx, (const uint8_t*)Wq, (const uint8_t*)Ws, tsw, Y, ldy, (int)M, (int)N,
+      (int)K, tiles_m, tiles_n, tiled);
+  return hipGetLastError();
+}
+
 template <bool OUT_F32, int CB, int FMT>
 hipError_t launch_shape(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
                         const float* tsw, int64_t M, int64_t N, int64_t K, int tiled, void* Y, int64_t ldy,
@@ -404,6 +680,14 @@ hipError_t launch_w4_f16_gemm(const void* Xq, const void* Xs, const float* tsx, 
     if (width_cost(M, N, cb, cus) < width_cost(M, N, best, cus)) best = cb;   // ties keep the wider tile
   if (const char* f = getenv("WUSH_NVFP4_WIDTH")) {  // tests: force a tile width (output channels / 64)
     if (f[0] >= '2' && f[0] <= '4' && f[1] == 0) best = f[0] - '0';
+  }
+  if constexpr (FMT == kNvfp4) {
+    if (K % 128 == 0) {   // an even number of K steps: W in registers
+#define WUSH_WR_LAUNCH(F32, CB) launch_wreg<F32, CB>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, tiled, Y, ldy, stream)
+      if (out_f32) return best == 4 ? WUSH_WR_LAUNCH(true, 4) : best == 3 ? WUSH_WR_LAUNCH(true, 3) : WUSH_WR_LAUNCH(true, 2);
+      return best == 4 ? WUSH_WR_LAUNCH(false, 4) : best == 3 ? WUSH_WR_LAUNCH(false, 3) : WUSH_WR_LAUNCH(false, 2);
+#undef WUSH_WR_LAUNCH
+    }
   }
 #define WUSH_NV_LAUNCH(F32, CB) launch_shape<F32, CB, FMT>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, tiled, Y, ldy, stream)
   if (out_f32) return best == 4 ? WUSH_NV_LAUNCH(true, 4) : best == 3 ? WUSH_NV_LAUNCH(true, 3) : WUSH_NV_LAUNCH(true, 2);

@@ -268,14 +268,35 @@ def test_linear_against_oracle(P, G, M, N, K, out):
     assert O.rel_fro(y[:, :N], ref) <= (1e-5 if f32 else 2e-3)
 
 
+def _tile_operand(packed, scales):
+    """Canonical packed codes [rows][K/2] and scale bytes [rows][K/16] -> the tiled buffers, from the
+    statement of the layout: rows padded to 32; the 16-byte chunk (row, kt, hh) of a 64-element K step at
+    ((((row / 32) KT + kt) 2 + hh) 32 + row % 32) 16, the scale dword (row, kt) at (((row / 32) KT + kt) 32 + row % 32) 4."""
+    rows, K = packed.shape[0], packed.shape[1] * 2
+    KT, RB = K // 64, (rows + 31) // 32
+    q = np.zeros((RB, KT, 2, 32, 16), dtype=np.uint8)
+    sc = np.zeros((RB, KT, 32, 4), dtype=np.uint8)
+    pq = np.zeros((RB * 32, KT, 2, 16), dtype=np.uint8)
+    pq[:rows] = packed.reshape(rows, KT, 2, 16)
+    ps = np.zeros((RB * 32, KT, 4), dtype=np.uint8)
+    ps[:rows] = scales.reshape(rows, KT, 4)
+    q[:] = pq.reshape(RB, 32, KT, 2, 16).transpose(0, 2, 3, 1, 4)
+    sc[:] = ps.reshape(RB, 32, KT, 4).transpose(0, 2, 1, 3)
+    return q.reshape(-1), sc.reshape(-1)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("K", [320, 384])
 @pytest.mark.parametrize("width", ["2", "3", "4"])
-def test_linear_every_tile_width(P, G, width, monkeypatch):
-    """The three tile widths (128, 192, 256 output channels) on a shape with several
-    tiles and ragged edges in both directions; the library normally chooses by cost."""
+def test_linear_every_tile_width(P, G, width, K, layout, monkeypatch):
+    """The three tile widths (128, 192, 256 output channels) on a shape with several tiles and ragged
+    edges in both directions; the library normally chooses by cost.  An odd number of 64-element K
+    steps (K = 320) takes the kernel that stages both operands in LDS, an even one (K = 384) the one
+    that keeps W in registers; both read either layout."""
     import torch
     monkeypatch.setenv("WUSH_NVFP4_WIDTH", width)
-    M, N, K = 300, 700, 320
-    rng = np.random.default_rng(77)
+    M, N = 300, 700
+    rng = np.random.default_rng(77 + K)
     xc = rng.integers(0, 16, (M, K), dtype=np.uint8)
     wc = rng.integers(0, 16, (N, K), dtype=np.uint8)
     xs = rng.integers(30, 100, (M, K // 16), dtype=np.uint8)
@@ -283,8 +304,11 @@ def test_linear_every_tile_width(P, G, width, monkeypatch):
     tsx, tsw = np.float32(1.7), np.float32(3.1e-3)
     ref = NV.linear_dequant(xc, xs, tsx, wc, ws_, tsw)
     Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
-    P.wush_linear_nvfp4(G.u8_dev(_pack(xc)), G.u8_dev(xs), _f32_dev(tsx), G.u8_dev(_pack(wc)), G.u8_dev(ws_),
-                        _f32_dev(tsw), Y, out_dtype=1)
+    xq, wq = _pack(xc), _pack(wc)
+    if layout:
+        (xq, xs), (wq, ws_) = _tile_operand(xq, xs), _tile_operand(wq, ws_)
+    P.wush_linear_nvfp4(G.u8_dev(xq), G.u8_dev(xs), _f32_dev(tsx), G.u8_dev(wq), G.u8_dev(ws_), _f32_dev(tsw), Y,
+                        layout=layout, out_dtype=1, K=K)
     torch.cuda.synchronize()
     assert O.rel_fro(Y.cpu().numpy().astype(np.float64), ref) <= 1e-5
 
