@@ -57,36 +57,63 @@ struct Raw {
   uint32_t s;  // their 4 scale bytes
 };
 
-// Where a row's K steps live: byte offset of step 0 plus a stride per step, for the
-// codes (two 16-byte halves, `half` bytes apart) and for the scale dword.  Covers
-// the canonical row-major layout and the tiled one (nvfp4_layout.hpp).
-struct RowAddr {
-  const uint8_t* q;
-  const uint8_t* s;
-  int q_step, q_half, s_step;
+// Where a lane finds its row of a tile's packed operand: a uniform 64-bit base (the tile's
+// first row, K step 0: scalar registers) plus a 32-bit lane offset, for the codes and for the
+// scale dwords; a K step adds a uniform stride.  Covers the canonical row-major layout and the
+// tiled one (nvfp4_layout.hpp).  A load then takes its base from scalar registers and no vector
+// instruction computes an address.
+struct Strides {
+  int q_step, q_half, s_step;   // bytes per K step (codes), between a step's two 16-byte halves, per K step (scales)
 };
-
-__device__ __forceinline__ RowAddr row_addr(const uint8_t* __restrict__ q, const uint8_t* __restrict__ s, int64_t row,
-                                            int K, int tiled) {
-  RowAddr a;
+__device__ __forceinline__ Strides layout_strides(int tiled) {
+  Strides st = {tiled ? 1024 : 32, tiled ? 512 : 16, tiled ? 128 : 4};
+  asm volatile("" : "+s"(st.q_step), "+s"(st.q_half), "+s"(st.s_step));   // plain numbers from here on: one loop, not one per layout
+  return st;
+}
+struct OperandAddr {
+  const uint8_t* q0;
+  const uint8_t* s0;
+  uint32_t oq, os;
+};
+// row0 = the tile's first row (a multiple of 32), row >= row0 the lane's row, hh = which 16-byte half
+// of a K step the code offset points at.
+__device__ __forceinline__ OperandAddr operand_addr(const uint8_t* __restrict__ q, const uint8_t* __restrict__ s,
+                                                    int64_t row0, int64_t row, int hh, int K, int tiled) {
+  OperandAddr a;
+  const int KT = K >> 6;
   if (tiled) {
-    const int KT = K >> 6;
-    a.q = q + nv_tiled_chunk_offset(row, 0, 0, KT);
-    a.s = s + nv_tiled_scale_offset(row, 0, KT);
-    a.q_step = 1024; a.q_half = 512; a.s_step = 128;
+    const int64_t bq = nv_tiled_chunk_offset(row0, 0, 0, KT), bs = nv_tiled_scale_offset(row0, 0, KT);
+    a.q0 = q + bq;
+    a.s0 = s + bs;
+    a.oq = (uint32_t)(nv_tiled_chunk_offset(row, 0, hh, KT) - bq);
+    a.os = (uint32_t)(nv_tiled_scale_offset(row, 0, KT) - bs);
   } else {
-    a.q = q + row * (K / 2);
-    a.s = s + row * (K / 16);
-    a.q_step = 32; a.q_half = 16; a.s_step = 4;
+    a.q0 = q + row0 * (K / 2);
+    a.s0 = s + row0 * (K / 16);
+    a.oq = (uint32_t)((row - row0) * (K / 2) + hh * 16);
+    a.os = (uint32_t)((row - row0) * (K / 16));
   }
   return a;
 }
-
-__device__ __forceinline__ void load_raw(Raw& r, const RowAddr& a, int kt) {
-  const uint8_t* p = a.q + (int64_t)kt * a.q_step;
-  r.q[0] = *reinterpret_cast<const v4u*>(p);
-  r.q[1] = *reinterpret_cast<const v4u*>(p + a.q_half);
-  r.s = *reinterpret_cast<const uint32_t*>(a.s + (int64_t)kt * a.s_step);
+// One load of K step kt.  The empty asm keeps the lane offset apart from the scalar base (otherwise
+// the compiler folds both into a 64-bit vector address that it then has to advance per step).
+__device__ __forceinline__ v4u load_codes(OperandAddr& a, const Strides& st, int kt, int half) {
+  asm volatile("" : "+v"(a.oq));
+  return *reinterpret_cast<const v4u*>(a.q0 + ((int64_t)kt * st.q_step + half * st.q_half) + a.oq);
+}
+__device__ __forceinline__ uint32_t load_scales(OperandAddr& a, const Strides& st, int kt) {
+  asm volatile("" : "+v"(a.os));
+  return *reinterpret_cast<const uint32_t*>(a.s0 + (int64_t)kt * st.s_step + a.os);
+}
+// which = 0, 1: the two halves of the row's codes, 2: its scale dword
+__device__ __forceinline__ void load_raw_piece(Raw& r, OperandAddr& a, const Strides& st, int kt, int which) {
+  if (which < 2) r.q[which] = load_codes(a, st, kt, which);
+  else r.s = load_scales(a, st, kt);
+}
+__device__ __forceinline__ void load_raw(Raw& r, OperandAddr& a, const Strides& st, int kt) {
+  r.q[0] = load_codes(a, st, kt, 0);
+  r.q[1] = load_codes(a, st, kt, 1);
+  r.s = load_scales(a, st, kt);
 }
 
 // Two E4M3 scale bytes (word `HI` of the row's scale dword) -> two FP16 values, by the
@@ -267,13 +294,14 @@ __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
 
   // Packed operands in flight: (ax_, aw_) = step kt+1, converted during step kt; (bx_, bw_) = step
   // kt+2, loaded at the start of step kt.  Step numbers are clamped (surplus loads re-read the last step).
-  const RowAddr ax = row_addr(Xq, Xs, rowX, K, tiled), aw = row_addr(Wq, Ws, rowW, K, tiled);
+  const Strides st = layout_strides(tiled);
+  OperandAddr ax = operand_addr(Xq, Xs, m0, rowX, 0, K, tiled), aw = operand_addr(Wq, Ws, n0, rowW, 0, K, tiled);
   Raw ax_, aw_, bx_, bw_;
-  load_raw(ax_, ax, 0);
-  load_raw(aw_, aw, 0);
+  load_raw(ax_, ax, st, 0);
+  load_raw(aw_, aw, st, 0);
   convert(ax_, aw_, lds);
-  load_raw(ax_, ax, min(1, KT - 1));
-  load_raw(aw_, aw, min(1, KT - 1));
+  load_raw(ax_, ax, st, min(1, KT - 1));
+  load_raw(aw_, aw, st, min(1, KT - 1));
   __syncthreads();
 
   v16f acc[4][CB];
@@ -305,10 +333,8 @@ __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
     if (NEXT) {
       step_scales<FMT>(ax_.s, sx);
       step_scales<FMT>(aw_.s, sw);
-      const int kl = min(kt + 2, KT - 1);
-      load_raw(bx_, ax, kl);
-      load_raw(bw_, aw, kl);
     }
+    const int kl = min(kt + 2, KT - 1);
     __builtin_amdgcn_sched_barrier(0);
     static_for<kSlots>([&](auto slot) {
       constexpr int S = decltype(slot)::value;
@@ -324,6 +350,13 @@ __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
         constexpr int left = kSlots - kConvSlots, r0 = (S - kConvSlots) * (4 + CB) / left,
                       r1 = (S - kConvSlots + 1) * (4 + CB) / left;
         static_for<r1 - r0>([&](auto q) { read_frag(nxt, 0, r0 + decltype(q)::value, 0); });
+      }
+      // the six loads of step kt+2, one per slot (a load costs its slot about 30 cycles; six in a row
+      // stall the MFMA pipe for all of them): the last two slots of the groups 0 to 2
+      if constexpr (NEXT && g < 3 && idx >= kGroup - 2) {
+        constexpr int piece = 2 * g + (idx - (kGroup - 2));
+        if constexpr (piece < 3) load_raw_piece(bx_, ax, st, kl, piece);
+        else load_raw_piece(bw_, aw, st, kl, piece - 3);
       }
       // conversion micro-operations of this slot: 8 X tasks, then 8 W tasks
       if constexpr (NEXT && S < kConvSlots) {
@@ -450,46 +483,16 @@ __global__ __launch_bounds__(256) void nvfp4_wreg_gemm_kernel(
   const int m0 = tm * kBM, n0 = tn * kBN;
   const int KT = K / kBK;   // even
 
-  // Addresses: a uniform 64-bit base per operand and K step (scalar registers) plus a 32-bit lane
-  // offset inside the tile.
-  int q_step = tiled ? 1024 : 32, q_half = tiled ? 512 : 16, s_step = tiled ? 128 : 4;
-  asm volatile("" : "+s"(q_step), "+s"(q_half), "+s"(s_step));   // plain numbers from here on: one loop, not one per layout
-  auto lane_off = [&](const int64_t row, const int64_t row0, int hh, uint32_t& oq, uint32_t& os) {
-    if (tiled) {
-      oq = (uint32_t)(nv_tiled_chunk_offset(row, 0, hh, KT) - nv_tiled_chunk_offset(row0, 0, 0, KT));
-      os = (uint32_t)(nv_tiled_scale_offset(row, 0, KT) - nv_tiled_scale_offset(row0, 0, KT));
-    } else {
-      oq = (uint32_t)((row - row0) * (K / 2) + hh * 16);
-      os = (uint32_t)((row - row0) * (K / 16));
-    }
-  };
-  const uint8_t* xq0 = Xq + (tiled ? nv_tiled_chunk_offset(m0, 0, 0, KT) : (int64_t)m0 * (K / 2));
-  const uint8_t* xs0 = Xs + (tiled ? nv_tiled_scale_offset(m0, 0, KT) : (int64_t)m0 * (K / 16));
-  const uint8_t* wq0 = Wq + (tiled ? nv_tiled_chunk_offset(n0, 0, 0, KT) : (int64_t)n0 * (K / 2));
-  const uint8_t* ws0 = Ws + (tiled ? nv_tiled_scale_offset(n0, 0, KT) : (int64_t)n0 * (K / 16));
-  uint32_t xoq, xos, woq[CB], wos[CB];
-  lane_off(min(m0 + tid, M - 1), m0, 0, xoq, xos);   // rows past the end re-read the last valid row
+  const Strides st = layout_strides(tiled);
+  OperandAddr ax = operand_addr(Xq, Xs, m0, min(m0 + tid, M - 1), 0, K, tiled);   // rows past the end re-read the last valid row
   // W fragment j of this wave: rows n0 + 32 CB wn + 32 j + l32; lane half h takes the 16-byte half h of the K step
+  OperandAddr aw[CB];
 #pragma unroll
-  for (int j = 0; j < CB; ++j) lane_off(min(n0 + wn * (32 * CB) + 32 * j + l32, N - 1), n0, h, woq[j], wos[j]);
+  for (int j = 0; j < CB; ++j) aw[j] = operand_addr(Wq, Ws, n0, min(n0 + wn * (32 * CB) + 32 * j + l32, N - 1), h, K, tiled);
   const int sh = 16 * h;
-
-  // One load of K step `kt` at a time.  which = 0, 1: the two 16-byte halves of the X row, 2: its
-  // scale dword.  The empty asm keeps the 32-bit lane offset apart from the scalar base, so that the
-  // load takes the base from scalar registers and no vector instruction computes an address.
-  auto load_x = [&](Raw& r, int kt, int which) {
-    asm volatile("" : "+v"(xoq), "+v"(xos));
-    if (which < 2) r.q[which] = *reinterpret_cast<const v4u*>(xq0 + ((int64_t)kt * q_step + which * q_half) + xoq);
-    else r.s = *reinterpret_cast<const uint32_t*>(xs0 + (int64_t)kt * s_step + xos);
-  };
-  auto load_wq = [&](RawW& r, int kt, int j) {
-    asm volatile("" : "+v"(woq[j]));
-    r.q = *reinterpret_cast<const v4u*>(wq0 + (int64_t)kt * q_step + woq[j]);
-  };
-  auto load_ws = [&](RawW& r, int kt, int j) {
-    asm volatile("" : "+v"(wos[j]));
-    r.s = *reinterpret_cast<const uint32_t*>(ws0 + (int64_t)kt * s_step + wos[j]);
-  };
+  auto load_x = [&](Raw& r, int kt, int which) { load_raw_piece(r, ax, st, kt, which); };
+  auto load_wq = [&](RawW& r, int kt, int j) { r.q = load_codes(aw[j], st, kt, 0); };
+  auto load_ws = [&](RawW& r, int kt, int j) { r.s = load_scales(aw[j], st, kt); };
 
   Raw xr[2];                  // X of step kt+1 lives in xr[(kt+1) & 1] during step kt; the other set receives step kt+2
   RawW wr[2][CB];             // W of step kt in wr[kt & 1]; refilled with step kt+2 as its groups are converted
