@@ -16,7 +16,11 @@
 //     the tiled layout a fragment is 1 KiB contiguous in lane order, so every
 //     load is a perfectly coalesced 128-bit access and no two waves load the
 //     same bytes.  Two register sets; a fragment register is refilled with
-//     tile kt+2 right after the MFMA issue of tile kt that consumed it.
+//     tile kt+2 right after the MFMA issue of tile kt that consumed it.  The
+//     last issue runs column by column (and its last column out of register
+//     copies), so that the fragments and scale dwords it consumes are refilled
+//     one per MFMA slot as well instead of in a block behind the last MFMA
+//     (a block of 2 CB loads there cost 70 to 160 cycles per iteration).
 //   * X fragments and X scales (shared by all four waves) go global -> LDS with
 //     direct-to-LDS loads (no VGPRs in flight) into a 4-stage ring; the LDS
 //     image is the same lane-linear fragment order, so the ds_read_b128 of the
@@ -157,20 +161,21 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   // asynchronously; nothing may read them before the explicit wait at the start
   // of the iteration that consumes them (the generated code is checked for that:
   // no spill and no register copy in the loop).
+  auto load_w_scale = [&](WSet<CB>& w, int kt, int j) {
+    const uint8_t* p = Ws + (wblk[j] * KT + kt) * 256;
+    asm volatile("global_load_dword %0, %1, %2" : "+v"(w.s[j]) : "v"(soff), "s"(p));
+  };
   auto load_w_scales = [&](WSet<CB>& w, int kt) {
 #pragma unroll
-    for (int j = 0; j < CB; ++j) {
-      const uint8_t* p = Ws + (wblk[j] * KT + kt) * 256;
-      asm volatile("global_load_dword %0, %1, %2" : "=v"(w.s[j]) : "v"(soff), "s"(p));
-    }
+    for (int j = 0; j < CB; ++j) load_w_scale(w, kt, j);
   };
   auto load_w_frag = [&](WSet<CB>& w, int kt, int kk, int j) {
     const uint8_t* p = Wq + (wblk[j] * KT + kt) * tile_step;
     switch (kk) {
-      case 0: asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
-      case 1: asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024" : "=v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
-      case 2: asm volatile("global_load_dwordx4 %0, %1, %2 offset:2048" : "=v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
-      default: asm volatile("global_load_dwordx4 %0, %1, %2 offset:3072" : "=v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
+      case 0: asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
+      case 1: asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024" : "+v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
+      case 2: asm volatile("global_load_dwordx4 %0, %1, %2 offset:2048" : "+v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
+      default: asm volatile("global_load_dwordx4 %0, %1, %2 offset:3072" : "+v"(w.f[j][kk]) : "v"(loff), "s"(p)); break;
     }
   };
   auto read_x_frag = [&](int kt, int kk, int i) {
@@ -190,6 +195,16 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   // iteration, chosen so that the LAST iteration always runs on set 0: the
   // drain code then exists in a single version.
   WSet<CB> wset[2];
+  // The load asm takes its destination as a read-write operand, which ties every load of a W
+  // register to the register its predecessor used; the chain starts here.
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) wset[t].f[j][kk] = (v4i){0, 0, 0, 0};
+      wset[t].s[j] = 0;
+    }
   int xsc[2][RB];
   v4i af0[RB], af1[RB];
   const int p0 = (KT - 1) & 1;                 // set of iteration 0
@@ -283,8 +298,15 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
       af1[i] = nx_;
       WUSH_FENCE
     }
+    // Copies of the last column's issue-3 fragment and scale dword (one register move per slot, by
+    // asm so that they are values of their own: the W registers keep their assignment): issue 3
+    // multiplies the last column out of these, and its registers can be refilled a pass earlier.
+    v4i last_f;
+    int last_s;
 #pragma unroll
     for (int i = 0; i < RB; ++i) {           // issue 2: W fragments of issue 1, next tile's issue-0 operands
+      if (i >= RB - 4) asm volatile("v_mov_b32 %0, %1" : "=v"(last_f[i - (RB - 4)]) : "v"(w.f[CB - 1][3][i - (RB - 4)]));
+      if (i == RB - 1) asm volatile("v_mov_b32 %0, %1" : "=v"(last_s) : "v"(w.s[CB - 1]));
       WUSH_MMA(2, af0, i, 0)
       v4i nx_ = af0[i];
       if (NEXT) nx_ = read_x_frag(kt + 1, 0, i);
@@ -295,25 +317,36 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
       af0[i] = nx_;
       WUSH_FENCE
     }
+    // issue 3, column by column: a column's last fragment and its scale dword are free as soon as its
+    // pass is through and are refilled (tile kt+2) in the first slots of the next pass; the last column
+    // multiplies out of copies, so that its registers are free from the start of its pass.  Every
+    // global load has a slot of its own: a block of loads behind the last MFMA would stall the MFMA
+    // pipe for its whole length (some 30 cycles per load).  The last pass also fetches the next tile's
+    // issue-1 operands and scales.
 #pragma unroll
-    for (int i = 0; i < RB; ++i) {           // issue 3: W fragments of issue 2, next tile's issue-1 operands, scales
-      WUSH_MMA(3, af1, i, 0)
-      v4i nx_ = af1[i];
-      if (NEXT) {
-        nx_ = read_x_frag(kt + 1, 1, i);
-        xs_next[i] = read_x_scale(kt + 1, i);
+    for (int j = 0; j < CB; ++j) {
+#pragma unroll
+      for (int i = 0; i < RB; ++i) {
+        {
+          const v4i f_ = j == CB - 1 ? last_f : w.f[j][3];
+          const int s_ = j == CB - 1 ? last_s : w.s[j];
+          const v8i A_ = {af1[i][0], af1[i][1], af1[i][2], af1[i][3], 0, 0, 0, 0};
+          const v8i B_ = {f_[0], f_[1], f_[2], f_[3], 0, 0, 0, 0};
+          acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B_, A_, acc[i][j], 4, 4, 3, s_, 3, xs[i]);
+        }
+        if (NEXT && j == CB - 1) {
+          af1[i] = read_x_frag(kt + 1, 1, i);
+          xs_next[i] = read_x_scale(kt + 1, i);
+        }
+        if (PFW) {
+          if (j * RB + i < CB) load_w_frag(w, kt + 2, 2, j * RB + i);
+          if (j >= 1 && i == 0) load_w_frag(w, kt + 2, 3, j - 1);
+          if (j >= 1 && i == 1) load_w_scale(w, kt + 2, j - 1);
+          if (j == CB - 1 && i == 2) load_w_frag(w, kt + 2, 3, CB - 1);
+          if (j == CB - 1 && i == 3) load_w_scale(w, kt + 2, CB - 1);
+        }
+        WUSH_FENCE
       }
-      WUSH_FENCE
-      if (CB > 1) WUSH_MMA(3, af1, i, 1)
-      if (PFW && i < CB) load_w_frag(w, kt + 2, 2, i);
-      WUSH_MMA_REST(3, af1, i)
-      af1[i] = nx_;
-      WUSH_FENCE
-    }
-    if (PFW) {
-#pragma unroll
-      for (int j = 0; j < CB; ++j) load_w_frag(w, kt + 2, 3, j);
-      load_w_scales(w, kt + 2);
     }
     // Ring stage kt+2 (this wave's share, issued during iteration kt-1) must have
     // landed before the barrier publishes it; vmcnt retires in order, and since
