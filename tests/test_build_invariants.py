@@ -115,6 +115,43 @@ def test_f16_gemm_has_no_scratch_and_a_tight_loop():
         assert loop, name
         assert len(re.findall(r"v_mfma_f32_32x32x16_f16", loop)) == 16 * cb, name
         assert len(re.findall(r"s_barrier", loop)) == 1, name
+        _assert_loads_cost_no_vector_arithmetic(name, loop, 6)
+
+
+def _loop_of(body):
+    blocks = re.split(r"^(\.LBB\d+_\d+:.*)$", body, flags=re.M)
+    return "".join(blocks[i + 1] for i in range(1, len(blocks) - 1, 2)
+                   if "Loop Header" in blocks[i] or "in Loop" in blocks[i])
+
+
+def _assert_loads_cost_no_vector_arithmetic(name, loop, n_loads):
+    """Every global load of the K loop takes its base from a scalar register pair and a 32-bit lane
+    offset (`global_load_* vdst, voffset, s[base:base+1]`), and no 64-bit address arithmetic runs on the
+    vector unit: measured, either costs more than the conversion it sits next to."""
+    loads = re.findall(r"^\s*global_load_\S+\s+(.*)$", loop, flags=re.M)
+    assert len(loads) == n_loads, (name, len(loads))
+    for ops in loads:
+        assert re.search(r",\s*v\d+,\s*s\[\d+:\d+\]", ops), (name, ops)
+    for insn in ("v_mad_i64_i32", "v_mad_u64_u32", "v_lshl_add_u64", "v_add_co_u32", "v_addc_co_u32"):
+        assert insn not in loop, (name, insn)
+
+
+def test_register_w_gemm_loop():
+    """The NVFP4 kernel that keeps W in registers: no scratch, two K steps per loop trip (2 x 16 CB MFMAs,
+    two barriers), 3 + 2 CB loads per step in scalar-base form, and no register move in the loop (the
+    prefetched operand sets swap roles between the two steps instead of being copied)."""
+    text = _compile("nvfp4_gemm.hip")
+    kernels = _bodies(text, "nvfp4_wreg_gemm_kernel")
+    assert len(kernels) == 6, list(kernels)           # {bf16, f32 output} x {4, 3, 2 column blocks}
+    for name, body in kernels.items():
+        cb = int(re.search(r"ILb[01]ELi(\d+)E", name).group(1))
+        assert "scratch_" not in body, f"{name}: spills to scratch"
+        loop = _loop_of(body)
+        assert loop, name
+        assert len(re.findall(r"v_mfma_f32_32x32x16_f16", loop)) == 2 * 16 * cb, name
+        assert len(re.findall(r"s_barrier", loop)) == 2, name
+        _assert_loads_cost_no_vector_arithmetic(name, loop, 2 * (3 + 2 * cb))
+        assert "v_mov_b32" not in loop and "v_accvgpr" not in loop, name
 
 
 @pytest.mark.parametrize("src,pattern,count", [("nvfp4_quant.hip", "nvfp4_transform_quant_kernel", 4),
