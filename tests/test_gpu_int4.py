@@ -229,11 +229,12 @@ def test_layer_end_to_end_both_layouts(P, G, width, monkeypatch):
     assert abs(O.rel_fro(y, exact) - O.rel_fro(ref, exact)) <= 1e-3
 
 
-def test_c2_shape_full_size(P, G):
-    """The configuration bench.py times for workload i2 (2048 x 4096 -> 6144, tiled layout, BF16 output):
-    sampled token rows, weight rows and output entries against the oracle."""
+@pytest.mark.parametrize("name", ["c2", "c5"])
+def test_bench_shapes_full_size(P, G, name):
+    """The configurations bench.py times for the workloads i2 (2048 x 4096 -> 6144) and i5 (8192 x 8192 ->
+    57344), tiled layout, BF16 output: sampled token rows, weight rows and output entries against the oracle."""
     import torch
-    L = I.make_layer(I.CONFIGS["c2"])
+    L = I.make_layer(I.CONFIGS[name])
     cfg = L["cfg"]
     M, K, N = cfg.M, cfg.K, cfg.N
     T = np.empty((K // 32, 32, 32))
