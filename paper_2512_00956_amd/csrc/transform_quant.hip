@@ -30,13 +30,19 @@ using tq::kTileM;
 using tq::XFrag;
 constexpr int kWaves = 4;    // waves per workgroup
 
-template <bool DBG, bool TILED>
-__global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
+// TG = token tiles a workgroup handles at a time: its 4 TG waves are TG groups of four, group g
+// walking the tiles first + g, first + g + TG, ...  A wave's tile is one long dependent chain (MFMA,
+// accumulator reads, max tree, lane swap, scale, converts: about 2600 cycles for 280 instructions), so
+// a CU with one wave per SIMD idles most of the time; a second group per workgroup fills the gaps
+// without leaving the placement of more, smaller workgroups to the dispatcher.
+template <bool DBG, bool TILED, int TG>
+__global__ __launch_bounds__(kWaves * TG * 64) void transform_quant_kernel(
     const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ T,
     uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs, float* __restrict__ dbg,
     int M, int K, int C, int tiles_per_wg, int rule) {
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = (threadIdx.x >> 6) % kWaves;   // which four blocks
+  const int tg = (threadIdx.x >> 6) / kWaves;     // which tile group
   const int tok = lane & 31;
   const int h = lane >> 5;
   const int bfirst = (blockIdx.y * kWaves + wave) * kNB;
@@ -47,17 +53,17 @@ __global__ __launch_bounds__(kWaves * 64) void transform_quant_kernel(
   tq::load_transforms(ta, T, bfirst, C, tok, h);
 
   const int ntiles = (M + kTileM - 1) / kTileM;
-  int t = blockIdx.x * tiles_per_wg;
-  const int tend = min(t + tiles_per_wg, ntiles);
+  int t = blockIdx.x * tiles_per_wg + tg;
+  const int tend = min(blockIdx.x * tiles_per_wg + tiles_per_wg, ntiles);
   if (t >= tend) return;
 
   XFrag cur[kNB], nxt[kNB];
   tq::load_tile(cur, X, ldx, min(t * kTileM + tok, M - 1), bfirst, C, h);
 
-  for (; t < tend; ++t) {
+  for (; t < tend; t += TG) {
     const int m = t * kTileM + tok;
     const bool row_ok = m < M;
-    if (t + 1 < tend) tq::load_tile(nxt, X, ldx, min((t + 1) * kTileM + tok, M - 1), bfirst, C, h);
+    if (t + TG < tend) tq::load_tile(nxt, X, ldx, min((t + TG) * kTileM + tok, M - 1), bfirst, C, h);
 
     v4u out[2];
     uint32_t sbytes;
@@ -99,7 +105,7 @@ int device_cu_count() {
 }
 
 // Token tiles each workgroup walks down (the register-resident transforms are loaded once per
-// workgroup).  Chosen from the number of (tile, channel group) units T against the CU count, after
+// wave).  Chosen from the number of (tile, channel group) units T against the CU count, after
 // sweeps of the walk on 512..32768 tokens x 4096..28672 channels (graph replay for the small ones):
 //   T <= 1.5 CUs : 1   (latency bound: 1024 x 4096 takes 3.7 us with a walk of 1, 4.6 with 2)
 //   T <= 6 CUs   : 2   (2048 x 4096: 4.9 us against 5.2; 2048 x 8192: 8.8 against 9.7)
@@ -117,22 +123,51 @@ int token_walk(int ntiles, int col_groups) {
   return (ntiles + wg_rows - 1) / wg_rows;
 }
 
+namespace {
+
+// The same for a kernel whose workgroups can take two tiles at a time (tile groups, above):
+// tiles per workgroup and groups.  Up to 3 CUs' worth of units the single group wins or ties
+// (2048 x 4096: 5.0 us against 5.2).  Beyond, two groups and a grid of at most one workgroup per CU
+// (a CU holds one eight-wave workgroup of this kernel at a time): 2048 x 8192: 8.2 us against 8.7,
+// 4096 x 8192: 15.0 against 15.9, 16384 x 4096: 26.2 against 28.3, 8192 x 8192: 26.7 against 28.4
+// (three and four groups: 26.7-27.6).
+struct Walk {
+  int tiles_per_wg, groups;
+};
+Walk token_walk_groups(int ntiles, int col_groups) {
+  const int cus = device_cu_count();
+  const int64_t units = (int64_t)ntiles * col_groups;
+  if (units <= 3 * cus) return {token_walk(ntiles, col_groups), 1};
+  const int wg_rows = cus / col_groups > 0 ? cus / col_groups : 1;
+  const int walk = (ntiles + wg_rows - 1) / wg_rows;
+  return {walk < 2 ? 2 : walk, 2};
+}
+
+}  // namespace
+
 hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T,
                                   int rule, int tiled, void* Xq, void* Xs, float* dbg, hipStream_t stream) {
   const int C = (int)(K / 32);
   const int col_groups = (C + kWaves * kNB - 1) / (kWaves * kNB);
   const int ntiles = (int)((M + kTileM - 1) / kTileM);
-  const int tiles_per_wg = token_walk(ntiles, col_groups);
+  const Walk walk = token_walk_groups(ntiles, col_groups);
+  const int tiles_per_wg = walk.tiles_per_wg;
   dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
-  dim3 block(kWaves * 64);
-#define WUSH_TQ_LAUNCH(DBG, TILED)                                                                   \
-  transform_quant_kernel<DBG, TILED><<<grid, block, 0, stream>>>(                                    \
+  dim3 block(kWaves * 64 * walk.groups);
+#define WUSH_TQ_LAUNCH(DBG, TILED, TG)                                                                 \
+  transform_quant_kernel<DBG, TILED, TG><<<grid, block, 0, stream>>>(                                  \
       (const uint16_t*)X, ldx, (const uint16_t*)T, (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M, (int)K, C, \
       tiles_per_wg, rule)
-  if (dbg) {
-    if (tiled) WUSH_TQ_LAUNCH(true, true); else WUSH_TQ_LAUNCH(true, false);
+  if (walk.groups == 2) {
+    if (dbg) {
+      if (tiled) WUSH_TQ_LAUNCH(true, true, 2); else WUSH_TQ_LAUNCH(true, false, 2);
+    } else {
+      if (tiled) WUSH_TQ_LAUNCH(false, true, 2); else WUSH_TQ_LAUNCH(false, false, 2);
+    }
+  } else if (dbg) {
+    if (tiled) WUSH_TQ_LAUNCH(true, true, 1); else WUSH_TQ_LAUNCH(true, false, 1);
   } else {
-    if (tiled) WUSH_TQ_LAUNCH(false, true); else WUSH_TQ_LAUNCH(false, false);
+    if (tiled) WUSH_TQ_LAUNCH(false, true, 1); else WUSH_TQ_LAUNCH(false, false, 1);
   }
 #undef WUSH_TQ_LAUNCH
   return hipGetLastError();
