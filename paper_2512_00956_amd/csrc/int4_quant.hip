@@ -99,12 +99,14 @@ __device__ __forceinline__ void transform_quantize_int4(const v8bf (&ta)[kNB][2]
   }
 }
 
-template <bool DBG, bool TILED>
-__global__ __launch_bounds__(kWaves * 64, 3) void int4_transform_quant_kernel(
+// TG: groups of four waves per workgroup, each walking every TG-th of its tiles (transform_quant.hip).
+template <bool DBG, bool TILED, int TG>
+__global__ __launch_bounds__(kWaves * TG * 64, 3) void int4_transform_quant_kernel(
     const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ T, uint8_t* __restrict__ Xq,
     uint8_t* __restrict__ Xs, float* __restrict__ dbg, int M, int K, int C, int tiles_per_wg) {
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = (threadIdx.x >> 6) % kWaves;
+  const int tg = (threadIdx.x >> 6) / kWaves;
   const int tok = lane & 31;
   const int h = lane >> 5;
   const int bfirst = (blockIdx.y * kWaves + wave) * kNB;
@@ -115,17 +117,17 @@ __global__ __launch_bounds__(kWaves * 64, 3) void int4_transform_quant_kernel(
   tq::load_transforms(ta, T, bfirst, C, tok, h);
 
   const int ntiles = (M + kTileM - 1) / kTileM;
-  int t = blockIdx.x * tiles_per_wg;
-  const int tend = min(t + tiles_per_wg, ntiles);
+  int t = blockIdx.x * tiles_per_wg + tg;
+  const int tend = min(blockIdx.x * tiles_per_wg + tiles_per_wg, ntiles);
   if (t >= tend) return;
 
   XFrag cur[kNB], nxt[kNB];
   tq::load_tile(cur, X, ldx, min(t * kTileM + tok, M - 1), bfirst, C, h);
 
-  for (; t < tend; ++t) {
+  for (; t < tend; t += TG) {
     const int m = t * kTileM + tok;
     const bool row_ok = m < M;
-    if (t + 1 < tend) tq::load_tile(nxt, X, ldx, min((t + 1) * kTileM + tok, M - 1), bfirst, C, h);
+    if (t + TG < tend) tq::load_tile(nxt, X, ldx, min((t + TG) * kTileM + tok, M - 1), bfirst, C, h);
 
     v4u out[2];
     uint32_t sc[kNB];
@@ -199,16 +201,23 @@ hipError_t launch_int4_transform_quant(const void* X, int64_t M, int64_t K, int6
   const int C = (int)(K / 32);
   const int col_groups = (C + kWaves * kNB - 1) / (kWaves * kNB);
   const int ntiles = (int)((M + kTileM - 1) / kTileM);
-  const int tiles_per_wg = token_walk(ntiles, col_groups);
+  const Walk walk = token_walk_groups(ntiles, col_groups);
+  const int tiles_per_wg = walk.tiles_per_wg;
   dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
-  dim3 block(kWaves * 64);
-#define WUSH_I4Q_LAUNCH(DBG, TILED)                                                                       \
-  int4_transform_quant_kernel<DBG, TILED><<<grid, block, 0, stream>>>(                                    \
+  dim3 block(kWaves * 64 * walk.groups);
+#define WUSH_I4Q_LAUNCH(DBG, TILED, TG)                                                                       \
+  int4_transform_quant_kernel<DBG, TILED, TG><<<grid, block, 0, stream>>>(                                    \
       (const uint16_t*)X, ldx, (const uint16_t*)T, (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M, (int)K, C, tiles_per_wg)
-  if (dbg) {
-    if (tiled) WUSH_I4Q_LAUNCH(true, true); else WUSH_I4Q_LAUNCH(true, false);
+  if (walk.groups == 2) {
+    if (dbg) {
+      if (tiled) WUSH_I4Q_LAUNCH(true, true, 2); else WUSH_I4Q_LAUNCH(true, false, 2);
+    } else {
+      if (tiled) WUSH_I4Q_LAUNCH(false, true, 2); else WUSH_I4Q_LAUNCH(false, false, 2);
+    }
+  } else if (dbg) {
+    if (tiled) WUSH_I4Q_LAUNCH(true, true, 1); else WUSH_I4Q_LAUNCH(true, false, 1);
   } else {
-    if (tiled) WUSH_I4Q_LAUNCH(false, true); else WUSH_I4Q_LAUNCH(false, false);
+    if (tiled) WUSH_I4Q_LAUNCH(false, true, 1); else WUSH_I4Q_LAUNCH(false, false, 1);
   }
 #undef WUSH_I4Q_LAUNCH
   return hipGetLastError();

@@ -123,17 +123,12 @@ int token_walk(int ntiles, int col_groups) {
   return (ntiles + wg_rows - 1) / wg_rows;
 }
 
-namespace {
-
 // The same for a kernel whose workgroups can take two tiles at a time (tile groups, above):
 // tiles per workgroup and groups.  Up to 3 CUs' worth of units the single group wins or ties
 // (2048 x 4096: 5.0 us against 5.2).  Beyond, two groups and a grid of at most one workgroup per CU
 // (a CU holds one eight-wave workgroup of this kernel at a time): 2048 x 8192: 8.2 us against 8.7,
 // 4096 x 8192: 15.0 against 15.9, 16384 x 4096: 26.2 against 28.3, 8192 x 8192: 26.7 against 28.4
 // (three and four groups: 26.7-27.6).
-struct Walk {
-  int tiles_per_wg, groups;
-};
 Walk token_walk_groups(int ntiles, int col_groups) {
   const int cus = device_cu_count();
   const int64_t units = (int64_t)ntiles * col_groups;
@@ -142,8 +137,6 @@ Walk token_walk_groups(int ntiles, int col_groups) {
   const int walk = (ntiles + wg_rows - 1) / wg_rows;
   return {walk < 2 ? 2 : walk, 2};
 }
-
-}  // namespace
 
 hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T,
                                   int rule, int tiled, void* Xq, void* Xs, float* dbg, hipStream_t stream) {

@@ -12,6 +12,12 @@ int device_cu_count();
 // Token tiles per workgroup of the fused transform + quantize kernels (ntiles 32-token tiles,
 // col_groups workgroups across the channels).
 int token_walk(int ntiles, int col_groups);
+// The same for kernels whose workgroups can hold two groups of waves that walk alternate tiles:
+// tiles per workgroup and the number of groups (1 or 2).
+struct Walk {
+  int tiles_per_wg, groups;
+};
+Walk token_walk_groups(int ntiles, int col_groups);
 
 // `tiled` != 0 selects the fragment-order layout of wush_device.hpp (K % 256 == 0).
 hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T,

@@ -154,8 +154,8 @@ def test_register_w_gemm_loop():
         assert "v_mov_b32" not in loop and "v_accvgpr" not in loop, name
 
 
-@pytest.mark.parametrize("src,pattern,count", [("nvfp4_quant.hip", "nvfp4_transform_quant_kernel", 4),
-                                                ("int4_quant.hip", "int4_transform_quant_kernel", 4),
+@pytest.mark.parametrize("src,pattern,count", [("nvfp4_quant.hip", "nvfp4_transform_quant_kernel", 8),
+                                                ("int4_quant.hip", "int4_transform_quant_kernel", 8),
                                                 ("transform_quant.hip", "22transform_quant_kernel", 8)])
 def test_quantizers_do_not_spill_and_keep_three_waves_per_simd(src, pattern, count):
     text = _compile(src)
