@@ -229,6 +229,29 @@ def test_layer_end_to_end_both_layouts(P, G, width, monkeypatch):
     assert abs(O.rel_fro(y, exact) - O.rel_fro(ref, exact)) <= 1e-3
 
 
+def test_transform_quant_is_independent_of_the_launch_shape(P, G):
+    """A large, ragged batch (workgroups of two wave groups, nine tiles each, a last tile of three tokens)
+    gives, row for row, the bytes the same rows give in small batches, in both layouts."""
+    import torch
+    M, K = 4099, 8192
+    X = torch.from_numpy(I.random_f32((M, K), seed=43, spread=2.0)).cuda().to(torch.bfloat16)
+    T = G.bf16_dev(I.make_transforms_random(K // 32, 5))
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    P.wush_quantize_act_int4(X, T, Xq, Xs)
+    cb, sb = P.wush_packed_sizes_nvfp4(M, K, 1)
+    Xqt, Xst = G.empty_u8(cb), G.empty_u8(sb)
+    P.wush_quantize_act_int4(X, T, Xqt, Xst, layout=1)
+    Xqu, Xsu = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    P.wush_unpack_tiled_nvfp4(Xqt, Xst, M, K, Xqu, Xsu)
+    torch.cuda.synchronize()
+    assert torch.equal(Xqu, Xq) and torch.equal(Xsu, Xs)
+    for lo, hi in ((0, 256), (1500, 1533), (4064, 4099)):
+        q, s_ = G.empty_u8(hi - lo, K // 2), G.empty_u8(hi - lo, K // 16)
+        P.wush_quantize_act_int4(X[lo:hi], T, q, s_)
+        torch.cuda.synchronize()
+        assert torch.equal(q, Xq[lo:hi]) and torch.equal(s_, Xs[lo:hi]), (lo, hi)
+
+
 @pytest.mark.parametrize("name", ["c2", "c5"])
 def test_bench_shapes_full_size(P, G, name):
     """The configurations bench.py times for the workloads i2 (2048 x 4096 -> 6144) and i5 (8192 x 8192 ->

@@ -188,6 +188,30 @@ def test_calibrate_act(P, G, name):
     assert abs(float(ts.cpu()[0]) - ref1) <= 1e-5 * ref1
 
 
+def test_transform_quant_is_independent_of_the_launch_shape(P, G):
+    """A large, ragged batch (workgroups of two wave groups, nine tiles each, a last tile of three tokens)
+    gives, row for row, the bytes the same rows give in small batches, in both layouts."""
+    import torch
+    M, K = 4099, 8192
+    X = torch.from_numpy(I.random_f32((M, K), seed=42, spread=2.0)).cuda().to(torch.bfloat16)
+    T = G.bf16_dev(I.make_transforms_random(K // 16, 4, block=16))
+    ts = _f32_dev(0.01)
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    P.wush_quantize_act_nvfp4(X, T, ts, Xq, Xs)
+    cb, sb = P.wush_packed_sizes_nvfp4(M, K, 1)
+    Xqt, Xst = G.empty_u8(cb), G.empty_u8(sb)
+    P.wush_quantize_act_nvfp4(X, T, ts, Xqt, Xst, layout=1)
+    Xqu, Xsu = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+    P.wush_unpack_tiled_nvfp4(Xqt, Xst, M, K, Xqu, Xsu)
+    torch.cuda.synchronize()
+    assert torch.equal(Xqu, Xq) and torch.equal(Xsu, Xs)
+    for lo, hi in ((0, 256), (1500, 1533), (4064, 4099)):
+        q, s_ = G.empty_u8(hi - lo, K // 2), G.empty_u8(hi - lo, K // 16)
+        P.wush_quantize_act_nvfp4(X[lo:hi], T, ts, q, s_)
+        torch.cuda.synchronize()
+        assert torch.equal(q, Xq[lo:hi]) and torch.equal(s_, Xs[lo:hi]), (lo, hi)
+
+
 def test_transform_quant_strided_rows(P, G):
     import torch
     cfg, L, X, W, T = _layer("ragged")

@@ -129,6 +129,25 @@ def test_transform_quant(P, G, case, rule):
     assert rate <= 1e-4 and unexplained == 0, (rate, unexplained)
 
 
+def test_transform_quant_is_independent_of_the_launch_shape(P, G):
+    """A large, ragged batch (4099 tokens x 8192 channels: workgroups of two wave groups that walk nine
+    tiles each, the last tile with three tokens) gives, row for row, the bytes the same rows give in
+    small batches (one tile per workgroup, one wave group): how tiles are dealt to workgroups and
+    waves does not enter the result."""
+    import torch
+    M, K = 4099, 8192
+    X = torch.from_numpy(I.random_f32((M, K), seed=41, spread=2.0)).cuda().to(torch.bfloat16)
+    T = G.bf16_dev(I.make_transforms_random(K // 32, 3))
+    fmt = P.default_fmt()
+    Xq, Xs = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+    P.wush_quantize_act(X, T, Xq, Xs, fmt)
+    for lo, hi in ((0, 256), (1500, 1533), (4064, 4099)):
+        q, s_ = G.empty_u8(hi - lo, K // 2), G.empty_u8(hi - lo, K // 32)
+        P.wush_quantize_act(X[lo:hi], T, q, s_, fmt)
+        torch.cuda.synchronize()
+        assert torch.equal(q, Xq[lo:hi]) and torch.equal(s_, Xs[lo:hi]), (lo, hi)
+
+
 def test_transform_quant_strided_rows(P, G):
     """ldx > K: the kernel reads rows of a wider buffer."""
     import torch
