@@ -501,7 +501,7 @@ def int4_bench(args, P, torch, dev):
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
                    "packed_layout": args.layout, "launch": "host loop"},
-        "roofline": {"bound": "mfma", "kernel": "wush_linear_int4 (dequantize to FP16 in LDS + FP16 MFMA)",
+        "roofline": {"bound": "mfma", "kernel": "wush_linear_int4 (dequantize to FP16: X through LDS, W in registers; FP16 MFMA)",
                      "achieved": flops / g_ms / 1e9, "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / g_ms / 1e9 / PEAK_F16_TFLOPS, "traffic": None, "avg_launch_ms": g_ms},
         "kernels": {"wush_quantize_act_int4": {"ms": q_ms, "GB/s": qb / q_ms / 1e6,

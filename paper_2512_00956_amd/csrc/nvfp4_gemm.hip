@@ -20,9 +20,9 @@
 // 256, 192 or 128 output channels, chosen per problem so that the last round of tiles
 // leaves few CUs idle), K in steps of 64 (= 4 scale groups), two LDS stages.  Two kernels:
 //   * w4_f16_gemm_kernel stages both operands in LDS (each thread converts one X row and one
-//     W row of the next step); it serves INT4 and any K;
-//   * nvfp4_wreg_gemm_kernel (NVFP4, K a multiple of 128) keeps W out of LDS: every wave
-//     converts the W fragments it multiplies in its own registers.
+//     W row of the next step); it serves any K;
+//   * w4_wreg_gemm_kernel (K a multiple of 128) keeps W out of LDS: every wave converts the W
+//     fragments it multiplies in its own registers.
 // In both the conversion of the next step is cut into single instructions and dealt out over
 // the MFMAs of the current one: with one wave per SIMD the MFMA pipe is busy 32 cycles per
 // instruction and a handful of independent vector instructions issue in that shadow for free,
@@ -135,23 +135,28 @@ __device__ __forceinline__ v4u dequant8(uint32_t w, v2h s) {
   return c.u;
 }
 
-// Eight two's-complement INT4 codes times the group scale -> 8 FP16.  A nibble n becomes the
-// FP16 number 1024 + (n ^ 8) by OR-ing it into the fraction of 0x6400; subtracting 1032 leaves
-// the signed code, exactly; code * scale has at most 3 + 8 significant bits: exact in FP16 too.
+// Eight two's-complement INT4 codes times the group scale -> 8 FP16.  With the sign bits flipped a
+// nibble n' = n ^ 8 holds code + 8.  OR-ed into the fraction of an FP16 constant where it stands, it
+// becomes 1024 + n' (nibble in bits 0-3 of a half: unit 2^0 in the binade of 1024) or 64 + n' (bits
+// 4-7: unit 2^-6 * 64); subtracting 1032 or 72 leaves the signed code, exactly; code * scale has at
+// most 3 + 8 significant bits: exact in FP16 too.  One shift by 8 brings the other four nibbles to the
+// same two positions, so the eight codes come out in the order 0 4 | 1 5 | 2 6 | 3 7: both operands
+// of the GEMM go through this function, and the MFMA's sum over k does not care about the order.
+constexpr uint32_t kInt4Mask[2] = {0x000F000Fu, 0x00F000F0u}, kInt4Magic[2] = {0x64006400u, 0x54005400u};
+__device__ __forceinline__ v2h int4_pair(uint32_t x, int pos) {   // pos = 0: nibbles at bits 0-3, 1: bits 4-7
+  union { uint32_t u; v2h h; } t;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t.u) : "v"(x), "s"(kInt4Mask[pos]), "v"(kInt4Magic[pos]));
+  return t.h;
+}
+__device__ __forceinline__ v2h int4_bias(int pos) {
+  const _Float16 b = pos ? (_Float16)72.0f : (_Float16)1032.0f;
+  return (v2h){b, b};
+}
 __device__ __forceinline__ v4u dequant8_int4(uint32_t w, v2h s) {
-  const uint32_t x = w ^ 0x88888888u, y = x >> 4;
-  const v2h bias = {(_Float16)1032.0f, (_Float16)1032.0f};
-  union { v2h h[4]; v4u u; uint32_t d[4]; } c;
-  // (permuted & 0x000F000F) | 0x64006400 as one v_and_or_b32 each (the compiler emits an and and an or)
-  const uint32_t mask = 0x000F000Fu, magic = 0x64006400u;
-  const uint32_t p0 = __builtin_amdgcn_perm(y, x, 0x0C040C00u), p1 = __builtin_amdgcn_perm(y, x, 0x0C050C01u);
-  const uint32_t p2 = __builtin_amdgcn_perm(y, x, 0x0C060C02u), p3 = __builtin_amdgcn_perm(y, x, 0x0C070C03u);
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(c.d[0]) : "v"(p0), "s"(mask), "v"(magic));
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(c.d[1]) : "v"(p1), "s"(mask), "v"(magic));
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(c.d[2]) : "v"(p2), "s"(mask), "v"(magic));
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(c.d[3]) : "v"(p3), "s"(mask), "v"(magic));
+  const uint32_t x = w ^ 0x88888888u, y = x >> 8;
+  union { v2h h[4]; v4u u; } c;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) c.h[i] = (c.h[i] - bias) * s;
+  for (int i = 0; i < 4; ++i) c.h[i] = (int4_pair(i < 2 ? x : y, i & 1) - int4_bias(i & 1)) * s;
   return c.u;
 }
 
@@ -191,9 +196,9 @@ __device__ __forceinline__ void convert_group(const Raw& r, int g, char* operand
 // ---------------------------------------------------------------------------
 template <int FMT>
 struct Conv {
-  static constexpr int kOpsPerTask = FMT == kNvfp4 ? 9 : 19;   // micro-operations per 8 codes
+  static constexpr int kOpsPerTask = FMT == kNvfp4 ? 9 : 15;   // micro-operations per 8 codes
   v2h h[4];
-  uint32_t x, y, p[4];
+  uint32_t x, y;
 };
 
 // Micro-operation U of the dword task (8 codes -> one 16-byte LDS chunk).  w = the 8 codes,
@@ -210,19 +215,10 @@ __device__ __forceinline__ void micro_op(Conv<FMT>& c, uint32_t w, v2h s, char* 
     }
   } else {
     if constexpr (U == 0) c.x = w ^ 0x88888888u;
-    else if constexpr (U == 1) c.y = c.x >> 4;
-    else if constexpr (U < 6) c.p[U - 2] = __builtin_amdgcn_perm(c.y, c.x, 0x0C040C00u + 0x00010001u * (U - 2));
-    else if constexpr (U < 10) {
-      uint32_t d;
-      const uint32_t mask = 0x000F000Fu, magic = 0x64006400u;
-      asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(c.p[U - 6]), "s"(mask), "v"(magic));
-      union { uint32_t u; v2h h; } t;
-      t.u = d;
-      c.h[U - 6] = t.h;
-    } else if constexpr (U < 14) {
-      const v2h bias = {(_Float16)1032.0f, (_Float16)1032.0f};
-      c.h[U - 10] = c.h[U - 10] - bias;
-    } else if constexpr (U < 18) c.h[U - 14] = c.h[U - 14] * s;
+    else if constexpr (U == 1) c.y = c.x >> 8;
+    else if constexpr (U < 6) c.h[U - 2] = int4_pair(U < 4 ? c.x : c.y, (U - 2) & 1);
+    else if constexpr (U < 10) c.h[U - 6] = c.h[U - 6] - int4_bias((U - 6) & 1);
+    else if constexpr (U < 14) c.h[U - 10] = c.h[U - 10] * s;
     else {
       union { v2h h[4]; v4u u; } o;
       o.h[0] = c.h[0]; o.h[1] = c.h[1]; o.h[2] = c.h[2]; o.h[3] = c.h[3];
@@ -403,21 +399,22 @@ __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// NVFP4, K a multiple of 128: the W operand goes straight into registers.  Every wave loads the
+// K a multiple of 128: the W operand goes straight into registers.  Every wave loads the
 // packed W fragments it multiplies by itself and converts them in registers (the two waves that
 // share the columns each do it); only X passes through LDS.  The order of the 16 k of an MFMA is
 // free as long as both operands agree: MFMA group g of a K step takes, in lane half h, the eight
 // codes of dword 4h+g of the row's 32 bytes, so the four groups of a lane are ONE 16-byte load
-// and its two scale bytes are bytes 2h, 2h+1 of the row's scale dword.  Against the staged kernel:
-// half the LDS traffic and half the barriers' work for 40 % more conversion arithmetic, which
-// costs nothing as long as it sits in the shadow of the MFMAs.
+// and its scales are bytes 2h, 2h+1 of the row's scale dword (NVFP4: two E4M3 bytes, one per two
+// groups; INT4: the one BF16 number of its 32 codes).  Against the staged kernel: half the LDS
+// traffic and half the barriers' work for 40 % more conversion arithmetic, which costs nothing as
+// long as it sits in the shadow of the MFMAs.
 //
 // What the slots of a K step carry besides their MFMA (measured: arithmetic dealt out like this is
 // free, a global load costs its slot about 30 cycles, so there is one per slot at most, with a
 // scalar base and a 32-bit lane offset; a block of loads or register moves stalls the MFMA pipe
 // for its whole length, hence two K steps per loop trip with the register sets swapping roles
 // instead of being copied):
-//   every slot        two conversion operations of the W fragments of the next group
+//   every slot        two (INT4: three or four) conversion operations of the W fragments of the next group
 //   group 0           the three loads of X for step kt+2        (its register set is free)
 //   group 1           the W scale dwords for step kt+2          (consumed in group 3 of step kt-1)
 //   group 2           the W codes for step kt+2, fragment by fragment as its last group is through
@@ -428,11 +425,11 @@ __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
 // Room a slot of the register-W kernel has for X conversion work, in instructions: about six issue
 // in the shadow of one MFMA; the slot's own fragment read, W conversion pair, scale conversion and
 // global load (which costs several) come off that.
-template <int CB>
+template <int CB, int FMT>
 constexpr int wreg_slot_room(int S) {
-  constexpr int kRoom = 6, kLoadCost = 3;
+  constexpr int kRoom = FMT == kNvfp4 ? 6 : 7, kLoadCost = 3;
   const int kGroup = 4 * CB, g = S / kGroup, idx = S % kGroup;
-  int used = 2;                                              // the W conversion pair
+  int used = FMT == kNvfp4 ? 2 : 4;                          // the W conversion operations
   if (g < 3 && idx >= 1 && idx <= 4) used += 1;              // A fragment read
   if (g == 3 && idx < CB) used += 2;                         // W scale pair: shift and convert
   if (g == 0 && idx >= kGroup - 3) used += kLoadCost;                // global loads
@@ -441,12 +438,12 @@ constexpr int wreg_slot_room(int S) {
   return used >= kRoom ? 0 : kRoom - used;
 }
 // Conversion operations of X dealt to the slots before `S`, out of `total`, in proportion to the room.
-template <int CB>
+template <int CB, int FMT>
 constexpr int wreg_x_ops_before(int S, int total, int conv_slots) {
   int all = 0, before = 0;
   for (int t = 0; t < conv_slots; ++t) {
-    all += wreg_slot_room<CB>(t);
-    if (t < S) before += wreg_slot_room<CB>(t);
+    all += wreg_slot_room<CB, FMT>(t);
+    if (t < S) before += wreg_slot_room<CB, FMT>(t);
   }
   return (int)((long long)total * before / all);
 }
@@ -456,21 +453,53 @@ struct RawW {
 };
 union Frag {
   v2h h[4];
+  v4u u;
   v8h v;
 };
 
-template <bool OUT_F32, int CB>
-__global__ __launch_bounds__(256) void nvfp4_wreg_gemm_kernel(
+// Conversion of a W fragment (8 codes of one lane -> 8 FP16 in registers) as micro-operations.
+template <int FMT>
+struct ConvW {
+  static constexpr int kOps = FMT == kNvfp4 ? 8 : 14;
+  uint32_t x, y;
+};
+template <int FMT, int U>
+__device__ __forceinline__ void w_micro_op(ConvW<FMT>& c, uint32_t w, v2h s, Frag& f) {
+  if constexpr (FMT == kNvfp4) {
+    if constexpr (U < 4) f.h[U] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, U);
+    else f.h[U - 4] = f.h[U - 4] * s;
+  } else {
+    if constexpr (U == 0) c.x = w ^ 0x88888888u;
+    else if constexpr (U == 1) c.y = c.x >> 8;
+    else if constexpr (U < 6) f.h[U - 2] = int4_pair(U < 4 ? c.x : c.y, (U - 2) & 1);
+    else if constexpr (U < 10) f.h[U - 6] = f.h[U - 6] - int4_bias((U - 6) & 1);
+    else f.h[U - 10] = f.h[U - 10] * s;
+  }
+}
+// The scales of a lane's 32 W codes of a K step as FP16: bytes 2h, 2h+1 of the row's scale dword,
+// h = the lane's half.  NVFP4: two E4M3 bytes, [0] for groups 0 and 1, [1] for groups 2 and 3.
+// INT4: one BF16 number, in both.  sel = 0x05040C0C + 0x02020000 h (byte selector that moves the
+// two bytes to the top of a dword).
+template <int FMT>
+__device__ __forceinline__ v2h w_step_scales(uint32_t sdw, int h, uint32_t sel) {
+  if constexpr (FMT == kNvfp4) return e4m3x2_to_f16<false>(sdw >> (16 * h));
+  else {
+    const _Float16 sc = (_Float16)__uint_as_float(__builtin_amdgcn_perm(sdw, sdw, sel));
+    return (v2h){sc, sc};
+  }
+}
+
+template <bool OUT_F32, int CB, int FMT>
+__global__ __launch_bounds__(256) void w4_wreg_gemm_kernel(
     const uint8_t* __restrict__ Xq, const uint8_t* __restrict__ Xs, const float* __restrict__ tsx,
     const uint8_t* __restrict__ Wq, const uint8_t* __restrict__ Ws, const float* __restrict__ tsw,
     void* __restrict__ Yv, int64_t ldy, int M, int N, int K, int tiles_m, int tiles_n, int tiled) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  constexpr int FMT = kNvfp4;
   constexpr int kBN = 64 * CB;
   constexpr int kSlots = 16 * CB, kGroup = 4 * CB;
   constexpr int kConvSlots = 16 * CB - 4;
-  constexpr int kXSlots = CB == 4 ? 48 : 16 * CB - 4;   // slots that carry X conversion work (measured)
-  constexpr int kOps = Conv<FMT>::kOpsPerTask;
+  constexpr int kXSlots = (FMT == kNvfp4 && CB == 4) ? 48 : 16 * CB - 4;   // slots that carry X conversion work (measured)
+  constexpr int kOps = Conv<FMT>::kOpsPerTask, kWOps = ConvW<FMT>::kOps;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -489,7 +518,7 @@ __global__ __launch_bounds__(256) void nvfp4_wreg_gemm_kernel(
   OperandAddr aw[CB];
 #pragma unroll
   for (int j = 0; j < CB; ++j) aw[j] = operand_addr(Wq, Ws, n0, min(n0 + wn * (32 * CB) + 32 * j + l32, N - 1), h, K, tiled);
-  const int sh = 16 * h;
+  const uint32_t ssel = 0x05040C0Cu + 0x02020000u * h;
   auto load_x = [&](Raw& r, int kt, int which) { load_raw_piece(r, ax, st, kt, which); };
   auto load_wq = [&](RawW& r, int kt, int j) { r.q = load_codes(aw[j], st, kt, 0); };
   auto load_ws = [&](RawW& r, int kt, int j) { r.s = load_scales(aw[j], st, kt); };
@@ -497,6 +526,7 @@ __global__ __launch_bounds__(256) void nvfp4_wreg_gemm_kernel(
   Raw xr[2];                  // X of step kt+1 lives in xr[(kt+1) & 1] during step kt; the other set receives step kt+2
   RawW wr[2][CB];             // W of step kt in wr[kt & 1]; refilled with step kt+2 as its groups are converted
   v2h wsc[2][CB];             // their scales as FP16 pairs: [group >> 1]
+  ConvW<FMT> cw;
   Frag fb[2][CB];
   v8h fa[2][4];
 
@@ -518,12 +548,9 @@ __global__ __launch_bounds__(256) void nvfp4_wreg_gemm_kernel(
   for (int w = 0; w < 3; ++w) load_x(xr[1], 1, w);
 #pragma unroll
   for (int j = 0; j < CB; ++j) {
-    wsc[0][j] = e4m3x2_to_f16<false>(wr[0][j].s >> sh);
+    wsc[0][j] = w_step_scales<FMT>(wr[0][j].s, h, ssel);
     const v2h s = {wsc[0][j][0], wsc[0][j][0]};
-    fb[0][j].h[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(wr[0][j].q[0], 1.0f, 0) * s;
-    fb[0][j].h[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(wr[0][j].q[0], 1.0f, 1) * s;
-    fb[0][j].h[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(wr[0][j].q[0], 1.0f, 2) * s;
-    fb[0][j].h[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(wr[0][j].q[0], 1.0f, 3) * s;
+    fb[0][j].u = FMT == kNvfp4 ? dequant8(wr[0][j].q[0], s) : dequant8_int4(wr[0][j].q[0], s);
   }
   __syncthreads();
 
@@ -566,16 +593,16 @@ __global__ __launch_bounds__(256) void nvfp4_wreg_gemm_kernel(
         if constexpr (idx >= 1 && idx <= 4) read_frag(cur, g + 1, idx - 1, (g + 1) & 1);
       }
       if constexpr (S >= kConvSlots) read_frag(nxt, 0, S - kConvSlots, 0);
-      // W fragments of the next group (group 0 of the next step behind group 3): two operations per slot
+      // W fragments of the next group (group 0 of the next step behind group 3): a fragment's
+      // operations spread over four slots
       {
         constexpr int tg = (g + 1) & 3, set = (g + 1) & 1, R = g == 3 ? Q : P;
-        if constexpr (g == 3 && idx < CB) wsc[Q][idx] = e4m3x2_to_f16<false>(wr[Q][idx].s >> sh);
-        static_for<2>([&](auto q) {
-          constexpr int u = 2 * idx + decltype(q)::value, task = u / 8, op = u % 8;
-          const RawW& r = wr[R][task];
+        if constexpr (g == 3 && idx < CB) wsc[Q][idx] = w_step_scales<FMT>(wr[Q][idx].s, h, ssel);
+        constexpr int u0 = idx * kWOps / 4, u1 = (idx + 1) * kWOps / 4;
+        static_for<u1 - u0>([&](auto q) {
+          constexpr int u = u0 + decltype(q)::value, task = u / kWOps, op = u % kWOps;
           const v2h& sp = wsc[R][task];
-          if constexpr (op < 4) fb[set][task].h[op] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(r.q[tg], 1.0f, op);
-          else fb[set][task].h[op - 4] = fb[set][task].h[op - 4] * (v2h){sp[tg >> 1], sp[tg >> 1]};
+          w_micro_op<FMT, op>(cw, wr[R][task].q[tg], (v2h){sp[tg >> 1], sp[tg >> 1]}, fb[set][task]);
         });
       }
       // refills, one load per slot, each once its registers are free
@@ -583,8 +610,8 @@ __global__ __launch_bounds__(256) void nvfp4_wreg_gemm_kernel(
       if constexpr (g == 1 && idx >= kGroup - CB) load_ws(wr[P][idx - (kGroup - CB)], kl, idx - (kGroup - CB));
       if constexpr (g == 2 && (idx & 3) == 3) load_wq(wr[P][idx >> 2], kl, idx >> 2);
       if constexpr (S < kXSlots) {
-        constexpr int total = 8 * kOps, u0 = wreg_x_ops_before<CB>(S, total, kXSlots),
-                      u1 = wreg_x_ops_before<CB>(S + 1, total, kXSlots);
+        constexpr int total = 8 * kOps, u0 = wreg_x_ops_before<CB, FMT>(S, total, kXSlots),
+                      u1 = wreg_x_ops_before<CB, FMT>(S + 1, total, kXSlots);
         static_for<u1 - u0>([&](auto q) {
           constexpr int u = u0 + decltype(q)::value, d = u / kOps, op = u % kOps;
           micro_op<FMT, op>(cv, xr[Q].q[d >> 2][d & 3], (v2h){sx[d >> 2][(d >> 1) & 1], sx[d >> 2][(d >> 1) & 1]},
@@ -601,7 +628,7 @@ __global__ __launch_bounds__(256) void nvfp4_wreg_gemm_kernel(
     step(kt + 1, std::integral_constant<int, 1>{});
   }
 
-  const float scale = *tsx * *tsw;
+  const float scale = FMT == kNvfp4 ? *tsx * *tsw : 1.0f;   // INT4 has no tensor scales (null pointers)
   // Output coordinates from a fresh copy of the thread index: nothing of the prologue's index
   // arithmetic has to stay in registers across the loop.
   int te = threadIdx.x;
@@ -626,19 +653,19 @@ __global__ __launch_bounds__(256) void nvfp4_wreg_gemm_kernel(
   }
 }
 
-template <bool OUT_F32, int CB>
+template <bool OUT_F32, int CB, int FMT>
 hipError_t launch_wreg(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
                        const float* tsw, int64_t M, int64_t N, int64_t K, int tiled, void* Y, int64_t ldy,
                        hipStream_t stream) {
   static bool configured = false;
   if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nvfp4_wreg_gemm_kernel<OUT_F32, CB>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4_wreg_gemm_kernel<OUT_F32, CB, FMT>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kXBytes);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + 64 * CB - 1) / (64 * CB));
-  nvfp4_wreg_gemm_kernel<OUT_F32, CB><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 2 * kXBytes, stream>>>(
+  w4_wreg_gemm_kernel<OUT_F32, CB, FMT><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 2 * kXBytes, stream>>>(
       (const uint8_t*)Xq, (const uint8_t*)Xs, tsx, (const uint8_t*)Wq, (const uint8_t*)Ws, tsw, Y, ldy, (int)M, (int)N,
       (int)K, tiles_m, tiles_n, tiled);
   return hipGetLastError();
@@ -684,13 +711,11 @@ hipError_t launch_w4_f16_gemm(const void* Xq, const void* Xs, const float* tsx, 
   if (const char* f = getenv("WUSH_NVFP4_WIDTH")) {  // tests: force a tile width (output channels / 64)
     if (f[0] >= '2' && f[0] <= '4' && f[1] == 0) best = f[0] - '0';
   }
-  if constexpr (FMT == kNvfp4) {
-    if (K % 128 == 0) {   // an even number of K steps: W in registers
-#define WUSH_WR_LAUNCH(F32, CB) launch_wreg<F32, CB>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, tiled, Y, ldy, stream)
-      if (out_f32) return best == 4 ? WUSH_WR_LAUNCH(true, 4) : best == 3 ? WUSH_WR_LAUNCH(true, 3) : WUSH_WR_LAUNCH(true, 2);
-      return best == 4 ? WUSH_WR_LAUNCH(false, 4) : best == 3 ? WUSH_WR_LAUNCH(false, 3) : WUSH_WR_LAUNCH(false, 2);
+  if (K % 128 == 0) {   // an even number of K steps: W in registers
+#define WUSH_WR_LAUNCH(F32, CB) launch_wreg<F32, CB, FMT>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, tiled, Y, ldy, stream)
+    if (out_f32) return best == 4 ? WUSH_WR_LAUNCH(true, 4) : best == 3 ? WUSH_WR_LAUNCH(true, 3) : WUSH_WR_LAUNCH(true, 2);
+    return best == 4 ? WUSH_WR_LAUNCH(false, 4) : best == 3 ? WUSH_WR_LAUNCH(false, 3) : WUSH_WR_LAUNCH(false, 2);
 #undef WUSH_WR_LAUNCH
-    }
   }
 #define WUSH_NV_LAUNCH(F32, CB) launch_shape<F32, CB, FMT>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, tiled, Y, ldy, stream)
   if (out_f32) return best == 4 ? WUSH_NV_LAUNCH(true, 4) : best == 3 ? WUSH_NV_LAUNCH(true, 3) : WUSH_NV_LAUNCH(true, 2);

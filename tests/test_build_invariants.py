@@ -137,12 +137,12 @@ def _assert_loads_cost_no_vector_arithmetic(name, loop, n_loads):
 
 
 def test_register_w_gemm_loop():
-    """The NVFP4 kernel that keeps W in registers: no scratch, two K steps per loop trip (2 x 16 CB MFMAs,
+    """The NVFP4 / INT4 kernel that keeps W in registers: no scratch, two K steps per loop trip (2 x 16 CB MFMAs,
     two barriers), 3 + 2 CB loads per step in scalar-base form, and no register move in the loop (the
     prefetched operand sets swap roles between the two steps instead of being copied)."""
     text = _compile("nvfp4_gemm.hip")
-    kernels = _bodies(text, "nvfp4_wreg_gemm_kernel")
-    assert len(kernels) == 6, list(kernels)           # {bf16, f32 output} x {4, 3, 2 column blocks}
+    kernels = _bodies(text, "w4_wreg_gemm_kernel")
+    assert len(kernels) == 12, list(kernels)          # {bf16, f32 output} x {4, 3, 2 column blocks} x {NVFP4, INT4}
     for name, body in kernels.items():
         cb = int(re.search(r"ILb[01]ELi(\d+)E", name).group(1))
         assert "scratch_" not in body, f"{name}: spills to scratch"
