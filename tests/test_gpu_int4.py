@@ -198,6 +198,46 @@ def test_linear_against_oracle(P, G, M, N, K, out):
     assert O.rel_fro(y[:, :N], ref) <= (1e-5 if f32 else 2e-3)
 
 
+def _tile_operand(packed, scale_bytes):
+    """Canonical packed codes [rows][K/2] and scale bytes [rows][K/16] (two BF16 numbers per 64-element K
+    step) -> the tiled buffers, from the statement of the layout: rows padded to 32; the 16-byte chunk
+    (row, kt, hh) at ((((row / 32) KT + kt) 2 + hh) 32 + row % 32) 16, the scale dword (row, kt) at
+    (((row / 32) KT + kt) 32 + row % 32) 4."""
+    rows, K = packed.shape[0], packed.shape[1] * 2
+    KT, RB = K // 64, (rows + 31) // 32
+    pq = np.zeros((RB * 32, KT, 2, 16), dtype=np.uint8)
+    pq[:rows] = packed.reshape(rows, KT, 2, 16)
+    ps = np.zeros((RB * 32, KT, 4), dtype=np.uint8)
+    ps[:rows] = scale_bytes.reshape(rows, KT, 4)
+    q = pq.reshape(RB, 32, KT, 2, 16).transpose(0, 2, 3, 1, 4)
+    sc = ps.reshape(RB, 32, KT, 4).transpose(0, 2, 1, 3)
+    return np.ascontiguousarray(q).reshape(-1), np.ascontiguousarray(sc).reshape(-1)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("K", [320, 384])
+@pytest.mark.parametrize("width", ["2", "3", "4"])
+def test_linear_every_tile_width(P, G, width, K, layout, monkeypatch):
+    """The three tile widths on a shape with several tiles and ragged edges in both directions, GEMM alone.
+    An odd number of 64-element K steps (K = 320) takes the kernel that stages both operands in LDS, an
+    even one (K = 384) the one that converts W in registers; both read either layout."""
+    import torch
+    monkeypatch.setenv("WUSH_NVFP4_WIDTH", width)
+    M, N = 300, 700
+    rng = np.random.default_rng(91 + K)
+    xq, xs = _random_operand(rng, M, K, -13, 9)
+    wq, ws_ = _random_operand(rng, N, K, -10, -2)
+    ref = Q.linear_dequant(xq, xs, wq, ws_)
+    xp, wp = Q.pack_codes(xq), Q.pack_codes(wq)
+    xsb, wsb = xs.view(np.uint8).reshape(M, -1), ws_.view(np.uint8).reshape(N, -1)
+    if layout:
+        (xp, xsb), (wp, wsb) = _tile_operand(xp, xsb), _tile_operand(wp, wsb)
+    Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_linear_int4(G.u8_dev(xp), G.u8_dev(xsb), G.u8_dev(wp), G.u8_dev(wsb), Y, layout=layout, out_dtype=1, K=K)
+    torch.cuda.synchronize()
+    assert O.rel_fro(Y.cpu().numpy().astype(np.float64), ref) <= 1e-5
+
+
 @pytest.mark.parametrize("width", ["2", "3", "4"])
 def test_layer_end_to_end_both_layouts(P, G, width, monkeypatch):
     import torch
