@@ -280,13 +280,9 @@ hipError_t launch_mxfp4_gemm(const void* Xq, const void* Xs, const void* Wq, con
   }();
   const bool tiled_ok = !force_simple && (K % 256 == 0) && (M * N >= 128 * 128);
   if (tiled_ok) {
-    static const hipError_t attr = [] {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tiled_kernel<false>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-      if (e != hipSuccess) return e;
-      return hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tiled_kernel<true>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-    }();
+    static DynamicLdsLimit lds_bf16, lds_f32;
+    hipError_t attr = lds_bf16.ensure(reinterpret_cast<const void*>(gemm_tiled_kernel<false>), kGemmLds);
+    if (attr == hipSuccess) attr = lds_f32.ensure(reinterpret_cast<const void*>(gemm_tiled_kernel<true>), kGemmLds);
     if (attr != hipSuccess) return attr;
     const int tiles_m = (int)((M + kTM - 1) / kTM), tiles_n = (int)((N + kTN - 1) / kTN);
     dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);

@@ -464,8 +464,8 @@ template <bool OUT_F32, int RB, int CB>
 hipError_t launch_shape(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M, int64_t N, int64_t K,
                         void* Y, int64_t ldy, hipStream_t stream) {
   constexpr int kLds = lds_bytes(RB);
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_frag_kernel<OUT_F32, RB, CB>),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  static DynamicLdsLimit lds_limit;   // per instantiation
+  const hipError_t attr = lds_limit.ensure(reinterpret_cast<const void*>(gemm_frag_kernel<OUT_F32, RB, CB>), kLds);
   if (attr != hipSuccess) return attr;
   constexpr int kTM = 32 * RB, kTN = 4 * 32 * CB;
   const int tiles_m = (int)((M + kTM - 1) / kTM), tiles_n = (int)((N + kTN - 1) / kTN);
@@ -491,12 +491,7 @@ int64_t shape_cost(int64_t M, int64_t N, int tm, int tn, int mfma_per_iter, int 
 hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq, const void* Ws,
                                   int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
                                   hipStream_t stream) {
-  static const int cus = [] {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
-    return n;
-  }();
+  const int cus = device_cu_count();
   // Four instantiations: 256 x 256 (8 x 2 MFMA tiles per wave), 128 x 384 (4 x 3), 128 x 256 (4 x 2)
   // and 128 x 128 (4 x 1).
   // The cheapest by "rounds of the CUs x MFMAs per K iteration" wins, ties go to the larger tile

@@ -657,13 +657,9 @@ template <bool OUT_F32, int CB, int FMT>
 hipError_t launch_wreg(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
                        const float* tsw, int64_t M, int64_t N, int64_t K, int tiled, void* Y, int64_t ldy,
                        hipStream_t stream) {
-  static bool configured = false;
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4_wreg_gemm_kernel<OUT_F32, CB, FMT>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kXBytes);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static DynamicLdsLimit lds_limit;   // per instantiation
+  const hipError_t e = lds_limit.ensure(reinterpret_cast<const void*>(w4_wreg_gemm_kernel<OUT_F32, CB, FMT>), 2 * kXBytes);
+  if (e != hipSuccess) return e;
   const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + 64 * CB - 1) / (64 * CB));
   w4_wreg_gemm_kernel<OUT_F32, CB, FMT><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 2 * kXBytes, stream>>>(
       (const uint8_t*)Xq, (const uint8_t*)Xs, tsx, (const uint8_t*)Wq, (const uint8_t*)Ws, tsw, Y, ldy, (int)M, (int)N,
@@ -675,13 +671,9 @@ template <bool OUT_F32, int CB, int FMT>
 hipError_t launch_shape(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
                         const float* tsw, int64_t M, int64_t N, int64_t K, int tiled, void* Y, int64_t ldy,
                         hipStream_t stream) {
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4_f16_gemm_kernel<OUT_F32, CB, FMT>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static DynamicLdsLimit lds_limit;   // per instantiation
+  const hipError_t e = lds_limit.ensure(reinterpret_cast<const void*>(w4_f16_gemm_kernel<OUT_F32, CB, FMT>), kLdsBytes);
+  if (e != hipSuccess) return e;
   const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + 64 * CB - 1) / (64 * CB));
   w4_f16_gemm_kernel<OUT_F32, CB, FMT><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), kLdsBytes, stream>>>(
       (const uint8_t*)Xq, (const uint8_t*)Xs, tsx, (const uint8_t*)Wq, (const uint8_t*)Ws, tsw, Y, ldy, (int)M, (int)N,

@@ -94,14 +94,14 @@ __global__ __launch_bounds__(kWaves * TG * 64) void transform_quant_kernel(
 }  // namespace
 
 int device_cu_count() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
-    cus = n;
-  }
-  return cus;
+  static std::atomic<int> cus[64];   // zero-initialized; per device
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  const bool tracked = dev >= 0 && dev < 64;
+  if (tracked && (n = cus[dev].load(std::memory_order_relaxed)) > 0) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
+  if (tracked) cus[dev].store(n, std::memory_order_relaxed);
+  return n;
 }
 
 // Token tiles each workgroup walks down (the register-resident transforms are loaded once per

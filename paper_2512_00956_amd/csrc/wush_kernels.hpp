@@ -5,10 +5,32 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace wush {
 
-// Compute units of the current device (queried once).
+// Compute units of the current device (queried once per device).
 int device_cu_count();
+
+// Raises a kernel's dynamic LDS limit, once per device: the attribute belongs to the device's copy of
+// the code object, so a process that drives several GPUs has to set it on each.  One object per
+// kernel instantiation (a function-local static of its launcher).
+class DynamicLdsLimit {
+ public:
+  hipError_t ensure(const void* kernel, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && (done_.load(std::memory_order_acquire) >> dev & 1)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && tracked) done_.fetch_or(uint64_t(1) << dev, std::memory_order_release);
+    return e;
+  }
+
+ private:
+  std::atomic<uint64_t> done_{0};
+};
 // Token tiles per workgroup of the fused transform + quantize kernels (ntiles 32-token tiles,
 // col_groups workgroups across the channels).
 int token_walk(int ntiles, int col_groups);
