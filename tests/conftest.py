@@ -9,4 +9,4 @@ if ROOT not in sys.path:
 
 
 def pytest_configure(config):
-    config.addinivalue_line("markers", "gpu: needs a real MI355X (run under gpurun)")
+    config.addinivalue_line("markers", "gpu: needs a real MI355X")
