@@ -51,6 +51,9 @@
  *   - Requirements: M, N, K > 0; K % 32 == 0; data pointers 16-byte aligned;
  *     input leading dimensions (in elements) >= K and a multiple of 8;
  *     fmt.block == 32, fmt.elem == WUSH_E2M1, fmt.scale == WUSH_E8M0.
+ *   - Largest sizes: row counts (M, N, calibration tokens) up to 2^30, K up to
+ *     2^22, M * N of one GEMM up to 2^40; beyond that WUSH_ERR_SHAPE (the
+ *     workspace-size queries return 0).
  */
 #ifndef WUSH_H_
 #define WUSH_H_
@@ -65,7 +68,7 @@ extern "C" {
 typedef enum {
   WUSH_OK = 0,
   WUSH_ERR_NULL = 1,      /* a required pointer is NULL */
-  WUSH_ERR_SHAPE = 2,     /* non-positive size, K % 32 != 0, bad leading dimension */
+  WUSH_ERR_SHAPE = 2,     /* non-positive or too large size, K % 32 != 0, bad leading dimension */
   WUSH_ERR_ALIGN = 3,     /* pointer not 16-byte aligned */
   WUSH_ERR_FMT = 4,       /* unsupported format descriptor */
   WUSH_ERR_WORKSPACE = 5, /* workspace missing or too small */

@@ -25,11 +25,19 @@ inline wush_status check_layout(const wush_fmt& f, int64_t K) {
   return (f.layout == WUSH_LAYOUT_TILED && K % 256 != 0) ? WUSH_ERR_SHAPE : WUSH_OK;
 }
 
-// Kernel index arithmetic uses 32-bit row/column counters and 64-bit offsets.
-constexpr int64_t kMaxDim = (int64_t)1 << 30;
+// Kernel index arithmetic uses 32-bit row/column counters, 64-bit offsets of rows and tiles, and
+// 32-bit offsets inside a tile of at most 256 rows (256 rows of packed codes must stay below 4 GiB);
+// a GEMM launches one workgroup per output tile of at least 128 x 128.
+constexpr int64_t kMaxDim = (int64_t)1 << 30;    // rows: M, N, calibration tokens
+constexpr int64_t kMaxK = (int64_t)1 << 22;      // channels
+constexpr int64_t kMaxOutputs = (int64_t)1 << 40;   // M * N of one GEMM
+
+inline bool gemm_too_large(int64_t M, int64_t N, int64_t K) {
+  return M > kMaxDim || N > kMaxDim || K > kMaxK || M * N > kMaxOutputs;   // M, N <= 2^30: the product fits
+}
 
 inline wush_status check_rows(int64_t rows, int64_t K, int64_t ld) {
-  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxDim) return WUSH_ERR_SHAPE;
+  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxK) return WUSH_ERR_SHAPE;
   if (K % 32 != 0) return WUSH_ERR_SHAPE;
   if (ld < K || ld % 8 != 0) return WUSH_ERR_SHAPE;
   return WUSH_OK;
@@ -97,7 +105,7 @@ wush_status wush_workspace_status(const void* workspace, int64_t K, void* stream
 }
 
 size_t wush_build_transforms_workspace(int64_t K) {
-  if (K <= 0 || K % 32 != 0 || K > kMaxDim) return 0;
+  if (K <= 0 || K % 32 != 0 || K > kMaxK) return 0;
   return wush::build_transforms_workspace_bytes(K);
 }
 
@@ -131,7 +139,7 @@ wush_status wush_build_transforms_nvfp4(const void* W, int64_t N, int64_t ldw, c
 
 wush_status wush_build_transforms_status(const void* workspace, int64_t K, void* stream) {
   if (!workspace) return WUSH_ERR_NULL;
-  if (K <= 0 || K % 32 != 0 || K > kMaxDim) return WUSH_ERR_SHAPE;
+  if (K <= 0 || K % 32 != 0 || K > kMaxK) return WUSH_ERR_SHAPE;
   int flag = 0;
   const char* p = static_cast<const char*>(workspace) + wush::build_transforms_status_offset(K);
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -144,8 +152,7 @@ wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const vo
                         int64_t N, int64_t K, wush_fmt fmt, void* Y, int64_t ldy, void* stream) {
   if (!Xq || !Xs || !Wq || !Ws || !Y) return WUSH_ERR_NULL;
   if (wush_status s = check_fmt(fmt)) return s;
-  if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim || K % 32 != 0)
-    return WUSH_ERR_SHAPE;
+  if (M <= 0 || N <= 0 || K <= 0 || gemm_too_large(M, N, K) || K % 32 != 0) return WUSH_ERR_SHAPE;
   if (ldy < N) return WUSH_ERR_SHAPE;
   if (wush_status s = check_layout(fmt, K)) return s;
   if (!aligned16(Xq) || !aligned16(Xs) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
@@ -157,7 +164,7 @@ wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const vo
 }
 
 size_t wush_prepare_weight_gptq_workspace(int64_t N, int64_t K) {
-  if (N <= 0 || K <= 0 || K % 32 != 0 || N > kMaxDim || K > kMaxDim) return 0;
+  if (N <= 0 || K <= 0 || K % 32 != 0 || N > kMaxDim || K > kMaxK) return 0;
   return wush::gptq_prep_workspace_bytes(N, K);
 }
 
@@ -182,7 +189,7 @@ wush_status wush_prepare_weight_gptq(const void* W, int64_t N, int64_t K, int64_
 
 wush_status wush_prepare_weight_gptq_status(const void* workspace, int64_t N, int64_t K, void* stream) {
   if (!workspace) return WUSH_ERR_NULL;
-  if (N <= 0 || K <= 0 || K % 32 != 0 || N > kMaxDim || K > kMaxDim) return WUSH_ERR_SHAPE;
+  if (N <= 0 || K <= 0 || K % 32 != 0 || N > kMaxDim || K > kMaxK) return WUSH_ERR_SHAPE;
   int flag = 0;
   const char* p = static_cast<const char*>(workspace) + wush::gptq_prep_status_offset(N, K);
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -192,13 +199,13 @@ wush_status wush_prepare_weight_gptq_status(const void* workspace, int64_t N, in
 }
 
 size_t wush_layer_decode_workspace(int64_t K) {
-  if (K <= 0 || K % 256 != 0 || K > kMaxDim) return 0;
+  if (K <= 0 || K % 256 != 0 || K > kMaxK) return 0;
   return wush::layer_decode_workspace_bytes(K);
 }
 
 wush_status wush_layer_decode_init(void* workspace, size_t workspace_bytes, int64_t K, void* stream) {
   if (!workspace) return WUSH_ERR_NULL;
-  if (K <= 0 || K % 256 != 0 || K > kMaxDim) return WUSH_ERR_SHAPE;
+  if (K <= 0 || K % 256 != 0 || K > kMaxK) return WUSH_ERR_SHAPE;
   if (workspace_bytes < wush::layer_decode_workspace_bytes(K)) return WUSH_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return WUSH_ERR_ALIGN;
   return from_hip(wush::launch_layer_decode_init(workspace, K, static_cast<hipStream_t>(stream)));
@@ -243,7 +250,7 @@ wush_status wush_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx, 
 
 wush_status wush_layer_decode_status(const void* workspace, int64_t K, void* stream) {
   if (!workspace) return WUSH_ERR_NULL;
-  if (K <= 0 || K % 256 != 0 || K > kMaxDim) return WUSH_ERR_SHAPE;
+  if (K <= 0 || K % 256 != 0 || K > kMaxK) return WUSH_ERR_SHAPE;
   unsigned flag = 0;
   const char* p = static_cast<const char*>(workspace) + wush::layer_decode_error_offset(K);
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -295,7 +302,7 @@ wush_status wush_calibrate_act_nvfp4(const void* X, int64_t M, int64_t K, int64_
 }
 
 size_t wush_prepare_weight_nvfp4_workspace(int64_t K) {
-  if (K <= 0 || K % 32 != 0 || K > kMaxDim) return 0;
+  if (K <= 0 || K % 32 != 0 || K > kMaxK) return 0;
   return wush::nvfp4_weight_prep_workspace_bytes(K);
 }
 
@@ -315,7 +322,7 @@ wush_status wush_prepare_weight_nvfp4(const void* W, int64_t N, int64_t K, int64
 
 wush_status wush_prepare_weight_nvfp4_status(const void* workspace, int64_t K, void* stream) {
   if (!workspace) return WUSH_ERR_NULL;
-  if (K <= 0 || K % 32 != 0 || K > kMaxDim) return WUSH_ERR_SHAPE;
+  if (K <= 0 || K % 32 != 0 || K > kMaxK) return WUSH_ERR_SHAPE;
   int flag = 0;
   const char* p = static_cast<const char*>(workspace) + wush::nvfp4_weight_prep_status_offset(K);
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -330,7 +337,7 @@ wush_status wush_linear_nvfp4(const void* Xq, const void* Xs, const float* tsx, 
   if (!Xq || !Xs || !tsx || !Wq || !Ws || !tsw || !Y) return WUSH_ERR_NULL;
   if (out_dtype != WUSH_OUT_BF16 && out_dtype != WUSH_OUT_F32) return WUSH_ERR_FMT;
   if (layout != WUSH_LAYOUT_CANONICAL && layout != WUSH_LAYOUT_TILED) return WUSH_ERR_FMT;
-  if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim || K % 64 != 0) return WUSH_ERR_SHAPE;
+  if (M <= 0 || N <= 0 || K <= 0 || gemm_too_large(M, N, K) || K % 64 != 0) return WUSH_ERR_SHAPE;
   if (ldy < N) return WUSH_ERR_SHAPE;
   if (!aligned16(Xq) || !aligned16(Xs) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(tsx) % 4 != 0 || reinterpret_cast<uintptr_t>(tsw) % 4 != 0) return WUSH_ERR_ALIGN;
@@ -343,7 +350,7 @@ wush_status wush_linear_nvfp4(const void* Xq, const void* Xs, const float* tsx, 
 wush_status wush_quantize_f32_nvfp4(const float* Yt, int64_t M, int64_t K, const float* tensor_scale, int32_t layout,
                                     void* q, void* s, void* stream) {
   if (!Yt || !tensor_scale || !q || !s) return WUSH_ERR_NULL;
-  if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxK || K % 32 != 0) return WUSH_ERR_SHAPE;
   if (wush_status st = check_nv_layout(layout, K)) return st;
   if (!aligned16(Yt) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(tensor_scale) % 4 != 0) return WUSH_ERR_ALIGN;
@@ -353,7 +360,7 @@ wush_status wush_quantize_f32_nvfp4(const float* Yt, int64_t M, int64_t K, const
 
 wush_status wush_packed_sizes_nvfp4(int64_t rows, int64_t K, int32_t layout, size_t* code_bytes, size_t* scale_bytes) {
   if (!code_bytes || !scale_bytes) return WUSH_ERR_NULL;
-  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxK || K % 32 != 0) return WUSH_ERR_SHAPE;
   if (wush_status st = check_nv_layout(layout, K)) return st;
   const int64_t r = layout == WUSH_LAYOUT_TILED ? (rows + 31) / 32 * 32 : rows;
   *code_bytes = (size_t)r * (size_t)(K / 2);
@@ -364,7 +371,7 @@ wush_status wush_packed_sizes_nvfp4(int64_t rows, int64_t K, int32_t layout, siz
 wush_status wush_unpack_tiled_nvfp4(const void* q_tiled, const void* s_tiled, int64_t rows, int64_t K, void* q, void* s,
                                     void* stream) {
   if (!q_tiled || !s_tiled || !q || !s) return WUSH_ERR_NULL;
-  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxDim || K % 64 != 0) return WUSH_ERR_SHAPE;
+  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxK || K % 64 != 0) return WUSH_ERR_SHAPE;
   if (!aligned16(q_tiled) || !aligned16(s_tiled) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
   return from_hip(wush::launch_nvfp4_unpack_tiled(q_tiled, s_tiled, rows, K, q, s, static_cast<hipStream_t>(stream)));
 }
@@ -398,7 +405,7 @@ wush_status wush_linear_int4(const void* Xq, const void* Xs, const void* Wq, con
   if (!Xq || !Xs || !Wq || !Ws || !Y) return WUSH_ERR_NULL;
   if (out_dtype != WUSH_OUT_BF16 && out_dtype != WUSH_OUT_F32) return WUSH_ERR_FMT;
   if (layout != WUSH_LAYOUT_CANONICAL && layout != WUSH_LAYOUT_TILED) return WUSH_ERR_FMT;
-  if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim || K % 64 != 0) return WUSH_ERR_SHAPE;
+  if (M <= 0 || N <= 0 || K <= 0 || gemm_too_large(M, N, K) || K % 64 != 0) return WUSH_ERR_SHAPE;
   if (ldy < N) return WUSH_ERR_SHAPE;
   if (!aligned16(Xq) || !aligned16(Xs) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
   const uintptr_t elem = out_dtype == WUSH_OUT_F32 ? 4 : 2;
@@ -410,7 +417,7 @@ wush_status wush_linear_int4(const void* Xq, const void* Xs, const void* Wq, con
 wush_status wush_quantize_f32_int4(const float* Yt, int64_t M, int64_t K, int32_t layout, void* q, void* s,
                                    void* stream) {
   if (!Yt || !q || !s) return WUSH_ERR_NULL;
-  if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxK || K % 32 != 0) return WUSH_ERR_SHAPE;
   if (wush_status st = check_nv_layout(layout, K)) return st;
   if (!aligned16(Yt) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
   return from_hip(wush::launch_int4_quantize_f32(Yt, M, K, layout == WUSH_LAYOUT_TILED, q, s,
@@ -421,7 +428,7 @@ wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fm
                               void* stream) {
   if (!Yt || !q || !s) return WUSH_ERR_NULL;
   if (wush_status st = check_fmt(fmt)) return st;
-  if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (M <= 0 || K <= 0 || M > kMaxDim || K > kMaxK || K % 32 != 0) return WUSH_ERR_SHAPE;
   if (wush_status st = check_layout(fmt, K)) return st;
   if (!aligned16(Yt) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
   return from_hip(wush::launch_quantize_f32(Yt, M, K, fmt.scale_rule, fmt.layout == WUSH_LAYOUT_TILED, q, s,
@@ -431,7 +438,7 @@ wush_status wush_quantize_f32(const float* Yt, int64_t M, int64_t K, wush_fmt fm
 wush_status wush_packed_sizes(int64_t rows, int64_t K, wush_fmt fmt, size_t* code_bytes, size_t* scale_bytes) {
   if (!code_bytes || !scale_bytes) return WUSH_ERR_NULL;
   if (wush_status st = check_fmt(fmt)) return st;
-  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxDim || K % 32 != 0) return WUSH_ERR_SHAPE;
+  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxK || K % 32 != 0) return WUSH_ERR_SHAPE;
   if (wush_status st = check_layout(fmt, K)) return st;
   const int64_t padded = fmt.layout == WUSH_LAYOUT_TILED ? (rows + 255) / 256 * 256 : rows;
   *code_bytes = (size_t)(padded * (K / 2));
@@ -442,7 +449,7 @@ wush_status wush_packed_sizes(int64_t rows, int64_t K, wush_fmt fmt, size_t* cod
 wush_status wush_unpack_tiled(const void* q_tiled, const void* s_tiled, int64_t rows, int64_t K, void* q,
                               void* s, void* stream) {
   if (!q_tiled || !s_tiled || !q || !s) return WUSH_ERR_NULL;
-  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxDim || K % 256 != 0) return WUSH_ERR_SHAPE;
+  if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxK || K % 256 != 0) return WUSH_ERR_SHAPE;
   if (!aligned16(q_tiled) || !aligned16(s_tiled) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
   return from_hip(wush::launch_unpack_tiled(q_tiled, s_tiled, rows, K, q, s, static_cast<hipStream_t>(stream)));
 }

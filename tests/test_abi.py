@@ -217,3 +217,19 @@ def test_int4_validation(L):
     assert lin(A, A, A, A, 4, 8, 64, 0, 0, A + 1, 8, None) == 3
     tap = lambda *a: L.wush_quantize_f32_int4(*a)
     assert tap(A, 4, 64, 0, None, A, None) == 1 and tap(A, 4, 65, 0, A, A, None) == 2
+
+
+def test_size_limits(L):
+    """Row counts up to 2^30, K up to 2^22, M * N of a GEMM up to 2^40: anything larger is a shape error
+    before any launch (kernel index arithmetic is sized for these)."""
+    f = P.default_fmt()
+    big_rows, big_k = (1 << 30) + 1, (1 << 22) + 32
+    assert L.wush_quantize_act(A, big_rows, 64, 64, A, f, A, A, None, None) == 2
+    assert L.wush_quantize_act(A, 4, big_k, big_k, A, f, A, A, None, None) == 2
+    assert L.wush_linear(A, A, A, A, 1 << 21, 1 << 20, 64, f, A, 1 << 20, None) == 2        # M * N = 2^41
+    assert L.wush_linear(A, A, A, A, 4, 8, big_k, f, A, 8, None) == 2
+    assert L.wush_linear_nvfp4(A, A, A, A, A, A, 1 << 21, 1 << 20, 64, 0, 0, A, 1 << 20, None) == 2
+    assert L.wush_linear_int4(A, A, A, A, 1 << 21, 1 << 20, 64, 0, 0, A, 1 << 20, None) == 2
+    assert L.wush_linear_int4(A, A, A, A, 4, 8, big_k + 32, 0, 0, A, 8, None) == 2
+    assert L.wush_build_transforms_workspace(big_k) == 0
+    assert L.wush_prepare_weight_gptq_workspace(big_rows, 64) == 0

@@ -151,3 +151,60 @@ def test_c5_full(P, G):
     T = _transforms_blockwise(L)
     out = _run_layer(P, G, L, T)
     _check_samples(G, L, T, out, np.random.default_rng(5), n_rows=24, n_wrows=32, n_cols=256)
+
+
+def test_offsets_beyond_4_gib(P, G):
+    """Buffers larger than 4 GiB: 2^21 + 100 tokens of 4096 channels (X 17 GB, packed codes 4.3 GB) through the
+    activation path and the GEMM (1100 output channels: 4.6 GB of BF16) in both layouts.  Rows at the start, at
+    the 4 GiB marks of X, of the codes and of Y, and at the very end are compared with the oracle: a 32-bit
+    offset anywhere in the path would send them elsewhere."""
+    import torch
+    M, K, N = (1 << 21) + 100, 4096, 1100
+    g = torch.Generator(device="cuda").manual_seed(11)
+    X = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
+    step = 1 << 18
+    for r0 in range(0, M, step):
+        X[r0:r0 + step].normal_(generator=g)
+    X[:, 7::64] *= 12.0                                   # a few outlier channels
+    T = O.round_to_bf16(O.hadamard_transforms(K // 32))
+    Td = G.bf16_dev(O.bf16_values_to_bits(T))
+    W = (torch.randn((N, K), device="cuda", generator=g) * 0.05).to(torch.bfloat16)
+    y_mark = (1 << 32) // (2 * N)
+    marks = [0, 1, (1 << 19) - 1, 1 << 19, (1 << 19) + 1, y_mark - 1, y_mark, y_mark + 1, (1 << 21) - 1, 1 << 21,
+             (1 << 21) + 1, M - 33, M - 2, M - 1]
+    rows = np.unique(np.array(marks + np.random.default_rng(12).integers(0, M, 16).tolist()))
+    Xs_f64 = O.bf16_bits_to_f64(G.host(X[rows.tolist()].contiguous()))
+    Yt = O.transform_act(Xs_f64, T)
+    cr, sr = O.quantize_mxfp4(Yt)
+    wsp = G.empty_u8(P.wush_prepare_weight_workspace(N, K))
+    ys = []
+    for layout in (0, 1):
+        fmt = P.default_fmt(layout=layout)
+        xcb, xsb = P.wush_packed_sizes(M, K, fmt)
+        assert xcb > (1 << 32)
+        Xq, Xsc = G.empty_u8(xcb), G.empty_u8(xsb)
+        P.wush_quantize_act(X, Td, Xq, Xsc, fmt)
+        wcb, wsb = P.wush_packed_sizes(N, K, fmt)
+        Wq, Ws = G.empty_u8(wcb), G.empty_u8(wsb)
+        P.wush_prepare_weight(W, Td, Wq, Ws, wsp, fmt)
+        Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        P.wush_linear(Xq, Xsc, Wq, Ws, Y, fmt, K=K)
+        if layout:
+            q2, s2 = G.empty_u8(M, K // 2), G.empty_u8(M, K // 32)
+            P.wush_unpack_tiled(Xq, Xsc, M, K, q2, s2)
+            wq2, ws2 = G.empty_u8(N, K // 2), G.empty_u8(N, K // 32)
+            P.wush_unpack_tiled(Wq, Ws, N, K, wq2, ws2)
+            Xq, Xsc, Wq, Ws = q2, s2, wq2, ws2
+        torch.cuda.synchronize()
+        xq = Xq.view(M, K // 2)[rows.tolist()].cpu().numpy()
+        xs = Xsc.view(M, K // 32)[rows.tolist()].cpu().numpy()
+        rate, unexplained = G.code_mismatch_report(Yt, O.unpack_codes(xq), xs, cr, sr)
+        assert rate <= 1e-4 and unexplained == 0, (layout, rate, unexplained)
+        y = O.bf16_bits_to_f64(G.host(Y[rows.tolist()].contiguous()))
+        own = O.dequantize(O.unpack_codes(xq), xs) @ \
+            O.dequantize(O.unpack_codes(Wq.view(N, K // 2).cpu().numpy()), Ws.view(N, K // 32).cpu().numpy()).T
+        assert np.isfinite(y).all() and O.rel_fro(y, own) <= 2e-3, layout
+        assert not bool(Y[-4096:].isnan().any()) and not bool(Y[:4096].isnan().any())
+        ys.append(y)
+        del Xq, Xsc, Y
+    assert O.rel_fro(ys[0], ys[1]) <= 2e-3   # two kernels, two accumulation orders

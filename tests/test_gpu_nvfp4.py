@@ -523,3 +523,52 @@ def test_argument_validation(P, G):
         P.wush_quantize_f32_nvfp4(torch.zeros((4, 96), device="cuda"), one, G.empty_u8(32 * 48), G.empty_u8(32 * 6),
                                   layout=1)
     assert e.value.code == 2
+
+
+def test_offsets_beyond_4_gib(P, G):
+    """Buffers larger than 4 GiB (2^21 + 100 tokens of 4096 channels: X 17 GB, codes 4.3 GB; 1100 output
+    channels: 4.6 GB of BF16): the quantizer and the GEMM give, for row ranges at the start, around the
+    4 GiB marks of X, of the codes and of Y, and at the end, exactly the bytes the same rows give as a
+    small batch (parity of small batches with the oracle is tested above).  A 32-bit offset anywhere in
+    the path would send those rows elsewhere."""
+    import torch
+    M, K, N = (1 << 21) + 100, 4096, 1100
+    g = torch.Generator(device="cuda").manual_seed(21)
+    X = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
+    for r0 in range(0, M, 1 << 18):
+        X[r0:r0 + (1 << 18)].normal_(generator=g)
+    T = G.bf16_dev(I.make_transforms_random(K // 16, 6, block=16))
+    W = (torch.randn((N, K), device="cuda", generator=g) * 0.05).to(torch.bfloat16)
+    tsx, tsw = _f32_dev(0.01), torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = G.empty_u8(P.wush_prepare_weight_nvfp4_workspace(K))
+    y_mark = (1 << 32) // (2 * N)
+    ranges = [(0, 64), ((1 << 19) - 32, (1 << 19) + 32), (y_mark - 32, y_mark + 32), ((1 << 21) - 32, (1 << 21) + 32),
+              (M - 70, M)]
+    for layout in (0, 1):
+        (xcb, xsb), (wcb, wsb) = P.wush_packed_sizes_nvfp4(M, K, layout), P.wush_packed_sizes_nvfp4(N, K, layout)
+        assert xcb > (1 << 32)
+        Xq, Xs, Wq, Ws = G.empty_u8(xcb), G.empty_u8(xsb), G.empty_u8(wcb), G.empty_u8(wsb)
+        P.wush_prepare_weight_nvfp4(W, T, Wq, Ws, tsw, ws, layout=layout)
+        P.wush_quantize_act_nvfp4(X, T, tsx, Xq, Xs, layout=layout)
+        Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        P.wush_linear_nvfp4(Xq, Xs, tsx, Wq, Ws, tsw, Y, layout=layout, K=K)
+        if layout:
+            qu, su = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
+            P.wush_unpack_tiled_nvfp4(Xq, Xs, M, K, qu, su)
+        else:
+            qu, su = Xq.view(M, K // 2), Xs.view(M, K // 16)
+        torch.cuda.synchronize()
+        assert not bool(Y[-4096:].isnan().any()) and not bool(Y[:4096].isnan().any())
+        for lo, hi in ranges:
+            m = hi - lo
+            q, s_ = G.empty_u8(m, K // 2), G.empty_u8(m, K // 16)
+            P.wush_quantize_act_nvfp4(X[lo:hi], T, tsx, q, s_)
+            cb, sb = P.wush_packed_sizes_nvfp4(m, K, layout)
+            ql, sl = G.empty_u8(cb), G.empty_u8(sb)
+            P.wush_quantize_act_nvfp4(X[lo:hi], T, tsx, ql, sl, layout=layout)
+            y = torch.full((m, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+            P.wush_linear_nvfp4(ql, sl, tsx, Wq, Ws, tsw, y, layout=layout, K=K)
+            torch.cuda.synchronize()
+            assert torch.equal(q, qu[lo:hi]) and torch.equal(s_, su[lo:hi]), (layout, lo, hi)
+            assert torch.equal(y, Y[lo:hi]), (layout, lo, hi)
+        del Xq, Xs, Y, qu, su
