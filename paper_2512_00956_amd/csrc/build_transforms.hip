@@ -123,9 +123,7 @@ __global__ __launch_bounds__(64) void wush_block_kernel(const double* __restrict
   // reduce the partial moments in a fixed order and normalize
   auto moment = [&](int half, int r, int c) {
     const double* p = partial + ((int64_t)half * S * C + b) * 1024;
-    double acc = 0.0;
-    for (int s = 0; s < S; ++s) acc += p[(int64_t)s * C * 1024 + r * 32 + c];
-    return acc * (1.0 / (double)(half ? Mc : N));
+    return ordered_sum(p + r * 32 + c, (int64_t)C * 1024, S) * (1.0 / (double)(half ? Mc : N));
   };
   wush_block_wave<32>(moment, lambda, T_out + (int64_t)b * 1024, T_f64 ? T_f64 + (int64_t)b * 1024 : nullptr, nullptr,
                       status);
@@ -139,9 +137,7 @@ __global__ __launch_bounds__(64) void wush_block16_kernel(const double* __restri
   const int b = blockIdx.x, b32 = b >> 1, off = 16 * (b & 1);
   auto moment = [&](int half, int r, int c) {
     const double* p = partial + ((int64_t)half * S * C + b32) * 1024;
-    double acc = 0.0;
-    for (int s = 0; s < S; ++s) acc += p[(int64_t)s * C * 1024 + (off + r) * 32 + off + c];
-    return acc * (1.0 / (double)(half ? Mc : N));
+    return ordered_sum(p + (off + r) * 32 + off + c, (int64_t)C * 1024, S) * (1.0 / (double)(half ? Mc : N));
   };
   wush_block_wave<16>(moment, lambda, T_out + (int64_t)b * 256, T_f64 ? T_f64 + (int64_t)b * 256 : nullptr, nullptr,
                       status);

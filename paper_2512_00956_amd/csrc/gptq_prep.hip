@@ -305,9 +305,7 @@ __global__ __launch_bounds__(64) void gptq_wush_kernel(const double* __restrict_
                                                        int* __restrict__ status) {
   auto moment = [&](int half, int r, int c) {
     if (half) return MX_i[r * 32 + c];
-    double acc = 0.0;
-    for (int s = 0; s < S; ++s) acc += partial[(int64_t)s * 1024 + r * 32 + c];
-    return acc / (double)N;
+    return ordered_sum(partial + r * 32 + c, 1024, S) / (double)N;
   };
   wush_block_wave<32>(moment, lambda, T_bits_i, nullptr, Tb, status);
 }

@@ -5,6 +5,49 @@
 
 namespace wush {
 
+// Sum of the S values p[0], p[stride], ..., in ascending order (a fixed summation order), with the loads
+// of eight terms in flight at a time: one at a time, each waits out a full memory latency.
+__device__ __forceinline__ double ordered_sum(const double* __restrict__ p, int64_t stride, int S) {
+  double acc = 0.0;
+  for (int s0 = 0; s0 < S; s0 += 8) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = s0 + u < S ? p[(int64_t)(s0 + u) * stride] : 0.0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  return acc;
+}
+
+// 1 / sqrt(x) for a positive normal x: the hardware estimate and two Newton steps (relative error of a
+// few 2^-53; not correctly rounded, which the Jacobi rotations below do not need).
+__device__ __forceinline__ double rsqrt_newton(double x) {
+  double y = __builtin_amdgcn_rsq(x);
+  const double hx = 0.5 * x;
+  y = fma(y, fma(-hx * y, y, 0.5), y);
+  y = fma(y, fma(-hx * y, y, 0.5), y);
+  return y;
+}
+
+// The value of x in another lane of the same row of 16, chosen by a DPP control word (no LDS round trip).
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x) {
+  const long long b = __double_as_longlong(x);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)b, CTRL, 0xF, 0xF, true);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, true);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+// Sum of x over the LANES adjacent lanes (4 or 8, aligned) that share a column pair, the same in each of
+// them: partner lane ^ 1, then lane ^ 2 (quad permutes), then the mirrored lane of the other quad.
+template <int LANES>
+__device__ __forceinline__ double group_sum(double x) {
+  static_assert(LANES == 4 || LANES == 8, "lanes per column pair");
+  x += dpp_f64<0xB1>(x);    // quad_perm [1, 0, 3, 2]
+  x += dpp_f64<0x4E>(x);    // quad_perm [2, 3, 0, 1]
+  if (LANES == 8) x += dpp_f64<0x141>(x);   // row_half_mirror: lane i <-> 7 - i
+  return x;
+}
+
 // Alg. 1 for one D x D block (D = 32, or 16 for the NVFP4 variant), by ONE wavefront (64 lanes, all active):
 //   W' W'^T = M_W + lambda d^-1 tr(M_W) I,  X' X'^T likewise  (Cholesky, side by side)
 //   U S V^T = W'^T X'  (one-sided Jacobi on the columns; V never needed)
@@ -36,23 +79,43 @@ __device__ __forceinline__ void wush_block_wave(MomentFn moment, double lambda, 
   const int half = (lane / D) & 1, r = lane % D;
   double (*L)[D + 1] = half ? LX : LW;
   {
-    double tr = 0.0;
-    for (int c = 0; c < D; ++c) L[r][c] = moment(half, r, c);
+    // consecutive lanes fetch consecutive entries of a row (the moments come from global memory),
+    // four entries per lane at a time so that their loads overlap
+    constexpr int kPerLane = 2 * D * D / 64;
+#pragma unroll 1
+    for (int i0 = 0; i0 < kPerLane; i0 += 4) {
+      double v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = lane + 64 * (i0 + u);
+        v[u] = moment(e / (D * D), (e % (D * D)) / D, e % D);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = lane + 64 * (i0 + u);
+        (e / (D * D) ? LX : LW)[(e % (D * D)) / D][e % D] = v[u];
+      }
+    }
     __syncthreads();
+    double tr = 0.0;
     for (int c = 0; c < D; ++c) tr += L[c][c];
-    L[r][r] += lambda * tr / (double)D;
+    const double damped = L[r][r] + lambda * tr / (double)D;
+    __syncthreads();
+    L[r][r] = damped;
     __syncthreads();
   }
   // ---- Cholesky (lower), both matrices at once: lane r owns row r of its matrix
   bool bad = false;
   for (int j = 0; j < D; ++j) {
     double d = L[j][j];
+#pragma unroll 4
     for (int k = 0; k < j; ++k) d -= L[j][k] * L[j][k];
     if (!(d > 0.0)) { bad = true; d = 1.0; }
     const double dj = sqrt(d);
     double v = 0.0;
     if (r > j) {
       v = L[r][j];
+#pragma unroll 4
       for (int k = 0; k < j; ++k) v -= L[r][k] * L[j][k];
       v /= dj;
     }
@@ -69,6 +132,7 @@ __device__ __forceinline__ void wush_block_wave(MomentFn moment, double lambda, 
   for (int o = lane; o < D * D; o += 64) {
     const int i = o / D, j = o % D;
     double acc = 0.0;
+#pragma unroll 4
     for (int k = max(i, j); k < D; ++k) acc = fma(LW[k][i], LX[k][j], acc);
     A[i][j] = acc;
   }
@@ -93,14 +157,22 @@ __device__ __forceinline__ void wush_block_wave(MomentFn moment, double lambda, 
         be = fma(aq[i], aq[i], be);
         ga = fma(ap[i], aq[i], ga);
       }
-#pragma unroll
-      for (int m = 1; m < kLpp; m <<= 1) {
-        al += __shfl_xor(al, m, 64); be += __shfl_xor(be, m, 64); ga += __shfl_xor(ga, m, 64);
-      }
-      if (fabs(ga) > 1e-15 * sqrt(al * be) && ga != 0.0) {
-        const double zeta = (be - al) / (2.0 * ga);
-        const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-        const double c = 1.0 / sqrt(1.0 + t * t), s = c * t;
+      al = group_sum<kLpp>(al);
+      be = group_sum<kLpp>(be);
+      ga = group_sum<kLpp>(ga);
+      if (ga * ga > 1e-30 * (al * be)) {             // |ga| > 1e-15 sqrt(al be)
+        // The rotation by the angle of smaller magnitude that makes the two columns orthogonal:
+        // tan(2 theta) = 2 ga / (be - al), |theta| <= pi / 4.  From cos(2 theta) = |be - al| / h and
+        // sin(2 theta) = |2 ga| / h, h = hypot(be - al, 2 ga):  c^2 = (1 + cos 2 theta) / 2,
+        // |s| = sin 2 theta / (2 c) -- two reciprocal square roots, no division, no cancellation.
+        const double dd = be - al, g2 = 2.0 * ga;
+        const double ih = rsqrt_newton(fma(dd, dd, g2 * g2));
+        const double c2 = fma(0.5 * fabs(dd), ih, 0.5);
+        const double ic = rsqrt_newton(c2);
+        const double c = c2 * ic;
+        const bool pos = dd == 0.0 || (dd > 0.0) == (g2 > 0.0);
+        const double sa = 0.5 * fabs(g2) * ih * ic;
+        const double s = pos ? sa : -sa;
 #pragma unroll
         for (int i = 0; i < kRpl; ++i) {
           A[kRpl * sub + i][p] = c * ap[i] - s * aq[i];
