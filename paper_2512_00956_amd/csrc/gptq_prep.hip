@@ -221,40 +221,58 @@ __global__ __launch_bounds__(64) void gptq_triinv_diag_kernel(const double* __re
 
 // block row i of V: V_ij = -(sum_{k=i}^{j-1} V_ik U_kj) V_jj for j = i+1 .. C-1.
 // The workgroup reads back what it wrote for smaller j; the workgroup barrier orders that.
+// The 32 x 32 block products run on the FP64 MFMA (16 x 16 x 4), one 16 x 16 output tile per wave:
+// with scalar FMAs the kernel was bound by its LDS reads (five per four FMAs), and its longest chain
+// (block row 0: C^2 / 2 products one after the other) is the whole kernel's duration.
+typedef double v4d_t __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void gptq_triinv_rows_kernel(const double* __restrict__ H, int K, int C,
                                                                double* __restrict__ V) {
   __shared__ double va[32][33], ub[32][33], acc_s[32][33];
   const int i = blockIdx.x;
-  const int r = threadIdx.x >> 3, c0 = (threadIdx.x & 7) * 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tr = 16 * (wave >> 1), tc = 16 * (wave & 1);      // this wave's output tile
+  const int l16 = lane & 15, l4 = lane >> 4;
+  // A[row l16][k l4] and B[k l4][column l16] of the MFMA; accumulator element v is (row l4 + 4 v, column l16)
+  auto product = [&](const double (*a)[33], const double (*b)[33], v4d_t acc) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[tr + l16][4 * kk + l4], b[4 * kk + l4][tc + l16], acc, 0, 0, 0);
+    return acc;
+  };
+  // the blocks of step k + 1 travel from memory into registers while step k is multiplied
+  double rv[4], ru[4];
+  auto fetch = [&](int k, int j) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int o = threadIdx.x + 256 * u;
+      rv[u] = V[(int64_t)(32 * i + (o >> 5)) * K + 32 * k + (o & 31)];
+      ru[u] = H[(int64_t)(32 * k + (o >> 5)) * K + 32 * j + (o & 31)];
+    }
+  };
   for (int j = i + 1; j < C; ++j) {
-    double acc[4] = {0, 0, 0, 0};
+    v4d_t acc = {0, 0, 0, 0};
+    fetch(i, j);
     for (int k = i; k < j; ++k) {
       __syncthreads();
-      for (int o = threadIdx.x; o < 1024; o += 256) {
-        va[o >> 5][o & 31] = V[(int64_t)(32 * i + (o >> 5)) * K + 32 * k + (o & 31)];
-        ub[o >> 5][o & 31] = H[(int64_t)(32 * k + (o >> 5)) * K + 32 * j + (o & 31)];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int o = threadIdx.x + 256 * u;
+        va[o >> 5][o & 31] = rv[u];
+        ub[o >> 5][o & 31] = ru[u];
       }
       __syncthreads();
-      for (int m = 0; m < 32; ++m) {
-        const double a = va[r][m];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) acc[t] = fma(a, ub[m][c0 + t], acc[t]);
-      }
+      if (k + 1 < j) fetch(k + 1, j);
+      acc = product(va, ub, acc);
     }
     __syncthreads();
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc_s[r][c0 + t] = acc[t];
+    for (int v = 0; v < 4; ++v) acc_s[tr + l4 + 4 * v][tc + l16] = acc[v];
     for (int o = threadIdx.x; o < 1024; o += 256)
       ub[o >> 5][o & 31] = V[(int64_t)(32 * j + (o >> 5)) * K + 32 * j + (o & 31)];   // V_jj
     __syncthreads();
-    double out[4] = {0, 0, 0, 0};
-    for (int m = 0; m < 32; ++m) {
-      const double a = acc_s[r][m];
+    const v4d_t out = product(acc_s, ub, (v4d_t){0, 0, 0, 0});
 #pragma unroll
-      for (int t = 0; t < 4; ++t) out[t] = fma(a, ub[m][c0 + t], out[t]);
-    }
-#pragma unroll
-    for (int t = 0; t < 4; ++t) V[(int64_t)(32 * i + r) * K + 32 * j + c0 + t] = -out[t];
+    for (int v = 0; v < 4; ++v) V[(int64_t)(32 * i + tr + l4 + 4 * v) * K + 32 * j + tc + l16] = -out[v];
     __threadfence_block();
   }
 }
