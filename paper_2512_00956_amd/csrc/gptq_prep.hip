@@ -115,12 +115,14 @@ __device__ __forceinline__ bool reverse_cholesky32(double (*S)[33], int lane) {
   const int r = lane & 31;
   for (int j = 31; j >= 0; --j) {
     double d = S[j][j];
+#pragma unroll 4
     for (int l = j + 1; l < 32; ++l) d -= S[j][l] * S[j][l];
     if (!(d > 0.0)) { bad = true; d = 1.0; }
     const double dj = sqrt(d);
     double v = 0.0;
     if (r < j) {
       v = S[r][j];
+#pragma unroll 4
       for (int l = j + 1; l < 32; ++l) v -= S[r][l] * S[j][l];
       v /= dj;
     }
@@ -367,30 +369,37 @@ __global__ __launch_bounds__(64) void gptq_block_mats_kernel(const double* __res
     const double prow = a[p][lane] * inv_piv;
     a[p][lane] = prow;
     __syncthreads();
-    for (int r = 0; r < 32; ++r) {
-      if (r == p) continue;
-      const double f = a[r][p];
-      __syncthreads();
-      a[r][lane] -= f * prow;
-    }
+    // column p (the factors) is read whole before any lane touches it: lane p updates it below
+    double f[32];
+#pragma unroll
+    for (int r = 0; r < 32; ++r) f[r] = a[r][p];
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 32; ++r)
+      if (r != p) a[r][lane] -= f[r] * prow;
     __syncthreads();
   }
   if (singular && lane == 0) atomicExch(status, 1);
   for (int r = 0; r < 32; ++r)
     if (lane >= 32) Tinv[r * 32 + (lane - 32)] = singular ? 0.0 : a[r][lane];
   // ---- B = T_i U_ii (U_ii upper triangular), Hbar = B B^T
-  for (int o = lane; o < 1024; o += 64) Rm[o >> 5][o & 31] = H[(int64_t)(32 * i + (o >> 5)) * K + 32 * i + (o & 31)];
+  for (int o = lane; o < 1024; o += 64) {
+    Rm[o >> 5][o & 31] = H[(int64_t)(32 * i + (o >> 5)) * K + 32 * i + (o & 31)];
+    Hb[o >> 5][o & 31] = Tb[o];                       // T_i, until Hbar takes its place
+  }
   __syncthreads();
   for (int o = lane; o < 1024; o += 64) {
     const int r = o >> 5, c = o & 31;
     double acc = 0.0;
-    for (int m = 0; m <= c; ++m) acc = fma(Tb[r * 32 + m], Rm[m][c], acc);
+#pragma unroll 4
+    for (int m = 0; m <= c; ++m) acc = fma(Hb[r][m], Rm[m][c], acc);
     B[r][c] = acc;
   }
   __syncthreads();
   for (int o = lane; o < 1024; o += 64) {
     const int r = o >> 5, c = o & 31;
     double acc = 0.0;
+#pragma unroll 8
     for (int m = 0; m < 32; ++m) acc = fma(B[r][m], B[c][m], acc);
     Hb[r][c] = acc;
   }
@@ -500,25 +509,35 @@ __global__ __launch_bounds__(256) void gptq_propagate_kernel(double* __restrict_
     ps[m][c] = (c0 + c < K) ? P[(int64_t)m * K + c0 + c] : 0.0;
   }
   __syncthreads();
-  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
-  double acc[4][4] = {};
-#pragma unroll 2
-  for (int m = 0; m < 32; ++m) {
-    double ev[4], pv[4];
+  // rank-32 update on the FP64 MFMA (16 x 16 x 4): wave w owns rows 16 w .. 16 w + 15 of the tile and its
+  // four 16-column blocks; A[row l16][k l4] is shared by the four, B[k l4][column l16] differs
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l16 = lane & 15, l4 = lane >> 4;
+  // accumulator element v of column block tc: row l4 + 4 v, column l16.  The weights it updates are
+  // requested before the products, so that the kernel runs at the rate of its memory traffic.
+  double w[4][4];
 #pragma unroll
-    for (int a = 0; a < 4; ++a) { ev[a] = es[4 * ty + a][m]; pv[a] = ps[m][4 * tx + a]; }
+  for (int tc = 0; tc < 4; ++tc)
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) acc[a][b] = fma(ev[a], pv[b], acc[a][b]);
-  }
-#pragma unroll
-  for (int a = 0; a < 4; ++a)
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int n = n0 + 4 * ty + a, c = c0 + 4 * tx + b;
-      if (n < N && c < K) Wf[(int64_t)n * K + c] += acc[a][b];
+    for (int v = 0; v < 4; ++v) {
+      const int n = n0 + 16 * wave + l4 + 4 * v, c = c0 + 16 * tc + l16;
+      w[tc][v] = (n < N && c < K) ? Wf[(int64_t)n * K + c] : 0.0;
     }
+  double ev[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) ev[kk] = es[16 * wave + l16][4 * kk + l4];
+#pragma unroll
+  for (int tc = 0; tc < 4; ++tc) {
+    v4d_t acc = {0, 0, 0, 0};
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(ev[kk], ps[4 * kk + l4][16 * tc + l16], acc, 0, 0, 0);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int n = n0 + 16 * wave + l4 + 4 * v, c = c0 + 16 * tc + l16;
+      if (n < N && c < K) Wf[(int64_t)n * K + c] = w[tc][v] + acc[v];
+    }
+  }
 }
 
 __global__ void gptq_reset_status_kernel(int* status) {
