@@ -11,6 +11,8 @@
 #include <stdlib.h>
 
 #include "wush_device.hpp"
+#include <math.h>
+
 #include "wush_kernels.hpp"
 
 namespace wush {
@@ -257,19 +259,29 @@ hipError_t launch_mxfp4_gemm(const void* Xq, const void* Xs, const void* Wq, con
                              int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y, int64_t ldy,
                              hipStream_t stream) {
   if (tiled) {
-    // Small batches stream the weights once instead of padding M to a 128- or 256-row tile.
-    // Up to 64 tokens always; for 65..128 the streaming kernel runs at about 3.1 TB/s of packed
-    // weights (it re-reads four token blocks of activations per weight tile), so a layer big
-    // enough to fill the CUs with 128 x 384 tiles in one round is faster there
-    // (8192 x 57344: 57 against 79 us; 4096 x 6144: 17.6 against 7.2 us).
-    bool skinny = M <= 64;
+    // Small batches: the streaming kernel (one workgroup per 32 output channels, the whole K) or
+    // the tiled kernel with one row of 128-row tiles.  Up to 32 tokens the streaming kernel always
+    // wins or ties.  Beyond, whichever the timing models below put first; they are fits to
+    // measurements on ten layer shapes (4096 x 4096 .. 8192 x 57344 and 28672 x 8192), in us:
+    //   streaming, 33..64 tokens : max(0.8 K/1024 + 2.5, MiB of weights / 5.5 + 3)
+    //   streaming, 65..128 tokens: rounds of (N/32 workgroups over the CUs) x (1.05 K/1024 + 2.5)
+    //   tiled                    : max(4.3 + 0.3 x K/256 x rounds of (N/128 tiles over the CUs),
+    //                                  MiB of weights / 6.4 + 4)
+    // (8192 x 57344, 64 tokens: 45.6 against 38.0; 128 tokens: 78.5 against 39.3;
+    //  4096 x 24576, 128 tokens: 21.8 against 11.3; 28672 x 8192, 128 tokens: 31.1 against 41.4).
+    bool skinny = M <= 32;
     if (!skinny && M <= 128) {
+      const double cus = (double)device_cu_count();
       const double weight_mib = (double)N * (double)K * (17.0 / 32.0) / 1048576.0;
-      const double skinny_us = weight_mib / 3.1 + 4.0;
-      const double rounds = (double)(((N + 383) / 384 + 255) / 256);
-      const double tiled_us = rounds * (double)(K / 256) * 1.45 + 8.0;
+      const double kk = (double)K / 1024.0;
+      const double skinny_us = M <= 64 ? fmax(0.8 * kk + 2.5, weight_mib / 5.5 + 3.0)
+                                       : ceil((double)((N + 31) / 32) / cus) * (1.05 * kk + 2.5);
+      const double tile_rounds = ceil((double)((N + 127) / 128) / cus);
+      const double tiled_us = fmax(4.3 + 0.3 * (double)(K / 256) * tile_rounds, weight_mib / 6.4 + 4.0);
       skinny = skinny_us < tiled_us;
     }
+    if (M <= 128)
+      if (const char* e = getenv("WUSH_GEMM_SKINNY")) skinny = e[0] == '1';   // debug knob: force either kernel up to 128 tokens
     if (skinny) return launch_mxfp4_gemm_skinny(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
     return launch_mxfp4_gemm_frag(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
   }
