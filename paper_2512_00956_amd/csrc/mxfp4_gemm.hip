@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
   // an XCD runs concurrently share A and B panels.
   int id = blockIdx.x;
   const int total = tiles_m * tiles_n;
-  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  id = xcd_contiguous_id(id, total);
   constexpr int kBand = 8;
   const int width = kBand * tiles_n;
   const int band = id / width;

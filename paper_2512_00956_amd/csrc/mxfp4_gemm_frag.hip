@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   // runs concurrently share X and W panels in its L2.
   int id = blockIdx.x;
   const int total = tiles_m * tiles_n;
-  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  id = xcd_contiguous_id(id, total);
   constexpr int kBand = 8;
   const int width = kBand * tiles_n;
   const int band = id / width;
@@ -479,11 +479,18 @@ hipError_t launch_shape(const void* Xq, const void* Xs, const void* Wq, const vo
   return hipGetLastError();
 }
 
-// Rounds of the chip a tile shape needs, weighted by the MFMAs one of its K iterations
-// issues per wave (64 for 256 x 256, 48 for 128 x 384).
-int64_t shape_cost(int64_t M, int64_t N, int tm, int tn, int mfma_per_iter, int cus) {
+// Estimated duration of the GEMM with tiles of tm x tn, in us: rounds of the CUs times the time one
+// tile takes, t_iter per K iteration of 256 plus a fixed part (prologue, epilogue, dispatch).  A partly
+// filled last round costs a whole one (workgroups are dispatched as CUs fall free).  The pairs
+// (t_iter, fixed) are fits to launches of 8192 tokens on 4096 -> 14336 and 8192 -> 28672 with each
+// shape forced: 256 x 256: (1.51, 7.4), 128 x 384: (1.175, 5.1), 128 x 256: (0.8125, 4.1),
+// 128 x 128: (0.5125, 0.6; several of its workgroups share a CU and cover each other's fixed part).
+// Against the earlier weight "rounds x MFMAs per iteration" this accounts for what small tiles lose
+// to their operand traffic (8192 -> 28672, 5120 tokens: 490 us with 256 x 256 tiles, 598 us with
+// 128 x 128, which the MFMA count alone put first).
+double shape_cost_us(int64_t M, int64_t N, int64_t K, int tm, int tn, double t_iter, double fixed, int cus) {
   const int64_t tiles = ((M + tm - 1) / tm) * ((N + tn - 1) / tn);
-  return (tiles + cus - 1) / cus * mfma_per_iter;
+  return (double)((tiles + cus - 1) / cus) * (t_iter * (double)(K / 256) + fixed);
 }
 
 }  // namespace
@@ -493,11 +500,10 @@ hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq
                                   hipStream_t stream) {
   const int cus = device_cu_count();
   // Four instantiations: 256 x 256 (8 x 2 MFMA tiles per wave), 128 x 384 (4 x 3), 128 x 256 (4 x 2)
-  // and 128 x 128 (4 x 1).
-  // The cheapest by "rounds of the CUs x MFMAs per K iteration" wins, ties go to the larger tile
+  // and 128 x 128 (4 x 1).  The cheapest by the estimate above wins, ties go to the larger tile
   // (less operand traffic).  WUSH_GEMM_TILE=0..3 forces one of them (debug knob).
-  const int64_t cost[4] = {shape_cost(M, N, 256, 256, 64, cus), shape_cost(M, N, 128, 384, 48, cus),
-                           shape_cost(M, N, 128, 256, 32, cus), shape_cost(M, N, 128, 128, 16, cus)};
+  const double cost[4] = {shape_cost_us(M, N, K, 256, 256, 1.51, 7.4, cus), shape_cost_us(M, N, K, 128, 384, 1.175, 5.1, cus),
+                          shape_cost_us(M, N, K, 128, 256, 0.8125, 4.1, cus), shape_cost_us(M, N, K, 128, 128, 0.5125, 0.6, cus)};
   int shape = 0;
   for (int c = 1; c < 4; ++c)
     if (cost[c] < cost[shape]) shape = c;

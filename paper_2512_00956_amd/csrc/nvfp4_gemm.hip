@@ -273,7 +273,7 @@ __global__ __launch_bounds__(256) void w4_f16_gemm_kernel(
   // run of tiles, M fastest, so that they share W tiles in that XCD's L2.
   const int ntiles = tiles_m * tiles_n;
   int id = blockIdx.x;
-  if ((ntiles & 7) == 0) id = (id & 7) * (ntiles >> 3) + (id >> 3);
+  id = xcd_contiguous_id(id, ntiles);
   const int tm = id % tiles_m, tn = id / tiles_m;
   const int m0 = tm * kBM, n0 = tn * kBN;
 
@@ -507,7 +507,7 @@ __global__ __launch_bounds__(256) void w4_wreg_gemm_kernel(
 
   const int ntiles = tiles_m * tiles_n;
   int id = blockIdx.x;
-  if ((ntiles & 7) == 0) id = (id & 7) * (ntiles >> 3) + (id >> 3);
+  id = xcd_contiguous_id(id, ntiles);
   const int tm = id % tiles_m, tn = id / tiles_m;
   const int m0 = tm * kBM, n0 = tn * kBN;
   const int KT = K / kBK;   // even

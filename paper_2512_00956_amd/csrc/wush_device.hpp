@@ -105,6 +105,14 @@ __host__ __device__ __forceinline__ int64_t tiled_scale_offset(int row, int g, i
   return (((int64_t)rb * KT + kt) * 64 + kh * 32 + r) * 4 + kk;
 }
 
+// Workgroup id -> tile id such that every XCD (the hardware deals workgroup ids round-robin over the
+// eight XCDs, each with an L2 of its own) works on one contiguous range of tile ids: XCD x takes
+// total / 8 ids, one more if x < total % 8.
+__device__ __forceinline__ int xcd_contiguous_id(int id, int total) {
+  const int xcd = id & 7, pos = id >> 3, base = total >> 3, rem = total & 7;
+  return xcd * base + min(xcd, rem) + pos;
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
   return __uint_as_float((uint32_t)b << 16);
 }
