@@ -428,6 +428,47 @@ def test_linear_both_tile_shapes(P, G, M, N, K, shape):
     assert O.rel_fro(y, ref) <= 1e-5
 
 
+@pytest.mark.parametrize("kernel", ["0", "1"], ids=["tiled", "streaming"])
+@pytest.mark.parametrize("M", [33, 64, 65, 100, 128])
+def test_linear_small_batches_on_either_kernel(P, G, M, kernel):
+    """For 33 to 128 tokens wush_linear chooses between the weight-streaming kernel and the tiled one from a
+    timing model; each is forced in turn (WUSH_GEMM_SKINNY) on a ragged shape and checked against the oracle."""
+    import os
+    import torch
+    N, K = 1000, 1024
+    rng = np.random.default_rng(5 * M + 11)
+    xc = rng.integers(0, 16, (M, K), dtype=np.uint8)
+    wc = rng.integers(0, 16, (N, K), dtype=np.uint8)
+    xs = rng.integers(118, 134, (M, K // 32), dtype=np.uint8)
+    ws = rng.integers(112, 128, (N, K // 32), dtype=np.uint8)
+    fmt = P.default_fmt(layout=1)
+    bufs = []
+    for codes, scales, rows in ((xc, xs, M), (wc, ws, N)):     # canonical -> tiled through the quantizer tap's layout
+        cb, sb = P.wush_packed_sizes(rows, K, fmt)
+        qt, st = torch.full((cb,), 0xEE, dtype=torch.uint8, device="cuda"), torch.full((sb,), 0xEE, dtype=torch.uint8, device="cuda")
+        KT = K // 256
+        r = np.arange(rows)[:, None]
+        g = np.arange(K // 32)[None, :]
+        rb, rr, kt, kh, kk = r // 32, r % 32, g // 8, (g % 8) // 4, g % 4
+        off = ((((rb * KT + kt) * 4 + kk) * 64) + kh * 32 + rr) * 16
+        q = np.full(cb, 0xEE, dtype=np.uint8)
+        sc = np.full(sb, 0xEE, dtype=np.uint8)
+        q[(off[..., None] + np.arange(16)).reshape(-1)] = O.pack_codes(codes).reshape(rows, K // 32, 16).reshape(-1)
+        sc[(((rb * KT + kt) * 64 + kh * 32 + rr) * 4 + kk).reshape(-1)] = scales.reshape(-1)
+        bufs += [G.u8_dev(q), G.u8_dev(sc)]
+    Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    os.environ["WUSH_GEMM_SKINNY"] = kernel
+    try:
+        P.wush_linear(*bufs, Y, P.default_fmt(out_dtype=1, layout=1), K=K)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["WUSH_GEMM_SKINNY"]
+    ref = O.dequantize(xc, xs) @ O.dequantize(wc, ws).T
+    y = G.host(Y).astype(np.float64)
+    assert np.isfinite(y).all()
+    assert O.rel_fro(y, ref) <= 1e-5
+
+
 def test_mfma_probe_reports_the_instruction_rate(P, G):
     """The measurement aid: one block-scaled 32x32x64 FP4 MFMA issues every 32 shader cycles (8 passes),
     whatever the operand bits; only the clock depends on them."""
