@@ -19,16 +19,17 @@ Readings of what the paper leaves open (listed in the design notes as well):
     what Table 1 shows: with the identity transform INT4 loses an order of
     magnitude more than MXFP4 (outlier channels are clipped), behind a Hadamard
     or WUSH transform it loses less -- a pattern an AbsMax-based step would not give.
-  * elements: q = clip(round-half-even(v / scale), -8, 7); a scale below BF16's
-    normal range (an all-zero group) is stored as 0 and gives q = 0.
-  * arithmetic: every step is one IEEE operation in ONE working precision `prec`
-    (FP32 for activations, the precision of the kernel's accumulators; FP64 for
-    the offline weight path), in this order:
-        t_i = v_i * v_i,   s_lo = t_0 + ... + t_15,  s_hi = t_16 + ... + t_31
-        (each left to right),  ss = s_lo + s_hi,   sigma = sqrt(ss / 32),
-        scale = BF16(STEP * sigma)  (STEP rounded to `prec`; round to nearest even),
-        rcp = 1 / scale,            q = clip(rint(v * rcp), -8, 7).
-    The two half sums are how the GPU holds a group (16 channels per lane).
+  * elements: q = clip(round-half-even(v / scale), -8, 7).
+  * edge cases (each its own reading): a scale whose BF16 rounding falls below
+    BF16's normal range (an all-zero group, or one of FP32 denormals) is stored
+    as 0 -- sub-normal BF16 numbers are flushed by the FP16/BF16 conversion
+    hardware of every current GPU, so a stored sub-normal scale could not be
+    used -- and a group whose scale is 0 has q = 0 everywhere (0 / 0 has no value).
+  * arithmetic: FP64 throughout, the formulas as written: sigma =
+    sqrt(sum(v^2) / 32) with numpy's sum, scale = BF16(STEP * sigma) (one
+    rounding to nearest even from the FP64 product), a true division v / scale.
+    The GPU decides in FP32 (activations) with a reciprocal; a model of those
+    steps lives with the tests (tests/kernel_models.py), not here.
 
 Conventions: as in wush_oracle.py (row-major, channels last, T[b][j][k]); codes
 are int8 values -8 .. 7; packed: two's-complement nibbles, even k in the low
@@ -83,28 +84,18 @@ def round_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return O.bf16_values_to_bits(v)
 
 
-def quantize_int4(Y: np.ndarray, prec=np.float32):
-    """INT4 quantizer on values Y [..., K].  Returns (q int8 [..., K] in -8..7,
+def quantize_int4(Y: np.ndarray):
+    """INT4 quantizer on values Y [..., K], FP64.  Returns (q int8 [..., K] in -8..7,
     scale bits uint16 [..., K/32])."""
-    Y = np.asarray(Y, dtype=prec)
+    Y = np.asarray(Y, dtype=np.float64)
     *lead, K = Y.shape
     Gr = Y.reshape(-1, K // G, G)
-    with np.errstate(over="ignore"):                           # squares beyond the range of `prec` give an infinite scale
-        t = (Gr * Gr).astype(prec)
-        s_lo = np.zeros(t.shape[:2], dtype=prec)
-        s_hi = np.zeros(t.shape[:2], dtype=prec)
-        for i in range(16):                                    # left to right, one rounding per addition
-            s_lo = (s_lo + t[..., i]).astype(prec)
-            s_hi = (s_hi + t[..., 16 + i]).astype(prec)
-        ss = (s_lo + s_hi).astype(prec)
-        sigma = np.sqrt((ss / prec(32)).astype(prec)).astype(prec)
-        sbits = round_to_bf16_bits((prec(STEP) * sigma).astype(prec))
-    sbits = np.where(sbits < 0x80, 0, sbits).astype(np.uint16)      # below BF16's normal range: an empty group
-    scale = O.bf16_bits_to_f64(sbits).astype(prec)
-    with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
-        rcp = (prec(1) / scale).astype(prec)
-        v = (Gr * rcp[..., None]).astype(prec)
-        q = np.clip(np.rint(v), QMIN, QMAX)
+    sigma = np.sqrt(np.sum(Gr * Gr, axis=-1) / G)
+    sbits = round_to_bf16_bits(STEP * sigma)
+    sbits = np.where(sbits < 0x80, 0, sbits).astype(np.uint16)      # below BF16's normal range: stored as 0
+    scale = O.bf16_bits_to_f64(sbits)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        q = np.clip(np.rint(Gr / scale[..., None]), QMIN, QMAX)
     q = np.where(scale[..., None] == 0, 0, q).astype(np.int8)
     return q.reshape(*lead, K), sbits.reshape(*lead, K // G)
 
@@ -137,7 +128,7 @@ def linear_dequant(Xq, Xs, Wq, Ws) -> np.ndarray:
 
 def layer_forward(X, W, T):
     """Quantized forward with INT4 on both operands; X, W on the BF16 grid, T
-    16-bit values [K/32][32][32] (activations decided in FP32, weights in FP64)."""
-    Xq, Xs = quantize_int4(O.transform_act(X, T).astype(np.float32), prec=np.float32)
-    Wq, Ws = quantize_int4(O.transform_weight(W, T), prec=np.float64)
+    16-bit values [K/32][32][32]."""
+    Xq, Xs = quantize_int4(O.transform_act(X, T))
+    Wq, Ws = quantize_int4(O.transform_weight(W, T))
     return linear_dequant(Xq, Xs, Wq, Ws)

@@ -25,15 +25,16 @@ Readings of what the paper leaves open (listed in the design notes as well):
     MXFP4 case, no stochastic part).
   * elements: value / (group scale * tensor scale), rounded to the nearest E2M1
     value, ties to even, saturating; the sign bit of the input is kept even when
-    the magnitude rounds to zero; a group whose scale byte is 0 has all
-    magnitudes 0.
-  * arithmetic: the decision steps are IEEE operations in ONE working precision
-    `prec` (FP32 for activations -- the precision of the kernel's accumulators --
-    and FP64 for the offline weight path), in this order:
-        c   = 1 / (6 * ts)            r   = amax * c       byte = E4M3(r)
-        d   = value(byte) * ts        rcp = 1 / d          code = E2M1(v * rcp)
-    A reciprocal and a multiplication stand where the definition has a division;
-    the tests bound the difference to the real-number definition.
+    the magnitude rounds to zero.
+  * edge cases (each its own reading): a group whose scale byte is 0 (its AbsMax
+    is below half the smallest E4M3 value times 6 ts) has all magnitudes 0 -- the
+    value / 0 of the definition has no nearest grid point, and 0 is what the
+    stored data can represent; a tensor scale of 0 (an all-zero tensor) gives
+    scale bytes 0 and magnitudes 0 for the same reason.
+  * arithmetic: FP64 throughout, the formulas as written, with true divisions:
+        r = amax / (6 ts)    byte = E4M3(r)    code = E2M1(v / (value(byte) ts)).
+    The GPU decides in FP32 (activations) with reciprocals; a model of those
+    steps lives with the tests (tests/kernel_models.py), not here.
 
 Conventions: row-major, channels last; X [M][K], W [N][K]; T[b][j][k] with
 b = 0 .. K/16-1; codes hold 4-bit patterns (bit 3 sign, bits 2..0 magnitude).
@@ -83,24 +84,21 @@ def tensor_scale(Y: np.ndarray) -> np.float32:
     return np.float32(np.max(np.abs(np.asarray(Y, dtype=np.float64))) / (6.0 * E4M3_MAX))
 
 
-def quantize_nvfp4(Y: np.ndarray, ts, prec=np.float32):
-    """NVFP4 quantizer on values Y [..., K] with tensor scale ts.
-
-    Every decision step is one IEEE operation in `prec` (see the header).
-    Returns (codes uint8 [..., K], scale bytes uint8 [..., K/16]).
-    """
-    Y = np.asarray(Y, dtype=prec)
-    ts = prec(ts)
+def quantize_nvfp4(Y: np.ndarray, ts):
+    """NVFP4 quantizer on values Y [..., K] with tensor scale ts, FP64.
+    Returns (codes uint8 [..., K], scale bytes uint8 [..., K/16])."""
+    Y = np.asarray(Y, dtype=np.float64)
+    ts = float(ts)
     *lead, K = Y.shape
     Gr = Y.reshape(*lead, K // G, G)
-    with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
-        amax = np.max(np.abs(Gr), axis=-1)
-        c = prec(0) if ts == 0 else prec(1) / (prec(6) * ts)   # ts = 0: an all-zero tensor
-        r = (amax * c).astype(prec)
-        sb = round_e4m3(r)
-        d = (e4m3_value(sb).astype(prec) * ts).astype(prec)
-        rcp = np.where(sb == 0, prec(0), prec(1) / d).astype(prec)
-        v = (Gr * rcp[..., None]).astype(prec)
+    amax = np.max(np.abs(Gr), axis=-1)
+    if ts == 0.0:                                       # an all-zero tensor
+        sb = np.zeros(amax.shape, dtype=np.uint8)
+    else:
+        sb = round_e4m3(amax / (6.0 * ts))
+    d = e4m3_value(sb) * ts
+    with np.errstate(divide="ignore", invalid="ignore"):
+        v = np.where(d[..., None] == 0, 0.0, Gr / d[..., None])
     code = round_e2m1(v) | (np.signbit(Gr).astype(np.uint8) << 3)
     return code.reshape(*lead, K), sb
 
@@ -137,10 +135,10 @@ def transform_weight(W: np.ndarray, T: np.ndarray) -> np.ndarray:
 
 def prepare_weight(W: np.ndarray, T: np.ndarray):
     """Offline weight side: transformed weights, their tensor scale (FP32) and
-    their NVFP4 codes / scale bytes, decided in FP64."""
+    their NVFP4 codes / scale bytes."""
     Wt = transform_weight(W, T)
     ts = tensor_scale(Wt)
-    codes, sb = quantize_nvfp4(Wt, np.float64(ts), prec=np.float64)
+    codes, sb = quantize_nvfp4(Wt, ts)
     return codes, sb, ts
 
 
@@ -155,6 +153,6 @@ def layer_forward(X, W, T, tsx=None):
     Yt = transform_act(X, T)
     if tsx is None:
         tsx = tensor_scale(Yt)
-    Xc, Xs = quantize_nvfp4(Yt.astype(np.float32), tsx, prec=np.float32)
+    Xc, Xs = quantize_nvfp4(Yt, tsx)
     Wc, Ws, tsw = prepare_weight(W, T)
     return linear_dequant(Xc, Xs, tsx, Wc, Ws, tsw)

@@ -10,6 +10,7 @@ import pytest
 import wush_inputs as I
 from oracle import wush_int4_oracle as Q
 from oracle import wush_oracle as O
+from tests import kernel_models as KM
 
 pytestmark = pytest.mark.gpu
 
@@ -52,30 +53,6 @@ def _u16(t):
     return np.ascontiguousarray(t.cpu().numpy()).view(np.uint16)
 
 
-def _explained(vals64, q_gpu, s_gpu, q_ref, s_ref, tol):
-    """(mismatch rate, number of differing elements that sit neither within tol (relative to
-    the group's largest |v / scale|) of a rounding midpoint nor in a group whose STEP * sigma
-    is within tol of a BF16 rounding boundary)."""
-    R, K = vals64.shape
-    Gr = vals64.reshape(R, K // 32, 32)
-    qg, qr = q_gpu.reshape(R, K // 32, 32), q_ref.reshape(R, K // 32, 32)
-    sdiff = s_gpu != s_ref
-    bad = (qg != qr) | sdiff[..., None]
-    if not bad.any():
-        return 0.0, 0
-    s_real = Q.STEP * np.sqrt(np.mean(Gr * Gr, axis=-1))
-    sref = O.bf16_bits_to_f64(s_ref)
-    lo = np.minimum(O.bf16_bits_to_f64(s_gpu), sref)
-    hi = np.maximum(O.bf16_bits_to_f64(s_gpu), sref)
-    near_scale = sdiff & (np.abs(s_real - 0.5 * (lo + hi)) <= tol * s_real)
-    with np.errstate(divide="ignore", invalid="ignore"):
-        v = Gr / sref[..., None]
-    frac = np.abs(v - np.floor(v) - 0.5)
-    near_mid = frac <= tol * np.maximum(np.max(np.abs(v), axis=-1, keepdims=True), 1.0)
-    unexplained = bad & ~near_mid & ~near_scale[..., None]
-    return float(np.mean(bad)), int(unexplained.sum())
-
-
 def _adversarial_groups():
     rows = []
     for scale in (1.0, 3.7e-3, 911.0):
@@ -107,9 +84,16 @@ def test_quantizer_tap_bit_exact(P, G):
     q, s = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
     P.wush_quantize_f32_int4(torch.from_numpy(Y).cuda(), q, s)
     torch.cuda.synchronize()
-    qr, sr = Q.quantize_int4(Y, prec=np.float32)
+    # the kernel does exactly the steps it states (bit for bit) ...
+    qr, sr = KM.int4_steps(Y, np.float32)
     assert np.array_equal(_u16(s), sr)
     assert np.array_equal(G.host(q), Q.pack_codes(qr))
+    # ... and those steps differ from the definition (FP64, numpy's sum, a true division) only next to a
+    # rounding boundary of the scale or of a code (values beyond FP32's square range aside: the last row)
+    fin = np.isfinite(Y.astype(np.float64) ** 2).all(axis=1) & (np.abs(Y).max(axis=1) < 1e18)
+    qd, sd = Q.quantize_int4(Y[fin])
+    rate, unexplained = KM.int4_explained(Y[fin].astype(np.float64), qr[fin], sr[fin], qd, sd, tol=2e-6)
+    assert unexplained == 0, (rate, unexplained)
 
 
 @pytest.mark.parametrize("name", list(SHAPES))
@@ -128,7 +112,7 @@ def test_transform_quant(P, G, name):
     assert np.array_equal(xq, G.host(Xq2)) and np.array_equal(xs, _u16(Xs2))
     # (1) quantizer bit-exact on the kernel's own FP32 values
     assert np.isfinite(yt).all()
-    qr, sr = Q.quantize_int4(yt, prec=np.float32)
+    qr, sr = KM.int4_steps(yt, np.float32)
     assert np.array_equal(xs, sr)
     assert np.array_equal(xq, Q.pack_codes(qr))
     # (2) transformed values against FP64
@@ -137,8 +121,8 @@ def test_transform_quant(P, G, name):
     err = np.max(np.abs(yt.astype(np.float64) - Yt).reshape(M, K // 32, 32), axis=-1)
     assert np.max(err / amax) <= 1e-5
     # (3) codes against the all-FP64 path
-    q64, s64 = Q.quantize_int4(Yt, prec=np.float64)
-    rate, unexplained = _explained(Yt, Q.unpack_codes(xq), xs, q64, s64, tol=1e-5)
+    q64, s64 = Q.quantize_int4(Yt)
+    rate, unexplained = KM.int4_explained(Yt, Q.unpack_codes(xq), xs, q64, s64, tol=1e-5)
     assert rate <= 1e-3 and unexplained == 0, (rate, unexplained)
 
 
@@ -152,8 +136,8 @@ def test_prepare_weight(P, G, name):
     P.wush_prepare_weight_int4(Wd, Td, Wq, Ws, ws)
     P.wush_workspace_status(ws, K)
     Wt = O.transform_weight(W, T)
-    qr, sr = Q.quantize_int4(Wt, prec=np.float64)
-    rate, unexplained = _explained(Wt, Q.unpack_codes(G.host(Wq)), _u16(Ws), qr, sr, tol=1e-9)
+    qr, sr = Q.quantize_int4(Wt)
+    rate, unexplained = KM.int4_explained(Wt, Q.unpack_codes(G.host(Wq)), _u16(Ws), qr, sr, tol=1e-9)
     assert rate <= 1e-3 and unexplained == 0, (rate, unexplained)
 
 
@@ -326,13 +310,13 @@ def test_bench_shapes_full_size(P, G, name):
     X = O.bf16_bits_to_f64(L["X"][rows])
     Yt = O.transform_act(X, T)
     xq, xs = Q.unpack_codes(Xqc[rows.tolist()].cpu().numpy()), _u16(Xsc[rows.tolist()])
-    q64, s64 = Q.quantize_int4(Yt, prec=np.float64)
-    rate, unexplained = _explained(Yt, xq, xs, q64, s64, tol=1e-5)
+    q64, s64 = Q.quantize_int4(Yt)
+    rate, unexplained = KM.int4_explained(Yt, xq, xs, q64, s64, tol=1e-5)
     assert rate <= 1e-3 and unexplained == 0, ("activation codes", rate, unexplained)
     Wt = O.transform_weight(O.bf16_bits_to_f64(L["W"][cols]), T)
-    qw, sw = Q.quantize_int4(Wt, prec=np.float64)
+    qw, sw = Q.quantize_int4(Wt)
     wq, wsc = Q.unpack_codes(Wqc[cols.tolist()].cpu().numpy()), _u16(Wsc[cols.tolist()])
-    rate, unexplained = _explained(Wt, wq, wsc, qw, sw, tol=1e-9)
+    rate, unexplained = KM.int4_explained(Wt, wq, wsc, qw, sw, tol=1e-9)
     assert rate <= 1e-3 and unexplained == 0, ("weight codes", rate, unexplained)
     y = O.bf16_bits_to_f64(G.host(Y[rows.tolist()][:, cols.tolist()].contiguous()))
     own = Q.linear_dequant(xq, xs, wq, wsc)

@@ -10,6 +10,7 @@ import pytest
 import wush_inputs as I
 from oracle import wush_nvfp4_oracle as NV
 from oracle import wush_oracle as O
+from tests import kernel_models as KM
 
 pytestmark = pytest.mark.gpu
 
@@ -65,31 +66,6 @@ def _pack(codes):
     return O.pack_codes(codes)
 
 
-def _explained(vals64, ts, codes_gpu, sb_gpu, codes_ref, sb_ref, tol):
-    """Counts differing elements that do NOT sit within tol (relative to the group
-    AbsMax) of an E2M1 midpoint and whose group is NOT within tol of an E4M3 midpoint."""
-    R, K = vals64.shape
-    Gr = vals64.reshape(R, K // 16, 16)
-    amax = np.max(np.abs(Gr), axis=-1)
-    cg, cr = codes_gpu.reshape(R, K // 16, 16), codes_ref.reshape(R, K // 16, 16)
-    same = (cg == cr) | (((cg & 7) == 0) & ((cr & 7) == 0))
-    bad = ~same | (sb_gpu != sb_ref)[..., None]
-    if not bad.any():
-        return 0.0, 0
-    r = amax / (6.0 * float(ts))
-    grid = NV.e4m3_value(np.arange(127))
-    mids = (grid[1:] + grid[:-1]) / 2
-    near_scale = np.min(np.abs(r[..., None] - mids), axis=-1) <= tol * np.maximum(r, 2.0 ** -9)
-    d = NV.e4m3_value(sb_ref) * float(ts)
-    with np.errstate(divide="ignore", invalid="ignore"):
-        v = np.abs(Gr) / d[..., None]
-        a = amax / d
-    emid = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
-    near_mid = np.min(np.abs(v[..., None] - emid), axis=-1) <= tol * a[..., None]
-    unexplained = bad & ~near_mid & ~near_scale[..., None]
-    return float(np.mean(bad)), int(unexplained.sum())
-
-
 def _adversarial_groups():
     """Groups on every E2M1 midpoint, with AbsMax on E4M3 midpoints and thresholds."""
     pts = []
@@ -125,9 +101,14 @@ def test_quantizer_tap_bit_exact(P, G, ts):
     q, s = G.empty_u8(M, K // 2), G.empty_u8(M, K // 16)
     P.wush_quantize_f32_nvfp4(torch.from_numpy(Y).cuda(), _f32_dev(ts), q, s)
     torch.cuda.synchronize()
-    cr, sr = NV.quantize_nvfp4(Y, np.float32(ts), prec=np.float32)
+    # the kernel does exactly the steps it states (bit for bit) ...
+    cr, sr = KM.nvfp4_steps(Y, np.float32(ts), np.float32)
     assert np.array_equal(G.host(s), sr)
     assert np.array_equal(G.host(q), _pack(cr))
+    # ... and those steps differ from the definition (FP64, true divisions) only next to a rounding boundary
+    cd, sd = NV.quantize_nvfp4(Y, np.float32(ts))
+    rate, unexplained = KM.nvfp4_explained(Y.astype(np.float64), np.float32(ts), cr, sr, cd, sd, tol=1e-6)
+    assert unexplained == 0, (rate, unexplained)
 
 
 def test_quantizer_tap_zero_tensor_scale(P, G):
@@ -136,7 +117,7 @@ def test_quantizer_tap_zero_tensor_scale(P, G):
     q, s = G.empty_u8(4, 32), G.empty_u8(4, 4)
     P.wush_quantize_f32_nvfp4(torch.from_numpy(Y).cuda(), _f32_dev(0.0), q, s)
     torch.cuda.synchronize()
-    cr, sr = NV.quantize_nvfp4(Y, np.float32(0.0), prec=np.float32)
+    cr, sr = NV.quantize_nvfp4(Y, 0.0)       # no arithmetic left to model: the definition itself
     assert not sr.any() and np.array_equal(G.host(s), sr) and np.array_equal(G.host(q), _pack(cr))
 
 
@@ -158,7 +139,7 @@ def test_transform_quant(P, G, name):
     assert np.array_equal(xq, G.host(Xq2)) and np.array_equal(xs, G.host(Xs2))
     # (1) quantizer bit-exact on the kernel's own FP32 values
     assert np.isfinite(yt).all()
-    cr, sr = NV.quantize_nvfp4(yt, ts, prec=np.float32)
+    cr, sr = KM.nvfp4_steps(yt, ts, np.float32)
     assert np.array_equal(xs, sr)
     assert np.array_equal(xq, _pack(cr))
     # (2) transformed values against FP64
@@ -166,8 +147,8 @@ def test_transform_quant(P, G, name):
     err = np.max(np.abs(yt.astype(np.float64) - Yt).reshape(M, K // 16, 16), axis=-1)
     assert np.max(err / amax) <= 1e-5
     # (3) codes against the all-FP64 path: differences only next to a decision boundary
-    c64, s64 = NV.quantize_nvfp4(Yt, np.float64(ts), prec=np.float64)
-    rate, unexplained = _explained(Yt, ts, O.unpack_codes(xq), xs, c64, s64, tol=1e-5)
+    c64, s64 = NV.quantize_nvfp4(Yt, ts)
+    rate, unexplained = KM.nvfp4_explained(Yt, ts, O.unpack_codes(xq), xs, c64, s64, tol=1e-5)
     assert rate <= 2e-4 and unexplained == 0, (rate, unexplained)
 
 
@@ -244,8 +225,8 @@ def test_prepare_weight(P, G, name):
     assert abs(float(ts_gpu) - float(ts_ref)) <= 1.2e-7 * float(ts_ref)      # at most one FP32 ulp
     Wt = NV.transform_weight(W, T)
     if ts_gpu != ts_ref:
-        cr, sr = NV.quantize_nvfp4(Wt, np.float64(ts_gpu), prec=np.float64)
-    rate, unexplained = _explained(Wt, ts_gpu, O.unpack_codes(G.host(Wq)), G.host(Ws), cr, sr, tol=1e-9)
+        cr, sr = NV.quantize_nvfp4(Wt, ts_gpu)
+    rate, unexplained = KM.nvfp4_explained(Wt, ts_gpu, O.unpack_codes(G.host(Wq)), G.host(Ws), cr, sr, tol=1e-9)
     assert rate <= 1e-4 and unexplained == 0, (rate, unexplained)
 
 
@@ -471,17 +452,17 @@ def test_bench_shapes_full_size(P, G, name):
     assert not bool(Y.isnan().any())
     # activation rows against the all-FP64 path
     xq, xs = Xqc[rows.tolist()].cpu().numpy(), Xsc[rows.tolist()].cpu().numpy()
-    c64, s64 = NV.quantize_nvfp4(Yt, np.float64(ts), prec=np.float64)
-    rate, unexplained = _explained(Yt, ts, O.unpack_codes(xq), xs, c64, s64, tol=1e-5)
+    c64, s64 = NV.quantize_nvfp4(Yt, ts)
+    rate, unexplained = KM.nvfp4_explained(Yt, ts, O.unpack_codes(xq), xs, c64, s64, tol=1e-5)
     assert rate <= 2e-4 and unexplained == 0, ("activation codes", rate, unexplained)
     # weight rows (= output columns): the tensor scale needs the whole tensor, so take the GPU's
     # (checked against the oracle's on the small shapes) and verify it bounds the sampled rows
     ts_w = np.float32(tsw.cpu().numpy()[0])
     Wt = NV.transform_weight(O.bf16_bits_to_f64(L["W"][cols]), T)
     assert np.max(np.abs(Wt)) <= float(ts_w) * 2688.0 * (1 + 1e-6)
-    cw, sw = NV.quantize_nvfp4(Wt, np.float64(ts_w), prec=np.float64)
+    cw, sw = NV.quantize_nvfp4(Wt, ts_w)
     wq, wsb_ = Wqc[cols.tolist()].cpu().numpy(), Wsc[cols.tolist()].cpu().numpy()
-    rate, unexplained = _explained(Wt, ts_w, O.unpack_codes(wq), wsb_, cw, sw, tol=1e-9)
+    rate, unexplained = KM.nvfp4_explained(Wt, ts_w, O.unpack_codes(wq), wsb_, cw, sw, tol=1e-9)
     assert rate <= 1e-4 and unexplained == 0, ("weight codes", rate, unexplained)
     # output entries: the GEMM on the GPU's own codes, and the oracle's whole forward
     y = O.bf16_bits_to_f64(G.host(Y[rows.tolist()][:, cols.tolist()].contiguous()))
@@ -491,21 +472,6 @@ def test_bench_shapes_full_size(P, G, name):
     exact = X @ O.bf16_bits_to_f64(L["W"][cols]).T
     q_err = O.rel_fro(ref, exact)
     assert O.rel_fro(y, ref) <= max(2e-3, 0.05 * q_err) and q_err < 0.25, (O.rel_fro(y, ref), q_err)
-
-
-def test_f16_mfma_probe_reports_the_instruction_rate(P, G):
-    """The measurement aid of the NVFP4 GEMM's roofline: one 32x32x16 FP16 MFMA issues every 32 shader
-    cycles per wave, whatever the operand values; only the clock depends on them."""
-    import torch
-    vals = (torch.randn(8192, device="cuda") * 3).half()
-    out = torch.zeros((8, 2), dtype=torch.int64, device="cuda")
-    P.wush_probe_mfma_f16(vals, 200, 8, out)
-    torch.cuda.synchronize()
-    t = out.cpu().numpy().astype(np.float64)
-    per_mfma = t[:, 0] / (200 * 64)
-    assert np.all((per_mfma > 31.5) & (per_mfma < 36.0)), per_mfma
-    ghz = t[:, 0] / (t[:, 1] * 10.0)
-    assert np.all((ghz > 0.5) & (ghz < 3.0)), ghz
 
 
 def test_argument_validation(P, G):

@@ -66,7 +66,7 @@ def _exact_reference(y):
         vals = [Fraction(float(v)) for v in y[g]]
         ss = sum(v * v for v in vals) / 32
         sigma = (Decimal(ss.numerator) / Decimal(ss.denominator)).sqrt()
-        s_real = float(Decimal(repr(float(np.float32(Q.STEP)))) * sigma)
+        s_real = float(Decimal(repr(Q.STEP)) * sigma)
         s = float(O.round_to_bf16(np.array([s_real]))[0])
         sc[g] = s
         for i, v in enumerate(vals):
@@ -78,19 +78,16 @@ def _exact_reference(y):
     return qs, sc
 
 
-@pytest.mark.parametrize("prec", [np.float32, np.float64])
-def test_quantizer_against_exact_rational_brute_force(prec):
+def test_quantizer_against_exact_rational_brute_force():
     rng = np.random.default_rng(5)
     y = (rng.standard_normal((300, 32)) * np.exp(rng.uniform(-6, 6, (300, 1)))).astype(np.float32)
-    q, sb = Q.quantize_int4(y, prec=prec)
+    q, sb = Q.quantize_int4(y)
     qe, se = _exact_reference(y)
     s = O.bf16_bits_to_f64(sb)[:, 0]
-    # rounded sums may move STEP * sigma across a BF16 rounding boundary: rare, and then by one BF16 step
-    assert np.mean(s != se) <= 0.02
-    assert np.all(np.abs(s - se) <= se * 2.0 ** -7)
-    same = s == se
-    assert np.mean(q[same] != qe[same]) <= (1e-3 if prec == np.float32 else 1e-9)
-    assert np.all(np.abs(q[same].astype(int) - qe[same]) <= 1)
+    # FP64 sums and a true division: off by an ulp or two of FP64, out of reach of the BF16 and code
+    # rounding boundaries for random inputs
+    assert np.array_equal(s, se)
+    assert np.array_equal(q, qe)
 
 
 def test_error_bound_and_clipping():
@@ -112,7 +109,7 @@ def test_worked_group_and_zero_group():
     y = np.full((1, 32), 2.0, dtype=np.float32)
     y[0, ::2] *= -1
     q, sb = Q.quantize_int4(y)
-    assert O.bf16_bits_to_f64(sb)[0, 0] == float(O.round_to_bf16(np.array([np.float32(Q.STEP) * np.float32(2.0)]))[0])
+    assert O.bf16_bits_to_f64(sb)[0, 0] == float(O.round_to_bf16(np.array([Q.STEP * 2.0]))[0])
     assert np.array_equal(q[0], np.where(np.arange(32) % 2 == 0, -3, 3))
     q0, s0 = Q.quantize_int4(np.zeros((1, 32), dtype=np.float32))
     assert not q0.any() and not s0.any()

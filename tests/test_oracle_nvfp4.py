@@ -80,20 +80,16 @@ def _exact_reference(y, ts):
     return codes, sbytes
 
 
-@pytest.mark.parametrize("prec", [np.float32, np.float64])
-def test_quantizer_against_exact_rational_brute_force(prec):
+def test_quantizer_against_exact_rational_brute_force():
     rng = np.random.default_rng(7)
     y = (rng.standard_normal((300, 16)) * np.exp(rng.uniform(-6, 6, (300, 1)))).astype(np.float32)
     ts = NV.tensor_scale(y)
-    c, s = NV.quantize_nvfp4(y, ts, prec=prec)
+    c, s = NV.quantize_nvfp4(y, ts)
     ce, se = _exact_reference(y, ts)
-    # the reciprocal-multiply in working precision may flip a value that sits within rounding
-    # of a decision boundary; with random inputs that is rare, and never off by more than one code
-    assert np.mean(s[:, 0] != se) <= 2 / 300
-    same_scale = s[:, 0] == se
-    diff = c[same_scale] != ce[same_scale]
-    assert diff.mean() <= (1e-3 if prec == np.float32 else 1e-9)
-    assert np.all(np.abs((c[same_scale] & 7).astype(int) - (ce[same_scale] & 7)) <= 1)
+    # FP64 with true divisions: a quotient is off by half an ulp at most, which random inputs never
+    # bring within reach of a decision boundary
+    assert np.array_equal(s[:, 0], se)
+    assert np.array_equal(c, ce)
 
 
 def test_reconstruction_error_bound():
