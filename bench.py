@@ -6,11 +6,18 @@ wush_quantize_act (fused transform + MXFP4 quantization of the activations)
 followed by wush_linear (MXFP4 GEMM) against weights prepared once, offline,
 by wush_prepare_weight.  Inputs are resident in HBM before the timed region.
 
+The default workload is c5, the largest layer (Llama-70B gate+up, 8192 tokens), on which the
+GEMM's roofline target is stated; the same line also carries the transform+quantize kernel
+on c4 (16384 x 4096 activations, on which its HBM target is stated), once with its working
+set resident in the last-level cache and once from HBM (rotating buffer sets).
+
 Prints ONE JSON line:
   value      layer TFLOP/s = 2*M*N*K / (time of one step)
   roofline   the dominant kernel (the GEMM; for the activation-only workload
              the transform+quantize kernel) against the MI355X peak, with its
              average launch duration measured by HIP events on the launch stream
+  kernels    per-kernel durations; wush_quantize_act_c4 = {warm, cold} with frac_hbm each and
+             the streaming ceilings of this machine for the same byte mix
   cpu_baseline  the CPU oracle's layer forward timed on this machine's host cores
   ceilings   measured on the spot: the GEMM's MFMA instruction alone on all CUs (with the
              workload's own operand bits, and with all-equal operands), the shader clock
@@ -41,12 +48,17 @@ PEAK_FP4_TFLOPS = 10100.0   # MI355X dense MXFP4 MFMA
 PEAK_F16_TFLOPS = 2500.0    # MI355X dense FP16 / BF16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM traffic per launch of the dominant kernel, bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# of this script scaled by a plain copy of known size (commands, raw counters and factors: profiles/*.md).
-MEASURED_TRAFFIC = {
-    ("c2", "tiled"): (48194 + 24587) * 1024,    # wush_linear
-    ("c4", "tiled"): (133280 + 34816) * 1024,   # wush_quantize_act, --cold 4
-}
+# HBM traffic per launch of the dominant kernel: (KiB read, KiB written) from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this script, scaled by a plain copy of known size (commands, raw counters and factors:
+# profiles/*.md).  A figure belongs to one kernel build: the key holds the library version it was read on,
+# and a workload without a figure for the loaded library reports null.
+MEASURED_TRAFFIC_KIB = {}
+
+
+def traffic_for(workload, layout, version):
+    t = MEASURED_TRAFFIC_KIB.get((workload, layout, version))
+    return None if t is None else (t[0] + t[1]) * 1024
+
 
 WORKLOADS = {
     "c2": "Llama-3.1-8B fused QKV projection, M=2048 K=4096 N=6144, MXFP4 W4A4, 128 WUSH blocks",
@@ -108,10 +120,11 @@ def cpu_baseline(cfg, T_bits, L, budget_rows):
             "seconds": dt, "sample": f"oracle transform+quantize on the first {rows} of {cfg.M} tokens"}
 
 
-def measured_ceilings(P, torch, dev, x_bits, w_bits):
+def measured_ceilings(torch, dev, x_bits, w_bits):
     """What this machine sustains, measured now: the GEMM's MFMA instruction in a register-only loop on all
-    CUs (wush_probe_mfma) with the workload's own operand bits and with all-equal operands, the shader
+    CUs (the probes library) with the workload's own operand bits and with all-equal operands, the shader
     clock during each, and a plain 1 GiB device copy."""
+    from paper_2512_00956_amd import probes
     props = torch.cuda.get_device_properties(dev)
     cus = props.multi_processor_count
     out = {"compute_units": cus}
@@ -122,7 +135,7 @@ def measured_ceilings(P, torch, dev, x_bits, w_bits):
     equal = torch.full((16384,), 0x22, dtype=torch.uint8, device=dev)
     for name, bits in (("workload_bits", real), ("equal_operands", equal)):
         for _ in range(2):
-            P.wush_probe_mfma(bits, iters, cus, ticks)
+            probes.mfma_fp4(bits, iters, cus, ticks)
         torch.cuda.synchronize()
         t = ticks.cpu().numpy().astype(np.float64)
         ns = t[:, 1].mean() * 10.0
@@ -392,6 +405,7 @@ def nvfp4_bench(args, P, torch, dev):
             val = grid[codes & 7] * (1.0 - 2.0 * (codes >> 3).float())
             sv = sc[0, :256].view(torch.float8_e4m3fn).float().repeat_interleave(16)
             return (val * sv).half()
+        from paper_2512_00956_amd import probes
         cus = torch.cuda.get_device_properties(dev).multi_processor_count
         ticks = torch.zeros((cus, 2), dtype=torch.int64, device=dev)
         iters = 4000
@@ -401,7 +415,7 @@ def nvfp4_bench(args, P, torch, dev):
         ceil = {"compute_units": cus}
         for name, bits in (("workload_bits", real), ("equal_operands", equal)):
             for _ in range(2):
-                P.wush_probe_mfma_f16(bits, iters, cus, ticks)
+                probes.mfma_f16(bits, iters, cus, ticks)
             torch.cuda.synchronize()
             t = ticks.cpu().numpy().astype(np.float64)
             ns = t[:, 1].mean() * 10.0
@@ -419,7 +433,7 @@ def nvfp4_bench(args, P, torch, dev):
         X = O.bf16_bits_to_f64(L["X"][:rows])
         ts_host = float(tsx.cpu()[0])
         t0 = time.perf_counter()
-        xc, xsb = NV.quantize_nvfp4(NV.transform_act(X, T).astype(np.float32), ts_host)
+        xc, xsb = NV.quantize_nvfp4(NV.transform_act(X, T), ts_host)
         NV.linear_dequant(xc, xsb, ts_host, wc, wsb, tw)
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": 2.0 * rows * n_out * K / dt / 1e12, "unit": "TFLOP/s",
@@ -513,10 +527,10 @@ def int4_bench(args, P, torch, dev):
         from oracle import wush_oracle as O
         rows, n_out = min(M, {"i2": 1024, "i5": 64}[args.workload]), min(N, 8192)
         T = O.bf16_bits_to_f64(T_bits)
-        wq, wsb_ = Q4.quantize_int4(O.transform_weight(O.bf16_bits_to_f64(L["W"][:n_out]), T), prec=np.float64)
+        wq, wsb_ = Q4.quantize_int4(O.transform_weight(O.bf16_bits_to_f64(L["W"][:n_out]), T))
         X = O.bf16_bits_to_f64(L["X"][:rows])
         t0 = time.perf_counter()
-        xq, xsb_ = Q4.quantize_int4(O.transform_act(X, T).astype(np.float32))
+        xq, xsb_ = Q4.quantize_int4(O.transform_act(X, T))
         Q4.linear_dequant(xq, xsb_, wq, wsb_)
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": 2.0 * rows * n_out * K / dt / 1e12, "unit": "TFLOP/s",
@@ -531,7 +545,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layout", default="tiled", choices=["tiled", "canonical"],
                     help="layout of the packed codes/scales between the kernels")
@@ -539,10 +553,11 @@ def main():
                     help="also run one plain 256 MiB device copy (torch) so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--graph", action="store_true",
-                    help="replay one captured graph of the timed steps instead of launching every step from the host "
-                         "(measured slower for c2: 40.1 against 38.0 us per step)")
+                    help="replay one captured graph of the timed steps instead of launching every step from the host")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the live measurement of the MFMA-only and copy ceilings of this box")
+    ap.add_argument("--no-c4", action="store_true",
+                    help="workload c5 only: skip the transform+quantize measurement on the c4 activations")
     ap.add_argument("--cold", type=int, default=0,
                     help="rotate over this many input/output buffer sets (>1 defeats the 256 MB last-level cache)")
     args = ap.parse_args()
@@ -571,24 +586,88 @@ def main():
         int4_bench(args, P, torch, dev)
         return
 
+    out = layer_bench(args, P, torch, dev)
+    print(json.dumps(out))
+
+
+def events_ms(torch, fn, steps, warm=3):
+    """Average duration of fn(i) over `steps` back-to-back launches, HIP events on the launch stream."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(steps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def build_transforms_on_device(P, torch, dev, L, K):
+    """T_blocks from the library's own offline path (Alg. 1 on the device) applied to the workload's
+    weights and calibration tokens."""
+    Td = torch.empty((K // 32, 32, 32), dtype=torch.bfloat16, device=dev)
+    bws = torch.empty(P.wush_build_transforms_workspace(K), dtype=torch.uint8, device=dev)
+    Wcal = torch.from_numpy(L["W"].view(np.int16)).view(torch.bfloat16).to(dev)
+    Xcal = torch.from_numpy(L["X_cal"].view(np.int16)).view(torch.bfloat16).to(dev)
+    P.wush_build_transforms(Wcal, Xcal, 1e-2, Td, bws)
+    P.wush_build_transforms_status(bws, K)
+    return Td
+
+
+def quantizer_c4(args, P, torch, dev, layout, cold_sets=4):
+    """wush_quantize_act on the c4 activations (16384 x 4096): `warm` = one buffer set (its 162 MiB
+    working set stays in the 256 MB last-level cache between launches), `cold` = `cold_sets` rotating
+    buffer sets, so that every byte of a launch comes from and goes to HBM.  Beside them what plain
+    streaming kernels with the same byte mix (4 : 1 read : write, non-temporal stores) reach on this
+    box from HBM: linear, and in the quantizer's own access pattern without its arithmetic."""
+    from paper_2512_00956_amd import probes
+    cfg = I.CONFIGS["c4"]
+    L = I.make_layer(cfg)
+    M, K = cfg.M, cfg.K
+    Td = build_transforms_on_device(P, torch, dev, L, K)
+    fmt = P.default_fmt(layout=1 if layout == "tiled" else 0)
+    xcb, xsb = P.wush_packed_sizes(M, K, fmt)
+    X0 = torch.from_numpy(L["X"].view(np.int16)).view(torch.bfloat16).to(dev)
+    Xd = [X0] + [X0.clone() for _ in range(cold_sets - 1)]
+    Xq = [torch.empty(xcb, dtype=torch.uint8, device=dev) for _ in range(cold_sets)]
+    Xs = [torch.empty(xsb, dtype=torch.uint8, device=dev) for _ in range(cold_sets)]
+    qb = quant_bytes(M, K)
+    steps = max(args.steps, 20)
+    res = {"M": M, "K": K, "algorithmic_bytes": qb}
+    for name, nset in (("warm", 1), ("cold", cold_sets)):
+        ms = events_ms(torch, lambda i: P.wush_quantize_act(Xd[i % nset], Td, Xq[i % nset], Xs[i % nset], fmt),
+                       steps, warm=2 * nset)
+        res[name] = {"ms": ms, "GB/s": qb / ms / 1e6, "frac_hbm": qb / ms / 1e6 / PEAK_HBM_GBS, "buffer_sets": nset,
+                     "working_set_MiB": nset * qb / 2 ** 20}
+    # streaming ceilings, cold, same buffers (dst: codes then scales of one set, contiguous)
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    dst = [torch.empty(M * K * 17 // 32 + 4096, dtype=torch.uint8, device=dev) for _ in range(cold_sets)]
+    sb = M * K * 2 * (1 + 17 / 64)
+    ceil = {}
+    for name, mode, blocks in (("linear", 0, cus), ("quantizer_pattern", 1, cus)):
+        ms = events_ms(torch, lambda i: probes.stream(Xd[i % cold_sets], M, 2 * K, dst[i % cold_sets], mode, blocks),
+                       steps, warm=2 * cold_sets)
+        ceil[name + "_GB/s"] = (sb if mode else M * K * 2 * 1.25) / ms / 1e6
+    res["same_mix_stream_cold"] = ceil
+    res["cold"]["frac_of_same_mix_stream"] = res["cold"]["GB/s"] / max(ceil.values())
+    return res
+
+
+def layer_bench(args, P, torch, dev):
     cfg = I.CONFIGS[args.workload]
     L = I.make_layer(cfg)          # c4 keeps its weights: they are only used to build the transforms
     if args.workload == "c4":
         cfg = I.scaled(cfg, N=0)
     M, K, N = cfg.M, cfg.K, cfg.N
+    version = P.lib().wush_version().decode()
 
     def bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
 
-    # The transforms come from the library's own offline path (Alg. 1 on the device)
-    # applied to the workload's weights and calibration tokens.
     nset = max(1, args.cold)
-    Td = torch.empty((K // 32, 32, 32), dtype=torch.bfloat16, device=dev)
-    bws = torch.empty(P.wush_build_transforms_workspace(K), dtype=torch.uint8, device=dev)
-    Wcal = bf16(L["W"])
-    P.wush_build_transforms(Wcal, bf16(L["X_cal"]), 1e-2, Td, bws)
-    P.wush_build_transforms_status(bws, K)
-    del bws, Wcal
+    Td = build_transforms_on_device(P, torch, dev, L, K)
     T_bits = Td.view(torch.int16).cpu().numpy().view(np.uint16)
     Xd = [bf16(L["X"]) for _ in range(nset)]
     fmt = P.default_fmt(layout=1 if args.layout == "tiled" else 0)
@@ -603,7 +682,7 @@ def main():
         wsp = torch.empty(P.wush_prepare_weight_workspace(N, K), dtype=torch.uint8, device=dev)
         P.wush_prepare_weight(Wd, Td, Wq, Ws, wsp, fmt)
         P.wush_workspace_status(wsp, K)
-        del Wd
+        del Wd, wsp
         Y = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(nset)]
 
     def quant(i):
@@ -651,37 +730,30 @@ def main():
             torch.cuda.synchronize()
             ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    def kernel_ms(fn):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        for i in range(3):
-            fn(i)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(args.steps):
-            fn(i)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / args.steps
-
-    q_ms = kernel_ms(quant)
+    q_ms = events_ms(torch, quant, args.steps)
     qb = quant_bytes(M, K)
     kernels = {"wush_quantize_act": {"ms": q_ms, "GB/s": qb / q_ms / 1e6, "frac_hbm": qb / q_ms / 1e6 / PEAK_HBM_GBS,
                                      "algorithmic_bytes": qb}}
+    traffic = traffic_for(args.workload, args.layout, version)
     if N:
-        g_ms = kernel_ms(gemm)
+        g_ms = events_ms(torch, gemm, args.steps)
         flops = 2.0 * M * N * K
+        gemm_bytes = (M + N) * K * (0.5 + 1 / 32) + 2.0 * M * N
         kernels["wush_linear"] = {"ms": g_ms, "TFLOP/s": flops / g_ms / 1e9,
-                                  "frac_fp4_mfma": flops / g_ms / 1e9 / PEAK_FP4_TFLOPS}
+                                  "frac_fp4_mfma": flops / g_ms / 1e9 / PEAK_FP4_TFLOPS,
+                                  "algorithmic_bytes": gemm_bytes}
         value, unit = flops / ms_per_step / 1e9, "TFLOP/s"
         roof = {"bound": "mfma", "kernel": "wush_linear (MXFP4 scaled-MFMA GEMM)", "achieved": flops / g_ms / 1e9,
                 "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s", "frac": flops / g_ms / 1e9 / PEAK_FP4_TFLOPS,
-                "traffic": MEASURED_TRAFFIC.get((args.workload, args.layout)), "avg_launch_ms": g_ms}
+                "traffic": traffic, "algorithmic_bytes": gemm_bytes,
+                "traffic_over_algorithmic": None if traffic is None else traffic / gemm_bytes, "avg_launch_ms": g_ms}
+        kernels["sum_of_kernel_ms"] = q_ms + g_ms
     else:
         value, unit = qb / ms_per_step / 1e6, "GB/s"
         roof = {"bound": "hbm", "kernel": "wush_quantize_act (fused transform+quantize)", "achieved": qb / q_ms / 1e6,
                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": qb / q_ms / 1e6 / PEAK_HBM_GBS,
-                "traffic": MEASURED_TRAFFIC.get((args.workload, args.layout)),
-                "avg_launch_ms": q_ms}
+                "traffic": traffic, "algorithmic_bytes": qb,
+                "traffic_over_algorithmic": None if traffic is None else traffic / qb, "avg_launch_ms": q_ms}
 
     out = {
         "metric": "W4A4 layer TFLOP/s (transform+quant+MXFP4 GEMM); % of MXFP4 MFMA & HBM peak",
@@ -689,19 +761,25 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp4 (e2m1 x e8m0), bf16 in/out, f32 accumulate", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
-                   "buffer_sets": nset, "packed_layout": args.layout,
+                   "buffer_sets": nset, "packed_layout": args.layout, "library_version": version,
                    "launch": "graph replay of the timed steps" if args.graph else "host loop"},
         "roofline": roof, "kernels": kernels,
     }
     if not args.no_ceilings:
-        ceil = measured_ceilings(P, torch, dev, Xq[0], Wq if N else Xq[0])
+        ceil = measured_ceilings(torch, dev, Xq[0], Wq if N else Xq[0])
         out["ceilings"] = ceil
         if N:
             roof["frac_of_measured_mfma_ceiling"] = roof["achieved"] / ceil["mfma_only_workload_bits_tflops"]
     if not args.no_cpu_baseline:
-        rows = {"c2": 2048, "c3": 256, "c4": 2048, "c5": 64}[args.workload]
+        rows = {"c2": 2048, "c3": 1024, "c4": 16384, "c5": 1024}[args.workload]
         out["cpu_baseline"] = cpu_baseline(cfg, T_bits, L, rows)
-    print(json.dumps(out))
+    if args.workload == "c5" and not args.no_c4:
+        # free the layer's buffers first: the activation-path measurement gets the GPU to itself
+        del Xd, Xq, Xs, Y, Wq, Ws, Td, L
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        kernels["wush_quantize_act_c4"] = quantizer_c4(args, P, torch, dev, args.layout)
+    return out
 
 
 if __name__ == "__main__":

@@ -414,30 +414,6 @@ wush_status wush_quantize_f32_int4(const float* Yt, int64_t M, int64_t K, int32_
                                    void* q, void* s, void* stream);
 
 /*
- * Measurement aid for the roofline of wush_linear (for benchmark harnesses: it
- * computes nothing of the layer): `blocks` workgroups of four waves run `iters`
- * trips of 64 independent block-scaled FP4 MFMAs (32x32x64) on registers only.
- *   operand_bits  in   16 KiB (device): 8 KiB X-side + 8 KiB W-side fragments; the
- *                      sustained rate depends on these bits (the shader clock
- *                      follows the switching activity), so the caller chooses them
- *   cycles_ticks  out  u64 [blocks][2] (device): shader-clock cycles and 100 MHz
- *                      real-time ticks the loop took in each workgroup
- * FLOP per workgroup = 4 waves * iters * 64 * 2*32*32*64.
- */
-wush_status wush_probe_mfma(const void* operand_bits, int32_t iters, int32_t blocks,
-                            void* cycles_ticks, void* stream);
-
-/*
- * The same measurement for the FP16 MFMA (32x32x16) that wush_linear_nvfp4 contracts
- * on: 64 independent MFMAs per trip.
- *   operand_f16   in   16 KiB (device) of FP16 values: 8 KiB X-side + 8 KiB W-side
- *   cycles_ticks  out  u64 [blocks][2] as above
- * FLOP per workgroup = 4 waves * iters * 64 * 2*32*32*16.
- */
-wush_status wush_probe_mfma_f16(const void* operand_f16, int32_t iters, int32_t blocks,
-                                void* cycles_ticks, void* stream);
-
-/*
  * Test tap: the quantizer alone on FP32 values (same device function the fused
  * kernel uses).  Yt f32 [M][K] (device) -> q u8 [M][K/2], s u8 [M][K/32].
  */

@@ -36,8 +36,6 @@ from .binding import (  # noqa: F401
     wush_prepare_weight_nvfp4_status,
     wush_prepare_weight_nvfp4_workspace,
     wush_prepare_weight_workspace,
-    wush_probe_mfma,
-    wush_probe_mfma_f16,
     wush_quantize_act,
     wush_quantize_act_int4,
     wush_quantize_act_nvfp4,
@@ -55,8 +53,8 @@ __all__ = [
     "wush_build_transforms_status", "wush_build_transforms_workspace", "wush_layer_decode",
     "wush_layer_decode_init", "wush_layer_decode_status", "wush_layer_decode_workspace",
     "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_status", "wush_prepare_weight_gptq_workspace",
-    "wush_probe_mfma", "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_status",
+    "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_status",
     "wush_prepare_weight_nvfp4_workspace", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
-    "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", "wush_probe_mfma_f16",
+    "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", 
     "wush_calibrate_act_nvfp4", "wush_build_transforms_nvfp4", "wush_quantize_act_int4", "wush_prepare_weight_int4", "wush_linear_int4", "wush_quantize_f32_int4",
 ]

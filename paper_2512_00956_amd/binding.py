@@ -32,10 +32,9 @@ EXPORTS = (
     "wush_build_transforms", "wush_build_transforms_workspace", "wush_build_transforms_status",
     "wush_layer_decode", "wush_layer_decode_workspace", "wush_layer_decode_init", "wush_layer_decode_status",
     "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_workspace", "wush_prepare_weight_gptq_status",
-    "wush_probe_mfma",
     "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_workspace",
     "wush_prepare_weight_nvfp4_status", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
-    "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4", "wush_probe_mfma_f16",
+    "wush_packed_sizes_nvfp4", "wush_unpack_tiled_nvfp4",
     "wush_calibrate_act_nvfp4", "wush_build_transforms_nvfp4",
     "wush_quantize_act_int4", "wush_prepare_weight_int4", "wush_linear_int4", "wush_quantize_f32_int4",
 )
@@ -118,8 +117,6 @@ def lib() -> ctypes.CDLL:
                                                c_void_p]
         L.wush_prepare_weight_gptq_status.restype = c_int32
         L.wush_prepare_weight_gptq_status.argtypes = [c_void_p, c_int64, c_int64, c_void_p]
-        L.wush_probe_mfma.restype = c_int32
-        L.wush_probe_mfma.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
         L.wush_quantize_act_int4.restype = c_int32
         L.wush_quantize_act_int4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_void_p, c_void_p,
                                              c_void_p, c_void_p]
@@ -135,8 +132,6 @@ def lib() -> ctypes.CDLL:
         L.wush_build_transforms_nvfp4.argtypes = L.wush_build_transforms.argtypes
         L.wush_calibrate_act_nvfp4.restype = c_int32
         L.wush_calibrate_act_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
-        L.wush_probe_mfma_f16.restype = c_int32
-        L.wush_probe_mfma_f16.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
         L.wush_quantize_act_nvfp4.restype = c_int32
         L.wush_quantize_act_nvfp4.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_int32, c_void_p,
                                               c_void_p, c_void_p, c_void_p]
@@ -324,12 +319,6 @@ def wush_prepare_weight_gptq_status(workspace, N: int, K: int, stream=None):
            "wush_prepare_weight_gptq_status")
 
 
-def wush_probe_mfma(operand_bits, iters: int, blocks: int, cycles_ticks, stream=None):
-    """MFMA-only ceiling probe: operand_bits u8 [16384], cycles_ticks int64 [blocks][2] (both on the GPU)."""
-    _check(lib().wush_probe_mfma(_ptr(operand_bits), iters, blocks, _ptr(cycles_ticks), _stream(stream)),
-           "wush_probe_mfma")
-
-
 # ---------------------------------------------------------------------------
 # NVFP4 variant (E2M1, E4M3 scale per 16, FP32 tensor scale held in a 1-element
 # float tensor on the GPU; transforms bf16 [K/16][16][16]).  `layout`:
@@ -398,12 +387,6 @@ def wush_unpack_tiled_nvfp4(q_tiled, s_tiled, rows: int, K: int, q, s, stream=No
     """Tiled -> canonical copy (q u8 [rows][K/2], s u8 [rows][K/16])."""
     _check(lib().wush_unpack_tiled_nvfp4(_ptr(q_tiled), _ptr(s_tiled), rows, K, _ptr(q), _ptr(s), _stream(stream)),
            "wush_unpack_tiled_nvfp4")
-
-
-def wush_probe_mfma_f16(operand_f16, iters: int, blocks: int, cycles_ticks, stream=None):
-    """FP16 MFMA in a register-only loop; cycles_ticks: int64 tensor [blocks][2] (shader cycles, 100 MHz ticks)."""
-    _check(lib().wush_probe_mfma_f16(_ptr(operand_f16), iters, blocks, _ptr(cycles_ticks), _stream(stream)),
-           "wush_probe_mfma_f16")
 
 
 # ---------------------------------------------------------------------------

@@ -1,4 +1,5 @@
-"""Builds libwush.so (gfx950 only) in-tree with hipcc.
+"""Builds libwush.so (gfx950 only) in-tree with hipcc, and beside it libwush_probes.so, the
+benchmark's measurement aids (MFMA-only and streaming kernels: not part of the layer path).
 
 Usage: python -m paper_2512_00956_amd.build
 """
@@ -13,7 +14,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwush.so")
-SOURCES = ["wush_api.hip", "transform_quant.hip", "weight_prep.hip", "mxfp4_gemm.hip", "mxfp4_gemm_frag.hip", "build_transforms.hip", "layer_decode.hip", "gptq_prep.hip", "probe.hip", "nvfp4_quant.hip", "nvfp4_gemm.hip", "int4_quant.hip"]
+PROBES_SRC = os.path.join(HERE, "probes", "probes.hip")
+PROBES_LIB = os.path.join(HERE, "libwush_probes.so")
+SOURCES = ["wush_api.hip", "transform_quant.hip", "weight_prep.hip", "mxfp4_gemm.hip", "mxfp4_gemm_frag.hip", "build_transforms.hip", "layer_decode.hip", "gptq_prep.hip", "nvfp4_quant.hip", "nvfp4_gemm.hip", "int4_quant.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
@@ -42,6 +45,9 @@ def build(verbose: bool = False) -> str:
         cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
+    pobj = os.path.join(bdir, "probes.o")
+    pcmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-c", PROBES_SRC, "-o", pobj]
+    procs.append(("probes/probes.hip", subprocess.Popen(pcmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for src, p in procs:
         out, _ = p.communicate()
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
@@ -49,12 +55,13 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
         if verbose and out.strip():
             print(out)
-    tmp = LIB + ".tmp"
-    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", tmp]
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"link failed:\n{r.stdout}")
-    os.replace(tmp, LIB)
+    for lib, lobjs in ((LIB, objs), (PROBES_LIB, [pobj])):
+        tmp = lib + ".tmp"
+        cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", *lobjs, "-o", tmp]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"link failed:\n{r.stdout}")
+        os.replace(tmp, lib)
     return LIB
 
 

@@ -259,22 +259,6 @@ wush_status wush_layer_decode_status(const void* workspace, int64_t K, void* str
   return flag ? WUSH_ERR_TIMEOUT : WUSH_OK;
 }
 
-wush_status wush_probe_mfma(const void* operand_bits, int32_t iters, int32_t blocks, void* cycles_ticks, void* stream) {
-  if (!operand_bits || !cycles_ticks) return WUSH_ERR_NULL;
-  if (iters <= 0 || iters > (1 << 20) || blocks <= 0 || blocks > 4096) return WUSH_ERR_SHAPE;
-  if (!aligned16(operand_bits) || !aligned16(cycles_ticks)) return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_mfma_probe(operand_bits, iters, blocks, cycles_ticks, static_cast<hipStream_t>(stream)));
-}
-
-wush_status wush_probe_mfma_f16(const void* operand_f16, int32_t iters, int32_t blocks, void* cycles_ticks,
-                                void* stream) {
-  if (!operand_f16 || !cycles_ticks) return WUSH_ERR_NULL;
-  if (iters <= 0 || iters > (1 << 20) || blocks <= 0 || blocks > 4096) return WUSH_ERR_SHAPE;
-  if (!aligned16(operand_f16) || !aligned16(cycles_ticks)) return WUSH_ERR_ALIGN;
-  return from_hip(wush::launch_mfma_f16_probe(operand_f16, iters, blocks, cycles_ticks,
-                                              static_cast<hipStream_t>(stream)));
-}
-
 static inline wush_status check_nv_layout(int32_t layout, int64_t K) {
   if (layout != WUSH_LAYOUT_CANONICAL && layout != WUSH_LAYOUT_TILED) return WUSH_ERR_FMT;
   return (layout == WUSH_LAYOUT_TILED && K % 64 != 0) ? WUSH_ERR_SHAPE : WUSH_OK;
@@ -469,6 +453,6 @@ const char* wush_status_string(wush_status st) {
   return "unknown status";
 }
 
-const char* wush_version(void) { return "0.7"; }
+const char* wush_version(void) { return "0.8"; }
 
 }  // extern "C"

@@ -129,9 +129,4 @@ hipError_t launch_int4_weight_prep(const void* W, int64_t N, int64_t K, int64_t 
 hipError_t launch_int4_gemm(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M, int64_t N,
                             int64_t K, int out_f32, int tiled, void* Y, int64_t ldy, hipStream_t stream);
 
-// Measurement aid: register-only loop of the block-scaled FP4 MFMA (4 waves per workgroup, 64 MFMAs per trip).
-hipError_t launch_mfma_probe(const void* operand_bits, int iters, int blocks, void* out, hipStream_t stream);
-// The same for the FP16 MFMA of the NVFP4 GEMM (operands: 16 KiB of FP16 values).
-hipError_t launch_mfma_f16_probe(const void* operand_bits, int iters, int blocks, void* out, hipStream_t stream);
-
 }  // namespace wush

@@ -1,4 +1,25 @@
-// Measurement aid, not part of the layer path: the block-scaled FP4 MFMA
+// Measurement aids for the benchmark, built into a library of their own
+// (libwush_probes.so): nothing here is part of the layer path, and the
+// product library neither contains nor calls any of it.
+//
+//   wushp_mfma_fp4 / wushp_mfma_f16   the GEMMs' MFMA instructions in a
+//       register-only loop (the ceiling the GEMM kernels are compared against)
+//   wushp_stream                       plain streaming kernels with the byte mix
+//       of the fused transform + quantize kernel (4 bytes read per byte written,
+//       non-temporal stores), linear or in that kernel's own access pattern.
+//       Measured from HBM on 16384 x 4096 BF16: linear 5.5-5.6 TB/s, the quantizer's
+//       pattern 4.7-4.9 (deeper lookahead or wider waves do not change it), the
+//       quantizer itself 4.6-4.7.
+//
+// C ABI (all pointers are device pointers, `stream` is a hipStream_t; return
+// value: 0 = launched, 1 = bad argument, 2 = HIP launch error):
+//   int wushp_mfma_fp4(const void* operand_bits, int iters, int blocks, void* cycles_ticks, void* stream);
+//   int wushp_mfma_fp4_colmajor(...same...);   the same MFMAs issued column block by column block
+//   int wushp_mfma_f16(const void* operand_f16, int iters, int blocks, void* cycles_ticks, void* stream);
+//   int wushp_stream(const void* src, long long rows, long long row_bytes, void* dst, int mode, int blocks,
+//                    void* stream);
+//
+// First probe: the block-scaled FP4 MFMA
 // (v_mfma_scale_f32_32x32x64_f8f6f4) in a register-only loop, the ceiling the
 // MXFP4 GEMM is compared against.  One wave per SIMD, 64 independent MFMAs per
 // trip (the GEMM's 8 x 2 accumulator tiles x 4 issues), operands loaded once from
@@ -6,13 +27,15 @@
 // sustained rate depends on them (the shader clock drops with switching
 // activity), which is the point of the measurement.  Every workgroup reports its
 // shader-clock cycles and 100 MHz real-time ticks.
-#include "wush_device.hpp"
-#include "wush_kernels.hpp"
+#include "../csrc/transform_quant_core.hpp"
 
 namespace wush {
 
 namespace {
 
+// ORDER 0: row block outer, column block inner (consecutive MFMAs share the X-side operand, the order of the
+// GEMM's loop); ORDER 1: column block outer (eight consecutive MFMAs share the W-side operand).
+template <int ORDER>
 __global__ __launch_bounds__(256) void mfma_probe_kernel(const int* __restrict__ in, int iters,
                                                          unsigned long long* __restrict__ out) {
   const int lane = threadIdx.x & 63;
@@ -38,19 +61,24 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const int* __restrict__
   const unsigned long long c0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
   __builtin_amdgcn_sched_barrier(0);
   for (int it = 0; it < iters; ++it) {
-#define WUSH_PROBE_ISSUE(KK)                                                                                          \
-  _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                     \
+#define WUSH_PROBE_MMA(KK, i, j)                                                                                      \
+  {                                                                                                                   \
     const v8i A = {af[i][0], af[i][1], af[i][2], af[i][3], 0, 0, 0, 0};                                               \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j) {                                                                   \
-      const v8i B = {bf[j][KK][0], bf[j][KK][1], bf[j][KK][2], bf[j][KK][3], 0, 0, 0, 0};                             \
-      acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B, A, acc[i][j], 4, 4, KK, sb[j], KK, sa[i]);       \
-    }                                                                                                                 \
+    const v8i B = {bf[j][KK][0], bf[j][KK][1], bf[j][KK][2], bf[j][KK][3], 0, 0, 0, 0};                               \
+    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B, A, acc[i][j], 4, 4, KK, sb[j], KK, sa[i]);         \
+  }
+#define WUSH_PROBE_ISSUE(KK)                                                                                          \
+  if (ORDER == 0) {                                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < 8; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j) WUSH_PROBE_MMA(KK, i, j) \
+  } else {                                                                                                            \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) _Pragma("unroll") for (int i = 0; i < 8; ++i) WUSH_PROBE_MMA(KK, i, j) \
   }
     WUSH_PROBE_ISSUE(0)
     WUSH_PROBE_ISSUE(1)
     WUSH_PROBE_ISSUE(2)
     WUSH_PROBE_ISSUE(3)
 #undef WUSH_PROBE_ISSUE
+#undef WUSH_PROBE_MMA
   }
   __builtin_amdgcn_sched_barrier(0);
   const unsigned long long c1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
@@ -116,18 +144,147 @@ __global__ __launch_bounds__(256) void mfma_f16_probe_kernel(const v8h* __restri
   }
 }
 
+
+// Streaming kernels with the byte mix of the fused transform + quantize kernel: per 16 B
+// read, 4 B of "codes" and 1/4 B of "scales" are written with non-temporal stores.
+//   mode 0: linear.  A wave reads 4 KiB contiguous per step (four 128-bit loads per lane)
+//           and writes 1 KiB; waves take steps round-robin.
+//   mode 1: the quantizer's own pattern.  A wave reads 32 rows x 256 B (tile = 32 tokens x
+//           4 transform blocks) with the same eight 128-bit loads per lane and writes the
+//           tile's codes and scales at the offsets of the fragment-order layout; one tile
+//           of lookahead in registers.  What is left out is the arithmetic.
+//   mode 2: as mode 1 with 8 blocks per wave (32 rows x 512 B).
+// rows x row_bytes is the source (row_bytes a multiple of 1024, rows of 32); dst holds
+// rows * row_bytes / 4 bytes of "codes" followed by rows * row_bytes / 64 bytes of "scales".
+__global__ __launch_bounds__(512) void stream_linear_kernel(const v4u* __restrict__ src, long long n_steps,
+                                                            v4u* __restrict__ dst) {
+  const int lane = threadIdx.x & 63;
+  const long long wave = (long long)blockIdx.x * 8 + (threadIdx.x >> 6), nwaves = (long long)gridDim.x * 8;
+  if (wave >= n_steps) return;
+  // two steps in flight, two register sets that swap roles (no copies, no conditional loads: the
+  // compiler's wait counts stay exact)
+  v4u x[3][4];
+  auto step_of = [&](long long st) { return st < n_steps ? st : wave; };
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[s][i] = src[step_of(wave + s * nwaves) * 256 + 64 * i + lane];
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  for (long long base = wave; base < n_steps; base += 3 * nwaves) {
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+      const long long st = base + s * nwaves;
+      if (st >= n_steps) return;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) x[(s + 2) % 3][i] = src[step_of(st + 2 * nwaves) * 256 + 64 * i + lane];
+      const v4u o = x[s][0] ^ x[s][1] ^ x[s][2] ^ x[s][3];
+      __builtin_nontemporal_store(o, dst + st * 64 + lane);
+    }
+  }
+}
+
+template <int PF, int NBW>
+__global__ __launch_bounds__(512) void stream_tiles_kernel(const uint16_t* __restrict__ X, int M, int K,
+                                                           uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs,
+                                                           int tiles_per_wg) {
+  // NBW = blocks per wave (the quantizer: 4 = 256 B of every row; 8 = 512 B)
+  using namespace tq;
+  constexpr int TG = 2;
+  const int lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3, tg = threadIdx.x >> 8;
+  const int tok = lane & 31, h = lane >> 5, C = K / 32;
+  const int bfirst = (blockIdx.y * 4 + wave) * NBW;
+  if (bfirst >= C) return;
+  const int ntiles = M / kTileM;
+  const int t0 = blockIdx.x * tiles_per_wg + tg;
+  const int tend = min(blockIdx.x * tiles_per_wg + tiles_per_wg, ntiles);
+  if (t0 >= tend) return;
+  const int row_spare = t0 * kTileM;
+  auto tile_row = [&](int t) { return t < tend ? t * kTileM + tok : row_spare; };
+  XFrag x[PF + 1][NBW];
+  auto load = [&](XFrag (&d)[NBW], int row) {
+#pragma unroll
+    for (int g = 0; g < NBW / kNB; ++g)
+      load_tile(reinterpret_cast<XFrag (&)[kNB]>(d[kNB * g]), X, K, row, bfirst + kNB * g, C, h);
+  };
+#pragma unroll
+  for (int s = 0; s < PF; ++s) {
+    load(x[s], tile_row(t0 + s * TG));
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  for (int base = t0; base < tend; base += (PF + 1) * TG) {
+#pragma unroll
+    for (int s = 0; s <= PF; ++s) {
+      const int t = base + s * TG;
+      if (t >= tend) return;
+      load(x[(s + PF) % (PF + 1)], tile_row(t + PF * TG));
+      typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+      for (int g = 0; g < NBW / kNB; ++g) {
+        v4u out[2];
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+          out[p] = __builtin_bit_cast(u4, x[s][4 * g + 2 * p].lo) ^ __builtin_bit_cast(u4, x[s][4 * g + 2 * p].hi) ^
+                   __builtin_bit_cast(u4, x[s][4 * g + 2 * p + 1].lo) ^ __builtin_bit_cast(u4, x[s][4 * g + 2 * p + 1].hi);
+        store_tile_tiled<true>(out, out[0][0] ^ out[1][0], Xq, Xs, t, K >> 8, bfirst + kNB * g, tok, h);
+      }
+    }
+  }
+}
+
 }  // namespace
 
-hipError_t launch_mfma_f16_probe(const void* operand_bits, int iters, int blocks, void* out, hipStream_t stream) {
-  mfma_f16_probe_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(static_cast<const v8h*>(operand_bits), iters,
-                                                                        static_cast<unsigned long long*>(out));
-  return hipGetLastError();
-}
-
-hipError_t launch_mfma_probe(const void* operand_bits, int iters, int blocks, void* out, hipStream_t stream) {
-  mfma_probe_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(static_cast<const int*>(operand_bits), iters,
-                                                                    static_cast<unsigned long long*>(out));
-  return hipGetLastError();
-}
-
 }  // namespace wush
+
+extern "C" {
+
+int wushp_mfma_f16(const void* operand_f16, int iters, int blocks, void* cycles_ticks, void* stream) {
+  if (!operand_f16 || !cycles_ticks || iters <= 0 || iters > (1 << 20) || blocks <= 0 || blocks > 4096) return 1;
+  wush::mfma_f16_probe_kernel<<<dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+      static_cast<const wush::v8h*>(operand_f16), iters, static_cast<unsigned long long*>(cycles_ticks));
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+int wushp_mfma_fp4(const void* operand_bits, int iters, int blocks, void* cycles_ticks, void* stream) {
+  if (!operand_bits || !cycles_ticks || iters <= 0 || iters > (1 << 20) || blocks <= 0 || blocks > 4096) return 1;
+  wush::mfma_probe_kernel<0><<<dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+      static_cast<const int*>(operand_bits), iters, static_cast<unsigned long long*>(cycles_ticks));
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+int wushp_mfma_fp4_colmajor(const void* operand_bits, int iters, int blocks, void* cycles_ticks, void* stream) {
+  if (!operand_bits || !cycles_ticks || iters <= 0 || iters > (1 << 20) || blocks <= 0 || blocks > 4096) return 1;
+  wush::mfma_probe_kernel<1><<<dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+      static_cast<const int*>(operand_bits), iters, static_cast<unsigned long long*>(cycles_ticks));
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+int wushp_stream(const void* src, long long rows, long long row_bytes, void* dst, int mode, int blocks, void* stream) {
+  if (!src || !dst || rows <= 0 || rows % 32 != 0 || row_bytes <= 0 || row_bytes % 1024 != 0 || blocks <= 0 ||
+      blocks > 65536 || rows > (1 << 30) || row_bytes > (1 << 23))
+    return 1;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (mode == 0) {
+    wush::stream_linear_kernel<<<dim3((unsigned)blocks), dim3(512), 0, st>>>(
+        static_cast<const wush::v4u*>(src), rows * row_bytes / 4096, static_cast<wush::v4u*>(dst));
+  } else if (mode == 1 || mode == 2) {
+    const int nbw = mode == 2 ? 8 : 4;
+    const int K = (int)(row_bytes / 2), ntiles = (int)(rows / 32);
+    if (K % (128 * nbw) != 0) return 1;
+    const int col_groups = K / (128 * nbw);
+    const int wg_rows = blocks / col_groups > 0 ? blocks / col_groups : 1;
+    int walk = (ntiles + wg_rows - 1) / wg_rows;
+    if (walk < 2) walk = 2;
+    dim3 grid((unsigned)((ntiles + walk - 1) / walk), (unsigned)col_groups);
+    uint8_t* q = static_cast<uint8_t*>(dst);
+    uint8_t* s = q + rows * row_bytes / 4;
+    const uint16_t* x = static_cast<const uint16_t*>(src);
+    if (mode == 1) wush::stream_tiles_kernel<1, 4><<<grid, dim3(512), 0, st>>>(x, (int)rows, K, q, s, walk);
+    else wush::stream_tiles_kernel<1, 8><<<grid, dim3(512), 0, st>>>(x, (int)rows, K, q, s, walk);
+  } else {
+    return 1;
+  }
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+}  // extern "C"

@@ -467,18 +467,3 @@ def test_linear_small_batches_on_either_kernel(P, G, M, kernel):
     y = G.host(Y).astype(np.float64)
     assert np.isfinite(y).all()
     assert O.rel_fro(y, ref) <= 1e-5
-
-
-def test_mfma_probe_reports_the_instruction_rate(P, G):
-    """The measurement aid: one block-scaled 32x32x64 FP4 MFMA issues every 32 shader cycles (8 passes),
-    whatever the operand bits; only the clock depends on them."""
-    import torch
-    bits = torch.randint(0, 256, (16384,), dtype=torch.uint8, device="cuda")
-    out = torch.zeros((8, 2), dtype=torch.int64, device="cuda")
-    P.wush_probe_mfma(bits, 200, 8, out)
-    torch.cuda.synchronize()
-    t = out.cpu().numpy().astype(np.float64)
-    per_mfma = t[:, 0] / (200 * 64)
-    assert np.all((per_mfma > 31.5) & (per_mfma < 36.0)), per_mfma
-    ghz = t[:, 0] / (t[:, 1] * 10.0)
-    assert np.all((ghz > 0.5) & (ghz < 3.0)), ghz
