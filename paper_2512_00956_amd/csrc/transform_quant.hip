@@ -35,7 +35,12 @@ constexpr int kWaves = 4;    // waves per workgroup
 // accumulator reads, max tree, lane swap, scale, converts: about 2600 cycles for 280 instructions), so
 // a CU with one wave per SIMD idles most of the time; a second group per workgroup fills the gaps
 // without leaving the placement of more, smaller workgroups to the dispatcher.
-template <bool DBG, bool TILED, int TG>
+// PF = tiles a wave keeps in flight ahead of the one it computes on (PF + 1 operand register sets of
+// 32 VGPRs, rotated by unrolling, never copied).  Only PF = 1 is instantiated: with 2 or 3 tiles of
+// lookahead the kernel takes the same time to within 2 %, cache resident or from HBM, on 16384 x 4096,
+// 8192 x 8192 and 4096 x 14336 activations (a streaming kernel with this kernel's loads and stores and no
+// arithmetic is not faster either: from HBM the access pattern, 32 rows x 256 B per wave, is the limit).
+template <bool DBG, bool TILED, int TG, int PF>
 __global__ __launch_bounds__(kWaves * TG * 64) void transform_quant_kernel(
     const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ T,
     uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs, float* __restrict__ dbg,
@@ -53,41 +58,55 @@ __global__ __launch_bounds__(kWaves * TG * 64) void transform_quant_kernel(
   tq::load_transforms(ta, T, bfirst, C, tok, h);
 
   const int ntiles = (M + kTileM - 1) / kTileM;
-  int t = blockIdx.x * tiles_per_wg + tg;
+  const int t0 = blockIdx.x * tiles_per_wg + tg;
   const int tend = min(blockIdx.x * tiles_per_wg + tiles_per_wg, ntiles);
-  if (t >= tend) return;
+  if (t0 >= tend) return;
 
-  XFrag cur[kNB], nxt[kNB];
-  tq::load_tile(cur, X, ldx, min(t * kTileM + tok, M - 1), bfirst, C, h);
-
-  for (; t < tend; t += TG) {
-    const int m = t * kTileM + tok;
-    const bool row_ok = m < M;
-    if (t + TG < tend) tq::load_tile(nxt, X, ldx, min((t + TG) * kTileM + tok, M - 1), bfirst, C, h);
-
-    v4u out[2];
-    uint32_t sbytes;
-    float* dbg_row = (DBG && row_ok) ? dbg + (int64_t)m * K + 32 * bfirst + 16 * h : nullptr;
-    tq::transform_quantize<DBG>(ta, cur, rule, out, sbytes, dbg_row, nb);
-    if (TILED) {
-      if (row_ok) tq::store_tile_tiled<true>(out, sbytes, Xq, Xs, t, K >> 8, bfirst, tok, h);
-    } else if (row_ok) {
-      uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
-      if (nb == kNB && (C & 3) == 0) {
-        __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(q));
-        __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(q + 16));
-        if (h == 0) __builtin_nontemporal_store(sbytes, reinterpret_cast<uint32_t*>(Xs + (int64_t)m * C + bfirst));
-      } else {
-        // ragged tail of the channel dimension: blocks 2h and 2h+1 of this lane
+  // Every load of the walk is issued unconditionally: a tile past the end of the walk is replaced by
+  // one row of the first tile for all lanes (a single cache line per instruction, already resident).
+  // With a branch around the prefetch the compiler cannot know how many loads are outstanding where
+  // it waits for the current tile and drains them all, which ends the lookahead.
+  const int row_spare = min(t0 * kTileM, M - 1);
+  auto tile_row = [&](int t) { return t < tend ? min(t * kTileM + tok, M - 1) : row_spare; };
+  XFrag x[PF + 1][kNB];
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
-          if (2 * h + p < nb) *reinterpret_cast<v4u*>(q + 16 * p) = out[p];
-        if (h == 0)
-          for (int bb = 0; bb < nb; ++bb) Xs[(int64_t)m * C + bfirst + bb] = (uint8_t)(sbytes >> (8 * bb));
+  for (int s = 0; s < PF; ++s) {
+    tq::load_tile(x[s], X, ldx, tile_row(t0 + s * TG), bfirst, C, h);
+    // keeps the tiles' loads in walk order: the first wait of the loop counts the loads behind tile 0
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  for (int base = t0; base < tend; base += (PF + 1) * TG) {
+#pragma unroll
+    for (int s = 0; s <= PF; ++s) {
+      const int t = base + s * TG;
+      if (t >= tend) return;  // wave-uniform; leaves the kernel so that no path with fewer loads in flight rejoins the loop
+      const int m = t * kTileM + tok;
+      const bool row_ok = m < M;
+      tq::load_tile(x[(s + PF) % (PF + 1)], X, ldx, tile_row(t + PF * TG), bfirst, C, h);
+
+      v4u out[2];
+      uint32_t sbytes;
+      float* dbg_row = (DBG && row_ok) ? dbg + (int64_t)m * K + 32 * bfirst + 16 * h : nullptr;
+      tq::transform_quantize<DBG>(ta, x[s], rule, out, sbytes, dbg_row, nb);
+      if (TILED) {
+        if (row_ok) tq::store_tile_tiled<true>(out, sbytes, Xq, Xs, t, K >> 8, bfirst, tok, h);
+      } else if (row_ok) {
+        uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
+        if (nb == kNB && (C & 3) == 0) {
+          __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(q));
+          __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(q + 16));
+          if (h == 0) __builtin_nontemporal_store(sbytes, reinterpret_cast<uint32_t*>(Xs + (int64_t)m * C + bfirst));
+        } else {
+          // ragged tail of the channel dimension: blocks 2h and 2h+1 of this lane
+#pragma unroll
+          for (int p = 0; p < 2; ++p)
+            if (2 * h + p < nb) *reinterpret_cast<v4u*>(q + 16 * p) = out[p];
+          if (h == 0)
+            for (int bb = 0; bb < nb; ++bb) Xs[(int64_t)m * C + bfirst + bb] = (uint8_t)(sbytes >> (8 * bb));
+        }
       }
     }
-#pragma unroll
-    for (int bb = 0; bb < kNB; ++bb) cur[bb] = nxt[bb];
   }
 }
 
@@ -148,7 +167,7 @@ hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t l
   dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
   dim3 block(kWaves * 64 * walk.groups);
 #define WUSH_TQ_LAUNCH(DBG, TILED, TG)                                                                 \
-  transform_quant_kernel<DBG, TILED, TG><<<grid, block, 0, stream>>>(                                  \
+  transform_quant_kernel<DBG, TILED, TG, 1><<<grid, block, 0, stream>>>(                               \
       (const uint16_t*)X, ldx, (const uint16_t*)T, (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M, (int)K, C, \
       tiles_per_wg, rule)
   if (walk.groups == 2) {
