@@ -2,7 +2,9 @@
 times (tiled packed layout, BF16 output).  The oracle cannot redo these sizes
 element by element in reasonable time, so it checks seeded samples that it can
 compute one by one: whole token rows of the activation path, whole rows of the
-prepared weights, and (rows x columns) blocks of the layer output.
+prepared weights, (rows x columns) blocks of the layer output, and -- so that every
+output tile of every workgroup is looked at -- one seeded token row per band of 128
+rows across ALL output columns.
 """
 import numpy as np
 import pytest
@@ -63,7 +65,7 @@ def _run_layer(P, G, L, T, want_gemm=True):
         P.wush_linear(Xq, Xs, Wq, Ws, Y, fmt, K=K)
         Wqc, Wsc = G.empty_u8(N, K // 2), G.empty_u8(N, K // 32)
         P.wush_unpack_tiled(Wq, Ws, N, K, Wqc, Wsc)
-        out.update(Wq=Wqc, Ws=Wsc, Y=Y)
+        out.update(Wq=Wqc, Ws=Wsc, Y=Y, Wq_tiled=Wq, Ws_tiled=Ws, Xq_tiled=Xq, Xs_tiled=Xs)
     torch.cuda.synchronize()
     return out
 
@@ -114,12 +116,55 @@ def _check_samples(G, L, T, out, rng, n_rows=48, n_wrows=48, n_cols=384):
     assert q_err < 0.25
 
 
+def _check_every_tile(P, G, L, out, rng, band=128, col_chunk=2048):
+    """FP32 output of the GEMM, one seeded token row per band of `band` rows (every tile shape of the
+    kernel is a multiple of 128 rows high) x all N columns: each output tile of each workgroup holds
+    at least one checked row segment.  Reference: the dequantized FP64 product of the GPU's own codes
+    (exact inputs; FP32 accumulation is the only difference): relative Frobenius error <= 1e-5 and
+    every element within 1e-5 |x| |w| (the scale of its partial sums).  The BF16 output on the same
+    rows must be the FP32 output rounded to nearest even, bit for bit."""
+    import torch
+    cfg = L["cfg"]
+    M, K, N = cfg.M, cfg.K, cfg.N
+    Y32 = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_linear(out["Xq_tiled"], out["Xs_tiled"], out["Wq_tiled"], out["Ws_tiled"], Y32,
+                  P.default_fmt(layout=1, out_dtype=1), K=K)
+    torch.cuda.synchronize()
+    assert not bool(Y32.isnan().any())
+    rows = np.array([min(b + int(rng.integers(0, band)), M - 1) for b in range(0, M, band)])
+    y32 = Y32[rows.tolist()].cpu().numpy()
+    ybf = G.host(out["Y"][rows.tolist()].contiguous())
+    del Y32
+    assert np.array_equal(ybf, O.bf16_values_to_bits(O.round_to_bf16(y32.astype(np.float64))))
+    xd = O.dequantize(O.unpack_codes(out["Xq"][rows.tolist()].cpu().numpy()), out["Xs"][rows.tolist()].cpu().numpy())
+    xn = np.linalg.norm(xd, axis=1)
+    wq_host, ws_host = out["Wq"].cpu().numpy(), out["Ws"].cpu().numpy()
+
+    def chunk(c0):      # column chunks in parallel threads: the oracle's dequantization is plain numpy
+        c1 = min(N, c0 + col_chunk)
+        wd = O.dequantize(O.unpack_codes(wq_host[c0:c1]), ws_host[c0:c1])
+        ref = xd @ wd.T
+        d = y32[:, c0:c1].astype(np.float64) - ref
+        rel = np.max(np.abs(d) / (xn[:, None] * np.linalg.norm(wd, axis=1)[None, :] + 1e-300))
+        return float(np.sum(d * d)), float(np.sum(ref * ref)), float(rel)
+
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        parts = list(ex.map(chunk, range(0, N, col_chunk)))
+    num, den, worst = sum(p[0] for p in parts), sum(p[1] for p in parts), max(p[2] for p in parts)
+    print(f"{cfg.name}: every-tile check on {len(rows)} rows x {N} columns: rel. Frobenius {np.sqrt(num / den):.2e}, "
+          f"largest element error / (|x| |w|) {worst:.2e}")
+    assert np.sqrt(num / den) <= 1e-5
+    assert worst <= 1e-5
+
+
 def test_c2_full(P, G):
     L = I.make_layer(I.CONFIGS["c2"])
     T = _transforms_blockwise(L)
     out = _run_layer(P, G, L, T)
     _check_samples(G, L, T, out, np.random.default_rng(2))
     assert not bool(out["Y"].isnan().any())
+    _check_every_tile(P, G, L, out, np.random.default_rng(12))
 
 
 def test_c3_full_wush_and_hadamard(P, G):
@@ -127,6 +172,8 @@ def test_c3_full_wush_and_hadamard(P, G):
     for name, T in (("wush", _transforms_blockwise(L)), ("hadamard", O.round_to_bf16(O.hadamard_transforms(L["cfg"].C)))):
         out = _run_layer(P, G, L, T)
         _check_samples(G, L, T, out, np.random.default_rng(3), n_rows=24, n_wrows=24, n_cols=256)
+        if name == "wush":
+            _check_every_tile(P, G, L, out, np.random.default_rng(13))
 
 
 def test_c4_activation_path_full_and_decode_sweep(P, G):
@@ -151,6 +198,7 @@ def test_c5_full(P, G):
     T = _transforms_blockwise(L)
     out = _run_layer(P, G, L, T)
     _check_samples(G, L, T, out, np.random.default_rng(5), n_rows=24, n_wrows=32, n_cols=256)
+    _check_every_tile(P, G, L, out, np.random.default_rng(15))
 
 
 def test_offsets_beyond_4_gib(P, G):

@@ -2,10 +2,13 @@
 
 The schedule is sequential with feedback: a transform entry that lands on the other side of a
 BF16 rounding boundary, or a weight code that flips at an exact tie, changes everything after
-it a little.  Both sides are FP64 with different summation orders (1e-16 relative), so such
-events are rare but possible; the bars below are therefore: transforms equal except for a
-few entries one BF16 step apart, scales and codes equal except for a small fraction, and the
-quality of the result (the output error GPTQ minimizes) equal to the oracle's within 1 %.
+it a little.  Both sides are FP64 with different summation orders (1e-16 relative), so such an
+event needs a value within 1e-15 of a boundary: on the layers below none occurs and the outputs
+are identical (also on the full c2 layer, 25 million codes).  The bars are set at that level:
+at most 1e-4 of the transform entries (each one BF16 step apart), of the scales and of the codes
+may differ -- on these sizes that is a handful of elements at most, where a wrong index in the
+propagation of a single block shifts every later block (a tenth of all codes or more) -- and the
+output error GPTQ minimizes must equal the oracle's to 1e-6 when nothing differs, 1e-3 otherwise.
 """
 import numpy as np
 import pytest
@@ -73,12 +76,13 @@ def _compare(T_gpu, c_gpu, s_gpu, T_ref, c_ref, s_ref, W, X, what):
     step = np.abs(T_gpu - T_ref) / np.maximum(np.abs(T_ref), 1e-30)
     print(f"{what}: T entries differing {dT.mean():.2e} (max relative step {step.max():.2e}), "
           f"scales differing {np.mean(s_gpu != s_ref):.2e}, codes differing {np.mean(c_gpu != c_ref):.2e}")
-    assert dT.mean() <= 2e-3 and step.max() <= 2.0 ** -7          # at most one BF16 step
-    assert np.mean(s_gpu != s_ref) <= 2e-3
-    assert np.mean(c_gpu != c_ref) <= 2e-2
+    n_diff = int(dT.sum()) + int(np.sum(s_gpu != s_ref)) + int(np.sum(c_gpu != c_ref))
+    assert dT.mean() <= 1e-4 and step.max() <= 2.0 ** -7          # at most one BF16 step
+    assert np.mean(s_gpu != s_ref) <= 1e-4
+    assert np.mean(c_gpu != c_ref) <= 1e-4
     l_gpu, l_ref = Q.proxy_loss(T_gpu, c_gpu, s_gpu, W, X), Q.proxy_loss(T_ref, c_ref, s_ref, W, X)
-    print(f"{what}: weight-only output MSE  oracle {l_ref:.5e}  GPU {l_gpu:.5e}")
-    assert abs(l_gpu - l_ref) <= 0.01 * l_ref
+    print(f"{what}: weight-only output MSE  oracle {l_ref:.5e}  GPU {l_gpu:.5e}  ({n_diff} differing values)")
+    assert abs(l_gpu - l_ref) <= (1e-6 if n_diff == 0 else 1e-3) * l_ref
     return l_gpu
 
 
