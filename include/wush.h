@@ -42,7 +42,10 @@
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
- *     allocates nothing and keeps no state between calls.
+ *     allocates nothing.  What it keeps between calls, per process and device: the
+ *     compute-unit count, which kernels had their LDS limit raised, and the fixed
+ *     scratch array of wush_layer_decode_static; no call's result depends on an
+ *     earlier call.
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only
  *     enqueue work and return; results are valid after the stream is
  *     synchronized.
@@ -74,7 +77,8 @@ typedef enum {
   WUSH_ERR_WORKSPACE = 5, /* workspace missing or too small */
   WUSH_ERR_DEVICE = 6,    /* the HIP runtime reported a launch error */
   WUSH_ERR_SINGULAR = 7,  /* a transform block is singular / a moment not positive definite */
-  WUSH_ERR_TIMEOUT = 8    /* wush_layer_decode: a workgroup gave up waiting at the grid-wide barrier */
+  WUSH_ERR_TIMEOUT = 8,   /* wush_layer_decode: a workgroup gave up waiting at the grid-wide barrier */
+  WUSH_ERR_TOO_LARGE = 9  /* wush_layer_decode_static: K beyond what its fixed scratch holds */
 } wush_status;
 
 enum { WUSH_E2M1 = 1 };
@@ -251,6 +255,23 @@ wush_status wush_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx,
                               wush_fmt fmt, void* Y, int64_t ldy,
                               void* workspace, size_t workspace_bytes, void* stream);
 wush_status wush_layer_decode_status(const void* workspace, int64_t K, void* stream);
+
+/*
+ * wush_layer_decode for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments without the workspace, same results bit for bit (it enqueues
+ * the same two kernels: quantizer, weight-streaming GEMM).  The quantized activations
+ * live in a fixed device array inside the library (1 088 KiB; each GPU the library runs
+ * on holds its own copy until the process ends), which limits K:
+ *   K <= 32768, otherwise WUSH_ERR_TOO_LARGE (nothing is launched).
+ * The call allocates nothing, frees nothing and needs no init call.  Every call on a GPU
+ * uses that GPU's one array: calls that overlap on one GPU (two streams, two threads)
+ * race and give undefined results; calls on one stream are ordered and safe.  The array
+ * keeps the previous call's contents; no call depends on them.
+ */
+wush_status wush_layer_decode_static(const void* X, int64_t M, int64_t K, int64_t ldx,
+                                     const void* T_blocks, const void* Wq, const void* Ws, int64_t N,
+                                     wush_fmt fmt, void* Y, int64_t ldy, void* stream);
 
 /*
  * ---------------------------------------------------------------------------

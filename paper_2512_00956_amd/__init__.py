@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     wush_calibrate_act_nvfp4,
     wush_layer_decode,
     wush_layer_decode_init,
+    wush_layer_decode_static,
     wush_layer_decode_status,
     wush_layer_decode_workspace,
     wush_linear,
@@ -51,7 +52,7 @@ __all__ = [
     "wush_prepare_weight_workspace", "wush_quantize_act", "wush_quantize_f32", "wush_status_string",
     "wush_workspace_status", "wush_packed_sizes", "wush_unpack_tiled", "wush_build_transforms",
     "wush_build_transforms_status", "wush_build_transforms_workspace", "wush_layer_decode",
-    "wush_layer_decode_init", "wush_layer_decode_status", "wush_layer_decode_workspace",
+    "wush_layer_decode_init", "wush_layer_decode_static", "wush_layer_decode_status", "wush_layer_decode_workspace",
     "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_status", "wush_prepare_weight_gptq_workspace",
     "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_status",
     "wush_prepare_weight_nvfp4_workspace", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",

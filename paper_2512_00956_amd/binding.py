@@ -22,6 +22,7 @@ WUSH_LAYOUT_CANONICAL, WUSH_LAYOUT_TILED = 0, 1
 STATUS_NAMES = {
     0: "WUSH_OK", 1: "WUSH_ERR_NULL", 2: "WUSH_ERR_SHAPE", 3: "WUSH_ERR_ALIGN", 4: "WUSH_ERR_FMT",
     5: "WUSH_ERR_WORKSPACE", 6: "WUSH_ERR_DEVICE", 7: "WUSH_ERR_SINGULAR", 8: "WUSH_ERR_TIMEOUT",
+    9: "WUSH_ERR_TOO_LARGE",
 }
 
 # every symbol include/wush.h declares
@@ -31,6 +32,7 @@ EXPORTS = (
     "wush_packed_sizes", "wush_unpack_tiled",
     "wush_build_transforms", "wush_build_transforms_workspace", "wush_build_transforms_status",
     "wush_layer_decode", "wush_layer_decode_workspace", "wush_layer_decode_init", "wush_layer_decode_status",
+    "wush_layer_decode_static",
     "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_workspace", "wush_prepare_weight_gptq_status",
     "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_workspace",
     "wush_prepare_weight_nvfp4_status", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
@@ -107,6 +109,9 @@ def lib() -> ctypes.CDLL:
         L.wush_layer_decode.restype = c_int32
         L.wush_layer_decode.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_int64,
                                         WushFmt, c_void_p, c_int64, c_void_p, c_size_t, c_void_p]
+        L.wush_layer_decode_static.restype = c_int32
+        L.wush_layer_decode_static.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_int64,
+                                               WushFmt, c_void_p, c_int64, c_void_p]
         L.wush_layer_decode_status.restype = c_int32
         L.wush_layer_decode_status.argtypes = [c_void_p, c_int64, c_void_p]
         L.wush_prepare_weight_gptq_workspace.restype = c_size_t
@@ -293,6 +298,16 @@ def wush_layer_decode(X, T_blocks, Wq, Ws, Y, workspace, fmt: WushFmt | None = N
     _check(lib().wush_layer_decode(_ptr(X), M, K, X.stride(0), _ptr(T_blocks), _ptr(Wq), _ptr(Ws), N,
                                    fmt or default_fmt(layout=WUSH_LAYOUT_TILED), _ptr(Y), Y.stride(0),
                                    _ptr(workspace), _nbytes(workspace), _stream(stream)), "wush_layer_decode")
+
+
+def wush_layer_decode_static(X, T_blocks, Wq, Ws, Y, fmt: WushFmt | None = None, stream=None):
+    """wush_layer_decode without a workspace (K <= 32768): the library's own fixed scratch holds the
+    quantized activations; allocates nothing."""
+    M, K = X.shape
+    N = Y.shape[1]
+    _check(lib().wush_layer_decode_static(_ptr(X), M, K, X.stride(0), _ptr(T_blocks), _ptr(Wq), _ptr(Ws), N,
+                                          fmt or default_fmt(layout=WUSH_LAYOUT_TILED), _ptr(Y), Y.stride(0),
+                                          _stream(stream)), "wush_layer_decode_static")
 
 
 def wush_layer_decode_status(workspace, K: int, stream=None):

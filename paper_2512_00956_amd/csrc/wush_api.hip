@@ -248,6 +248,62 @@ wush_status wush_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx, 
   return from_hip(wush::launch_mxfp4_gemm_skinny(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, st));
 }
 
+// ---------------------------------------------------------------------------
+// wush_layer_decode_static: wush_layer_decode (two-launch form) for callers that can neither
+// allocate nor pass a workspace.  The quantized activations live in a file-scope device array;
+// every GPU the library runs on holds its own copy of it at its own address, looked up once per
+// device with hipGetSymbolAddress (the array's name is only a host-side stand-in: host code
+// must never pass it to a kernel) and kept in scratch_ptr[].
+// ---------------------------------------------------------------------------
+namespace {
+
+constexpr int64_t kStaticDecodeMaxK = 32768;
+// codes of two 32-token row blocks, then their scales: (K / 256) * (2 * 4096 + 2 * 256) bytes
+constexpr size_t kStaticScratchBytes = (size_t)(kStaticDecodeMaxK / 256) * (2 * 4096 + 2 * 256);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::atomic<unsigned char*> scratch_ptr[64];   // per device; zero-initialized
+
+wush_status scratch_of_current_device(unsigned char** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return WUSH_ERR_DEVICE;
+  const bool tracked = dev >= 0 && dev < 64;
+  unsigned char* p = tracked ? scratch_ptr[dev].load(std::memory_order_acquire) : nullptr;
+  if (!p) {
+    if (hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)) != hipSuccess || !p) return WUSH_ERR_DEVICE;
+    if (tracked) scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return WUSH_OK;
+}
+
+}  // namespace
+
+wush_status wush_layer_decode_static(const void* X, int64_t M, int64_t K, int64_t ldx, const void* T_blocks,
+                                     const void* Wq, const void* Ws, int64_t N, wush_fmt fmt, void* Y, int64_t ldy,
+                                     void* stream) {
+  if (!X || !T_blocks || !Wq || !Ws || !Y) return WUSH_ERR_NULL;
+  if (wush_status s = check_fmt(fmt)) return s;
+  if (fmt.layout != WUSH_LAYOUT_TILED) return WUSH_ERR_FMT;
+  if (wush_status s = check_rows(M, K, ldx)) return s;
+  if (M > 64 || K % 256 != 0 || N <= 0 || N > kMaxDim || ldy < N) return WUSH_ERR_SHAPE;
+  if (K > kStaticDecodeMaxK) return WUSH_ERR_TOO_LARGE;
+  if (!aligned16(X) || !aligned16(T_blocks) || !aligned16(Wq) || !aligned16(Ws)) return WUSH_ERR_ALIGN;
+  const uintptr_t elem = fmt.out_dtype == WUSH_OUT_F32 ? 4 : 2;
+  if (reinterpret_cast<uintptr_t>(Y) % elem != 0) return WUSH_ERR_ALIGN;
+  unsigned char* sc = nullptr;
+  if (wush_status s = scratch_of_current_device(&sc)) return s;
+  // Same positions inside the scratch as inside a wush_layer_decode workspace of this K.  Nothing has
+  // to start at zero: the quantizer writes every row below M of the row blocks the GEMM reads, and the
+  // rows from M to the end of the last block (whatever an earlier call left there: valid codes and
+  // scale bytes, or the zeros the array starts with) only reach output rows that are never stored.
+  void* Xq = sc;
+  void* Xs = sc + wush::layer_decode_scales_offset(K);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipError_t e = wush::launch_transform_quant(X, M, K, ldx, T_blocks, fmt.scale_rule, 1, Xq, Xs, nullptr, st))
+    return from_hip(e);
+  return from_hip(wush::launch_mxfp4_gemm_skinny(Xq, Xs, Wq, Ws, M, N, K, fmt.out_dtype == WUSH_OUT_F32, Y, ldy, st));
+}
+
 wush_status wush_layer_decode_status(const void* workspace, int64_t K, void* stream) {
   if (!workspace) return WUSH_ERR_NULL;
   if (K <= 0 || K % 256 != 0 || K > kMaxK) return WUSH_ERR_SHAPE;
@@ -449,6 +505,7 @@ const char* wush_status_string(wush_status st) {
     case WUSH_ERR_DEVICE: return "HIP runtime error";
     case WUSH_ERR_SINGULAR: return "singular transform block";
     case WUSH_ERR_TIMEOUT: return "grid barrier wait expired";
+    case WUSH_ERR_TOO_LARGE: return "size beyond the fixed scratch of this entry point";
   }
   return "unknown status";
 }
