@@ -23,7 +23,7 @@ Prints ONE JSON line:
              workload's own operand bits, and with all-equal operands), the shader clock
              under each, and a plain 1 GiB device copy
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|d2|d5|fig3|n2|n5|i2|i5]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|d2|d5|dn2|dn5|di2|di5|fig3|n2|n5|i2|i5]
 
 The decode workloads d2/d5 time wush_layer_decode (16 tokens) by replaying a
 captured graph of the steps, so that the host's launch cost is not what is
@@ -80,6 +80,11 @@ WORKLOADS["n2"] = "the c2 layer in the NVFP4 variant (E4M3 scale per 16, 16 x 16
 WORKLOADS["n5"] = "the c5 layer in the NVFP4 variant, M=8192 K=8192 N=57344"
 WORKLOADS["i2"] = "the c2 layer in the INT4 variant (BF16 scale per 32, Gaussian-MSE step), M=2048 K=4096 N=6144"
 WORKLOADS["i5"] = "the c5 layer in the INT4 variant, M=8192 K=8192 N=57344"
+WORKLOADS["dn2"] = "decode-sized batch on the c2 layer in the NVFP4 variant, M=16 K=4096 N=6144"
+WORKLOADS["dn5"] = "decode-sized batch on the c5 layer in the NVFP4 variant, M=16 K=8192 N=57344"
+WORKLOADS["di2"] = "decode-sized batch on the c2 layer in the INT4 variant, M=16 K=4096 N=6144"
+WORKLOADS["di5"] = "decode-sized batch on the c5 layer in the INT4 variant, M=16 K=8192 N=57344"
+W4_DECODE = {"dn2": ("nvfp4", "c2"), "dn5": ("nvfp4", "c5"), "di2": ("int4", "c2"), "di5": ("int4", "c5")}
 NVFP4 = {"n2": "c2", "n5": "c5"}
 INT4 = {"i2": "c2", "i5": "c5"}
 DECODE = {"d2": "c2", "d5": "c5"}
@@ -298,6 +303,90 @@ def decode_bench(args, P, torch, dev):
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, T_bits, L, M)
+    print(json.dumps(out))
+
+
+def w4_decode_bench(args, P, torch, dev):
+    """dn2 / dn5 / di2 / di5: one step = activation quantizer + weight-streaming GEMM of the NVFP4 or INT4
+    variant on 16 tokens (tiled layout), timed by replaying a captured graph of the steps.  Roofline: the
+    GEMM against HBM (the packed weights are read once per step)."""
+    fmt_name, base = W4_DECODE[args.workload]
+    cfg = I.scaled(I.CONFIGS[base], M=DECODE_TOKENS)
+    L = I.make_layer(I.CONFIGS[base])
+    M, K, N = cfg.M, cfg.K, cfg.N
+    nv = fmt_name == "nvfp4"
+
+    def bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    d = 16 if nv else 32
+    Td = torch.empty((K // d, d, d), dtype=torch.bfloat16, device=dev)
+    bws = torch.empty(P.wush_build_transforms_workspace(K), dtype=torch.uint8, device=dev)
+    Wd = bf16(L["W"])
+    (P.wush_build_transforms_nvfp4 if nv else P.wush_build_transforms)(Wd, bf16(L["X_cal"]), 1e-2, Td, bws)
+    P.wush_build_transforms_status(bws, K)
+    Xd = bf16(L["X"][:M])
+    (xcb, xsb), (wcb, wsb) = P.wush_packed_sizes_nvfp4(M, K, 1), P.wush_packed_sizes_nvfp4(N, K, 1)
+    Xq, Xs = (torch.empty(n, dtype=torch.uint8, device=dev) for n in (xcb, xsb))
+    Wq, Ws = (torch.empty(n, dtype=torch.uint8, device=dev) for n in (wcb, wsb))
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    if nv:
+        tsx, tsw = (torch.zeros(1, dtype=torch.float32, device=dev) for _ in range(2))
+        P.wush_calibrate_act_nvfp4(Xd, Td, tsx)
+        wsp = torch.empty(P.wush_prepare_weight_nvfp4_workspace(K), dtype=torch.uint8, device=dev)
+        P.wush_prepare_weight_nvfp4(Wd, Td, Wq, Ws, tsw, wsp, layout=1)
+        P.wush_prepare_weight_nvfp4_status(wsp, K)
+        quant = lambda: P.wush_quantize_act_nvfp4(Xd, Td, tsx, Xq, Xs, layout=1)
+        gemm = lambda: P.wush_linear_nvfp4(Xq, Xs, tsx, Wq, Ws, tsw, Y, layout=1, K=K)
+    else:
+        wsp = torch.empty(P.wush_prepare_weight_workspace(N, K), dtype=torch.uint8, device=dev)
+        P.wush_prepare_weight_int4(Wd, Td, Wq, Ws, wsp, layout=1)
+        P.wush_workspace_status(wsp, K)
+        quant = lambda: P.wush_quantize_act_int4(Xd, Td, Xq, Xs, layout=1)
+        gemm = lambda: P.wush_linear_int4(Xq, Xs, Wq, Ws, Y, layout=1, K=K)
+    del Wd, wsp, bws
+
+    def replay_ms(fn, calls):
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            for _ in range(max(3, args.warmup)):
+                fn()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                for _ in range(calls):
+                    fn()
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            g.replay()
+            e1.record(st)
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / calls
+
+    def step():
+        quant()
+        gemm()
+    ms_per_step = replay_ms(step, args.steps)
+    g_ms = replay_ms(gemm, args.steps)
+    gemm_bytes = (N + M) * K * (0.5 + 1 / 16) + M * N * 2
+    flops = 2.0 * M * N * K
+    name = "wush_linear_nvfp4" if nv else "wush_linear_int4"
+    out = {
+        "metric": f"W4A4 layer TFLOP/s (transform+quant+{fmt_name.upper()} GEMM); % of HBM peak",
+        "value": flops / ms_per_step / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": ("nvfp4 (e2m1 x e4m3 per 16 x f32 per tensor)" if nv else "int4 (two's complement x bf16 per 32)") +
+                 ", bf16 in/out, f16 MFMA operands, f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
+                   "launch": "graph replay of the timed steps", "packed_layout": "tiled"},
+        "roofline": {"bound": "hbm", "kernel": f"{name} for M <= 128 (weight-streaming, dequantize in registers)",
+                     "achieved": gemm_bytes / g_ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gemm_bytes / g_ms / 1e6 / PEAK_HBM_GBS, "traffic": None, "algorithmic_bytes": gemm_bytes,
+                     "avg_launch_ms": g_ms},
+        "kernels": {name: {"ms": g_ms, "GB/s": gemm_bytes / g_ms / 1e6}},
+    }
     print(json.dumps(out))
 
 
@@ -578,6 +667,9 @@ def main():
         return
     if args.workload == "fig3":
         fig3_bench(args, P, torch, dev)
+        return
+    if args.workload in W4_DECODE:
+        w4_decode_bench(args, P, torch, dev)
         return
     if args.workload in NVFP4:
         nvfp4_bench(args, P, torch, dev)

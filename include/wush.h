@@ -43,9 +43,9 @@
  * General conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
  *     allocates nothing.  What it keeps between calls, per process and device: the
- *     compute-unit count, which kernels had their LDS limit raised, and the fixed
- *     scratch array of wush_layer_decode_static; no call's result depends on an
- *     earlier call.
+ *     compute-unit count, which kernels had their LDS limit raised, the fixed
+ *     scratch array of wush_layer_decode_static, and the switches of wush_debug_set;
+ *     no call's result depends on an earlier call.
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only
  *     enqueue work and return; results are valid after the stream is
  *     synchronized.
@@ -226,8 +226,8 @@ wush_status wush_linear(const void* Xq, const void* Xs, const void* Wq, const vo
  * followed by wush_linear: identical codes and scales, identical FP32
  * accumulation order per output.  The quantized activations live only in the
  * workspace, and the GEMM is the weight-streaming kernel for few tokens.
- * Two forms exist.  The default enqueues two kernels (quantizer, GEMM).  With the
- * environment variable WUSH_DECODE_FUSED=1 the call is ONE kernel launch:
+ * Two forms exist.  The default enqueues two kernels (quantizer, GEMM).  After
+ * wush_debug_set(WUSH_DEBUG_DECODE_FUSED, 1) the call is ONE kernel launch:
  * quantization, a grid-wide barrier, then the GEMM, with the weight stream
  * started before the barrier.  On MI355X the barrier across the eight XCDs costs
  * more (4-6 us) than the gap between two kernels of one stream (1.5-2 us), so
@@ -456,6 +456,26 @@ wush_status wush_packed_sizes(int64_t rows, int64_t K, wush_fmt fmt,
  */
 wush_status wush_unpack_tiled(const void* q_tiled, const void* s_tiled, int64_t rows, int64_t K,
                               void* q, void* s, void* stream);
+
+/*
+ * Switches for tests and measurements: which kernel or tile shape a call takes where the
+ * library would otherwise choose by itself.  Process-wide, read by every later call on any
+ * thread; value -1 restores the library's own choice.  Results do not depend on them beyond
+ * the accumulation order of a GEMM; nothing reads the environment.
+ *   WUSH_DEBUG_GEMM_TILE            wush_linear, tiled layout: 0..3 = 256x256, 128x384, 128x256, 128x128 tiles
+ *   WUSH_DEBUG_GEMM_SKINNY          wush_linear up to 128 tokens: 1 = weight-streaming kernel, 0 = tiled kernel
+ *   WUSH_DEBUG_GEMM_SIMPLE          wush_linear, canonical layout: 1 = the general one-wave-per-tile kernel
+ *   WUSH_DEBUG_W4_WIDTH             wush_linear_nvfp4 / _int4: tile width 2..4 (x 64 output channels)
+ *   WUSH_DEBUG_W4_SKINNY            wush_linear_nvfp4 / _int4 up to 128 tokens: 1 = weight-streaming, 0 = tiled
+ *   WUSH_DEBUG_DECODE_FUSED         wush_layer_decode: 1 = one launch with a grid-wide barrier
+ *   WUSH_DEBUG_DECODE_TEST_TIMEOUT  wush_layer_decode: 1 = the barrier wait gives up at once (error-path test)
+ * Returns WUSH_ERR_FMT for an unknown option, WUSH_ERR_SHAPE for a value outside -1 .. 1023.
+ */
+enum {
+  WUSH_DEBUG_GEMM_TILE = 0, WUSH_DEBUG_GEMM_SKINNY = 1, WUSH_DEBUG_GEMM_SIMPLE = 2, WUSH_DEBUG_W4_WIDTH = 3,
+  WUSH_DEBUG_W4_SKINNY = 4, WUSH_DEBUG_DECODE_FUSED = 5, WUSH_DEBUG_DECODE_TEST_TIMEOUT = 6
+};
+wush_status wush_debug_set(int32_t option, int32_t value);
 
 /* Human-readable name of a status code; static storage, never NULL. */
 const char* wush_status_string(wush_status st);

@@ -18,6 +18,8 @@ _LIB_NAME = "libwush.so"
 WUSH_SCALE_NOSAT, WUSH_SCALE_OCP_FLOOR = 0, 1
 WUSH_OUT_BF16, WUSH_OUT_F32 = 0, 1
 WUSH_LAYOUT_CANONICAL, WUSH_LAYOUT_TILED = 0, 1
+(WUSH_DEBUG_GEMM_TILE, WUSH_DEBUG_GEMM_SKINNY, WUSH_DEBUG_GEMM_SIMPLE, WUSH_DEBUG_W4_WIDTH, WUSH_DEBUG_W4_SKINNY,
+ WUSH_DEBUG_DECODE_FUSED, WUSH_DEBUG_DECODE_TEST_TIMEOUT) = range(7)
 
 STATUS_NAMES = {
     0: "WUSH_OK", 1: "WUSH_ERR_NULL", 2: "WUSH_ERR_SHAPE", 3: "WUSH_ERR_ALIGN", 4: "WUSH_ERR_FMT",
@@ -32,7 +34,7 @@ EXPORTS = (
     "wush_packed_sizes", "wush_unpack_tiled",
     "wush_build_transforms", "wush_build_transforms_workspace", "wush_build_transforms_status",
     "wush_layer_decode", "wush_layer_decode_workspace", "wush_layer_decode_init", "wush_layer_decode_status",
-    "wush_layer_decode_static",
+    "wush_layer_decode_static", "wush_debug_set",
     "wush_prepare_weight_gptq", "wush_prepare_weight_gptq_workspace", "wush_prepare_weight_gptq_status",
     "wush_quantize_act_nvfp4", "wush_prepare_weight_nvfp4", "wush_prepare_weight_nvfp4_workspace",
     "wush_prepare_weight_nvfp4_status", "wush_linear_nvfp4", "wush_quantize_f32_nvfp4",
@@ -112,6 +114,8 @@ def lib() -> ctypes.CDLL:
         L.wush_layer_decode_static.restype = c_int32
         L.wush_layer_decode_static.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_int64,
                                                WushFmt, c_void_p, c_int64, c_void_p]
+        L.wush_debug_set.restype = c_int32
+        L.wush_debug_set.argtypes = [c_int32, c_int32]
         L.wush_layer_decode_status.restype = c_int32
         L.wush_layer_decode_status.argtypes = [c_void_p, c_int64, c_void_p]
         L.wush_prepare_weight_gptq_workspace.restype = c_size_t
@@ -181,6 +185,11 @@ def wush_unpack_tiled(q_tiled, s_tiled, rows: int, K: int, q, s, stream=None):
     """Tiled -> canonical copy (q u8 [rows][K/2], s u8 [rows][K/32])."""
     _check(lib().wush_unpack_tiled(_ptr(q_tiled), _ptr(s_tiled), rows, K, _ptr(q), _ptr(s), _stream(stream)),
            "wush_unpack_tiled")
+
+
+def wush_debug_set(option: int, value: int):
+    """Test / measurement switch (WUSH_DEBUG_*): force a kernel or tile shape; value -1 = the library's choice."""
+    _check(lib().wush_debug_set(int(option), int(value)), "wush_debug_set")
 
 
 def wush_status_string(code: int) -> str:

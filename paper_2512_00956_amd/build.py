@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwush.so")
 PROBES_SRC = os.path.join(HERE, "probes", "probes.hip")
 PROBES_LIB = os.path.join(HERE, "libwush_probes.so")
-SOURCES = ["wush_api.hip", "transform_quant.hip", "weight_prep.hip", "mxfp4_gemm.hip", "mxfp4_gemm_frag.hip", "build_transforms.hip", "layer_decode.hip", "gptq_prep.hip", "nvfp4_quant.hip", "nvfp4_gemm.hip", "int4_quant.hip"]
+SOURCES = ["wush_api.hip", "transform_quant.hip", "weight_prep.hip", "mxfp4_gemm.hip", "mxfp4_gemm_frag.hip", "build_transforms.hip", "layer_decode.hip", "gptq_prep.hip", "nvfp4_quant.hip", "nvfp4_gemm.hip", "int4_quant.hip", "w4_gemm_skinny.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

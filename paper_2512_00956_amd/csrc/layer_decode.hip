@@ -38,6 +38,7 @@
 // The barrier needs all workgroups resident: the grid is capped at one workgroup
 // per CU, and every wait is bounded -- on expiry the workgroup records an error
 // and exits without touching Y.
+#include "skinny_reduce.hpp"
 #include "transform_quant_core.hpp"
 #include "wush_kernels.hpp"
 
@@ -45,7 +46,10 @@ namespace wush {
 
 namespace {
 
-constexpr int kWaves = 4;
+using skinny::kWaves;
+using skinny::reduce_store_block;
+using skinny::wave_k_range;
+using skinny::decode_vec_store;
 constexpr uint32_t kSpinLimit = 1u << 21;   // polls of about 0.5 us each
 constexpr int kMaxGrid = 1024;              // barrier slots in the workspace
 
@@ -117,63 +121,6 @@ __device__ __forceinline__ void accumulate_block(v16f (&acc)[RB], FragTile (&w)[
       }
 #undef WUSH_SKINNY_ISSUE
   }
-}
-
-// Sum the four waves' partial tiles of column block j (fixed order 0,1,2,3) and
-// store.  Accumulator e of lane (r, kh), row block rb is token 32*rb + r, output
-// channel 32*j + 8*(e/4) + 4*kh + e%4; wave w finishes the quads e/4 == w.
-template <int RB, bool OUT_F32>
-__device__ __forceinline__ void reduce_store_block(const v16f (&acc)[RB], float (*red)[RB][16][64], int j, int M, int N,
-                                                   void* __restrict__ Y, int64_t ldy, int vec_store, int lane, int wave) {
-  const int r = lane & 31, kh = lane >> 5;
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) red[wave][rb][e][lane] = acc[rb][e];
-  __syncthreads();
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    float v[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int e = 4 * wave + t;
-      v[t] = ((red[0][rb][e][lane] + red[1][rb][e][lane]) + red[2][rb][e][lane]) + red[3][rb][e][lane];
-    }
-    const int row = 32 * rb + r;
-    const int col = 32 * j + 8 * wave + 4 * kh;
-    if (row < M && col < N) {
-      if (OUT_F32) {
-        float* y = reinterpret_cast<float*>(Y) + (int64_t)row * ldy + col;
-        if (vec_store) {
-          *reinterpret_cast<v4f*>(y) = (v4f){v[0], v[1], v[2], v[3]};
-        } else {
-#pragma unroll
-          for (int t = 0; t < 4; ++t)
-            if (col + t < N) y[t] = v[t];
-        }
-      } else {
-        uint16_t* y = reinterpret_cast<uint16_t*>(Y) + (int64_t)row * ldy + col;
-        if (vec_store) {
-          v2u two;
-          two[0] = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-          two[1] = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-          *reinterpret_cast<v2u*>(y) = two;
-        } else {
-#pragma unroll
-          for (int t = 0; t < 4; ++t)
-            if (col + t < N) y[t] = f32_to_bf16_bits(v[t]);
-        }
-      }
-    }
-  }
-  __syncthreads();   // red is rewritten by the next column block
-}
-
-// Contiguous K-tile range of a wave: the four waves split KT as evenly as possible.
-__device__ __forceinline__ void wave_k_range(int KT, int wave, int& kt0, int& kt1) {
-  const int q = (KT + kWaves - 1) / kWaves;
-  kt0 = min(wave * q, KT);
-  kt1 = min(kt0 + q, KT);
 }
 
 template <int RB, bool OUT_F32>
@@ -302,12 +249,6 @@ __global__ __launch_bounds__(kWaves * 64) void layer_decode_kernel(
 
 __global__ void decode_state_reset_kernel(uint32_t* state) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kStateWords; i += gridDim.x * blockDim.x) state[i] = 0;
-}
-
-// 8-byte (BF16) / 16-byte (FP32) stores of four consecutive channels
-int decode_vec_store(const void* Y, int64_t N, int64_t ldy, int out_f32) {
-  const uintptr_t a = reinterpret_cast<uintptr_t>(Y);
-  return (N % 4 == 0) && (ldy % 4 == 0) && (a % (out_f32 ? 16 : 8) == 0);
 }
 
 // Workgroups that are certainly resident together: one per CU, given that the

@@ -8,8 +8,6 @@
 // half l/32 -- 16 bytes of the canonical packed layout -- plus the one scale
 // byte of exactly that group.  Accumulator r of lane l is output row
 // 8*(r/4) + 4*(l/32) + r%4, column l%32.
-#include <stdlib.h>
-
 #include "wush_device.hpp"
 #include <math.h>
 
@@ -280,16 +278,11 @@ hipError_t launch_mxfp4_gemm(const void* Xq, const void* Xs, const void* Wq, con
       const double tiled_us = fmax(4.3 + 0.3 * (double)(K / 256) * tile_rounds, weight_mib / 6.4 + 4.0);
       skinny = skinny_us < tiled_us;
     }
-    if (M <= 128)
-      if (const char* e = getenv("WUSH_GEMM_SKINNY")) skinny = e[0] == '1';   // debug knob: force either kernel up to 128 tokens
+    if (M <= 128 && debug_option(kDbgGemmSkinny) >= 0) skinny = debug_option(kDbgGemmSkinny) == 1;   // tests: force either kernel
     if (skinny) return launch_mxfp4_gemm_skinny(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
     return launch_mxfp4_gemm_frag(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
   }
-  // Debug knob: WUSH_GEMM=simple forces the general kernel.
-  static const bool force_simple = [] {
-    const char* e = getenv("WUSH_GEMM");
-    return e && e[0] == 's';
-  }();
+  const bool force_simple = debug_option(kDbgGemmSimple) == 1;   // tests: the general kernel
   const bool tiled_ok = !force_simple && (K % 256 == 0) && (M * N >= 128 * 128);
   if (tiled_ok) {
     static DynamicLdsLimit lds_bf16, lds_f32;

@@ -42,8 +42,6 @@
 // register assignment over the whole kernel (no copy of a register whose load
 // is still in flight) and nothing spills; tests/test_build_invariants.py
 // checks both on the generated code.
-#include <stdlib.h>
-
 #include <type_traits>
 
 #include "wush_device.hpp"
@@ -501,13 +499,13 @@ hipError_t launch_mxfp4_gemm_frag(const void* Xq, const void* Xs, const void* Wq
   const int cus = device_cu_count();
   // Four instantiations: 256 x 256 (8 x 2 MFMA tiles per wave), 128 x 384 (4 x 3), 128 x 256 (4 x 2)
   // and 128 x 128 (4 x 1).  The cheapest by the estimate above wins, ties go to the larger tile
-  // (less operand traffic).  WUSH_GEMM_TILE=0..3 forces one of them (debug knob).
+  // (less operand traffic).  wush_debug_set(WUSH_DEBUG_GEMM_TILE, 0..3) forces one of them.
   const double cost[4] = {shape_cost_us(M, N, K, 256, 256, 1.51, 7.4, cus), shape_cost_us(M, N, K, 128, 384, 1.175, 5.1, cus),
                           shape_cost_us(M, N, K, 128, 256, 0.8125, 4.1, cus), shape_cost_us(M, N, K, 128, 128, 0.5125, 0.6, cus)};
   int shape = 0;
   for (int c = 1; c < 4; ++c)
     if (cost[c] < cost[shape]) shape = c;
-  if (const char* e = getenv("WUSH_GEMM_TILE")) shape = (e[0] >= '0' && e[0] <= '3') ? e[0] - '0' : 0;
+  if (const int forced = debug_option(kDbgGemmTile); forced >= 0 && forced <= 3) shape = forced;
   if (shape == 1) {
     if (out_f32) return launch_shape<true, 4, 3>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);
     return launch_shape<false, 4, 3>(Xq, Xs, Wq, Ws, M, N, K, Y, ldy, stream);

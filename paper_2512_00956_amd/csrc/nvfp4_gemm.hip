@@ -28,21 +28,17 @@
 // instruction and a handful of independent vector instructions issue in that shadow for free,
 // while anything issued as a block (conversions, register moves, global loads, address
 // arithmetic) stalls the pipe for its length.
-#include <stdlib.h>
-
 #include <type_traits>
 #include <utility>
 
 #include "nvfp4_layout.hpp"
+#include "w4_dequant.hpp"
 #include "wush_device.hpp"
 #include "wush_kernels.hpp"
 
 namespace wush {
 
 namespace {
-
-typedef _Float16 v2h __attribute__((ext_vector_type(2)));
-typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
 constexpr int kBM = 256, kBK = 64;
 constexpr int kXBytes = 8 * 256 * 16;            // X part of a stage: [k chunk of 8][256 rows][16 B]
@@ -116,51 +112,6 @@ __device__ __forceinline__ void load_raw(Raw& r, OperandAddr& a, const Strides& 
   r.s = load_scales(a, st, kt);
 }
 
-// Two E4M3 scale bytes (word `HI` of the row's scale dword) -> two FP16 values, by the
-// hardware FP8 convert (gfx950 reads FP8 as OCP E4M3); every finite E4M3 value is an
-// FP16 normal, so the conversion is exact.
-template <bool HI>
-__device__ __forceinline__ v2h e4m3x2_to_f16(uint32_t scales) {
-  return __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(scales, 1.0f, HI);
-}
-
-// Eight codes (one dword, element i in nibble i) times the group scale -> 8 FP16.
-__device__ __forceinline__ v4u dequant8(uint32_t w, v2h s) {
-  const float one = 1.0f;
-  union { v2h h[4]; v4u u; } c;
-  c.h[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, one, 0) * s;
-  c.h[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, one, 1) * s;
-  c.h[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, one, 2) * s;
-  c.h[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, one, 3) * s;
-  return c.u;
-}
-
-// Eight two's-complement INT4 codes times the group scale -> 8 FP16.  With the sign bits flipped a
-// nibble n' = n ^ 8 holds code + 8.  OR-ed into the fraction of an FP16 constant where it stands, it
-// becomes 1024 + n' (nibble in bits 0-3 of a half: unit 2^0 in the binade of 1024) or 64 + n' (bits
-// 4-7: unit 2^-6 * 64); subtracting 1032 or 72 leaves the signed code, exactly; code * scale has at
-// most 3 + 8 significant bits: exact in FP16 too.  One shift by 8 brings the other four nibbles to the
-// same two positions, so the eight codes come out in the order 0 4 | 1 5 | 2 6 | 3 7: both operands
-// of the GEMM go through this function, and the MFMA's sum over k does not care about the order.
-constexpr uint32_t kInt4Mask[2] = {0x000F000Fu, 0x00F000F0u}, kInt4Magic[2] = {0x64006400u, 0x54005400u};
-__device__ __forceinline__ v2h int4_pair(uint32_t x, int pos) {   // pos = 0: nibbles at bits 0-3, 1: bits 4-7
-  union { uint32_t u; v2h h; } t;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t.u) : "v"(x), "s"(kInt4Mask[pos]), "v"(kInt4Magic[pos]));
-  return t.h;
-}
-__device__ __forceinline__ v2h int4_bias(int pos) {
-  const _Float16 b = pos ? (_Float16)72.0f : (_Float16)1032.0f;
-  return (v2h){b, b};
-}
-__device__ __forceinline__ v4u dequant8_int4(uint32_t w, v2h s) {
-  const uint32_t x = w ^ 0x88888888u, y = x >> 8;
-  union { v2h h[4]; v4u u; } c;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) c.h[i] = (int4_pair(i < 2 ? x : y, i & 1) - int4_bias(i & 1)) * s;
-  return c.u;
-}
-
-constexpr int kNvfp4 = 0, kInt4 = 1;
 
 // Group g (16 elements) of a row's K step: two 16-byte LDS chunks, k = 16g + 8hh + 0..7.
 // `operand` = the X or W part of a stage, `rows` = its row count.  The row's scale dword holds
@@ -476,19 +427,6 @@ __device__ __forceinline__ void w_micro_op(ConvW<FMT>& c, uint32_t w, v2h s, Fra
     else f.h[U - 10] = f.h[U - 10] * s;
   }
 }
-// The scales of a lane's 32 W codes of a K step as FP16: bytes 2h, 2h+1 of the row's scale dword,
-// h = the lane's half.  NVFP4: two E4M3 bytes, [0] for groups 0 and 1, [1] for groups 2 and 3.
-// INT4: one BF16 number, in both.  sel = 0x05040C0C + 0x02020000 h (byte selector that moves the
-// two bytes to the top of a dword).
-template <int FMT>
-__device__ __forceinline__ v2h w_step_scales(uint32_t sdw, int h, uint32_t sel) {
-  if constexpr (FMT == kNvfp4) return e4m3x2_to_f16<false>(sdw >> (16 * h));
-  else {
-    const _Float16 sc = (_Float16)__uint_as_float(__builtin_amdgcn_perm(sdw, sdw, sel));
-    return (v2h){sc, sc};
-  }
-}
-
 template <bool OUT_F32, int CB, int FMT>
 __global__ __launch_bounds__(256) void w4_wreg_gemm_kernel(
     const uint8_t* __restrict__ Xq, const uint8_t* __restrict__ Xs, const float* __restrict__ tsx,
@@ -700,9 +638,7 @@ hipError_t launch_w4_f16_gemm(const void* Xq, const void* Xs, const float* tsx, 
   int best = 4;
   for (int cb = 3; cb >= 2; --cb)
     if (width_cost(M, N, cb, cus) < width_cost(M, N, best, cus)) best = cb;   // ties keep the wider tile
-  if (const char* f = getenv("WUSH_NVFP4_WIDTH")) {  // tests: force a tile width (output channels / 64)
-    if (f[0] >= '2' && f[0] <= '4' && f[1] == 0) best = f[0] - '0';
-  }
+  if (const int forced = debug_option(kDbgW4Width); forced >= 2 && forced <= 4) best = forced;   // tests: force a tile width
   if (K % 128 == 0) {   // an even number of K steps: W in registers
 #define WUSH_WR_LAUNCH(F32, CB) launch_wreg<F32, CB, FMT>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, tiled, Y, ldy, stream)
     if (out_f32) return best == 4 ? WUSH_WR_LAUNCH(true, 4) : best == 3 ? WUSH_WR_LAUNCH(true, 3) : WUSH_WR_LAUNCH(true, 2);
@@ -717,14 +653,24 @@ hipError_t launch_w4_f16_gemm(const void* Xq, const void* Xs, const float* tsx, 
 
 }  // namespace
 
+// Up to 128 tokens the layer is bound by reading the weights once: the weight-streaming kernel of
+// w4_gemm_skinny.hip takes over (tiled layout only; the switch kDbgW4Skinny forces either kernel).
+static bool w4_streaming(int64_t M, int tiled) {
+  if (!tiled || M > 128) return false;
+  const int forced = debug_option(kDbgW4Skinny);
+  return forced >= 0 ? forced == 1 : true;
+}
+
 hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
                              const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y,
                              int64_t ldy, hipStream_t stream) {
+  if (w4_streaming(M, tiled)) return launch_nvfp4_gemm_skinny(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, out_f32, Y, ldy, stream);
   return launch_w4_f16_gemm<kNvfp4>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, out_f32, tiled, Y, ldy, stream);
 }
 
 hipError_t launch_int4_gemm(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M, int64_t N,
                             int64_t K, int out_f32, int tiled, void* Y, int64_t ldy, hipStream_t stream) {
+  if (w4_streaming(M, tiled)) return launch_int4_gemm_skinny(Xq, Xs, Wq, Ws, M, N, K, out_f32, Y, ldy, stream);
   return launch_w4_f16_gemm<kInt4>(Xq, Xs, nullptr, Wq, Ws, nullptr, M, N, K, out_f32, tiled, Y, ldy, stream);
 }
 

@@ -1,10 +1,11 @@
 // C ABI of the library: argument validation, then kernel launches on the
-// caller's stream.  No allocation, no global state, no host synchronization
-// (except wush_workspace_status, which is documented to block).
+// caller's stream.  No allocation, no host synchronization (except the *_status
+// calls, which are documented to block).  Process-wide state: the switches of
+// wush_debug_set and the per-device caches named in the header.
 #include "../../include/wush.h"
 
 #include <hip/hip_runtime.h>
-#include <stdlib.h>
+#include <atomic>
 
 #include "wush_kernels.hpp"
 
@@ -45,7 +46,14 @@ inline wush_status check_rows(int64_t rows, int64_t K, int64_t ld) {
 
 inline wush_status from_hip(hipError_t e) { return e == hipSuccess ? WUSH_OK : WUSH_ERR_DEVICE; }
 
+// wush_debug_set's switches: 0 = unset, otherwise value + 1 (so that the array needs no initializer).
+std::atomic<int> g_debug[wush::kDbgCount];
+
 }  // namespace
+
+namespace wush {
+int debug_option(int opt) { return opt >= 0 && opt < kDbgCount ? g_debug[opt].load(std::memory_order_relaxed) - 1 : -1; }
+}  // namespace wush
 
 extern "C" {
 
@@ -224,18 +232,16 @@ wush_status wush_layer_decode(const void* X, int64_t M, int64_t K, int64_t ldx, 
   if (reinterpret_cast<uintptr_t>(Y) % elem != 0) return WUSH_ERR_ALIGN;
   if (!workspace || workspace_bytes < wush::layer_decode_workspace_bytes(K)) return WUSH_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return WUSH_ERR_ALIGN;
-  // WUSH_DECODE_TEST_TIMEOUT=1 (tests only): make every workgroup's barrier wait expire at once.
-  const char* hook = getenv("WUSH_DECODE_TEST_TIMEOUT");
-  const int test_timeout = hook && hook[0] == '1';
+  // WUSH_DEBUG_DECODE_TEST_TIMEOUT (tests only): make every workgroup's barrier wait expire at once.
+  const int test_timeout = wush::debug_option(wush::kDbgDecodeTestTimeout) == 1;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int out_f32 = fmt.out_dtype == WUSH_OUT_F32;
   // Two launches by default.  With the host's launch cost out of the picture (graph
   // replay) two back-to-back kernels are 1.5-2 us apart, while the single-launch
   // form pays 4-6 us for its grid-wide barrier across the eight XCDs: measured
   // 6.4 against 9.5 us on 4096 x 6144, 40 against 55 us on 8192 x 57344 (M = 1).
-  // WUSH_DECODE_FUSED=1 selects the single launch.
-  const char* f = getenv("WUSH_DECODE_FUSED");
-  const bool fused = f && f[0] == '1';
+  // wush_debug_set(WUSH_DEBUG_DECODE_FUSED, 1) selects the single launch.
+  const bool fused = wush::debug_option(wush::kDbgDecodeFused) == 1;
   if (fused || test_timeout)
     return from_hip(wush::launch_layer_decode(X, M, K, ldx, T_blocks, Wq, Ws, N, fmt.scale_rule, out_f32, Y, ldy,
                                               workspace, test_timeout, st));
@@ -492,6 +498,13 @@ wush_status wush_unpack_tiled(const void* q_tiled, const void* s_tiled, int64_t 
   if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxK || K % 256 != 0) return WUSH_ERR_SHAPE;
   if (!aligned16(q_tiled) || !aligned16(s_tiled) || !aligned16(q) || !aligned16(s)) return WUSH_ERR_ALIGN;
   return from_hip(wush::launch_unpack_tiled(q_tiled, s_tiled, rows, K, q, s, static_cast<hipStream_t>(stream)));
+}
+
+wush_status wush_debug_set(int32_t option, int32_t value) {
+  if (option < 0 || option >= wush::kDbgCount) return WUSH_ERR_FMT;
+  if (value < -1 || value > 1023) return WUSH_ERR_SHAPE;
+  g_debug[option].store(value + 1, std::memory_order_relaxed);
+  return WUSH_OK;
 }
 
 const char* wush_status_string(wush_status st) {

@@ -12,6 +12,21 @@ namespace wush {
 // Compute units of the current device (queried once per device).
 int device_cu_count();
 
+// Process-wide switches for tests and measurements (set through wush_debug_set, never from the
+// environment): which kernel or tile shape a launcher takes where it would otherwise choose by itself.
+// -1 = unset = the library's own choice.  The numbering is that of the WUSH_DEBUG_* constants of wush.h.
+enum DebugOption {
+  kDbgGemmTile = 0,          // tiled MXFP4 GEMM: 0..3 = 256x256, 128x384, 128x256, 128x128
+  kDbgGemmSkinny = 1,        // MXFP4 GEMM, up to 128 tokens: 1 = weight-streaming kernel, 0 = tiled kernel
+  kDbgGemmSimple = 2,        // canonical layout: 1 = the one-wave-per-tile kernel
+  kDbgW4Width = 3,           // NVFP4 / INT4 tiled GEMM: tile width 2..4 (x 64 output channels)
+  kDbgW4Skinny = 4,          // NVFP4 / INT4 GEMM, up to 128 tokens: 1 = weight-streaming kernel, 0 = tiled kernel
+  kDbgDecodeFused = 5,       // wush_layer_decode: 1 = single launch with a grid-wide barrier
+  kDbgDecodeTestTimeout = 6, // wush_layer_decode: 1 = the barrier wait gives up at once (error-path test)
+  kDbgCount
+};
+int debug_option(int opt);
+
 // Raises a kernel's dynamic LDS limit, once per device: the attribute belongs to the device's copy of
 // the code object, so a process that drives several GPUs has to set it on each.  One object per
 // kernel instantiation (a function-local static of its launcher).
@@ -116,6 +131,13 @@ hipError_t launch_nvfp4_weight_prep(const void* W, int64_t N, int64_t K, int64_t
 hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
                              const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, int tiled, void* Y,
                              int64_t ldy, hipStream_t stream);
+
+// Weight-streaming GEMMs of the two formats for M <= 128, tiled layout only (w4_gemm_skinny.hip).
+hipError_t launch_nvfp4_gemm_skinny(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
+                                    const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, void* Y,
+                                    int64_t ldy, hipStream_t stream);
+hipError_t launch_int4_gemm_skinny(const void* Xq, const void* Xs, const void* Wq, const void* Ws, int64_t M, int64_t N,
+                                   int64_t K, int out_f32, void* Y, int64_t ldy, hipStream_t stream);
 
 // INT4 variant (two's-complement codes, BF16 scale per 32, 32 x 32 transforms); layouts as for NVFP4
 // (the 4 scale bytes of a K step of 64 are two BF16 numbers).  Weight workspace: as launch_weight_prep.

@@ -156,6 +156,12 @@ def test_layer_decode_validation(L):
     assert L.wush_layer_decode_status(None, 512, None) == 1
 
 
+def test_debug_set_validation(L):
+    assert L.wush_debug_set(0, 2) == 0 and L.wush_debug_set(0, -1) == 0
+    assert L.wush_debug_set(7, 1) == 4 and L.wush_debug_set(-1, 1) == 4       # unknown option
+    assert L.wush_debug_set(0, -2) == 2 and L.wush_debug_set(0, 5000) == 2    # value out of range
+
+
 def test_nvfp4_validation(L):
     q = lambda *a: L.wush_quantize_act_nvfp4(*a)
     assert q(None, 4, 64, 64, A, A, 0, A, A, None, None) == 1          # null X

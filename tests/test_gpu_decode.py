@@ -4,8 +4,6 @@ layer forward wush_layer_decode (transform + quantize + GEMM behind a grid-wide
 barrier).  The oracle is the same FP64 layer forward as everywhere else; the
 fused call must in addition reproduce the two-call path bit for bit.
 """
-import os
-
 import numpy as np
 import pytest
 
@@ -109,13 +107,13 @@ def test_skinny_gemm_every_m(P, G):
         assert torch.equal(Y, Y64[:M]), M
 
 
-@pytest.fixture(params=["1", "0"], ids=["one_launch", "two_launches"])
-def forced_form(request):
-    """wush_layer_decode runs as one launch or as two (WUSH_DECODE_FUSED); both forms are
+@pytest.fixture(params=[1, 0], ids=["one_launch", "two_launches"])
+def forced_form(request, P):
+    """wush_layer_decode runs as one launch or as two (WUSH_DEBUG_DECODE_FUSED); both forms are
     checked on every shape."""
-    os.environ["WUSH_DECODE_FUSED"] = request.param
+    P.wush_debug_set(P.WUSH_DEBUG_DECODE_FUSED, request.param)
     yield request.param
-    del os.environ["WUSH_DECODE_FUSED"]
+    P.wush_debug_set(P.WUSH_DEBUG_DECODE_FUSED, -1)
 
 
 @pytest.mark.parametrize("M,K,N", SHAPES)
@@ -188,11 +186,11 @@ def test_layer_decode_barrier_timeout_is_reported(P, G):
     wsp = G.empty_u8(P.wush_layer_decode_workspace(K))
     P.wush_layer_decode_init(wsp, K)
     Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
-    os.environ["WUSH_DECODE_TEST_TIMEOUT"] = "1"
+    P.wush_debug_set(P.WUSH_DEBUG_DECODE_TEST_TIMEOUT, 1)
     try:
         P.wush_layer_decode(S["Xd"][:M], S["Td"], S["Wq"], S["Ws"], Y, wsp)
     finally:
-        del os.environ["WUSH_DECODE_TEST_TIMEOUT"]
+        P.wush_debug_set(P.WUSH_DEBUG_DECODE_TEST_TIMEOUT, -1)
     with pytest.raises(P.WushError) as ei:
         P.wush_layer_decode_status(wsp, K)
     assert ei.value.code == 8
@@ -207,7 +205,6 @@ def test_layer_decode_default_form(P, G):
     """Without the override (two launches) the call gives the same result."""
     import torch
     M, K, N = 5, 4096, 1024
-    assert "WUSH_DECODE_FUSED" not in os.environ
     S = _prepared_layer(P, G, M, K, N)
     Y2, _, _ = _two_call(P, G, S, M, K, N, 0)
     wsp = G.empty_u8(P.wush_layer_decode_workspace(K))

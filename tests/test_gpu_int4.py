@@ -24,6 +24,19 @@ def P():
     return P
 
 
+def _force_width(P, width):
+    """Force the tile width of the tiled GEMM and keep the weight-streaming kernel out of the way."""
+    P.wush_debug_set(P.WUSH_DEBUG_W4_WIDTH, int(width))
+    P.wush_debug_set(P.WUSH_DEBUG_W4_SKINNY, 0)
+
+
+@pytest.fixture(autouse=True)
+def _reset_switches(P):
+    yield
+    P.wush_debug_set(P.WUSH_DEBUG_W4_WIDTH, -1)
+    P.wush_debug_set(P.WUSH_DEBUG_W4_SKINNY, -1)
+
+
 @pytest.fixture(scope="module")
 def G():
     from tests import gpu_util
@@ -201,12 +214,12 @@ def _tile_operand(packed, scale_bytes):
 @pytest.mark.parametrize("layout", [0, 1])
 @pytest.mark.parametrize("K", [320, 384])
 @pytest.mark.parametrize("width", ["2", "3", "4"])
-def test_linear_every_tile_width(P, G, width, K, layout, monkeypatch):
+def test_linear_every_tile_width(P, G, width, K, layout):
     """The three tile widths on a shape with several tiles and ragged edges in both directions, GEMM alone.
     An odd number of 64-element K steps (K = 320) takes the kernel that stages both operands in LDS, an
     even one (K = 384) the one that converts W in registers; both read either layout."""
     import torch
-    monkeypatch.setenv("WUSH_NVFP4_WIDTH", width)
+    _force_width(P, width)
     M, N = 300, 700
     rng = np.random.default_rng(91 + K)
     xq, xs = _random_operand(rng, M, K, -13, 9)
@@ -222,10 +235,37 @@ def test_linear_every_tile_width(P, G, width, K, layout, monkeypatch):
     assert O.rel_fro(Y.cpu().numpy().astype(np.float64), ref) <= 1e-5
 
 
-@pytest.mark.parametrize("width", ["2", "3", "4"])
-def test_layer_end_to_end_both_layouts(P, G, width, monkeypatch):
+@pytest.mark.parametrize("kernel", [1, 0, -1], ids=["streaming", "tiled", "library_choice"])
+@pytest.mark.parametrize("M", [1, 2, 7, 16, 31, 32, 33, 48, 64, 65, 100, 128])
+@pytest.mark.parametrize("K", [64, 320, 1024])
+def test_linear_few_tokens_on_either_kernel(P, G, K, M, kernel):
+    """Up to 128 tokens the tiled layout takes a weight-streaming kernel (one workgroup per 32 output
+    channels, K split over its four waves); it and the tiled kernel are forced in turn on a ragged
+    shape, FP32 and BF16 output, against the oracle on the same codes and BF16 scales."""
     import torch
-    monkeypatch.setenv("WUSH_NVFP4_WIDTH", width)
+    N = 1000
+    rng = np.random.default_rng(5000 + 7 * M + K)
+    xq, xs = _random_operand(rng, M, K, -13, 9)
+    wq, ws_ = _random_operand(rng, N, K, -10, -2)
+    ref = Q.linear_dequant(xq, xs, wq, ws_)
+    (xp, xsb), (wp, wsb) = (_tile_operand(Q.pack_codes(xq), xs.view(np.uint8).reshape(M, -1)),
+                            _tile_operand(Q.pack_codes(wq), ws_.view(np.uint8).reshape(N, -1)))
+    P.wush_debug_set(P.WUSH_DEBUG_W4_SKINNY, kernel)
+    for f32 in (True, False):
+        Y = torch.full((M, N + 8), float("nan"), dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
+        P.wush_linear_int4(G.u8_dev(xp), G.u8_dev(xsb), G.u8_dev(wp), G.u8_dev(wsb), Y[:, :N], layout=1,
+                           out_dtype=1 if f32 else 0, K=K)
+        torch.cuda.synchronize()
+        y = Y.float().cpu().numpy().astype(np.float64)
+        assert np.isnan(y[:, N:]).all()
+        assert np.isfinite(y[:, :N]).all()
+        assert O.rel_fro(y[:, :N], ref) <= (1e-5 if f32 else 2e-3), (f32, O.rel_fro(y[:, :N], ref))
+
+
+@pytest.mark.parametrize("width", ["2", "3", "4"])
+def test_layer_end_to_end_both_layouts(P, G, width):
+    import torch
+    _force_width(P, width)
     cfg, L, X, W, T = _layer("tiles")
     M, N, K = cfg.M, cfg.N, cfg.K
     Xd, Wd, Td = G.bf16_dev(L["X"]), G.bf16_dev(L["W"]), G.bf16_dev(O.bf16_values_to_bits(T))
@@ -348,6 +388,7 @@ def test_offsets_beyond_4_gib(P, G):
     small batch (parity of small batches with the oracle is tested above).  A 32-bit offset anywhere in
     the path would send those rows elsewhere."""
     import torch
+    P.wush_debug_set(P.WUSH_DEBUG_W4_SKINNY, 0)     # the small batches on the big batch's kernel: same accumulation order
     M, K, N = (1 << 21) + 100, 4096, 1100
     g = torch.Generator(device="cuda").manual_seed(31)
     X = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")

@@ -24,6 +24,19 @@ def P():
     return P
 
 
+def _force_width(P, width):
+    """Force the tile width of the tiled GEMM and keep the weight-streaming kernel out of the way."""
+    P.wush_debug_set(P.WUSH_DEBUG_W4_WIDTH, int(width))
+    P.wush_debug_set(P.WUSH_DEBUG_W4_SKINNY, 0)
+
+
+@pytest.fixture(autouse=True)
+def _reset_switches(P):
+    yield
+    P.wush_debug_set(P.WUSH_DEBUG_W4_WIDTH, -1)
+    P.wush_debug_set(P.WUSH_DEBUG_W4_SKINNY, -1)
+
+
 @pytest.fixture(scope="module")
 def G():
     from tests import gpu_util
@@ -293,13 +306,13 @@ def _tile_operand(packed, scales):
 @pytest.mark.parametrize("layout", [0, 1])
 @pytest.mark.parametrize("K", [320, 384])
 @pytest.mark.parametrize("width", ["2", "3", "4"])
-def test_linear_every_tile_width(P, G, width, K, layout, monkeypatch):
+def test_linear_every_tile_width(P, G, width, K, layout):
     """The three tile widths (128, 192, 256 output channels) on a shape with several tiles and ragged
     edges in both directions; the library normally chooses by cost.  An odd number of 64-element K
     steps (K = 320) takes the kernel that stages both operands in LDS, an even one (K = 384) the one
     that keeps W in registers; both read either layout."""
     import torch
-    monkeypatch.setenv("WUSH_NVFP4_WIDTH", width)
+    _force_width(P, width)
     M, N = 300, 700
     rng = np.random.default_rng(77 + K)
     xc = rng.integers(0, 16, (M, K), dtype=np.uint8)
@@ -316,6 +329,35 @@ def test_linear_every_tile_width(P, G, width, K, layout, monkeypatch):
                         layout=layout, out_dtype=1, K=K)
     torch.cuda.synchronize()
     assert O.rel_fro(Y.cpu().numpy().astype(np.float64), ref) <= 1e-5
+
+
+@pytest.mark.parametrize("kernel", [1, 0, -1], ids=["streaming", "tiled", "library_choice"])
+@pytest.mark.parametrize("M", [1, 2, 7, 16, 31, 32, 33, 48, 64, 65, 100, 128])
+@pytest.mark.parametrize("K", [64, 320, 1024])
+def test_linear_few_tokens_on_either_kernel(P, G, K, M, kernel):
+    """Up to 128 tokens the tiled layout takes a weight-streaming kernel (one workgroup per 32 output
+    channels, K split over its four waves); it and the tiled kernel are forced in turn on a ragged
+    shape, FP32 and BF16 output, against the oracle on the same codes, scales and tensor scales."""
+    import torch
+    N = 1000
+    rng = np.random.default_rng(4000 + 7 * M + K)
+    xc = rng.integers(0, 16, (M, K), dtype=np.uint8)
+    wc = rng.integers(0, 16, (N, K), dtype=np.uint8)
+    xs = rng.integers(0, 127, (M, K // 16), dtype=np.uint8)
+    ws_ = rng.integers(40, 100, (N, K // 16), dtype=np.uint8)
+    tsx, tsw = np.float32(0.0371), np.float32(2.4e-4)
+    ref = NV.linear_dequant(xc, xs, tsx, wc, ws_, tsw)
+    (xq, xst), (wq, wst) = _tile_operand(_pack(xc), xs), _tile_operand(_pack(wc), ws_)
+    P.wush_debug_set(P.WUSH_DEBUG_W4_SKINNY, kernel)
+    for f32 in (True, False):
+        Y = torch.full((M, N + 8), float("nan"), dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
+        P.wush_linear_nvfp4(G.u8_dev(xq), G.u8_dev(xst), _f32_dev(tsx), G.u8_dev(wq), G.u8_dev(wst), _f32_dev(tsw),
+                            Y[:, :N], layout=1, out_dtype=1 if f32 else 0, K=K)
+        torch.cuda.synchronize()
+        y = Y.float().cpu().numpy().astype(np.float64)
+        assert np.isnan(y[:, N:]).all()
+        assert np.isfinite(y[:, :N]).all()
+        assert O.rel_fro(y[:, :N], ref) <= (1e-5 if f32 else 2e-3), (f32, O.rel_fro(y[:, :N], ref))
 
 
 @pytest.mark.parametrize("name", ["c1", "tiles"])
@@ -386,10 +428,10 @@ def test_tiled_layout_is_a_permutation_of_canonical(P, G):
 
 
 @pytest.mark.parametrize("width", ["2", "3", "4"])
-def test_layer_end_to_end_tiled(P, G, width, monkeypatch):
+def test_layer_end_to_end_tiled(P, G, width):
     """The path the benchmark times: tiled buffers from both quantizers into the GEMM."""
     import torch
-    monkeypatch.setenv("WUSH_NVFP4_WIDTH", width)
+    _force_width(P, width)
     cfg, L, X, W, T = _layer("tiles")
     M, N, K = cfg.M, cfg.N, cfg.K
     Yt = NV.transform_act(X, T)
@@ -498,6 +540,7 @@ def test_offsets_beyond_4_gib(P, G):
     small batch (parity of small batches with the oracle is tested above).  A 32-bit offset anywhere in
     the path would send those rows elsewhere."""
     import torch
+    P.wush_debug_set(P.WUSH_DEBUG_W4_SKINNY, 0)     # the small batches on the big batch's kernel: same accumulation order
     M, K, N = (1 << 21) + 100, 4096, 1100
     g = torch.Generator(device="cuda").manual_seed(21)
     X = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")

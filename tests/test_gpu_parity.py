@@ -388,7 +388,7 @@ def test_tiled_quantizer_tap(P, G):
 @pytest.mark.parametrize("M,N,K", [(130, 1000, 512), (300, 392, 1024), (257, 4096, 768)])
 def test_linear_both_tile_shapes(P, G, M, N, K, shape):
     """The tiled GEMM has four workgroup tile shapes and picks one by the size of the problem; each
-    is forced in turn (WUSH_GEMM_TILE).  N that is not a multiple of 384 makes the last 128 x 384
+    is forced in turn (WUSH_DEBUG_GEMM_TILE).  N that is not a multiple of 384 makes the last 128 x 384
     tile reach past the 256-row padding of the packed weights, which the kernel has to survive."""
     import os
     import torch
@@ -416,12 +416,12 @@ def test_linear_both_tile_shapes(P, G, M, N, K, shape):
     Xq, Xs = tiled(O.pack_codes(xc), xs, M)
     Wq, Ws = tiled(O.pack_codes(wc), ws, N)
     Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
-    os.environ["WUSH_GEMM_TILE"] = shape
+    P.wush_debug_set(P.WUSH_DEBUG_GEMM_TILE, int(shape))
     try:
         P.wush_linear(Xq, Xs, Wq, Ws, Y, P.default_fmt(out_dtype=1, layout=1), K=K)
         torch.cuda.synchronize()
     finally:
-        del os.environ["WUSH_GEMM_TILE"]
+        P.wush_debug_set(P.WUSH_DEBUG_GEMM_TILE, -1)
     ref = O.dequantize(xc, xs) @ O.dequantize(wc, ws).T
     y = G.host(Y).astype(np.float64)
     assert np.isfinite(y).all()
@@ -432,7 +432,7 @@ def test_linear_both_tile_shapes(P, G, M, N, K, shape):
 @pytest.mark.parametrize("M", [33, 64, 65, 100, 128])
 def test_linear_small_batches_on_either_kernel(P, G, M, kernel):
     """For 33 to 128 tokens wush_linear chooses between the weight-streaming kernel and the tiled one from a
-    timing model; each is forced in turn (WUSH_GEMM_SKINNY) on a ragged shape and checked against the oracle."""
+    timing model; each is forced in turn (WUSH_DEBUG_GEMM_SKINNY) on a ragged shape and checked against the oracle."""
     import os
     import torch
     N, K = 1000, 1024
@@ -457,12 +457,12 @@ def test_linear_small_batches_on_either_kernel(P, G, M, kernel):
         sc[(((rb * KT + kt) * 64 + kh * 32 + rr) * 4 + kk).reshape(-1)] = scales.reshape(-1)
         bufs += [G.u8_dev(q), G.u8_dev(sc)]
     Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
-    os.environ["WUSH_GEMM_SKINNY"] = kernel
+    P.wush_debug_set(P.WUSH_DEBUG_GEMM_SKINNY, int(kernel))
     try:
         P.wush_linear(*bufs, Y, P.default_fmt(out_dtype=1, layout=1), K=K)
         torch.cuda.synchronize()
     finally:
-        del os.environ["WUSH_GEMM_SKINNY"]
+        P.wush_debug_set(P.WUSH_DEBUG_GEMM_SKINNY, -1)
     ref = O.dequantize(xc, xs) @ O.dequantize(wc, ws).T
     y = G.host(Y).astype(np.float64)
     assert np.isfinite(y).all()
