@@ -33,6 +33,20 @@ def hipcc_path() -> str:
     return p
 
 
+def check_generated_code(hipcc: str, bdir: str) -> None:
+    """The tiled MXFP4 GEMM issues its main-loop loads from inline asm; what that relies on in the
+    generated code (build_checks.py) is verified on every build, with the flags of the build."""
+    from .build_checks import check_gemm_frag_asm
+    asm = os.path.join(bdir, "mxfp4_gemm_frag.s")
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-S", "--cuda-device-only",
+           os.path.join(CSRC, "mxfp4_gemm_frag.hip"), "-o", asm]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc -S failed on mxfp4_gemm_frag.hip:\n{r.stdout}")
+    with open(asm) as f:
+        check_gemm_frag_asm(f.read())      # raises InvariantError
+
+
 def build(verbose: bool = False) -> str:
     """Compile every kernel source and link libwush.so; returns its path."""
     hipcc = hipcc_path()
@@ -55,6 +69,7 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
         if verbose and out.strip():
             print(out)
+    check_generated_code(hipcc, bdir)
     for lib, lobjs in ((LIB, objs), (PROBES_LIB, [pobj])):
         tmp = lib + ".tmp"
         cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", *lobjs, "-o", tmp]

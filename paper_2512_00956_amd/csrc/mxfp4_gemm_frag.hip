@@ -124,7 +124,10 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
   // pipeline once per iteration.  Issued from asm they are invisible to its
   // bookkeeping; its own vmcnt(n) waits then undercount the younger operations
   // (they wait for more than needed, never for less) and the explicit wait in
-  // front of the barrier covers the LDS data.  m0 has no other user in this kernel.
+  // front of the barrier covers the LDS data.  m0 has no other user in this kernel, and the
+  // compiler never keeps a value of its own in it across statements: it is a reserved register of
+  // this target (naming it in the clobber list is rejected with "clobber list contains reserved
+  // registers"), written immediately before each instruction the compiler itself emits that reads it.
   const uint32_t lds_base = (uint32_t)(uintptr_t)smem;   // LDS byte address of the ring
   // The four fragments (kk) of one (row block, K tile) are 4 KiB contiguous both in
   // memory and in the ring stage; the instruction's immediate offset is added to
@@ -260,7 +263,7 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(B_, A_, acc[i][j], 4, 4, KK, w.s[j], KK, xs[i]); \
   }
 #define WUSH_MMA_REST(KK, AF, i)                   \
-  if (CB > 2) {                                    \
+  if constexpr (CB > 2) {                          \
     WUSH_FENCE                                     \
     WUSH_MMA(KK, AF, i, CB - 1)                    \
   }
@@ -278,7 +281,7 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
       WUSH_MMA(0, af0, i, 0)
       const v4i nx_ = read_x_frag(kt, 2, i);
       WUSH_FENCE
-      if (CB > 1) WUSH_MMA(0, af0, i, 1)
+      if constexpr (CB > 1) WUSH_MMA(0, af0, i, 1)
       if (PFX && i < 4 * kUB) dma_x_frag(kt + 3, i);
       WUSH_MMA_REST(0, af0, i)
       af0[i] = nx_;
@@ -289,7 +292,7 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
       WUSH_MMA(1, af1, i, 0)
       const v4i nx_ = read_x_frag(kt, 3, i);
       WUSH_FENCE
-      if (CB > 1) WUSH_MMA(1, af1, i, 1)
+      if constexpr (CB > 1) WUSH_MMA(1, af1, i, 1)
       if (PFX && i < kUB) dma_x_scale(kt + 3, i);
       if (PFW && i >= kUB && i < kUB + CB) load_w_frag(w, kt + 2, 0, i - kUB);
       WUSH_MMA_REST(1, af1, i)
@@ -309,7 +312,7 @@ __global__ __launch_bounds__(256) void gemm_frag_kernel(
       v4i nx_ = af0[i];
       if (NEXT) nx_ = read_x_frag(kt + 1, 0, i);
       WUSH_FENCE
-      if (CB > 1) WUSH_MMA(2, af0, i, 1)
+      if constexpr (CB > 1) WUSH_MMA(2, af0, i, 1)
       if (PFW && i < CB) load_w_frag(w, kt + 2, 1, i);
       WUSH_MMA_REST(2, af0, i)
       af0[i] = nx_;

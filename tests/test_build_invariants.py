@@ -14,7 +14,6 @@ import re
 import shutil
 import subprocess
 import tempfile
-from collections import Counter
 
 import pytest
 
@@ -36,44 +35,28 @@ def asm_text():
         return open(out).read()
 
 
-def _kernels(text):
-    """Split the assembly into {kernel symbol: body} for the two instantiations."""
-    parts = re.split(r"^(_ZN4wush\S*gemm_frag_kernel\S*):.*$", text, flags=re.M)
-    return {parts[i]: parts[i + 1].split("s_endpgm")[0] for i in range(1, len(parts) - 1, 2)}
+def test_gemm_frag_generated_code(asm_text):
+    """No scratch, one register assignment per W slot, no compiler-made full drain (vmcnt(0)) inside the
+    pipelined loop: the same checks the build runs (paper_2512_00956_amd/build_checks.py)."""
+    from paper_2512_00956_amd.build_checks import check_gemm_frag_asm
+    check_gemm_frag_asm(asm_text)
 
 
-def _shape(name):
-    """(RB, CB) from the mangled template arguments ...ILb<f32>ELi<RB>ELi<CB>E..."""
-    m = re.search(r"ILb[01]ELi(\d+)ELi(\d+)E", name)
-    return int(m.group(1)), int(m.group(2))
-
-
-def test_no_scratch_and_single_register_assignment(asm_text):
-    kernels = _kernels(asm_text)
-    assert len(kernels) == 8, list(kernels)
-    for name, body in kernels.items():
-        RB, CB = _shape(name)
-        assert "scratch_" not in body, f"{name}: spills to scratch"
-        frag = Counter(re.findall(r"global_load_dwordx4 (v\[\d+:\d+\])", body))
-        scale = Counter(re.findall(r"global_load_dword (v\d+),", body))
-        assert len(frag) == 2 * CB * 4, (name, sorted(frag))
-        assert len(scale) == 2 * CB, (name, sorted(scale))
-        assert len(set(frag.values())) == 1 and len(set(scale.values())) == 1, (name, frag, scale)
-        # the 16 tuples are disjoint
-        regs = [r for t in frag for r in range(*map(int, re.match(r"v\[(\d+):(\d+)\]", t).groups()))]
-        assert len(regs) == len(set(regs))
-
-
-def test_main_loop_waits_are_explicit(asm_text):
-    """No compiler-made full drain (vmcnt(0)) inside the pipelined loop."""
-    for name, body in _kernels(asm_text).items():
-        m = re.search(r"Inner Loop Header.*?s_cbranch_scc1", body, flags=re.S)
-        assert m, name
-        loop = m.group(0)
-        RB, CB = _shape(name)
-        assert loop.count("v_mfma_scale_f32_32x32x64_f8f6f4") == 2 * 4 * RB * CB, name     # two K iterations
-        assert "vmcnt(0)" not in loop and "lgkmcnt(0)" not in loop, name
-        assert loop.count("s_barrier") == 2, name
+def test_the_checks_catch_what_they_are_for(asm_text):
+    """Planted faults in the assembly text (not in any kernel): a spill, a second register assignment
+    of a W fragment, a full drain in the loop."""
+    from paper_2512_00956_amd.build_checks import InvariantError, check_gemm_frag_asm
+    import re as _re
+    with pytest.raises(InvariantError):
+        check_gemm_frag_asm(asm_text.replace("s_barrier", "scratch_store_dword off, v0, s0\n\ts_barrier", 1))
+    m = _re.search(r"global_load_dwordx4 v\[(\d+):(\d+)\]", asm_text)
+    moved = f"global_load_dwordx4 v[{int(m.group(1)) + 400}:{int(m.group(2)) + 400}]"
+    with pytest.raises(InvariantError):
+        check_gemm_frag_asm(asm_text[:m.start()] + moved + asm_text[m.end():])
+    loop = _re.search(r"Inner Loop Header.*?s_cbranch_scc1", asm_text, flags=_re.S)
+    drained = asm_text[:loop.start()] + loop.group(0).replace("s_barrier", "s_waitcnt vmcnt(0)\n\ts_barrier", 1) + asm_text[loop.end():]
+    with pytest.raises(InvariantError):
+        check_gemm_frag_asm(drained)
 
 
 # ---------------------------------------------------------------------------
