@@ -9,7 +9,10 @@
 //       non-temporal stores), linear or in that kernel's own access pattern.
 //       Measured from HBM on 16384 x 4096 BF16: linear 5.5-5.6 TB/s, the quantizer's
 //       pattern 4.7-4.9 (deeper lookahead or wider waves do not change it), the
-//       quantizer itself 4.6-4.7.
+//       quantizer itself 4.6-4.7.  The reads make the difference, not the stores
+//       (mode 10: same reads, linear stores, 4.7); whole cache lines per load
+//       instruction give 4.9 (mode 13), 8 rows x 1 KiB per wave 5.2 on this shape but
+//       4.9 against 5.1 on 8192 x 8192 (mode 11).
 //
 // C ABI (all pointers are device pointers, `stream` is a hipStream_t; return
 // value: 0 = launched, 1 = bad argument, 2 = HIP launch error):
@@ -154,6 +157,9 @@ __global__ __launch_bounds__(256) void mfma_f16_probe_kernel(const v8h* __restri
 //           tile's codes and scales at the offsets of the fragment-order layout; one tile
 //           of lookahead in registers.  What is left out is the arithmetic.
 //   mode 2: as mode 1 with 8 blocks per wave (32 rows x 512 B).
+//   modes 10, 11: read-pattern probes: a wave's tile is 32 or 8 rows x 256 B or 1 KiB of each,
+//           linear stores of a quarter of the bytes.  mode 13: the tile of mode 10 (32 rows x 256 B) read
+//           with whole 128-byte lines per load instruction (8 rows each) instead of 32 bytes of 32 rows.
 // rows x row_bytes is the source (row_bytes a multiple of 1024, rows of 32); dst holds
 // rows * row_bytes / 4 bytes of "codes" followed by rows * row_bytes / 64 bytes of "scales".
 __global__ __launch_bounds__(512) void stream_linear_kernel(const v4u* __restrict__ src, long long n_steps,
@@ -232,6 +238,55 @@ __global__ __launch_bounds__(512) void stream_tiles_kernel(const uint16_t* __res
   }
 }
 
+// Read-pattern probe: a wave's tile is ROWS rows x (8 KiB / ROWS) contiguous bytes of each (eight 128-bit
+// loads per lane, one tile of lookahead), the four column waves of a workgroup sit side by side, two wave
+// groups take alternate tiles; stores are linear (a quarter of the bytes read).  ROWS = 32 is the
+// quantizer's footprint, smaller ROWS make it more linear.
+// FULL_LINES (ROWS = 32 only): the same tile, but every load instruction covers 8 rows x one whole 128-byte line
+// instead of 32 rows x 32 bytes.
+template <int ROWS, bool FULL_LINES = false>
+__global__ __launch_bounds__(512) void stream_rows_kernel(const uint8_t* __restrict__ X, int rows, int row_bytes,
+                                                          v4u* __restrict__ dst, int tiles_per_wg) {
+  constexpr int kSeg = 8192 / ROWS;          // bytes of a row per wave tile
+  constexpr int kLanesPerRow = 64 / ROWS;    // lanes side by side on one row within a load instruction
+  const int lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3, tg = threadIdx.x >> 8;
+  const int r = lane / kLanesPerRow, c = lane % kLanesPerRow;
+  const int64_t col0 = ((int64_t)blockIdx.y * 4 + wave) * kSeg;
+  if (col0 >= row_bytes) return;
+  const int ntiles = rows / ROWS;
+  const int t0 = blockIdx.x * tiles_per_wg + tg;
+  const int tend = min(blockIdx.x * tiles_per_wg + tiles_per_wg, ntiles);
+  if (t0 >= tend) return;
+  auto load = [&](v4u (&d)[8], int t) {
+    const int tt = t < tend ? t : t0;
+    if (FULL_LINES) {
+      const uint8_t* p = X + ((int64_t)tt * ROWS + (lane >> 3)) * row_bytes + col0 + (lane & 7) * 16;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) d[i] = *reinterpret_cast<const v4u*>(p + (int64_t)(8 * (i & 3)) * row_bytes + 128 * (i >> 2));
+    } else {
+      const uint8_t* p = X + ((int64_t)tt * ROWS + r) * row_bytes + col0 + c * 16;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) d[i] = *reinterpret_cast<const v4u*>(p + i * (kSeg / 8));
+    }
+  };
+  v4u x[2][8];
+  load(x[0], t0);
+  __builtin_amdgcn_sched_barrier(0);
+  const int64_t units_per_tile = (int64_t)gridDim.y * 4;   // (tile, column wave) units
+  for (int base = t0; base < tend; base += 4) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int t = base + 2 * s;
+      if (t >= tend) return;
+      load(x[s ^ 1], t + 2);
+      v4u o0 = x[s][0] ^ x[s][1] ^ x[s][2] ^ x[s][3], o1 = x[s][4] ^ x[s][5] ^ x[s][6] ^ x[s][7];
+      const int64_t unit = (int64_t)t * units_per_tile + blockIdx.y * 4 + wave;
+      __builtin_nontemporal_store(o0, dst + unit * 128 + lane);
+      __builtin_nontemporal_store(o1, dst + unit * 128 + 64 + lane);
+    }
+  }
+}
+
 }  // namespace
 
 }  // namespace wush
@@ -281,6 +336,20 @@ int wushp_stream(const void* src, long long rows, long long row_bytes, void* dst
     const uint16_t* x = static_cast<const uint16_t*>(src);
     if (mode == 1) wush::stream_tiles_kernel<1, 4><<<grid, dim3(512), 0, st>>>(x, (int)rows, K, q, s, walk);
     else wush::stream_tiles_kernel<1, 8><<<grid, dim3(512), 0, st>>>(x, (int)rows, K, q, s, walk);
+  } else if (mode == 10 || mode == 11 || mode == 13) {
+    const int ROWS = mode == 11 ? 8 : 32;
+    const int seg = 8192 / ROWS;
+    if (row_bytes % (4 * seg) != 0 || rows % ROWS != 0) return 1;
+    const int col_groups = (int)(row_bytes / (4 * seg)), ntiles = (int)(rows / ROWS);
+    const int wg_rows = blocks / col_groups > 0 ? blocks / col_groups : 1;
+    int walk = (ntiles + wg_rows - 1) / wg_rows;
+    if (walk < 2) walk = 2;
+    dim3 grid((unsigned)((ntiles + walk - 1) / walk), (unsigned)col_groups);
+    const uint8_t* x = static_cast<const uint8_t*>(src);
+    wush::v4u* d = static_cast<wush::v4u*>(dst);
+    if (mode == 10) wush::stream_rows_kernel<32><<<grid, dim3(512), 0, st>>>(x, (int)rows, (int)row_bytes, d, walk);
+    else if (mode == 11) wush::stream_rows_kernel<8><<<grid, dim3(512), 0, st>>>(x, (int)rows, (int)row_bytes, d, walk);
+    else wush::stream_rows_kernel<32, true><<<grid, dim3(512), 0, st>>>(x, (int)rows, (int)row_bytes, d, walk);
   } else {
     return 1;
   }
