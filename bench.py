@@ -52,7 +52,11 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # WRITE_SIZE runs of this script, scaled by a plain copy of known size (commands, raw counters and factors:
 # profiles/*.md).  A figure belongs to one kernel build: the key holds the library version it was read on,
 # and a workload without a figure for the loaded library reports null.
-MEASURED_TRAFFIC_KIB = {}
+MEASURED_TRAFFIC_KIB = {
+    ("c5", "tiled", "0.9"): (2924879, 917627),   # gemm_frag_kernel<false,8,2>: profiles/wush_linear_gemm_frag_c5.md
+    ("c2", "tiled", "0.9"): (43802, 27102),      # gemm_frag_kernel<false,4,3>: profiles/wush_linear_gemm_frag_c2.md
+    ("c4", "tiled", "0.9"): (133687, 34816),     # transform_quant_kernel, four rotating buffer sets: profiles/transform_quant_c4.md
+}
 
 
 def traffic_for(workload, layout, version):
@@ -744,6 +748,9 @@ def quantizer_c4(args, P, torch, dev, layout, cold_sets=4):
         ceil[name + "_GB/s"] = (sb if mode else M * K * 2 * 1.25) / ms / 1e6
     res["same_mix_stream_cold"] = ceil
     res["cold"]["frac_of_same_mix_stream"] = res["cold"]["GB/s"] / max(ceil.values())
+    t = traffic_for("c4", layout, P.lib().wush_version().decode())
+    res["cold"]["traffic"] = t
+    res["cold"]["traffic_over_algorithmic"] = None if t is None else t / qb
     return res
 
 
@@ -863,7 +870,7 @@ def layer_bench(args, P, torch, dev):
         if N:
             roof["frac_of_measured_mfma_ceiling"] = roof["achieved"] / ceil["mfma_only_workload_bits_tflops"]
     if not args.no_cpu_baseline:
-        rows = {"c2": 2048, "c3": 1024, "c4": 16384, "c5": 1024}[args.workload]
+        rows = {"c2": 2048, "c3": 4096, "c4": 16384, "c5": 8192}[args.workload]
         out["cpu_baseline"] = cpu_baseline(cfg, T_bits, L, rows)
     if args.workload == "c5" and not args.no_c4:
         # free the layer's buffers first: the activation-path measurement gets the GPU to itself
