@@ -23,7 +23,7 @@ Prints ONE JSON line:
              workload's own operand bits, and with all-equal operands), the shader clock
              under each, and a plain 1 GiB device copy
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|d2|d5|dn2|dn5|di2|di5|fig3|n2|n5|i2|i5]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|d2|d5|dn2|dn5|di2|di5|n2|n5|i2|i5]
 
 The decode workloads d2/d5 time wush_layer_decode (16 tokens) by replaying a
 captured graph of the steps, so that the host's launch cost is not what is
@@ -72,14 +72,6 @@ WORKLOADS = {
     "d2": "decode-sized batch on the c2 layer (wush_layer_decode), M=16 K=4096 N=6144",
     "d5": "decode-sized batch on the c5 layer (wush_layer_decode), M=16 K=8192 N=57344",
 }
-WORKLOADS["fig3"] = ("per-layer speedup over a BF16 GEMM at M=1024 on the layer shapes of Qwen3-8B and "
-                     "Llama-3.1-70B (the paper's kernel figure, which it measured on another GPU)")
-FIG3_LAYERS = [  # (name, K, N)
-    ("qwen3-8b qkv", 4096, 6144), ("qwen3-8b o", 4096, 4096), ("qwen3-8b gate+up", 4096, 24576),
-    ("qwen3-8b down", 12288, 4096),
-    ("llama-3.1-70b qkv", 8192, 10240), ("llama-3.1-70b o", 8192, 8192), ("llama-3.1-70b gate+up", 8192, 57344),
-    ("llama-3.1-70b down", 28672, 8192),
-]
 WORKLOADS["n2"] = "the c2 layer in the NVFP4 variant (E4M3 scale per 16, 16 x 16 transforms), M=2048 K=4096 N=6144"
 WORKLOADS["n5"] = "the c5 layer in the NVFP4 variant, M=8192 K=8192 N=57344"
 WORKLOADS["i2"] = "the c2 layer in the INT4 variant (BF16 scale per 32, Gaussian-MSE step), M=2048 K=4096 N=6144"
@@ -163,76 +155,6 @@ def measured_ceilings(torch, dev, x_bits, w_bits):
     out["copy_1gib_gbs"] = 5 * 2.0 * (1 << 30) / e0.elapsed_time(e1) / 1e6
     del src, dst
     return out
-
-
-def fig3_bench(args, P, torch, dev):
-    """Layer by layer at M = 1024: BF16 GEMM (the library GEMM behind torch.matmul), the MXFP4 GEMM alone,
-    and transform + quantize + MXFP4 GEMM with per-block transforms; speedups relative to BF16.
-    Random BF16 data and random well-conditioned transforms: only the time is measured here."""
-    M = 1024
-    fmt = P.default_fmt(layout=1)
-    gen = torch.Generator(device=dev).manual_seed(7)
-
-    def timed(fn):
-        for _ in range(args.warmup):
-            fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.steps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / args.steps
-
-    rows = []
-    for name, K, N in FIG3_LAYERS:
-        X = torch.randn((M, K), device=dev, generator=gen).to(torch.bfloat16)
-        W = (torch.randn((N, K), device=dev, generator=gen) * 0.02).to(torch.bfloat16)
-        T = torch.from_numpy(I.make_transforms_random(K // 32, 3).view(np.int16)).view(torch.bfloat16).to(dev)
-        wcb, wsb = P.wush_packed_sizes(N, K, fmt)
-        Wq = torch.empty(wcb, dtype=torch.uint8, device=dev)
-        Ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
-        wsp = torch.empty(P.wush_prepare_weight_workspace(N, K), dtype=torch.uint8, device=dev)
-        P.wush_prepare_weight(W, T, Wq, Ws, wsp, fmt)
-        P.wush_workspace_status(wsp, K)
-        xcb, xsb = P.wush_packed_sizes(M, K, fmt)
-        Xq = torch.empty(xcb, dtype=torch.uint8, device=dev)
-        Xs = torch.empty(xsb, dtype=torch.uint8, device=dev)
-        Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-        Wt = W.t()
-        t_bf16 = timed(lambda: torch.matmul(X, Wt, out=Y))
-        P.wush_quantize_act(X, T, Xq, Xs, fmt)
-        t_gemm = timed(lambda: P.wush_linear(Xq, Xs, Wq, Ws, Y, fmt, K=K))
-
-        def layer():
-            P.wush_quantize_act(X, T, Xq, Xs, fmt)
-            P.wush_linear(Xq, Xs, Wq, Ws, Y, fmt, K=K)
-        t_layer = timed(layer)
-        flops = 2.0 * M * N * K
-        rows.append({"layer": name, "K": K, "N": N, "bf16_gemm_ms": t_bf16, "bf16_tflops": flops / t_bf16 / 1e9,
-                     "fp4_matmul_ms": t_gemm, "wush_quant_fp4_matmul_ms": t_layer,
-                     "speedup_fp4_matmul": t_bf16 / t_gemm, "speedup_wush_quant_fp4_matmul": t_bf16 / t_layer,
-                     "layer_tflops": flops / t_layer / 1e9})
-        del X, W, Wq, Ws, wsp, Xq, Xs, Y, Wt
-    sp = [r["speedup_wush_quant_fp4_matmul"] for r in rows]
-    total_flops = sum(2.0 * M * r["N"] * r["K"] for r in rows)
-    total_ms = sum(r["wush_quant_fp4_matmul_ms"] for r in rows)
-    out = {
-        "metric": "W4A4 layer TFLOP/s (transform+quant+MXFP4 GEMM); % of MXFP4 MFMA & HBM peak",
-        "value": total_flops / total_ms / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": total_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "mxfp4 (e2m1 x e8m0), bf16 in/out, f32 accumulate", "data": "synthetic",
-        "config": {"workload": f"fig3: {WORKLOADS['fig3']}", "M": M, "layers": len(rows), "packed_layout": "tiled",
-                   "launch": "host loop"},
-        "speedup_over_bf16": {"max": max(sp), "min": min(sp), "geomean": float(np.exp(np.mean(np.log(sp)))),
-                              "fp4_matmul_alone_max": max(r["speedup_fp4_matmul"] for r in rows),
-                              "peak_ratio_on_this_gpu": PEAK_FP4_TFLOPS / 2500.0},
-        "paper_context": {"gpu": "RTX 5090", "wush_quant_fp4_matmul_up_to": 5.8, "fp4_matmul_alone_up_to": 6.6,
-                          "peak_ratio_on_that_gpu": 8.0},
-        "layers": rows,
-    }
-    print(json.dumps(out))
 
 
 def decode_bench(args, P, torch, dev):
@@ -668,9 +590,6 @@ def main():
     torch.cuda.set_device(dev)
     if args.workload in DECODE:
         decode_bench(args, P, torch, dev)
-        return
-    if args.workload == "fig3":
-        fig3_bench(args, P, torch, dev)
         return
     if args.workload in W4_DECODE:
         w4_decode_bench(args, P, torch, dev)
