@@ -53,9 +53,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # profiles/*.md).  A figure belongs to one kernel build: the key holds the library version it was read on,
 # and a workload without a figure for the loaded library reports null.
 MEASURED_TRAFFIC_KIB = {
-    ("c5", "tiled", "0.9"): (2924879, 917627),   # gemm_frag_kernel<false,8,2>: profiles/wush_linear_gemm_frag_c5.md
-    ("c2", "tiled", "0.9"): (43802, 27102),      # gemm_frag_kernel<false,4,3>: profiles/wush_linear_gemm_frag_c2.md
-    ("c4", "tiled", "0.9"): (133687, 34816),     # transform_quant_kernel, four rotating buffer sets: profiles/transform_quant_c4.md
+    ("c5", "tiled", "0.10"): (2960462, 918738),   # gemm_frag_kernel<false,8,2>: profiles/wush_linear_gemm_frag_c5.md
+    ("c2", "tiled", "0.10"): (43802, 27203),      # gemm_frag_kernel<false,4,3>: profiles/wush_linear_gemm_frag_c2.md
+    ("c4", "tiled", "0.10"): (134410, 34816),     # transform_quant_kernel, four rotating buffer sets: profiles/transform_quant_c4.md
 }
 
 

@@ -116,18 +116,23 @@ __global__ __launch_bounds__(kWaves * TG * 64, 3) void int4_transform_quant_kern
   v8bf ta[kNB][2];
   tq::load_transforms(ta, T, bfirst, C, tok, h);
 
+  // Walk step j of this workgroup is tile j gridDim.x + blockIdx.x, so that the grid as a whole moves
+  // down the token rows front to back (transform_quant.hip: 10 % faster from HBM than a contiguous run of
+  // tiles per workgroup).
   const int ntiles = (M + kTileM - 1) / kTileM;
-  int t = blockIdx.x * tiles_per_wg + tg;
-  const int tend = min(blockIdx.x * tiles_per_wg + tiles_per_wg, ntiles);
-  if (t >= tend) return;
+  auto tile_of = [&](int j) { return j * (int)gridDim.x + (int)blockIdx.x; };
+  auto valid = [&](int j) { return j < tiles_per_wg && tile_of(j) < ntiles; };
+  int j = tg;
+  if (!valid(j)) return;
 
   XFrag cur[kNB], nxt[kNB];
-  tq::load_tile(cur, X, ldx, min(t * kTileM + tok, M - 1), bfirst, C, h);
+  tq::load_tile(cur, X, ldx, min(tile_of(j) * kTileM + tok, M - 1), bfirst, C, h);
 
-  for (; t < tend; t += TG) {
+  for (; valid(j); j += TG) {
+    const int t = tile_of(j);
     const int m = t * kTileM + tok;
     const bool row_ok = m < M;
-    if (t + TG < tend) tq::load_tile(nxt, X, ldx, min((t + TG) * kTileM + tok, M - 1), bfirst, C, h);
+    if (valid(j + TG)) tq::load_tile(nxt, X, ldx, min(tile_of(j + TG) * kTileM + tok, M - 1), bfirst, C, h);
 
     v4u out[2];
     uint32_t sc[kNB];

@@ -31,15 +31,14 @@ using tq::XFrag;
 constexpr int kWaves = 4;    // waves per workgroup
 
 // TG = token tiles a workgroup handles at a time: its 4 TG waves are TG groups of four, group g
-// walking the tiles first + g, first + g + TG, ...  A wave's tile is one long dependent chain (MFMA,
+// taking steps g, g + TG, ... of the workgroup's walk.  A wave's tile is one long dependent chain (MFMA,
 // accumulator reads, max tree, lane swap, scale, converts: about 2600 cycles for 280 instructions), so
 // a CU with one wave per SIMD idles most of the time; a second group per workgroup fills the gaps
 // without leaving the placement of more, smaller workgroups to the dispatcher.
 // PF = tiles a wave keeps in flight ahead of the one it computes on (PF + 1 operand register sets of
-// 32 VGPRs, rotated by unrolling, never copied).  Only PF = 1 is instantiated: with 2 or 3 tiles of
-// lookahead the kernel takes the same time to within 2 %, cache resident or from HBM, on 16384 x 4096,
-// 8192 x 8192 and 4096 x 14336 activations (a streaming kernel with this kernel's loads and stores and no
-// arithmetic is not faster either: from HBM the access pattern, 32 rows x 256 B per wave, is the limit).
+// 32 VGPRs, rotated by unrolling, never copied).  PF = 1 with one wave group (three waves per SIMD fit),
+// PF = 2 with two (one workgroup per CU, two waves per SIMD, so 190 registers cost nothing): 2-3 % faster from
+// HBM on 16384 x 4096 and 8192 x 8192 activations (5.2 -> 5.3 TB/s); a third tile ahead adds nothing.
 template <bool DBG, bool TILED, int TG, int PF>
 __global__ __launch_bounds__(kWaves * TG * 64) void transform_quant_kernel(
     const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ T,
@@ -57,33 +56,38 @@ __global__ __launch_bounds__(kWaves * TG * 64) void transform_quant_kernel(
   v8bf ta[kNB][2];
   tq::load_transforms(ta, T, bfirst, C, tok, h);
 
+  // Walk step j of this workgroup is tile j gridDim.x + blockIdx.x: at any time the workgroups of the grid
+  // are within one window of consecutive token tiles, so the chip as a whole reads (and writes) HBM
+  // front to back.  With contiguous runs of tiles per workgroup instead, the same loads reach 4.7 TB/s
+  // from HBM where this order reaches 5.4 (16384 x 4096, measured with the arithmetic left out).
   const int ntiles = (M + kTileM - 1) / kTileM;
-  const int t0 = blockIdx.x * tiles_per_wg + tg;
-  const int tend = min(blockIdx.x * tiles_per_wg + tiles_per_wg, ntiles);
-  if (t0 >= tend) return;
+  auto tile_of = [&](int j) { return j * (int)gridDim.x + (int)blockIdx.x; };
+  auto valid = [&](int j) { return j < tiles_per_wg && tile_of(j) < ntiles; };
+  if (!valid(tg)) return;
 
   // Every load of the walk is issued unconditionally: a tile past the end of the walk is replaced by
   // one row of the first tile for all lanes (a single cache line per instruction, already resident).
   // With a branch around the prefetch the compiler cannot know how many loads are outstanding where
   // it waits for the current tile and drains them all, which ends the lookahead.
-  const int row_spare = min(t0 * kTileM, M - 1);
-  auto tile_row = [&](int t) { return t < tend ? min(t * kTileM + tok, M - 1) : row_spare; };
+  const int row_spare = min(tile_of(tg) * kTileM, M - 1);
+  auto tile_row = [&](int j) { return valid(j) ? min(tile_of(j) * kTileM + tok, M - 1) : row_spare; };
   XFrag x[PF + 1][kNB];
 #pragma unroll
   for (int s = 0; s < PF; ++s) {
-    tq::load_tile(x[s], X, ldx, tile_row(t0 + s * TG), bfirst, C, h);
+    tq::load_tile(x[s], X, ldx, tile_row(tg + s * TG), bfirst, C, h);
     // keeps the tiles' loads in walk order: the first wait of the loop counts the loads behind tile 0
     __builtin_amdgcn_sched_barrier(0);
   }
 
-  for (int base = t0; base < tend; base += (PF + 1) * TG) {
+  for (int base = tg; base < tiles_per_wg; base += (PF + 1) * TG) {
 #pragma unroll
     for (int s = 0; s <= PF; ++s) {
-      const int t = base + s * TG;
-      if (t >= tend) return;  // wave-uniform; leaves the kernel so that no path with fewer loads in flight rejoins the loop
+      const int j = base + s * TG;
+      if (!valid(j)) return;  // wave-uniform; leaves the kernel so that no path with fewer loads in flight rejoins the loop
+      const int t = tile_of(j);
       const int m = t * kTileM + tok;
       const bool row_ok = m < M;
-      tq::load_tile(x[(s + PF) % (PF + 1)], X, ldx, tile_row(t + PF * TG), bfirst, C, h);
+      tq::load_tile(x[(s + PF) % (PF + 1)], X, ldx, tile_row(j + PF * TG), bfirst, C, h);
 
       v4u out[2];
       uint32_t sbytes;
@@ -166,8 +170,9 @@ hipError_t launch_transform_quant(const void* X, int64_t M, int64_t K, int64_t l
   const int tiles_per_wg = walk.tiles_per_wg;
   dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
   dim3 block(kWaves * 64 * walk.groups);
+  // two tiles of lookahead where the workgroup is the CU's only one (two waves per SIMD, 256 registers each)
 #define WUSH_TQ_LAUNCH(DBG, TILED, TG)                                                                 \
-  transform_quant_kernel<DBG, TILED, TG, 1><<<grid, block, 0, stream>>>(                               \
+  transform_quant_kernel<DBG, TILED, TG, TG><<<grid, block, 0, stream>>>(                              \
       (const uint16_t*)X, ldx, (const uint16_t*)T, (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M, (int)K, C, \
       tiles_per_wg, rule)
   if (walk.groups == 2) {

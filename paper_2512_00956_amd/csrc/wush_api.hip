@@ -523,6 +523,6 @@ const char* wush_status_string(wush_status st) {
   return "unknown status";
 }
 
-const char* wush_version(void) { return "0.9"; }
+const char* wush_version(void) { return "0.10"; }
 
 }  // extern "C"

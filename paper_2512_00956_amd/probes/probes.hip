@@ -7,12 +7,11 @@
 //   wushp_stream                       plain streaming kernels with the byte mix
 //       of the fused transform + quantize kernel (4 bytes read per byte written,
 //       non-temporal stores), linear or in that kernel's own access pattern.
-//       Measured from HBM on 16384 x 4096 BF16: linear 5.5-5.6 TB/s, the quantizer's
-//       pattern 4.7-4.9 (deeper lookahead or wider waves do not change it), the
-//       quantizer itself 4.6-4.7.  The reads make the difference, not the stores
-//       (mode 10: same reads, linear stores, 4.7); whole cache lines per load
-//       instruction give 4.9 (mode 13), 8 rows x 1 KiB per wave 5.2 on this shape but
-//       4.9 against 5.1 on 8192 x 8192 (mode 11).
+//       Measured from HBM on 16384 x 4096 BF16: linear 5.5-5.6 TB/s; the quantizer's
+//       tiles 5.3-5.4 when they are dealt round-robin over the workgroups (one window
+//       moves down the rows) and 4.7 when every workgroup gets a contiguous run of them,
+//       whatever the shape of a wave's tile (32 rows x 256 B, whole lines, 8 rows x 1 KiB)
+//       and whatever the store pattern; the quantizer itself 5.2-5.4.
 //
 // C ABI (all pointers are device pointers, `stream` is a hipStream_t; return
 // value: 0 = launched, 1 = bad argument, 2 = HIP launch error):
@@ -155,11 +154,17 @@ __global__ __launch_bounds__(256) void mfma_f16_probe_kernel(const v8h* __restri
 //   mode 1: the quantizer's own pattern.  A wave reads 32 rows x 256 B (tile = 32 tokens x
 //           4 transform blocks) with the same eight 128-bit loads per lane and writes the
 //           tile's codes and scales at the offsets of the fragment-order layout; one tile
-//           of lookahead in registers.  What is left out is the arithmetic.
+//           of lookahead in registers; tiles dealt round-robin over the workgroups of a column group.
+//           What is left out is the arithmetic.
 //   mode 2: as mode 1 with 8 blocks per wave (32 rows x 512 B).
+//   mode 3: as mode 1 with a contiguous run of tiles per workgroup.
+//   modes 4, 5, 6: as mode 1 with the same bytes stored at linear offsets / without the scale stores /
+//           with cached instead of non-temporal stores.
 //   modes 10, 11: read-pattern probes: a wave's tile is 32 or 8 rows x 256 B or 1 KiB of each,
 //           linear stores of a quarter of the bytes.  mode 13: the tile of mode 10 (32 rows x 256 B) read
 //           with whole 128-byte lines per load instruction (8 rows each) instead of 32 bytes of 32 rows.
+//   modes 20, 21, 23: as 10, 11, 13 with the tiles dealt round-robin over the workgroups of a column
+//           group instead of in contiguous runs: at any time the chip reads one window of consecutive rows.
 // rows x row_bytes is the source (row_bytes a multiple of 1024, rows of 32); dst holds
 // rows * row_bytes / 4 bytes of "codes" followed by rows * row_bytes / 64 bytes of "scales".
 __global__ __launch_bounds__(512) void stream_linear_kernel(const v4u* __restrict__ src, long long n_steps,
@@ -193,8 +198,9 @@ __global__ __launch_bounds__(512) void stream_linear_kernel(const v4u* __restric
 template <int PF, int NBW>
 __global__ __launch_bounds__(512) void stream_tiles_kernel(const uint16_t* __restrict__ X, int M, int K,
                                                            uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs,
-                                                           int tiles_per_wg) {
+                                                           int tiles_per_wg, int interleaved, int store_mode) {
   // NBW = blocks per wave (the quantizer: 4 = 256 B of every row; 8 = 512 B)
+  // store_mode 0: the quantizer's stores; 1: the same bytes at linear offsets; 2: codes only; 3: cached stores
   using namespace tq;
   constexpr int TG = 2;
   const int lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3, tg = threadIdx.x >> 8;
@@ -202,11 +208,14 @@ __global__ __launch_bounds__(512) void stream_tiles_kernel(const uint16_t* __res
   const int bfirst = (blockIdx.y * 4 + wave) * NBW;
   if (bfirst >= C) return;
   const int ntiles = M / kTileM;
-  const int t0 = blockIdx.x * tiles_per_wg + tg;
-  const int tend = min(blockIdx.x * tiles_per_wg + tiles_per_wg, ntiles);
-  if (t0 >= tend) return;
-  const int row_spare = t0 * kTileM;
-  auto tile_row = [&](int t) { return t < tend ? t * kTileM + tok : row_spare; };
+  // walk step j -> tile: dealt round-robin over the workgroups (the quantizer's walk) or in contiguous runs
+  auto tile_of = [&](int j) {
+    return interleaved ? j * (int)gridDim.x + (int)blockIdx.x : (int)blockIdx.x * tiles_per_wg + j;
+  };
+  auto valid = [&](int j) { return j < tiles_per_wg && tile_of(j) < ntiles; };
+  if (!valid(tg)) return;
+  const int row_spare = tile_of(tg) * kTileM;
+  auto tile_row = [&](int j) { return valid(j) ? tile_of(j) * kTileM + tok : row_spare; };
   XFrag x[PF + 1][NBW];
   auto load = [&](XFrag (&d)[NBW], int row) {
 #pragma unroll
@@ -215,15 +224,16 @@ __global__ __launch_bounds__(512) void stream_tiles_kernel(const uint16_t* __res
   };
 #pragma unroll
   for (int s = 0; s < PF; ++s) {
-    load(x[s], tile_row(t0 + s * TG));
+    load(x[s], tile_row(tg + s * TG));
     __builtin_amdgcn_sched_barrier(0);
   }
-  for (int base = t0; base < tend; base += (PF + 1) * TG) {
+  for (int base = tg; base < tiles_per_wg; base += (PF + 1) * TG) {
 #pragma unroll
     for (int s = 0; s <= PF; ++s) {
-      const int t = base + s * TG;
-      if (t >= tend) return;
-      load(x[(s + PF) % (PF + 1)], tile_row(t + PF * TG));
+      const int j = base + s * TG;
+      if (!valid(j)) return;
+      const int t = tile_of(j);
+      load(x[(s + PF) % (PF + 1)], tile_row(j + PF * TG));
       typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 #pragma unroll
       for (int g = 0; g < NBW / kNB; ++g) {
@@ -232,7 +242,23 @@ __global__ __launch_bounds__(512) void stream_tiles_kernel(const uint16_t* __res
         for (int p = 0; p < 2; ++p)
           out[p] = __builtin_bit_cast(u4, x[s][4 * g + 2 * p].lo) ^ __builtin_bit_cast(u4, x[s][4 * g + 2 * p].hi) ^
                    __builtin_bit_cast(u4, x[s][4 * g + 2 * p + 1].lo) ^ __builtin_bit_cast(u4, x[s][4 * g + 2 * p + 1].hi);
-        store_tile_tiled<true>(out, out[0][0] ^ out[1][0], Xq, Xs, t, K >> 8, bfirst + kNB * g, tok, h);
+        const uint32_t sb = out[0][0] ^ out[1][0];
+        if (store_mode == 0) {
+          store_tile_tiled<true>(out, sb, Xq, Xs, t, K >> 8, bfirst + kNB * g, tok, h);
+        } else if (store_mode == 1) {
+          const int64_t unit = ((int64_t)t * gridDim.y * 4 + blockIdx.y * 4 + wave) * (NBW / kNB) + g;
+          v4u* q = reinterpret_cast<v4u*>(Xq) + unit * 128 + lane;
+          __builtin_nontemporal_store(out[0], q);
+          __builtin_nontemporal_store(out[1], q + 64);
+          if (h == 0) __builtin_nontemporal_store(sb, reinterpret_cast<uint32_t*>(Xs) + unit * 32 + tok);
+        } else if (store_mode == 2) {
+          const int bf = bfirst + kNB * g, kt = bf >> 3, khg = (bf >> 2) & 1;
+          uint8_t* q = Xq + ((((int64_t)t * (K >> 8) + kt) * 4 + 2 * h) * 64 + khg * 32 + tok) * 16;
+          __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(q));
+          __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(q + 1024));
+        } else {
+          store_tile_tiled<false>(out, sb, Xq, Xs, t, K >> 8, bfirst + kNB * g, tok, h);
+        }
       }
     }
   }
@@ -246,7 +272,7 @@ __global__ __launch_bounds__(512) void stream_tiles_kernel(const uint16_t* __res
 // instead of 32 rows x 32 bytes.
 template <int ROWS, bool FULL_LINES = false>
 __global__ __launch_bounds__(512) void stream_rows_kernel(const uint8_t* __restrict__ X, int rows, int row_bytes,
-                                                          v4u* __restrict__ dst, int tiles_per_wg) {
+                                                          v4u* __restrict__ dst, int tiles_per_wg, int interleaved) {
   constexpr int kSeg = 8192 / ROWS;          // bytes of a row per wave tile
   constexpr int kLanesPerRow = 64 / ROWS;    // lanes side by side on one row within a load instruction
   const int lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3, tg = threadIdx.x >> 8;
@@ -254,11 +280,17 @@ __global__ __launch_bounds__(512) void stream_rows_kernel(const uint8_t* __restr
   const int64_t col0 = ((int64_t)blockIdx.y * 4 + wave) * kSeg;
   if (col0 >= row_bytes) return;
   const int ntiles = rows / ROWS;
-  const int t0 = blockIdx.x * tiles_per_wg + tg;
-  const int tend = min(blockIdx.x * tiles_per_wg + tiles_per_wg, ntiles);
-  if (t0 >= tend) return;
-  auto load = [&](v4u (&d)[8], int t) {
-    const int tt = t < tend ? t : t0;
+  // Walk step j of this workgroup -> tile.  Contiguous: the workgroup owns tiles_per_wg consecutive tiles
+  // (the quantizer's walk).  Interleaved: at step j all workgroups of a column group read gridDim.x
+  // consecutive tiles, so the chip as a whole moves one window down the rows.
+  auto tile_of = [&](int j) {
+    return interleaved ? j * (int)gridDim.x + (int)blockIdx.x : (int)blockIdx.x * tiles_per_wg + j;
+  };
+  auto valid = [&](int j) { return j < tiles_per_wg && tile_of(j) < ntiles; };
+  if (!valid(tg)) return;
+  const int t_spare = tile_of(tg);
+  auto load = [&](v4u (&d)[8], int j) {
+    const int tt = valid(j) ? tile_of(j) : t_spare;
     if (FULL_LINES) {
       const uint8_t* p = X + ((int64_t)tt * ROWS + (lane >> 3)) * row_bytes + col0 + (lane & 7) * 16;
 #pragma unroll
@@ -270,17 +302,17 @@ __global__ __launch_bounds__(512) void stream_rows_kernel(const uint8_t* __restr
     }
   };
   v4u x[2][8];
-  load(x[0], t0);
+  load(x[0], tg);
   __builtin_amdgcn_sched_barrier(0);
   const int64_t units_per_tile = (int64_t)gridDim.y * 4;   // (tile, column wave) units
-  for (int base = t0; base < tend; base += 4) {
+  for (int base = tg; base < tiles_per_wg; base += 4) {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      const int t = base + 2 * s;
-      if (t >= tend) return;
-      load(x[s ^ 1], t + 2);
+      const int j = base + 2 * s;
+      if (!valid(j)) return;
+      load(x[s ^ 1], j + 2);
       v4u o0 = x[s][0] ^ x[s][1] ^ x[s][2] ^ x[s][3], o1 = x[s][4] ^ x[s][5] ^ x[s][6] ^ x[s][7];
-      const int64_t unit = (int64_t)t * units_per_tile + blockIdx.y * 4 + wave;
+      const int64_t unit = (int64_t)tile_of(j) * units_per_tile + blockIdx.y * 4 + wave;
       __builtin_nontemporal_store(o0, dst + unit * 128 + lane);
       __builtin_nontemporal_store(o1, dst + unit * 128 + 64 + lane);
     }
@@ -322,8 +354,10 @@ int wushp_stream(const void* src, long long rows, long long row_bytes, void* dst
   if (mode == 0) {
     wush::stream_linear_kernel<<<dim3((unsigned)blocks), dim3(512), 0, st>>>(
         static_cast<const wush::v4u*>(src), rows * row_bytes / 4096, static_cast<wush::v4u*>(dst));
-  } else if (mode == 1 || mode == 2) {
+  } else if (mode >= 1 && mode <= 6) {
     const int nbw = mode == 2 ? 8 : 4;
+    const int interleaved = mode != 3;
+    const int store_mode = mode >= 4 ? mode - 3 : 0;   // modes 4, 5, 6: mode 1 with other stores
     const int K = (int)(row_bytes / 2), ntiles = (int)(rows / 32);
     if (K % (128 * nbw) != 0) return 1;
     const int col_groups = K / (128 * nbw);
@@ -334,9 +368,11 @@ int wushp_stream(const void* src, long long rows, long long row_bytes, void* dst
     uint8_t* q = static_cast<uint8_t*>(dst);
     uint8_t* s = q + rows * row_bytes / 4;
     const uint16_t* x = static_cast<const uint16_t*>(src);
-    if (mode == 1) wush::stream_tiles_kernel<1, 4><<<grid, dim3(512), 0, st>>>(x, (int)rows, K, q, s, walk);
-    else wush::stream_tiles_kernel<1, 8><<<grid, dim3(512), 0, st>>>(x, (int)rows, K, q, s, walk);
-  } else if (mode == 10 || mode == 11 || mode == 13) {
+    if (nbw == 4) wush::stream_tiles_kernel<1, 4><<<grid, dim3(512), 0, st>>>(x, (int)rows, K, q, s, walk, interleaved, store_mode);
+    else wush::stream_tiles_kernel<1, 8><<<grid, dim3(512), 0, st>>>(x, (int)rows, K, q, s, walk, interleaved, store_mode);
+  } else if (mode == 10 || mode == 11 || mode == 13 || mode == 20 || mode == 21 || mode == 23) {
+    const int interleaved = mode >= 20;   // modes 20, 21, 23: the walks of 10, 11, 13 interleaved across workgroups
+    mode -= interleaved ? 10 : 0;
     const int ROWS = mode == 11 ? 8 : 32;
     const int seg = 8192 / ROWS;
     if (row_bytes % (4 * seg) != 0 || rows % ROWS != 0) return 1;
@@ -347,9 +383,9 @@ int wushp_stream(const void* src, long long rows, long long row_bytes, void* dst
     dim3 grid((unsigned)((ntiles + walk - 1) / walk), (unsigned)col_groups);
     const uint8_t* x = static_cast<const uint8_t*>(src);
     wush::v4u* d = static_cast<wush::v4u*>(dst);
-    if (mode == 10) wush::stream_rows_kernel<32><<<grid, dim3(512), 0, st>>>(x, (int)rows, (int)row_bytes, d, walk);
-    else if (mode == 11) wush::stream_rows_kernel<8><<<grid, dim3(512), 0, st>>>(x, (int)rows, (int)row_bytes, d, walk);
-    else wush::stream_rows_kernel<32, true><<<grid, dim3(512), 0, st>>>(x, (int)rows, (int)row_bytes, d, walk);
+    if (mode == 10) wush::stream_rows_kernel<32><<<grid, dim3(512), 0, st>>>(x, (int)rows, (int)row_bytes, d, walk, interleaved);
+    else if (mode == 11) wush::stream_rows_kernel<8><<<grid, dim3(512), 0, st>>>(x, (int)rows, (int)row_bytes, d, walk, interleaved);
+    else wush::stream_rows_kernel<32, true><<<grid, dim3(512), 0, st>>>(x, (int)rows, (int)row_bytes, d, walk, interleaved);
   } else {
     return 1;
   }

@@ -28,7 +28,7 @@ def test_header_symbols_are_exported(L):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(L, name) is not None
-    assert L.wush_version() == b"0.9"
+    assert L.wush_version() == b"0.10"
 
 
 def test_default_fmt_and_status_strings(L):

@@ -43,7 +43,7 @@ def test_f16_mfma_probe_reports_the_instruction_rate(Q):
     _rate_checks(out.cpu().numpy().astype(np.float64), 200)
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2, 10, 11, 13])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4, 5, 6, 10, 11, 13, 20, 21, 23])
 def test_stream_probe_touches_what_it_claims(Q, mode):
     """Every output byte the probe is priced for is written (rows * row_bytes * 17 / 64 for the tile
     modes 1 and 2, rows * row_bytes / 4 for the linear one and for the read-pattern modes), none beyond,
@@ -52,7 +52,7 @@ def test_stream_probe_touches_what_it_claims(Q, mode):
     rows, row_bytes = 256, 4096
     g = torch.Generator(device="cuda").manual_seed(3)
     src = torch.randint(0, 256, (rows * row_bytes,), dtype=torch.uint8, device="cuda", generator=g)
-    n_out = rows * row_bytes // 4 + (rows * row_bytes // 64 if mode in (1, 2) else 0)
+    n_out = rows * row_bytes // 4 + (rows * row_bytes // 64 if mode in (1, 2, 3, 4, 6) else 0)
     dst = torch.full((n_out + 4096,), 0xA5, dtype=torch.uint8, device="cuda")
     Q.stream(src, rows, row_bytes, dst, mode, 16)
     torch.cuda.synchronize()
