@@ -466,7 +466,9 @@ wush_status wush_unpack_tiled(const void* q_tiled, const void* s_tiled, int64_t 
  *   WUSH_DEBUG_GEMM_SKINNY          wush_linear up to 128 tokens: 1 = weight-streaming kernel, 0 = tiled kernel
  *   WUSH_DEBUG_GEMM_SIMPLE          wush_linear, canonical layout: 1 = the general one-wave-per-tile kernel
  *   WUSH_DEBUG_W4_WIDTH             wush_linear_nvfp4 / _int4: tile width 2..4 (x 64 output channels)
- *   WUSH_DEBUG_W4_SKINNY            wush_linear_nvfp4 / _int4 up to 128 tokens: 1 = weight-streaming, 0 = tiled
+ *   WUSH_DEBUG_W4_SKINNY            wush_linear_nvfp4 / _int4 up to 128 tokens: 0 = tiled kernel; weight-streaming kernel with
+ *                                   1 = K split over a workgroup's waves, 2 = activations shared through LDS (65..128 tokens;
+ *                                   with fewer it is 1)
  *   WUSH_DEBUG_DECODE_FUSED         wush_layer_decode: 1 = one launch with a grid-wide barrier
  *   WUSH_DEBUG_DECODE_TEST_TIMEOUT  wush_layer_decode: 1 = the barrier wait gives up at once (error-path test)
  * Returns WUSH_ERR_FMT for an unknown option, WUSH_ERR_SHAPE for a value outside -1 .. 1023.

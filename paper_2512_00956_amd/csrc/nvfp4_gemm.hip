@@ -658,7 +658,7 @@ hipError_t launch_w4_f16_gemm(const void* Xq, const void* Xs, const float* tsx, 
 static bool w4_streaming(int64_t M, int tiled) {
   if (!tiled || M > 128) return false;
   const int forced = debug_option(kDbgW4Skinny);
-  return forced >= 0 ? forced == 1 : true;
+  return forced >= 0 ? forced >= 1 : true;   // 1, 2: either schedule of the streaming kernel
 }
 
 hipError_t launch_nvfp4_gemm(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,

@@ -75,6 +75,7 @@ __global__ __launch_bounds__(kWaves * 64) void w4_skinny_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r = lane & 31, h = lane >> 5;
   const int KT = K >> 6, NB = (N + 31) >> 5;
+  const int nrb = (M + 31) >> 5;   // row blocks the X buffers hold (a multiple of 32 rows): a block past them re-reads the last, never stored
   const int groups = (NB + CBW - 1) / CBW;
   const uint32_t sel = 0x05040C0Cu + 0x02020000u * h;
   const float scale = FMT == kNvfp4 ? *tsx * *tsw : 1.0f;   // INT4 has no tensor scales (null pointers)
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(kWaves * 64) void w4_skinny_kernel(
       for (int u = 0; u < U; ++u) {
         const int k = min(kt + u, kt1 - 1);
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) load_step(ch.x[rb][u], Xq, Xs, (int64_t)rb * KT + k, r, h);
+        for (int rb = 0; rb < RB; ++rb) load_step(ch.x[rb][u], Xq, Xs, (int64_t)min(rb, nrb - 1) * KT + k, r, h);
       }
     };
     auto multiply_chunk = [&](const Chunk& ch, int kt) {
@@ -147,9 +148,188 @@ __global__ __launch_bounds__(kWaves * 64) void w4_skinny_kernel(
   }
 }
 
+// Second schedule, for more than 32 tokens on layers with many output channels.  Above, every wave
+// converts the X fragments it multiplies, RB row blocks per K step and workgroup of 32 output channels:
+// beyond 32 tokens the activations, read from the L2 and converted once per workgroup, outweigh the weight
+// stream (128 tokens: four times its bytes and conversions).  Here the four waves of a workgroup take four
+// different groups of CBW output-channel blocks and all walk the WHOLE K range in step, so that they multiply
+// the same X fragments: each wave converts a quarter of them (two (row block, K step) pairs of a chunk of eight)
+// to FP16 and leaves them in LDS in MFMA operand order (lane-linear 16-byte accesses, conflict free); a chunk is
+// double buffered, one barrier per chunk; the barrier's fences name LDS only, so the weight loads of the next
+// chunk stay in flight across it.  Per 32 x 64 block of weights a wave now spends its 32 conversion operations, RB
+// x 4 LDS reads and RB x 4 MFMAs; the raw X traffic and its conversion drop by four.  No partial sums across
+// waves: a wave's accumulators are final and go straight to Y (one FP32 chain over K per element).
+// It needs a workgroup per 4 CBW blocks of output channels, so few channels leave CUs idle: the launcher
+// takes it when that still fills the chip.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Accumulator e of lane (r, h), row block rb: token 32 rb + r, output channel 32 j + 8 (e / 4) + 4 h + e % 4.
+template <int RB, bool OUT_F32>
+__device__ __forceinline__ void store_block(const v16f (&acc)[RB], int j, int M, int N, void* __restrict__ Y,
+                                            int64_t ldy, int vec_store, int r, int h, float scale) {
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int row = 32 * rb + r;
+    if (row >= M) continue;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int col = 32 * j + 8 * q + 4 * h;
+      if (col >= N) continue;
+      float v[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) v[t] = acc[rb][4 * q + t] * scale;
+      if (OUT_F32) {
+        float* y = reinterpret_cast<float*>(Y) + (int64_t)row * ldy + col;
+        if (vec_store) {
+          *reinterpret_cast<v4f*>(y) = (v4f){v[0], v[1], v[2], v[3]};
+        } else {
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            if (col + t < N) y[t] = v[t];
+        }
+      } else {
+        uint16_t* y = reinterpret_cast<uint16_t*>(Y) + (int64_t)row * ldy + col;
+        if (vec_store) {
+          v2u two;
+          two[0] = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
+          two[1] = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
+          *reinterpret_cast<v2u*>(y) = two;
+        } else {
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            if (col + t < N) y[t] = f32_to_bf16_bits(v[t]);
+        }
+      }
+    }
+  }
+}
+
+// (row block, K step) pairs of X per chunk, 4 KiB of FP16 fragments each: four K steps up to 64 tokens, two beyond
+template <int RB>
+struct Chunk {
+  static constexpr int kPairs = RB == 1 ? 4 : 8;
+};
+// chunks of weights in flight ahead of the multiply: what the registers next to the accumulators allow
+template <int RB, int CBW>
+struct Ahead { static constexpr int kChunks = RB == 1 ? 2 : (CBW == 2 ? 1 : (RB == 4 ? 3 : 2)); };
+static_assert(Chunk<4>::kPairs % kWaves == 0, "every wave converts the same number of pairs");
+
+template <int RB, int CBW, int FMT, bool OUT_F32>
+__global__ __launch_bounds__(kWaves * 64, 2) void w4_shared_x_kernel(
+    const uint8_t* __restrict__ Xq, const uint8_t* __restrict__ Xs, const float* __restrict__ tsx,
+    const uint8_t* __restrict__ Wq, const uint8_t* __restrict__ Ws, const float* __restrict__ tsw,
+    int M, int N, int K, void* __restrict__ Y, int64_t ldy, int vec_store) {
+  constexpr int kPairs = Chunk<RB>::kPairs;
+  constexpr int U = kPairs / RB;            // K steps per chunk
+  constexpr int kMine = kPairs / kWaves;    // pairs a wave converts per chunk
+  __shared__ v4u xf[2][kPairs][4][64];      // [buffer][pair = step RB + row block][MFMA of the step][lane]: 32 or 64 KiB
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = lane & 31, h = lane >> 5;
+  const int KT = K >> 6, NB = (N + 31) >> 5;
+  const int nrb = (M + 31) >> 5;   // row blocks the X buffers hold: a block past them re-reads the last, never stored
+  const int groups = (NB + kWaves * CBW - 1) / (kWaves * CBW);
+  const int nch = (KT + U - 1) / U;
+  const uint32_t sel = 0x05040C0Cu + 0x02020000u * h;
+  const float scale = FMT == kNvfp4 ? *tsx * *tsw : 1.0f;
+
+  for (int g = blockIdx.x; g < groups; g += gridDim.x) {
+    int64_t jb[CBW];   // this wave's weight blocks; one past the end repeats the last (never stored)
+#pragma unroll
+    for (int c = 0; c < CBW; ++c) jb[c] = min((g * kWaves + wave) * CBW + c, NB - 1);
+    v16f acc[CBW][RB];
+#pragma unroll
+    for (int c = 0; c < CBW; ++c)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) acc[c][rb] = (v16f){0};
+
+    // All loads are unconditional (a step past the end re-reads the last one): exact wait counts.
+    RawStep xr[kMine];
+    auto load_x = [&](int ch) {
+#pragma unroll
+      for (int m = 0; m < kMine; ++m) {
+        const int p = wave + kWaves * m, u = p / RB, rb = p % RB;
+        load_step(xr[m], Xq, Xs, (int64_t)min(rb, nrb - 1) * KT + min(ch * U + u, KT - 1), r, h);
+      }
+    };
+    auto convert_x = [&](int buf) {
+#pragma unroll
+      for (int m = 0; m < kMine; ++m) {
+        v8h f[4];
+        dequant_step<FMT>(xr[m], h, sel, f);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) xf[buf][wave + kWaves * m][d][lane] = __builtin_bit_cast(v4u, f[d]);
+      }
+    };
+    auto load_w = [&](RawStep (&w)[CBW][U], int ch) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < CBW; ++c) load_step(w[c][u], Wq, Ws, jb[c] * KT + min(ch * U + u, KT - 1), r, h);
+    };
+    auto multiply = [&](const RawStep (&w)[CBW][U], int ch, int buf) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ch * U + u < KT) {
+          v2h sc[CBW];
+#pragma unroll
+          for (int c = 0; c < CBW; ++c) sc[c] = w_step_scales<FMT>(w[c][u].s, h, sel);
+          // one MFMA of the step (8 of the lane's 32 codes per operand) at a time: few registers in flight
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            v8h fw[CBW];
+#pragma unroll
+            for (int c = 0; c < CBW; ++c) {
+              const v2h s2 = {sc[c][d >> 1], sc[c][d >> 1]};
+              fw[c] = __builtin_bit_cast(v8h, FMT == kNvfp4 ? dequant8(w[c][u].q[d], s2) : dequant8_int4(w[c][u].q[d], s2));
+            }
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+              const v8h fx = __builtin_bit_cast(v8h, xf[buf][u * RB + rb][d][lane]);
+#pragma unroll
+              for (int c = 0; c < CBW; ++c)
+                acc[c][rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[c], fx, acc[c][rb], 0, 0, 0);
+            }
+          }
+        }
+    };
+    // The weights of D chunks are in flight ahead of the one being multiplied (D + 1 register sets that take
+    // turns by unrolling); the X fragments of the next chunk are converted while this one is multiplied.
+    constexpr int D = Ahead<RB, CBW>::kChunks, NBUF = D + 1;
+    RawStep w[NBUF][CBW][U];
+#pragma unroll
+    for (int s = 0; s < D; ++s) load_w(w[s], s);
+    load_x(0);
+    convert_x(0);
+    load_x(1);
+    lds_barrier();
+    for (int base = 0; base < nch; base += NBUF) {
+#pragma unroll
+      for (int s = 0; s < NBUF; ++s) {
+        const int ch = base + s;           // past the last chunk: loads repeat the last step, nothing is multiplied,
+        load_w(w[(s + D) % NBUF], ch + D); // and every wave still meets the barrier
+        convert_x((ch + 1) & 1);
+        load_x(ch + 2);
+        multiply(w[s], ch, ch & 1);
+        lds_barrier();
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < CBW; ++c) {
+      const int j = (g * kWaves + wave) * CBW + c;
+      if (j < NB) store_block<RB, OUT_F32>(acc[c], j, M, N, Y, ldy, vec_store, r, h, scale);
+    }
+  }
+}
+
 template <int FMT>
-hipError_t launch(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws, const float* tsw,
-                  int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy, hipStream_t stream) {
+hipError_t launch_split_k(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
+                          const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
+                          hipStream_t stream) {
   const int NB = (int)((N + 31) / 32);
   // Two weight blocks per pass once that still leaves every CU two workgroups or more (up to 64 tokens:
   // beyond, the accumulators of two blocks leave room for a single wave per SIMD).
@@ -173,6 +353,45 @@ hipError_t launch(const void* Xq, const void* Xs, const float* tsx, const void* 
 #undef WUSH_W4S_BY_OUT
 #undef WUSH_W4S_LAUNCH
   return hipGetLastError();
+}
+
+// The shared-X schedule is built for 65..128 tokens with one weight block per wave: the only shape in which it
+// beats the K split (measured, us, K split | shared X, 8192 -> 57344 at 96 and 128 tokens: NVFP4 140 | 134 and
+// 147 | 127, INT4 206 | 150 and 205 | 150; 8192 -> 28672: NVFP4 71 | 85 and 72 | 86, INT4 114 | 92 and 120 | 97;
+// 4096 -> 24576: 32 | 46 and 51 | 50).  With fewer tokens the K split's conversions are already cheap, with two
+// weight blocks per wave too few workgroups are left, and with fewer output channels the whole-K walk of a wave
+// leaves CUs idle.
+template <int FMT>
+hipError_t launch_shared_x(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws,
+                           const float* tsw, int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy,
+                           hipStream_t stream) {
+  const int NB = (int)((N + 31) / 32);
+  const int groups = (NB + kWaves - 1) / kWaves;
+  dim3 grid((unsigned)(groups < 4096 ? groups : 4096)), block(kWaves * 64);
+  const int vec = skinny::decode_vec_store(Y, N, ldy, out_f32);
+  if (out_f32)
+    w4_shared_x_kernel<4, 1, FMT, true><<<grid, block, 0, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, tsx,
+                                                                    (const uint8_t*)Wq, (const uint8_t*)Ws, tsw,
+                                                                    (int)M, (int)N, (int)K, Y, ldy, vec);
+  else
+    w4_shared_x_kernel<4, 1, FMT, false><<<grid, block, 0, stream>>>((const uint8_t*)Xq, (const uint8_t*)Xs, tsx,
+                                                                     (const uint8_t*)Wq, (const uint8_t*)Ws, tsw,
+                                                                     (int)M, (int)N, (int)K, Y, ldy, vec);
+  return hipGetLastError();
+}
+
+// Which schedule: shared X for 65..128 tokens once the layer has enough output channels for it (fitted on the
+// cases above: from 3.5 workgroups of four blocks per CU for INT4, whose conversions cost more, from 7 for
+// NVFP4); the switch kDbgW4Skinny forces one (1 = K split across the waves, 2 = shared X where it exists).
+template <int FMT>
+hipError_t launch(const void* Xq, const void* Xs, const float* tsx, const void* Wq, const void* Ws, const float* tsw,
+                  int64_t M, int64_t N, int64_t K, int out_f32, void* Y, int64_t ldy, hipStream_t stream) {
+  const int forced = debug_option(kDbgW4Skinny);
+  const int64_t NB = (N + 31) / 32;
+  const bool wide = 2 * NB >= (FMT == kInt4 ? 7 : 14) * (int64_t)device_cu_count();
+  const bool shared_x = M > 64 && (forced == 2 || (forced != 1 && wide));
+  if (shared_x) return launch_shared_x<FMT>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, out_f32, Y, ldy, stream);
+  return launch_split_k<FMT>(Xq, Xs, tsx, Wq, Ws, tsw, M, N, K, out_f32, Y, ldy, stream);
 }
 
 }  // namespace

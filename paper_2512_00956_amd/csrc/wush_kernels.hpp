@@ -20,7 +20,8 @@ enum DebugOption {
   kDbgGemmSkinny = 1,        // MXFP4 GEMM, up to 128 tokens: 1 = weight-streaming kernel, 0 = tiled kernel
   kDbgGemmSimple = 2,        // canonical layout: 1 = the one-wave-per-tile kernel
   kDbgW4Width = 3,           // NVFP4 / INT4 tiled GEMM: tile width 2..4 (x 64 output channels)
-  kDbgW4Skinny = 4,          // NVFP4 / INT4 GEMM, up to 128 tokens: 1 = weight-streaming kernel, 0 = tiled kernel
+  kDbgW4Skinny = 4,          // NVFP4 / INT4 GEMM, up to 128 tokens: 0 = tiled kernel, 1, 2 = weight-streaming kernel (K split,
+                             // shared X)
   kDbgDecodeFused = 5,       // wush_layer_decode: 1 = single launch with a grid-wide barrier
   kDbgDecodeTestTimeout = 6, // wush_layer_decode: 1 = the barrier wait gives up at once (error-path test)
   kDbgCount

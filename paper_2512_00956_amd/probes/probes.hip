@@ -163,10 +163,19 @@ __global__ __launch_bounds__(256) void mfma_f16_probe_kernel(const v8h* __restri
 //   modes 10, 11: read-pattern probes: a wave's tile is 32 or 8 rows x 256 B or 1 KiB of each,
 //           linear stores of a quarter of the bytes.  mode 13: the tile of mode 10 (32 rows x 256 B) read
 //           with whole 128-byte lines per load instruction (8 rows each) instead of 32 bytes of 32 rows.
+//   modes 30, 40: as 0 and 20 with non-temporal loads.  From HBM the linear stream gains 3 % (5.75 TB/s) and
+//           loses 13 % cache resident; the tile pattern, whose load instructions take a 128-byte line in
+//           four parts, drops to 3.7 TB/s.
 //   modes 20, 21, 23: as 10, 11, 13 with the tiles dealt round-robin over the workgroups of a column
 //           group instead of in contiguous runs: at any time the chip reads one window of consecutive rows.
 // rows x row_bytes is the source (row_bytes a multiple of 1024, rows of 32); dst holds
 // rows * row_bytes / 4 bytes of "codes" followed by rows * row_bytes / 64 bytes of "scales".
+template <bool NT>
+__device__ __forceinline__ v4u load16(const v4u* p) {
+  return NT ? __builtin_nontemporal_load(p) : *p;
+}
+
+template <bool NT>
 __global__ __launch_bounds__(512) void stream_linear_kernel(const v4u* __restrict__ src, long long n_steps,
                                                             v4u* __restrict__ dst) {
   const int lane = threadIdx.x & 63;
@@ -179,7 +188,7 @@ __global__ __launch_bounds__(512) void stream_linear_kernel(const v4u* __restric
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) x[s][i] = src[step_of(wave + s * nwaves) * 256 + 64 * i + lane];
+    for (int i = 0; i < 4; ++i) x[s][i] = load16<NT>(src + step_of(wave + s * nwaves) * 256 + 64 * i + lane);
     __builtin_amdgcn_sched_barrier(0);
   }
   for (long long base = wave; base < n_steps; base += 3 * nwaves) {
@@ -188,7 +197,7 @@ __global__ __launch_bounds__(512) void stream_linear_kernel(const v4u* __restric
       const long long st = base + s * nwaves;
       if (st >= n_steps) return;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) x[(s + 2) % 3][i] = src[step_of(st + 2 * nwaves) * 256 + 64 * i + lane];
+      for (int i = 0; i < 4; ++i) x[(s + 2) % 3][i] = load16<NT>(src + step_of(st + 2 * nwaves) * 256 + 64 * i + lane);
       const v4u o = x[s][0] ^ x[s][1] ^ x[s][2] ^ x[s][3];
       __builtin_nontemporal_store(o, dst + st * 64 + lane);
     }
@@ -270,7 +279,7 @@ __global__ __launch_bounds__(512) void stream_tiles_kernel(const uint16_t* __res
 // quantizer's footprint, smaller ROWS make it more linear.
 // FULL_LINES (ROWS = 32 only): the same tile, but every load instruction covers 8 rows x one whole 128-byte line
 // instead of 32 rows x 32 bytes.
-template <int ROWS, bool FULL_LINES = false>
+template <int ROWS, bool FULL_LINES = false, bool NT = false>
 __global__ __launch_bounds__(512) void stream_rows_kernel(const uint8_t* __restrict__ X, int rows, int row_bytes,
                                                           v4u* __restrict__ dst, int tiles_per_wg, int interleaved) {
   constexpr int kSeg = 8192 / ROWS;          // bytes of a row per wave tile
@@ -294,11 +303,11 @@ __global__ __launch_bounds__(512) void stream_rows_kernel(const uint8_t* __restr
     if (FULL_LINES) {
       const uint8_t* p = X + ((int64_t)tt * ROWS + (lane >> 3)) * row_bytes + col0 + (lane & 7) * 16;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) d[i] = *reinterpret_cast<const v4u*>(p + (int64_t)(8 * (i & 3)) * row_bytes + 128 * (i >> 2));
+      for (int i = 0; i < 8; ++i) d[i] = load16<NT>(reinterpret_cast<const v4u*>(p + (int64_t)(8 * (i & 3)) * row_bytes + 128 * (i >> 2)));
     } else {
       const uint8_t* p = X + ((int64_t)tt * ROWS + r) * row_bytes + col0 + c * 16;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) d[i] = *reinterpret_cast<const v4u*>(p + i * (kSeg / 8));
+      for (int i = 0; i < 8; ++i) d[i] = load16<NT>(reinterpret_cast<const v4u*>(p + i * (kSeg / 8)));
     }
   };
   v4u x[2][8];
@@ -352,7 +361,10 @@ int wushp_stream(const void* src, long long rows, long long row_bytes, void* dst
     return 1;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (mode == 0) {
-    wush::stream_linear_kernel<<<dim3((unsigned)blocks), dim3(512), 0, st>>>(
+    wush::stream_linear_kernel<false><<<dim3((unsigned)blocks), dim3(512), 0, st>>>(
+        static_cast<const wush::v4u*>(src), rows * row_bytes / 4096, static_cast<wush::v4u*>(dst));
+  } else if (mode == 30) {
+    wush::stream_linear_kernel<true><<<dim3((unsigned)blocks), dim3(512), 0, st>>>(
         static_cast<const wush::v4u*>(src), rows * row_bytes / 4096, static_cast<wush::v4u*>(dst));
   } else if (mode >= 1 && mode <= 6) {
     const int nbw = mode == 2 ? 8 : 4;
@@ -370,6 +382,15 @@ int wushp_stream(const void* src, long long rows, long long row_bytes, void* dst
     const uint16_t* x = static_cast<const uint16_t*>(src);
     if (nbw == 4) wush::stream_tiles_kernel<1, 4><<<grid, dim3(512), 0, st>>>(x, (int)rows, K, q, s, walk, interleaved, store_mode);
     else wush::stream_tiles_kernel<1, 8><<<grid, dim3(512), 0, st>>>(x, (int)rows, K, q, s, walk, interleaved, store_mode);
+  } else if (mode == 40) {   // mode 20 with non-temporal loads
+    if (row_bytes % 1024 != 0) return 1;
+    const int col_groups = (int)(row_bytes / 1024), ntiles = (int)(rows / 32);
+    const int wg_rows = blocks / col_groups > 0 ? blocks / col_groups : 1;
+    int walk = (ntiles + wg_rows - 1) / wg_rows;
+    if (walk < 2) walk = 2;
+    dim3 grid((unsigned)((ntiles + walk - 1) / walk), (unsigned)col_groups);
+    wush::stream_rows_kernel<32, false, true><<<grid, dim3(512), 0, st>>>(
+        static_cast<const uint8_t*>(src), (int)rows, (int)row_bytes, static_cast<wush::v4u*>(dst), walk, 1);
   } else if (mode == 10 || mode == 11 || mode == 13 || mode == 20 || mode == 21 || mode == 23) {
     const int interleaved = mode >= 20;   // modes 20, 21, 23: the walks of 10, 11, 13 interleaved across workgroups
     mode -= interleaved ? 10 : 0;

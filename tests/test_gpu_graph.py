@@ -50,6 +50,7 @@ def test_layer_replays_to_the_eager_result(P, M):
     wsp = torch.empty(P.wush_prepare_weight_workspace(N, K), dtype=torch.uint8, device="cuda")
     Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     Yd = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    Yst = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     dws = torch.empty(P.wush_layer_decode_workspace(K), dtype=torch.uint8, device="cuda")
     P.wush_layer_decode_init(dws, K)
 
@@ -60,29 +61,33 @@ def test_layer_replays_to_the_eager_result(P, M):
         P.wush_linear(Xq, Xs, Wq, Ws, Y, fmt, K=K)
         if M <= 64:
             P.wush_layer_decode(X, T, Wq, Ws, Yd, dws, fmt)
+            P.wush_layer_decode_static(X, T, Wq, Ws, Yst, fmt)     # staging in the library's static device array
 
     g = _capture(layer)
     for rep in range(3):
         X.copy_(torch.randn((M, K), device="cuda", generator=gen).to(torch.bfloat16))   # new activations, same addresses
-        T.zero_(); Y.fill_(float("nan")); Yd.fill_(float("nan")); Xq.zero_(); Wq.zero_()
+        T.zero_(); Y.fill_(float("nan")); Yd.fill_(float("nan")); Yst.fill_(float("nan")); Xq.zero_(); Wq.zero_()
         g.replay()
         torch.cuda.synchronize()
-        got = (T.clone(), Wq.clone(), Ws.clone(), Xq.clone(), Xs.clone(), Y.clone(), Yd.clone())
+        got = (T.clone(), Wq.clone(), Ws.clone(), Xq.clone(), Xs.clone(), Y.clone(), Yd.clone(), Yst.clone())
         scratch = torch.randn((1 << 20,), device="cuda").sum().item()                     # unrelated eager work and a sync
         assert np.isfinite(scratch)
         layer()
         torch.cuda.synchronize()
         P.wush_workspace_status(wsp, K)
-        for name, a, b in zip(("T", "Wq", "Ws", "Xq", "Xs", "Y", "Yd"), got, (T, Wq, Ws, Xq, Xs, Y, Yd)):
-            if name == "Yd" and M > 64:
+        for name, a, b in zip(("T", "Wq", "Ws", "Xq", "Xs", "Y", "Yd", "Yst"), got, (T, Wq, Ws, Xq, Xs, Y, Yd, Yst)):
+            if name in ("Yd", "Yst") and M > 64:
                 continue
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (rep, name)
+        if M <= 64:
+            assert torch.equal(Yd.view(torch.uint8), Yst.view(torch.uint8))
         assert not bool(Y.isnan().any())
 
 
-def test_nvfp4_and_int4_layers_replay_to_the_eager_result(P):
+@pytest.mark.parametrize("M", [300, 40])          # the tiled GEMM, and the weight-streaming one for few tokens
+def test_nvfp4_and_int4_layers_replay_to_the_eager_result(P, M):
     import torch
-    M, K, N = 300, 1024, 520
+    K, N = 1024, 520
     gen = torch.Generator(device="cuda").manual_seed(7)
     W = (torch.randn((N, K), device="cuda", generator=gen) * 0.05).to(torch.bfloat16)
     X = torch.randn((M, K), device="cuda", generator=gen).to(torch.bfloat16)

@@ -235,12 +235,13 @@ def test_linear_every_tile_width(P, G, width, K, layout):
     assert O.rel_fro(Y.cpu().numpy().astype(np.float64), ref) <= 1e-5
 
 
-@pytest.mark.parametrize("kernel", [1, 0, -1], ids=["streaming", "tiled", "library_choice"])
+@pytest.mark.parametrize("kernel", [1, 2, 0, -1], ids=["streaming_split_k", "streaming_shared_x", "tiled", "library_choice"])
 @pytest.mark.parametrize("M", [1, 2, 7, 16, 31, 32, 33, 48, 64, 65, 100, 128])
 @pytest.mark.parametrize("K", [64, 320, 1024])
 def test_linear_few_tokens_on_either_kernel(P, G, K, M, kernel):
     """Up to 128 tokens the tiled layout takes a weight-streaming kernel (one workgroup per 32 output
-    channels, K split over its four waves); it and the tiled kernel are forced in turn on a ragged
+    channels, K split over its four waves; beyond 64 tokens also one workgroup per 128 output channels whose
+    waves share the converted activations through LDS); they and the tiled kernel are forced in turn on a ragged
     shape, FP32 and BF16 output, against the oracle on the same codes and BF16 scales."""
     import torch
     N = 1000

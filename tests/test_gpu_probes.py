@@ -43,7 +43,7 @@ def test_f16_mfma_probe_reports_the_instruction_rate(Q):
     _rate_checks(out.cpu().numpy().astype(np.float64), 200)
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4, 5, 6, 10, 11, 13, 20, 21, 23])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4, 5, 6, 10, 11, 13, 20, 21, 23, 30, 40])
 def test_stream_probe_touches_what_it_claims(Q, mode):
     """Every output byte the probe is priced for is written (rows * row_bytes * 17 / 64 for the tile
     modes 1 and 2, rows * row_bytes / 4 for the linear one and for the read-pattern modes), none beyond,
@@ -58,7 +58,7 @@ def test_stream_probe_touches_what_it_claims(Q, mode):
     torch.cuda.synchronize()
     d = dst.cpu().numpy()
     assert (d[n_out:] == 0xA5).all()
-    if mode == 0:
+    if mode in (0, 30):
         s = src.cpu().numpy().reshape(-1, 4, 1024)
         ref = s[:, 0] ^ s[:, 1] ^ s[:, 2] ^ s[:, 3]
         assert np.array_equal(d[:n_out].reshape(-1, 1024), ref)
