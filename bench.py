@@ -56,6 +56,8 @@ MEASURED_TRAFFIC_KIB = {
     ("c5", "tiled", "0.10"): (2960462, 918738),   # gemm_frag_kernel<false,8,2>: profiles/wush_linear_gemm_frag_c5.md
     ("c2", "tiled", "0.10"): (43802, 27203),      # gemm_frag_kernel<false,4,3>: profiles/wush_linear_gemm_frag_c2.md
     ("c4", "tiled", "0.10"): (134410, 34816),     # transform_quant_kernel, four rotating buffer sets: profiles/transform_quant_c4.md
+    ("d5", "tiled", "0.10"): (245616, 1794),      # gemm_skinny_kernel<1,false>: profiles/layer_decode_d2_d5.md
+    ("dn5", "tiled", "0.10"): (261307, 1793),     # w4_skinny_kernel<1,2,nvfp4,false>: profiles/w4_skinny_dn5_di5.md
 }
 
 
@@ -211,6 +213,7 @@ def decode_bench(args, P, torch, dev):
     P.wush_layer_decode_status(dws, K)
     g_ms = replay_ms(lambda: P.wush_linear(Xq, Xs, Wq, Ws, Y, fmt, K=K), args.steps)
     gemm_bytes = N * K * (0.5 + 1 / 32) + M * K * (0.5 + 1 / 32) + M * N * 2
+    traffic = traffic_for(args.workload, "tiled", P.lib().wush_version().decode())
     layer_bytes = N * K * (0.5 + 1 / 32) + quant_bytes(M, K) + M * K * (0.5 + 1 / 32) + M * N * 2
     flops = 2.0 * M * N * K
     out = {
@@ -218,11 +221,13 @@ def decode_bench(args, P, torch, dev):
         "value": flops / ms_per_step / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp4 (e2m1 x e8m0), bf16 in/out, f32 accumulate", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", **({"debug_set": args.debug_set} if args.debug_set else {}), "M": M, "K": K, "N": N,
                    "launch": "graph replay of the timed steps", "packed_layout": "tiled"},
         "roofline": {"bound": "hbm", "kernel": "wush_linear for M <= 64 (weight-streaming MXFP4 GEMM)",
                      "achieved": gemm_bytes / g_ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": gemm_bytes / g_ms / 1e6 / PEAK_HBM_GBS, "traffic": None, "avg_launch_ms": g_ms},
+                     "frac": gemm_bytes / g_ms / 1e6 / PEAK_HBM_GBS, "traffic": traffic,
+                     "algorithmic_bytes": gemm_bytes,
+                     "traffic_over_algorithmic": None if traffic is None else traffic / gemm_bytes, "avg_launch_ms": g_ms},
         "kernels": {"wush_layer_decode": {"ms": ms_per_step, "GB/s": layer_bytes / ms_per_step / 1e6,
                                           "algorithmic_bytes": layer_bytes},
                     "wush_linear": {"ms": g_ms, "GB/s": gemm_bytes / g_ms / 1e6, "algorithmic_bytes": gemm_bytes}},
@@ -298,6 +303,7 @@ def w4_decode_bench(args, P, torch, dev):
     g_ms = replay_ms(gemm, args.steps)
     gemm_bytes = (N + M) * K * (0.5 + 1 / 16) + M * N * 2
     flops = 2.0 * M * N * K
+    traffic = traffic_for(args.workload, "tiled", P.lib().wush_version().decode())
     name = "wush_linear_nvfp4" if nv else "wush_linear_int4"
     out = {
         "metric": f"W4A4 layer TFLOP/s (transform+quant+{fmt_name.upper()} GEMM); % of HBM peak",
@@ -305,11 +311,12 @@ def w4_decode_bench(args, P, torch, dev):
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": ("nvfp4 (e2m1 x e4m3 per 16 x f32 per tensor)" if nv else "int4 (two's complement x bf16 per 32)") +
                  ", bf16 in/out, f16 MFMA operands, f32 accumulate", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", **({"debug_set": args.debug_set} if args.debug_set else {}), "M": M, "K": K, "N": N,
                    "launch": "graph replay of the timed steps", "packed_layout": "tiled"},
         "roofline": {"bound": "hbm", "kernel": f"{name} for M <= 128 (weight-streaming, dequantize in registers)",
                      "achieved": gemm_bytes / g_ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": gemm_bytes / g_ms / 1e6 / PEAK_HBM_GBS, "traffic": None, "algorithmic_bytes": gemm_bytes,
+                     "frac": gemm_bytes / g_ms / 1e6 / PEAK_HBM_GBS, "traffic": traffic, "algorithmic_bytes": gemm_bytes,
+                     "traffic_over_algorithmic": None if traffic is None else traffic / gemm_bytes,
                      "avg_launch_ms": g_ms},
         "kernels": {name: {"ms": g_ms, "GB/s": gemm_bytes / g_ms / 1e6}},
     }
@@ -394,7 +401,7 @@ def nvfp4_bench(args, P, torch, dev):
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "nvfp4 (e2m1 x e4m3 per 16 x f32 per tensor), bf16 in/out, f16 MFMA operands, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", **({"debug_set": args.debug_set} if args.debug_set else {}), "M": M, "K": K, "N": N,
                    "packed_layout": args.layout, "launch": "host loop"},
         "roofline": {"bound": "mfma", "kernel": "wush_linear_nvfp4 (dequantize to FP16: X through LDS, W in registers; FP16 MFMA)",
                      "achieved": flops / g_ms / 1e9, "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
@@ -528,7 +535,7 @@ def int4_bench(args, P, torch, dev):
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int4 (two's complement x bf16 per 32), bf16 in/out, f16 MFMA operands, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", **({"debug_set": args.debug_set} if args.debug_set else {}), "M": M, "K": K, "N": N,
                    "packed_layout": args.layout, "launch": "host loop"},
         "roofline": {"bound": "mfma", "kernel": "wush_linear_int4 (dequantize to FP16: X through LDS, W in registers; FP16 MFMA)",
                      "achieved": flops / g_ms / 1e9, "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
@@ -575,6 +582,9 @@ def main():
                     help="workload c5 only: skip the transform+quantize measurement on the c4 activations")
     ap.add_argument("--cold", type=int, default=0,
                     help="rotate over this many input/output buffer sets (>1 defeats the 256 MB last-level cache)")
+    ap.add_argument("--debug-set", action="append", default=[], metavar="OPTION=VALUE",
+                    help="measurement switch of the library (wush_debug_set), e.g. DECODE_FUSED=1 or GEMM_TILE=0; "
+                         "never part of a benchmark line that is reported as the library's own choice")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -588,6 +598,9 @@ def main():
     P.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    for item in args.debug_set:
+        name, _, value = item.partition("=")
+        P.wush_debug_set(getattr(P, "WUSH_DEBUG_" + name.upper()), int(value))
     if args.workload in DECODE:
         decode_bench(args, P, torch, dev)
         return
@@ -778,7 +791,7 @@ def layer_bench(args, P, torch, dev):
         "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp4 (e2m1 x e8m0), bf16 in/out, f32 accumulate", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "M": M, "K": K, "N": N,
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", **({"debug_set": args.debug_set} if args.debug_set else {}), "M": M, "K": K, "N": N,
                    "buffer_sets": nset, "packed_layout": args.layout, "library_version": version,
                    "launch": "graph replay of the timed steps" if args.graph else "host loop"},
         "roofline": roof, "kernels": kernels,
