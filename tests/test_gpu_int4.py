@@ -366,6 +366,36 @@ def test_bench_shapes_full_size(P, G, name):
     exact = X @ O.bf16_bits_to_f64(L["W"][cols]).T
     q_err = O.rel_fro(ref, exact)
     assert O.rel_fro(y, ref) <= max(2e-3, 0.05 * q_err) and q_err < 0.25, (O.rel_fro(y, ref), q_err)
+    # every output tile: FP32 output, one seeded token row per band of 128 rows (the kernel's tiles are 256 rows
+    # high) x ALL N columns against the dequantized FP64 product of the GPU's own codes (exact inputs: FP32
+    # accumulation is the only difference), and BF16 == RNE(FP32) bit for bit
+    Y32 = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_linear_int4(Xq, Xs, Wq, Ws, Y32, layout=1, out_dtype=1, K=K)
+    torch.cuda.synchronize()
+    assert not bool(Y32.isnan().any())
+    band = np.array([min(b + int(rng.integers(0, 128)), M - 1) for b in range(0, M, 128)])
+    y32 = Y32[band.tolist()].cpu().numpy()
+    del Y32
+    assert np.array_equal(G.host(Y[band.tolist()].contiguous()), O.bf16_values_to_bits(O.round_to_bf16(y32.astype(np.float64))))
+    xq_b, xs_b = Q.unpack_codes(Xqc[band.tolist()].cpu().numpy()), _u16(Xsc[band.tolist()])
+    xn = np.linalg.norm(Q.dequantize_int4(xq_b, xs_b), axis=1)
+    wq_host, ws_host = Wqc.cpu().numpy(), _u16(Wsc)
+
+    def chunk(c0, width=2048):
+        c1 = min(N, c0 + width)
+        wc = Q.unpack_codes(wq_host[c0:c1])
+        part = Q.linear_dequant(xq_b, xs_b, wc, ws_host[c0:c1])
+        d = y32[:, c0:c1].astype(np.float64) - part
+        wn = np.linalg.norm(Q.dequantize_int4(wc, ws_host[c0:c1]), axis=1)
+        return float(np.sum(d * d)), float(np.sum(part * part)), float(np.max(np.abs(d) / (xn[:, None] * wn[None, :] + 1e-300)))
+
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        parts = list(ex.map(chunk, range(0, N, 2048)))
+    num, den, worst = sum(q[0] for q in parts), sum(q[1] for q in parts), max(q[2] for q in parts)
+    print(f"int4 {name}: every-tile check on {len(band)} rows x {N} columns: rel. Frobenius {np.sqrt(num / den):.2e}, "
+          f"largest element error / (|x| |w|) {worst:.2e}")
+    assert np.sqrt(num / den) <= 1e-5 and worst <= 1e-5
 
 
 def test_argument_validation(P, G):

@@ -515,6 +515,36 @@ def test_bench_shapes_full_size(P, G, name):
     exact = X @ O.bf16_bits_to_f64(L["W"][cols]).T
     q_err = O.rel_fro(ref, exact)
     assert O.rel_fro(y, ref) <= max(2e-3, 0.05 * q_err) and q_err < 0.25, (O.rel_fro(y, ref), q_err)
+    # every output tile: FP32 output, one seeded token row per band of 128 rows (the kernel's tiles are 256 rows
+    # high) x ALL N columns against the dequantized FP64 product of the GPU's own codes (exact inputs, so FP32
+    # accumulation and the FP32 tensor-scale multiply are the only differences), and BF16 == RNE(FP32) bit for bit
+    Y32 = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    P.wush_linear_nvfp4(Xq, Xs, tsx, Wq, Ws, tsw, Y32, layout=1, out_dtype=1, K=K)
+    torch.cuda.synchronize()
+    assert not bool(Y32.isnan().any())
+    band = np.array([min(b + int(rng.integers(0, 128)), M - 1) for b in range(0, M, 128)])
+    y32 = Y32[band.tolist()].cpu().numpy()
+    del Y32
+    assert np.array_equal(G.host(Y[band.tolist()].contiguous()), O.bf16_values_to_bits(O.round_to_bf16(y32.astype(np.float64))))
+    xc_b, xs_b = O.unpack_codes(Xqc[band.tolist()].cpu().numpy()), Xsc[band.tolist()].cpu().numpy()
+    xn = np.linalg.norm(NV.dequantize_nvfp4(xc_b, xs_b, ts), axis=1)
+    wq_host, ws_host = Wqc.cpu().numpy(), Wsc.cpu().numpy()
+
+    def chunk(c0, width=2048):
+        c1 = min(N, c0 + width)
+        wc = O.unpack_codes(wq_host[c0:c1])
+        part = NV.linear_dequant(xc_b, xs_b, ts, wc, ws_host[c0:c1], ts_w)
+        d = y32[:, c0:c1].astype(np.float64) - part
+        wn = np.linalg.norm(NV.dequantize_nvfp4(wc, ws_host[c0:c1], ts_w), axis=1)
+        return float(np.sum(d * d)), float(np.sum(part * part)), float(np.max(np.abs(d) / (xn[:, None] * wn[None, :] + 1e-300)))
+
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        parts = list(ex.map(chunk, range(0, N, 2048)))
+    num, den, worst = sum(q[0] for q in parts), sum(q[1] for q in parts), max(q[2] for q in parts)
+    print(f"nvfp4 {name}: every-tile check on {len(band)} rows x {N} columns: rel. Frobenius {np.sqrt(num / den):.2e}, "
+          f"largest element error / (|x| |w|) {worst:.2e}")
+    assert np.sqrt(num / den) <= 1e-5 and worst <= 1e-5
 
 
 def test_argument_validation(P, G):
