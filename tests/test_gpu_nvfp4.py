@@ -545,6 +545,24 @@ def test_bench_shapes_full_size(P, G, name):
     print(f"nvfp4 {name}: every-tile check on {len(band)} rows x {N} columns: rel. Frobenius {np.sqrt(num / den):.2e}, "
           f"largest element error / (|x| |w|) {worst:.2e}")
     assert np.sqrt(num / den) <= 1e-5 and worst <= 1e-5
+    # the same weights through the kernels for few tokens (16: K split over the waves, the shape bench.py times as
+    # dn2 / dn5; 100: activations shared through LDS on the wide layer), every output element, FP32 output
+    for m in (16, 100):
+        (mcb, msb) = P.wush_packed_sizes_nvfp4(m, K, 1)
+        xq_m, xs_m = G.empty_u8(mcb), G.empty_u8(msb)
+        P.wush_quantize_act_nvfp4(Xd[:m], Td, tsx, xq_m, xs_m, layout=1)
+        Ym = torch.full((m, N), float("nan"), dtype=torch.float32, device="cuda")
+        P.wush_linear_nvfp4(xq_m, xs_m, tsx, Wq, Ws, tsw, Ym, layout=1, out_dtype=1, K=K)
+        torch.cuda.synchronize()
+        y32 = Ym.cpu().numpy()
+        assert np.isfinite(y32).all()
+        xc_b, xs_b = O.unpack_codes(Xqc[:m].cpu().numpy()), Xsc[:m].cpu().numpy()     # rows of a batch do not depend on its size
+        xn = np.linalg.norm(NV.dequantize_nvfp4(xc_b, xs_b, ts), axis=1)
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            parts = list(ex.map(chunk, range(0, N, 2048)))
+        num, den, worst = sum(q[0] for q in parts), sum(q[1] for q in parts), max(q[2] for q in parts)
+        print(f"nvfp4 {name}, {m} tokens: rel. Frobenius {np.sqrt(num / den):.2e}, largest element error / (|x| |w|) {worst:.2e}")
+        assert np.sqrt(num / den) <= 1e-5 and worst <= 1e-5
 
 
 def test_argument_validation(P, G):
