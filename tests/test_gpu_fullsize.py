@@ -158,6 +158,59 @@ def _check_every_tile(P, G, L, out, rng, band=128, col_chunk=2048):
     assert worst <= 1e-5
 
 
+def _check_few_tokens(P, G, L, T, out, col_chunk=2048):
+    """The layer's weights through the kernels for few tokens, in the shapes bench.py times as d2 / d5: the first 16
+    and the first 100 tokens, FP32 output of wush_linear, EVERY output element against the dequantized FP64
+    product of the GPU's own codes (<= 1e-5 relative Frobenius, <= 1e-5 |x| |w| per element); for 16 tokens
+    wush_layer_decode and wush_layer_decode_static must give wush_linear's BF16 output bit for bit."""
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    cfg = L["cfg"]
+    K, N = cfg.K, cfg.N
+    fmt = P.default_fmt(layout=1)
+    Td = G.bf16_dev(O.bf16_values_to_bits(T))
+    wq_host, ws_host = out["Wq"].cpu().numpy(), out["Ws"].cpu().numpy()
+    for m in (16, 100):
+        Xd = G.bf16_dev(L["X"][:m])
+        xcb, xsb = P.wush_packed_sizes(m, K, fmt)
+        xq, xs = G.empty_u8(xcb), G.empty_u8(xsb)
+        P.wush_quantize_act(Xd, Td, xq, xs, fmt)
+        Y32 = torch.full((m, N), float("nan"), dtype=torch.float32, device="cuda")
+        P.wush_linear(xq, xs, out["Wq_tiled"], out["Ws_tiled"], Y32, P.default_fmt(layout=1, out_dtype=1), K=K)
+        Ybf = torch.full((m, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        P.wush_linear(xq, xs, out["Wq_tiled"], out["Ws_tiled"], Ybf, fmt, K=K)
+        torch.cuda.synchronize()
+        y32 = Y32.cpu().numpy()
+        assert np.isfinite(y32).all()
+        assert np.array_equal(G.host(Ybf), O.bf16_values_to_bits(O.round_to_bf16(y32.astype(np.float64))))
+        if m <= 64:
+            dws = G.empty_u8(P.wush_layer_decode_workspace(K))
+            P.wush_layer_decode_init(dws, K)
+            for call in (lambda Y: P.wush_layer_decode(Xd, Td, out["Wq_tiled"], out["Ws_tiled"], Y, dws, fmt),
+                         lambda Y: P.wush_layer_decode_static(Xd, Td, out["Wq_tiled"], out["Ws_tiled"], Y, fmt)):
+                Yd = torch.full((m, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+                call(Yd)
+                torch.cuda.synchronize()
+                assert torch.equal(Yd.view(torch.int16), Ybf.view(torch.int16))
+            P.wush_layer_decode_status(dws, K)
+        xd = O.dequantize(O.unpack_codes(out["Xq"][:m].cpu().numpy()), out["Xs"][:m].cpu().numpy())   # a row's codes do not depend on the batch
+        xn = np.linalg.norm(xd, axis=1)
+
+        def chunk(c0):
+            c1 = min(N, c0 + col_chunk)
+            wd = O.dequantize(O.unpack_codes(wq_host[c0:c1]), ws_host[c0:c1])
+            ref = xd @ wd.T
+            d = y32[:, c0:c1].astype(np.float64) - ref
+            rel = np.max(np.abs(d) / (xn[:, None] * np.linalg.norm(wd, axis=1)[None, :] + 1e-300))
+            return float(np.sum(d * d)), float(np.sum(ref * ref)), float(rel)
+
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            parts = list(ex.map(chunk, range(0, N, col_chunk)))
+        num, den, worst = sum(p[0] for p in parts), sum(p[1] for p in parts), max(p[2] for p in parts)
+        print(f"{cfg.name}, {m} tokens: rel. Frobenius {np.sqrt(num / den):.2e}, largest element error / (|x| |w|) {worst:.2e}")
+        assert np.sqrt(num / den) <= 1e-5 and worst <= 1e-5
+
+
 def test_c2_full(P, G):
     L = I.make_layer(I.CONFIGS["c2"])
     T = _transforms_blockwise(L)
@@ -165,6 +218,7 @@ def test_c2_full(P, G):
     _check_samples(G, L, T, out, np.random.default_rng(2))
     assert not bool(out["Y"].isnan().any())
     _check_every_tile(P, G, L, out, np.random.default_rng(12))
+    _check_few_tokens(P, G, L, T, out)
 
 
 def test_c3_full_wush_and_hadamard(P, G):
@@ -199,6 +253,7 @@ def test_c5_full(P, G):
     out = _run_layer(P, G, L, T)
     _check_samples(G, L, T, out, np.random.default_rng(5), n_rows=24, n_wrows=32, n_cols=256)
     _check_every_tile(P, G, L, out, np.random.default_rng(15))
+    _check_few_tokens(P, G, L, T, out)
 
 
 def test_offsets_beyond_4_gib(P, G):
