@@ -148,19 +148,20 @@ __global__ __launch_bounds__(kWaves * 64) void w4_skinny_kernel(
   }
 }
 
-// Second schedule, for more than 32 tokens on layers with many output channels.  Above, every wave
-// converts the X fragments it multiplies, RB row blocks per K step and workgroup of 32 output channels:
-// beyond 32 tokens the activations, read from the L2 and converted once per workgroup, outweigh the weight
-// stream (128 tokens: four times its bytes and conversions).  Here the four waves of a workgroup take four
-// different groups of CBW output-channel blocks and all walk the WHOLE K range in step, so that they multiply
-// the same X fragments: each wave converts a quarter of them (two (row block, K step) pairs of a chunk of eight)
-// to FP16 and leaves them in LDS in MFMA operand order (lane-linear 16-byte accesses, conflict free); a chunk is
-// double buffered, one barrier per chunk; the barrier's fences name LDS only, so the weight loads of the next
-// chunk stay in flight across it.  Per 32 x 64 block of weights a wave now spends its 32 conversion operations, RB
-// x 4 LDS reads and RB x 4 MFMAs; the raw X traffic and its conversion drop by four.  No partial sums across
-// waves: a wave's accumulators are final and go straight to Y (one FP32 chain over K per element).
-// It needs a workgroup per 4 CBW blocks of output channels, so few channels leave CUs idle: the launcher
-// takes it when that still fills the chip.
+// Second schedule, for 65..128 tokens on layers with many output channels.  Above, every wave converts the
+// X fragments it multiplies, RB row blocks per K step and workgroup of 32 output channels: with four row blocks the
+// activations, read from the L2 and converted once per workgroup, outweigh the weight stream (four times its bytes
+// and conversions).  Here the four waves of a workgroup take four different groups of CBW output-channel blocks
+// and all walk the WHOLE K range in step, so that they multiply the same X fragments: each wave converts a quarter
+// of them (two (row block, K step) pairs of a chunk of eight) to FP16 and leaves them in LDS in MFMA operand order
+// (lane-linear 16-byte accesses, conflict free); a chunk is double buffered, one barrier per chunk; the barrier's
+// fences name LDS only, so the weight loads of the chunks ahead stay in flight across it.  Per 32 x 64 block of
+// weights a wave now spends its 32 conversion operations, RB x 4 LDS reads and RB x 4 MFMAs; the raw X traffic and
+// its conversion drop by four.  No partial sums across waves: a wave's accumulators are final and go straight to
+// Y (one FP32 chain over K per element).
+// It needs a workgroup per 4 CBW blocks of output channels, so few channels leave CUs idle, and every MFMA reads
+// its X fragment from LDS (with CBW = 1): the launcher takes it where it was measured faster (launch()).  The
+// kernel is written for any RB and CBW; only RB = 4, CBW = 1 is instantiated.
 __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
