@@ -100,8 +100,10 @@ __device__ __forceinline__ void transform_quantize_int4(const v8bf (&ta)[kNB][2]
 }
 
 // TG: groups of four waves per workgroup, each walking every TG-th of its tiles (transform_quant.hip).
-template <bool DBG, bool TILED, int TG>
-__global__ __launch_bounds__(kWaves * TG * 64, 3) void int4_transform_quant_kernel(
+// PF: tiles in flight ahead of the computed one: 1 with one wave group (three waves per SIMD), 2 with two (the
+// workgroup is then its CU's only one: two waves per SIMD).
+template <bool DBG, bool TILED, int TG, int PF>
+__global__ __launch_bounds__(kWaves * TG * 64, (TG == 2 || DBG) ? 2 : 3) void int4_transform_quant_kernel(
     const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ T, uint8_t* __restrict__ Xq,
     uint8_t* __restrict__ Xs, float* __restrict__ dbg, int M, int K, int C, int tiles_per_wg) {
   const int lane = threadIdx.x & 63;
@@ -122,17 +124,31 @@ __global__ __launch_bounds__(kWaves * TG * 64, 3) void int4_transform_quant_kern
   const int ntiles = (M + kTileM - 1) / kTileM;
   auto tile_of = [&](int j) { return j * (int)gridDim.x + (int)blockIdx.x; };
   auto valid = [&](int j) { return j < tiles_per_wg && tile_of(j) < ntiles; };
-  int j = tg;
-  if (!valid(j)) return;
+  if (!valid(tg)) return;
 
-  XFrag cur[kNB], nxt[kNB];
-  tq::load_tile(cur, X, ldx, min(tile_of(j) * kTileM + tok, M - 1), bfirst, C, h);
+  // PF tiles in flight ahead of the one being computed, in PF + 1 register sets that take turns by unrolling
+  // (no copies); every load is unconditional (a tile past the end of the walk becomes one row of the first tile, a
+  // single resident cache line per instruction) and a finished wave leaves the kernel, so that the compiler's
+  // wait counts are exact ones (transform_quant.hip).
+  const int row_spare = min(tile_of(tg) * kTileM, M - 1);
+  auto tile_row = [&](int j) { return valid(j) ? min(tile_of(j) * kTileM + tok, M - 1) : row_spare; };
+  XFrag x[PF + 1][kNB];
+#pragma unroll
+  for (int s = 0; s < PF; ++s) {
+    tq::load_tile(x[s], X, ldx, tile_row(tg + s * TG), bfirst, C, h);
+    __builtin_amdgcn_sched_barrier(0);
+  }
 
-  for (; valid(j); j += TG) {
+  for (int base = tg; base < tiles_per_wg; base += (PF + 1) * TG) {
+#pragma unroll
+    for (int s = 0; s <= PF; ++s) {
+    const int j = base + s * TG;
+    if (!valid(j)) return;
+    const XFrag (&cur)[kNB] = x[s];
     const int t = tile_of(j);
     const int m = t * kTileM + tok;
     const bool row_ok = m < M;
-    if (valid(j + TG)) tq::load_tile(nxt, X, ldx, min(tile_of(j + TG) * kTileM + tok, M - 1), bfirst, C, h);
+    tq::load_tile(x[(s + PF) % (PF + 1)], X, ldx, tile_row(j + PF * TG), bfirst, C, h);
 
     v4u out[2];
     uint32_t sc[kNB];
@@ -166,8 +182,7 @@ __global__ __launch_bounds__(kWaves * TG * 64, 3) void int4_transform_quant_kern
         }
       }
     }
-#pragma unroll
-    for (int bb = 0; bb < kNB; ++bb) cur[bb] = nxt[bb];
+    }
   }
 }
 
@@ -211,7 +226,7 @@ hipError_t launch_int4_transform_quant(const void* X, int64_t M, int64_t K, int6
   dim3 grid((ntiles + tiles_per_wg - 1) / tiles_per_wg, col_groups);
   dim3 block(kWaves * 64 * walk.groups);
 #define WUSH_I4Q_LAUNCH(DBG, TILED, TG)                                                                       \
-  int4_transform_quant_kernel<DBG, TILED, TG><<<grid, block, 0, stream>>>(                                    \
+  int4_transform_quant_kernel<DBG, TILED, TG, TG><<<grid, block, 0, stream>>>(                                \
       (const uint16_t*)X, ldx, (const uint16_t*)T, (uint8_t*)Xq, (uint8_t*)Xs, dbg, (int)M, (int)K, C, tiles_per_wg)
   if (walk.groups == 2) {
     if (dbg) {

@@ -147,8 +147,8 @@ def test_quantizers_do_not_spill_and_keep_three_waves_per_simd(src, pattern, cou
     for name, body in kernels.items():
         assert "scratch_" not in body, f"{name}: spills to scratch"
     # register budget from the kernel descriptors: at most 168 VGPRs = three waves per SIMD of 512 (the
-    # instantiations that also write the FP32 transformed values, a test tap, are exempt).  The MXFP4 kernel
-    # with two wave groups and two tiles of lookahead runs as the only workgroup of its CU, two waves per
+    # instantiations that also write the FP32 transformed values, a test tap, are exempt).  The kernels
+    # with two wave groups and two tiles of lookahead run as the only workgroup of their CU, two waves per
     # SIMD: 256.
     for m in re.finditer(r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.vgpr_count:\s+(\d+)", text):
         if pattern in m.group(1) and "kernelILb1E" not in m.group(1):
