@@ -159,6 +159,43 @@ def measured_ceilings(torch, dev, x_bits, w_bits):
     return out
 
 
+COLD_WEIGHT_SETS = 4
+
+
+def cold_weights_ms(torch, replay_ms, weights, launch, steps):
+    """The few-token GEMM with the packed weights rotating over COLD_WEIGHT_SETS copies, so that every step streams
+    them from HBM (one copy of the c5 weights is about the size of the 256 MB last-level cache and is partly served
+    from it when the same buffers are read step after step).  Returns ms per launch, or None if the copies do not
+    fit (they do on this part: 4 x 240 MiB)."""
+    sets = [weights] + [[w.clone() for w in weights] for _ in range(COLD_WEIGHT_SETS - 1)]
+    state = {"i": 0}
+
+    def fn():
+        launch(sets[state["i"] % COLD_WEIGHT_SETS])
+        state["i"] += 1
+
+    calls = max(COLD_WEIGHT_SETS, steps - steps % COLD_WEIGHT_SETS)
+    ms = replay_ms(fn, calls)
+    del sets
+    return ms
+
+
+def read_stream_cold_gbs(torch, dev, nbytes):
+    """What a read-only linear stream of about nbytes reaches from HBM on this machine, now (probes library: the xor of
+    everything read, one small store per wave), over COLD_WEIGHT_SETS rotating buffers."""
+    from paper_2512_00956_amd import probes
+    n = max(1 << 22, nbytes // (1 << 22) * (1 << 22))
+    srcs = [torch.empty(n, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(COLD_WEIGHT_SETS)]
+    dst = torch.empty(256 * 8 * 1024, dtype=torch.uint8, device=dev)
+    ms = events_ms(torch, lambda i: probes.stream(srcs[i % COLD_WEIGHT_SETS], n // 4096, 4096, dst, 50, 256), 24, warm=8)
+    return n / ms / 1e6
+
+
+def cold_entry(ms, gemm_bytes):
+    return {"ms": ms, "GB/s": gemm_bytes / ms / 1e6, "frac_hbm": gemm_bytes / ms / 1e6 / PEAK_HBM_GBS,
+            "weight_sets": COLD_WEIGHT_SETS}
+
+
 def decode_bench(args, P, torch, dev):
     """d2 / d5: one step = one wush_layer_decode call on M = 16 tokens."""
     base = DECODE[args.workload]
@@ -213,6 +250,7 @@ def decode_bench(args, P, torch, dev):
     P.wush_layer_decode_status(dws, K)
     g_ms = replay_ms(lambda: P.wush_linear(Xq, Xs, Wq, Ws, Y, fmt, K=K), args.steps)
     gemm_bytes = N * K * (0.5 + 1 / 32) + M * K * (0.5 + 1 / 32) + M * N * 2
+    cold = cold_weights_ms(torch, replay_ms, [Wq, Ws], lambda w: P.wush_linear(Xq, Xs, w[0], w[1], Y, fmt, K=K), args.steps)
     traffic = traffic_for(args.workload, "tiled", P.lib().wush_version().decode())
     layer_bytes = N * K * (0.5 + 1 / 32) + quant_bytes(M, K) + M * K * (0.5 + 1 / 32) + M * N * 2
     flops = 2.0 * M * N * K
@@ -230,7 +268,9 @@ def decode_bench(args, P, torch, dev):
                      "traffic_over_algorithmic": None if traffic is None else traffic / gemm_bytes, "avg_launch_ms": g_ms},
         "kernels": {"wush_layer_decode": {"ms": ms_per_step, "GB/s": layer_bytes / ms_per_step / 1e6,
                                           "algorithmic_bytes": layer_bytes},
-                    "wush_linear": {"ms": g_ms, "GB/s": gemm_bytes / g_ms / 1e6, "algorithmic_bytes": gemm_bytes}},
+                    "wush_linear": {"ms": g_ms, "GB/s": gemm_bytes / g_ms / 1e6, "algorithmic_bytes": gemm_bytes},
+                    "wush_linear_cold_weights": cold_entry(cold, gemm_bytes)},
+        "read_only_stream_cold_GB/s": read_stream_cold_gbs(torch, dev, int(N * K * (0.5 + 1 / 32))),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, T_bits, L, M)
@@ -304,6 +344,12 @@ def w4_decode_bench(args, P, torch, dev):
     gemm_bytes = (N + M) * K * (0.5 + 1 / 16) + M * N * 2
     flops = 2.0 * M * N * K
     traffic = traffic_for(args.workload, "tiled", P.lib().wush_version().decode())
+    if nv:
+        cold = cold_weights_ms(torch, replay_ms, [Wq, Ws],
+                               lambda w: P.wush_linear_nvfp4(Xq, Xs, tsx, w[0], w[1], tsw, Y, layout=1, K=K), args.steps)
+    else:
+        cold = cold_weights_ms(torch, replay_ms, [Wq, Ws],
+                               lambda w: P.wush_linear_int4(Xq, Xs, w[0], w[1], Y, layout=1, K=K), args.steps)
     name = "wush_linear_nvfp4" if nv else "wush_linear_int4"
     out = {
         "metric": f"W4A4 layer TFLOP/s (transform+quant+{fmt_name.upper()} GEMM); % of HBM peak",
@@ -318,7 +364,9 @@ def w4_decode_bench(args, P, torch, dev):
                      "frac": gemm_bytes / g_ms / 1e6 / PEAK_HBM_GBS, "traffic": traffic, "algorithmic_bytes": gemm_bytes,
                      "traffic_over_algorithmic": None if traffic is None else traffic / gemm_bytes,
                      "avg_launch_ms": g_ms},
-        "kernels": {name: {"ms": g_ms, "GB/s": gemm_bytes / g_ms / 1e6}},
+        "kernels": {name: {"ms": g_ms, "GB/s": gemm_bytes / g_ms / 1e6},
+                    name + "_cold_weights": cold_entry(cold, gemm_bytes)},
+        "read_only_stream_cold_GB/s": read_stream_cold_gbs(torch, dev, int(N * K * (0.5 + 1 / 16))),
     }
     print(json.dumps(out))
 

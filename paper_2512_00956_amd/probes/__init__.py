@@ -69,6 +69,7 @@ def stream(src, rows: int, row_bytes: int, dst, mode: int, blocks: int):
     mode 3: mode 1 with a contiguous run of tiles per workgroup; modes 4, 5, 6: mode 1 with
     linear / no scale / cached stores; modes 10, 11, 13: read-pattern probes with
     linear stores of a quarter of the bytes (32 rows x 256 B per wave tile, 8 rows x 1 KiB, and the first
-    with whole 128-byte lines per load instruction), contiguous runs; 20, 21, 23: the same dealt round-robin; 30, 40: modes 0 and 20 with non-temporal loads.  dst: at least rows*row_bytes*17/64 bytes."""
+    with whole 128-byte lines per load instruction), contiguous runs; 20, 21, 23: the same dealt round-robin; 30, 40: modes 0 and 20 with non-temporal loads;
+    50: linear and read only (dst then holds blocks * 8 KiB: the xor of what each wave read).  dst: at least rows*row_bytes*17/64 bytes."""
     _check(lib().wushp_stream(c_void_p(src.data_ptr()), rows, row_bytes, c_void_p(dst.data_ptr()), mode, blocks,
                               _stream()), "wushp_stream")

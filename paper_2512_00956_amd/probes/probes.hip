@@ -163,6 +163,8 @@ __global__ __launch_bounds__(256) void mfma_f16_probe_kernel(const v8h* __restri
 //   modes 10, 11: read-pattern probes: a wave's tile is 32 or 8 rows x 256 B or 1 KiB of each,
 //           linear stores of a quarter of the bytes.  mode 13: the tile of mode 10 (32 rows x 256 B) read
 //           with whole 128-byte lines per load instruction (8 rows each) instead of 32 bytes of 32 rows.
+//   mode 50: linear, read only (what a weight-streaming kernel could reach): the xor of all a wave read is stored
+//           once, 1 KiB per wave, at the end.
 //   modes 30, 40: as 0 and 20 with non-temporal loads.  From HBM the linear stream gains 3 % (5.75 TB/s) and
 //           loses 13 % cache resident; the tile pattern, whose load instructions take a 128-byte line in
 //           four parts, drops to 3.7 TB/s.
@@ -175,7 +177,7 @@ __device__ __forceinline__ v4u load16(const v4u* p) {
   return NT ? __builtin_nontemporal_load(p) : *p;
 }
 
-template <bool NT>
+template <bool NT, bool READ_ONLY = false>
 __global__ __launch_bounds__(512) void stream_linear_kernel(const v4u* __restrict__ src, long long n_steps,
                                                             v4u* __restrict__ dst) {
   const int lane = threadIdx.x & 63;
@@ -184,6 +186,7 @@ __global__ __launch_bounds__(512) void stream_linear_kernel(const v4u* __restric
   // two steps in flight, two register sets that swap roles (no copies, no conditional loads: the
   // compiler's wait counts stay exact)
   v4u x[3][4];
+  v4u sum = {0, 0, 0, 0};   // READ_ONLY: the xor of everything the wave read, stored once at the end
   auto step_of = [&](long long st) { return st < n_steps ? st : wave; };
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
@@ -195,13 +198,18 @@ __global__ __launch_bounds__(512) void stream_linear_kernel(const v4u* __restric
 #pragma unroll
     for (int s = 0; s < 3; ++s) {
       const long long st = base + s * nwaves;
-      if (st >= n_steps) return;
+      if (st >= n_steps) {
+        if (READ_ONLY) dst[wave * 64 + lane] = sum;
+        return;
+      }
 #pragma unroll
       for (int i = 0; i < 4; ++i) x[(s + 2) % 3][i] = load16<NT>(src + step_of(st + 2 * nwaves) * 256 + 64 * i + lane);
       const v4u o = x[s][0] ^ x[s][1] ^ x[s][2] ^ x[s][3];
-      __builtin_nontemporal_store(o, dst + st * 64 + lane);
+      if (READ_ONLY) sum ^= o;
+      else __builtin_nontemporal_store(o, dst + st * 64 + lane);
     }
   }
+  if (READ_ONLY) dst[wave * 64 + lane] = sum;
 }
 
 template <int PF, int NBW>
@@ -362,6 +370,9 @@ int wushp_stream(const void* src, long long rows, long long row_bytes, void* dst
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (mode == 0) {
     wush::stream_linear_kernel<false><<<dim3((unsigned)blocks), dim3(512), 0, st>>>(
+        static_cast<const wush::v4u*>(src), rows * row_bytes / 4096, static_cast<wush::v4u*>(dst));
+  } else if (mode == 50) {   // read only: every wave stores 1 KiB once (dst: at least blocks * 8 KiB)
+    wush::stream_linear_kernel<false, true><<<dim3((unsigned)blocks), dim3(512), 0, st>>>(
         static_cast<const wush::v4u*>(src), rows * row_bytes / 4096, static_cast<wush::v4u*>(dst));
   } else if (mode == 30) {
     wush::stream_linear_kernel<true><<<dim3((unsigned)blocks), dim3(512), 0, st>>>(

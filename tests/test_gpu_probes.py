@@ -69,3 +69,21 @@ def test_stream_probe_touches_what_it_claims(Q, mode):
         Q.stream(src2, rows, row_bytes, dst, mode, 16)
         torch.cuda.synchronize()
         assert (dst.cpu().numpy() != first).any()
+
+
+def test_read_only_stream_reads_everything(Q):
+    """Mode 50 stores, per wave, the xor of all it read: the xor over all waves must be the xor of the source, and
+    flipping any byte must change it."""
+    import torch
+    rows, row_bytes, blocks = 512, 4096, 16
+    g = torch.Generator(device="cuda").manual_seed(5)
+    src = torch.randint(0, 256, (rows * row_bytes,), dtype=torch.uint8, device="cuda", generator=g)
+    dst = torch.zeros(blocks * 8 * 1024 + 4096, dtype=torch.uint8, device="cuda")
+    dst[blocks * 8 * 1024:] = 0xA5
+    Q.stream(src, rows, row_bytes, dst, 50, blocks)
+    torch.cuda.synchronize()
+    d = dst.cpu().numpy()
+    assert (d[blocks * 8 * 1024:] == 0xA5).all()
+    got = np.bitwise_xor.reduce(d[:blocks * 8 * 1024].reshape(-1, 16), axis=0)     # per wave 64 lanes x 16 B
+    want = np.bitwise_xor.reduce(src.cpu().numpy().reshape(-1, 16), axis=0)
+    assert np.array_equal(got, want)
