@@ -142,46 +142,46 @@ __global__ __launch_bounds__(kWaves * TG * 64, (TG == 2 || DBG) ? 2 : 3) void in
   for (int base = tg; base < tiles_per_wg; base += (PF + 1) * TG) {
 #pragma unroll
     for (int s = 0; s <= PF; ++s) {
-    const int j = base + s * TG;
-    if (!valid(j)) return;
-    const XFrag (&cur)[kNB] = x[s];
-    const int t = tile_of(j);
-    const int m = t * kTileM + tok;
-    const bool row_ok = m < M;
-    tq::load_tile(x[(s + PF) % (PF + 1)], X, ldx, tile_row(j + PF * TG), bfirst, C, h);
+      const int j = base + s * TG;
+      if (!valid(j)) return;
+      const XFrag (&cur)[kNB] = x[s];
+      const int t = tile_of(j);
+      const int m = t * kTileM + tok;
+      const bool row_ok = m < M;
+      tq::load_tile(x[(s + PF) % (PF + 1)], X, ldx, tile_row(j + PF * TG), bfirst, C, h);
 
-    v4u out[2];
-    uint32_t sc[kNB];
-    float* dbg_row = (DBG && row_ok) ? dbg + (int64_t)m * K + 32 * bfirst + 16 * h : nullptr;
-    transform_quantize_int4<DBG>(ta, cur, out, sc, dbg_row, nb);
-    if (row_ok && TILED) {
-      // K % 64 == 0: this lane's blocks 2h, 2h+1 are the two groups of K step bfirst/2 + h
-      const int KT = K >> 6, kt = (bfirst >> 1) + h;
-      if (2 * h < nb) {
-        __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(Xq + nv_tiled_chunk_offset(m, kt, 0, KT)));
-        __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(Xq + nv_tiled_chunk_offset(m, kt, 1, KT)));
-        const uint32_t pair = h ? (sc[2] | sc[3] << 16) : (sc[0] | sc[1] << 16);
-        __builtin_nontemporal_store(pair, reinterpret_cast<uint32_t*>(Xs + nv_tiled_scale_offset(m, kt, KT)));
-      }
-    } else if (row_ok) {
-      uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
-      uint16_t* sp = reinterpret_cast<uint16_t*>(Xs) + (int64_t)m * C + bfirst;
-      if (nb == kNB && (C & 3) == 0) {
-        __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(q));
-        __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(q + 16));
-        if (h == 0)
-          __builtin_nontemporal_store((v2u){sc[0] | sc[1] << 16, sc[2] | sc[3] << 16}, reinterpret_cast<v2u*>(sp));
-      } else {
+      v4u out[2];
+      uint32_t sc[kNB];
+      float* dbg_row = (DBG && row_ok) ? dbg + (int64_t)m * K + 32 * bfirst + 16 * h : nullptr;
+      transform_quantize_int4<DBG>(ta, cur, out, sc, dbg_row, nb);
+      if (row_ok && TILED) {
+        // K % 64 == 0: this lane's blocks 2h, 2h+1 are the two groups of K step bfirst/2 + h
+        const int KT = K >> 6, kt = (bfirst >> 1) + h;
+        if (2 * h < nb) {
+          __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(Xq + nv_tiled_chunk_offset(m, kt, 0, KT)));
+          __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(Xq + nv_tiled_chunk_offset(m, kt, 1, KT)));
+          const uint32_t pair = h ? (sc[2] | sc[3] << 16) : (sc[0] | sc[1] << 16);
+          __builtin_nontemporal_store(pair, reinterpret_cast<uint32_t*>(Xs + nv_tiled_scale_offset(m, kt, KT)));
+        }
+      } else if (row_ok) {
+        uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
+        uint16_t* sp = reinterpret_cast<uint16_t*>(Xs) + (int64_t)m * C + bfirst;
+        if (nb == kNB && (C & 3) == 0) {
+          __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(q));
+          __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(q + 16));
+          if (h == 0)
+            __builtin_nontemporal_store((v2u){sc[0] | sc[1] << 16, sc[2] | sc[3] << 16}, reinterpret_cast<v2u*>(sp));
+        } else {
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
-          if (2 * h + p < nb) *reinterpret_cast<v4u*>(q + 16 * p) = out[p];
-        if (h == 0) {
+          for (int p = 0; p < 2; ++p)
+            if (2 * h + p < nb) *reinterpret_cast<v4u*>(q + 16 * p) = out[p];
+          if (h == 0) {
 #pragma unroll
-          for (int bb = 0; bb < kNB; ++bb)
-            if (bb < nb) sp[bb] = (uint16_t)sc[bb];
+            for (int bb = 0; bb < kNB; ++bb)
+              if (bb < nb) sp[bb] = (uint16_t)sc[bb];
+          }
         }
       }
-    }
     }
   }
 }

@@ -186,43 +186,43 @@ __global__ __launch_bounds__(kWaves * TG * 64, (TG == 2 || DBG) ? 2 : 3) void nv
   for (int base = tg; base < tiles_per_wg; base += (PF + 1) * TG) {
 #pragma unroll
     for (int s = 0; s <= PF; ++s) {
-    const int j = base + s * TG;
-    if (!valid(j)) return;
-    const XFrag (&cur)[kNB] = x[s];
-    const int t = tile_of(j);
-    const int m = t * kTileM + tok;
-    const bool row_ok = m < M;
-    tq::load_tile(x[(s + PF) % (PF + 1)], X, ldx, tile_row(j + PF * TG), bfirst, C32, h);
+      const int j = base + s * TG;
+      if (!valid(j)) return;
+      const XFrag (&cur)[kNB] = x[s];
+      const int t = tile_of(j);
+      const int m = t * kTileM + tok;
+      const bool row_ok = m < M;
+      tq::load_tile(x[(s + PF) % (PF + 1)], X, ldx, tile_row(j + PF * TG), bfirst, C32, h);
 
-    v4u out[2];
-    v2u scales;
-    float* dbg_row = (DBG && row_ok) ? dbg + (int64_t)m * K + 32 * bfirst + 16 * h : nullptr;
-    transform_quantize16<DBG>(ta, cur, c, ts, out, scales, dbg_row, nb);
-    if (row_ok && TILED) {
-      // K % 64 == 0: this lane's chunks 2h, 2h+1 are the two halves of K step bfirst/2 + h
-      const int KT = K >> 6, kt = (bfirst >> 1) + h;
-      if (2 * h < nb) {
-        __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(Xq + nv_tiled_chunk_offset(m, kt, 0, KT)));
-        __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(Xq + nv_tiled_chunk_offset(m, kt, 1, KT)));
-        // every lane holds all 8 scale bytes of its token; each half writes its own step's four
-        __builtin_nontemporal_store(scales[h], reinterpret_cast<uint32_t*>(Xs + nv_tiled_scale_offset(m, kt, KT)));
-      }
-    } else if (row_ok) {
-      uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
-      uint8_t* sp = Xs + (int64_t)m * (K / 16) + 2 * bfirst;
-      if (nb == kNB && (C32 & 3) == 0) {
-        __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(q));
-        __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(q + 16));
-        if (h == 0) __builtin_nontemporal_store(scales, reinterpret_cast<v2u*>(sp));
-      } else {
-        // ragged tail of the channel dimension: chunks 2h and 2h+1 of this lane
+      v4u out[2];
+      v2u scales;
+      float* dbg_row = (DBG && row_ok) ? dbg + (int64_t)m * K + 32 * bfirst + 16 * h : nullptr;
+      transform_quantize16<DBG>(ta, cur, c, ts, out, scales, dbg_row, nb);
+      if (row_ok && TILED) {
+        // K % 64 == 0: this lane's chunks 2h, 2h+1 are the two halves of K step bfirst/2 + h
+        const int KT = K >> 6, kt = (bfirst >> 1) + h;
+        if (2 * h < nb) {
+          __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(Xq + nv_tiled_chunk_offset(m, kt, 0, KT)));
+          __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(Xq + nv_tiled_chunk_offset(m, kt, 1, KT)));
+          // every lane holds all 8 scale bytes of its token; each half writes its own step's four
+          __builtin_nontemporal_store(scales[h], reinterpret_cast<uint32_t*>(Xs + nv_tiled_scale_offset(m, kt, KT)));
+        }
+      } else if (row_ok) {
+        uint8_t* q = Xq + (int64_t)m * (K / 2) + 16 * bfirst + 32 * h;
+        uint8_t* sp = Xs + (int64_t)m * (K / 16) + 2 * bfirst;
+        if (nb == kNB && (C32 & 3) == 0) {
+          __builtin_nontemporal_store(out[0], reinterpret_cast<v4u*>(q));
+          __builtin_nontemporal_store(out[1], reinterpret_cast<v4u*>(q + 16));
+          if (h == 0) __builtin_nontemporal_store(scales, reinterpret_cast<v2u*>(sp));
+        } else {
+          // ragged tail of the channel dimension: chunks 2h and 2h+1 of this lane
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
-          if (2 * h + p < nb) *reinterpret_cast<v4u*>(q + 16 * p) = out[p];
-        if (h == 0)
-          for (int g = 0; g < 2 * nb; ++g) sp[g] = (uint8_t)(scales[g >> 2] >> (8 * (g & 3)));
+          for (int p = 0; p < 2; ++p)
+            if (2 * h + p < nb) *reinterpret_cast<v4u*>(q + 16 * p) = out[p];
+          if (h == 0)
+            for (int g = 0; g < 2 * nb; ++g) sp[g] = (uint8_t)(scales[g >> 2] >> (8 * (g & 3)));
+        }
       }
-    }
     }
   }
 }
